@@ -1,0 +1,249 @@
+"""Seeded synthetic inputs for the quantized GNN-layer primitives.
+
+This package only *generates inputs* (graphs, feature matrices, weights,
+upstream gradients).  It contains none of the method's arithmetic and is the
+one module that both the CPU oracle's tests and the GPU path's tests/bench may
+share.  Everything is a pure function of its seed.
+
+Graphs are returned as a ``Graph`` of int32 numpy arrays:
+
+* ``in_ptr[N+1]``, ``in_src[nnz]``   destination-major (CSC): in-edges of v are
+  positions ``in_ptr[v] .. in_ptr[v+1]-1``; edge tensors are indexed by this
+  position.
+* ``out_ptr[N+1]``, ``out_dst[nnz]``, ``out_eid[nnz]``  source-major (CSR) view
+  of the same edges; ``out_eid[j]`` is the destination-major position of
+  out-edge ``j``.
+
+The graphs are simple (no duplicate edges) and every node has a self-loop
+(the paper's preprocessing adds self-connections, Sec. 4.1 "Datasets").
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gen.c")
+_LIB = os.path.join(_HERE, "libtango_inputs.so")
+_lib = None
+
+BASE_SEED = 2308008900
+
+
+def build(force: bool = False) -> str:
+    """Compile gen.c with gcc (host code only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-o", tmp, _SRC]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.ti_rmat_keys.restype = None
+        _lib.ti_unique_sorted.restype = ctypes.c_int64
+        _lib.ti_select.restype = None
+        _lib.ti_csc_from_sorted_keys.restype = None
+        _lib.ti_csr_from_csc.restype = None
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+@dataclass
+class Graph:
+    n_nodes: int
+    n_edges: int
+    in_ptr: np.ndarray
+    in_src: np.ndarray
+    out_ptr: np.ndarray
+    out_dst: np.ndarray
+    out_eid: np.ndarray
+
+    def in_dst(self) -> np.ndarray:
+        """Destination of every edge in destination-major order."""
+        return np.repeat(np.arange(self.n_nodes, dtype=np.int32), np.diff(self.in_ptr))
+
+
+def graph_from_keys(n_nodes: int, keys: np.ndarray) -> Graph:
+    """``keys`` = unique ``(dst << 32) | src`` values, any order."""
+    lib = _load()
+    keys = np.sort(np.ascontiguousarray(keys, dtype=np.uint64))
+    nnz = int(keys.shape[0])
+    if nnz >= 2**31:
+        raise ValueError("n_edges must be below 2^31")
+    in_ptr = np.empty(n_nodes + 1, np.int32)
+    in_src = np.empty(nnz, np.int32)
+    lib.ti_csc_from_sorted_keys(ctypes.c_int64(n_nodes), ctypes.c_int64(nnz), _p(keys), _p(in_ptr), _p(in_src))
+    del keys
+    out_ptr = np.empty(n_nodes + 1, np.int32)
+    out_dst = np.empty(nnz, np.int32)
+    out_eid = np.empty(nnz, np.int32)
+    lib.ti_csr_from_csc(
+        ctypes.c_int64(n_nodes), ctypes.c_int64(nnz), _p(in_ptr), _p(in_src), _p(out_ptr), _p(out_dst), _p(out_eid)
+    )
+    return Graph(n_nodes, nnz, in_ptr, in_src, out_ptr, out_dst, out_eid)
+
+
+def graph_from_edges(n_nodes: int, src, dst, self_loops: bool = True) -> Graph:
+    """Simple graph from an explicit edge list (duplicates removed)."""
+    src = np.asarray(src, dtype=np.uint64)
+    dst = np.asarray(dst, dtype=np.uint64)
+    keys = (dst << np.uint64(32)) | src
+    if self_loops:
+        ids = np.arange(n_nodes, dtype=np.uint64)
+        keys = np.concatenate([keys, (ids << np.uint64(32)) | ids])
+    return graph_from_keys(n_nodes, np.unique(keys))
+
+
+def toy_graph(n_nodes: int = 1024, n_edges: int = 16384, seed: int = BASE_SEED + 1) -> Graph:
+    """``n_edges`` distinct ordered pairs u != v, uniform, plus one self-loop per node."""
+    rng = np.random.default_rng(seed)
+    total = n_nodes * (n_nodes - 1)
+    if n_edges > total:
+        raise ValueError("too many edges for a simple graph")
+    # index into the list of ordered pairs without the diagonal
+    pick = rng.choice(total, size=n_edges, replace=False)
+    u = pick // (n_nodes - 1)
+    r = pick % (n_nodes - 1)
+    v = r + (r >= u)
+    return graph_from_edges(n_nodes, u, v, self_loops=True)
+
+
+def rmat_graph(
+    n_nodes: int,
+    n_edges: int,
+    seed: int,
+    a: float = 0.57,
+    b: float = 0.19,
+    c: float = 0.19,
+    permute: bool = True,
+    self_loops: bool = True,
+) -> Graph:
+    """R-MAT graph with exactly ``n_edges`` distinct directed edges u != v (+ self-loops).
+
+    scale = ceil(log2 n_nodes); candidates with an endpoint >= n_nodes, self
+    pairs and duplicates are dropped and more candidates are drawn until the
+    count is met; the surplus of the last batch is cut by a seeded choice.
+    Node ids are randomly permuted (seeded) unless ``permute`` is False.
+    """
+    lib = _load()
+    scale = max(1, int(np.ceil(np.log2(max(n_nodes, 2)))))
+    thr = np.array(
+        [round(a * 65536), round((a + b) * 65536), round((a + b + c) * 65536)], dtype=np.uint32
+    )
+    rng = np.random.default_rng(seed)
+    perm = rng.permutation(n_nodes).astype(np.int32) if permute else None
+    have = np.empty(0, np.uint64)
+    first = 0
+    while have.shape[0] < n_edges:
+        batch = 2 * (n_edges - have.shape[0]) + 1024
+        keys = np.empty(have.shape[0] + batch, np.uint64)
+        keys[: have.shape[0]] = have
+        lib.ti_rmat_keys(
+            ctypes.c_int(scale),
+            ctypes.c_uint64(n_nodes),
+            ctypes.c_uint64(batch),
+            ctypes.c_uint64(seed),
+            ctypes.c_uint64(first),
+            _p(thr),
+            _p(perm) if perm is not None else None,
+            ctypes.c_void_p(keys.ctypes.data + 8 * have.shape[0]),
+        )
+        first += batch
+        keys.sort()
+        m = lib.ti_unique_sorted(_p(keys), ctypes.c_int64(keys.shape[0]))
+        if m > n_edges:
+            lib.ti_select(_p(keys), ctypes.c_int64(m), ctypes.c_int64(n_edges), ctypes.c_uint64(seed + 77))
+            m = n_edges
+        have = keys[:m].copy()
+        del keys
+    if self_loops:
+        ids = np.arange(n_nodes, dtype=np.uint64)
+        have = np.concatenate([have, (ids << np.uint64(32)) | ids])
+    return graph_from_keys(n_nodes, have)
+
+
+def normal(shape, seed: int) -> np.ndarray:
+    """i.i.d. N(0,1) fp32."""
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal(size=shape, dtype=np.float32)
+
+
+def xavier_uniform(fan_in: int, fan_out: int, shape, seed: int) -> np.ndarray:
+    """U(-b, b) with b = sqrt(6 / (fan_in + fan_out)), fp32."""
+    rng = np.random.default_rng(seed)
+    bound = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-bound, bound, size=shape).astype(np.float32)
+
+
+def gcn_edge_weights(g: Graph) -> np.ndarray:
+    """Fixed GCN edge weights 1/sqrt(d_out(src) * d_in(dst)), degrees counted with self-loops.
+
+    These are *inputs* of the GCN layer's SPMM (they are not learned).
+    """
+    d_in = np.diff(g.in_ptr).astype(np.float64)
+    d_out = np.diff(g.out_ptr).astype(np.float64)
+    w = 1.0 / np.sqrt(d_out[g.in_src] * d_in[g.in_dst()])
+    return w.astype(np.float32).reshape(-1, 1)
+
+
+@dataclass
+class LayerInputs:
+    graph: Graph
+    feat: np.ndarray  # N x K_in
+    weight: np.ndarray  # K_in x F
+    a_src: np.ndarray  # heads x dim (GAT only)
+    a_dst: np.ndarray
+    grad_out: np.ndarray  # N x F
+    heads: int
+    dim: int
+    sr_seed: int
+
+
+# name -> (n_nodes, directed edges without self-loops, K_in, heads, dim, kind)
+CONFIGS = {
+    "toy": dict(config=1, n_nodes=1024, n_edges=16384, k_in=64, heads=2, dim=32, kind="gat", graph="uniform"),
+    "gcn_arxiv": dict(config=2, n_nodes=169343, n_edges=1166243, k_in=128, heads=1, dim=256, kind="gcn", graph="rmat"),
+    "gat_dense": dict(config=3, n_nodes=232965, n_edges=114615892, k_in=602, heads=4, dim=64, kind="gat", graph="rmat"),
+    "gat_products": dict(config=4, n_nodes=2449029, n_edges=61859140, k_in=100, heads=3, dim=128, kind="gat", graph="rmat"),
+    "sweep22": dict(config=5, n_nodes=4194304, n_edges=4194304 * 15, k_in=0, heads=1, dim=0, kind="sweep", graph="rmat"),
+}
+
+
+def config_graph(name: str, scale_down: int = 1) -> Graph:
+    """Graph of a named configuration; ``scale_down`` divides nodes and edges (same mean degree)."""
+    c = CONFIGS[name]
+    seed = BASE_SEED + c["config"]
+    n = max(2, c["n_nodes"] // scale_down)
+    m = c["n_edges"] // scale_down
+    if c["graph"] == "uniform":
+        return toy_graph(n, m, seed)
+    return rmat_graph(n, m, seed)
+
+
+def layer_inputs(name: str, scale_down: int = 1, graph: Graph | None = None, k_in: int | None = None) -> LayerInputs:
+    """All tensors of one layer of a named configuration (seeds fixed per configuration)."""
+    c = CONFIGS[name]
+    seed = BASE_SEED + c["config"]
+    g = graph if graph is not None else config_graph(name, scale_down)
+    k = c["k_in"] if k_in is None else k_in
+    heads, dim = c["heads"], c["dim"]
+    f = heads * dim
+    feat = normal((g.n_nodes, k), seed + 100)
+    weight = xavier_uniform(k, f, (k, f), seed + 200)
+    a_src = xavier_uniform(heads, dim, (heads, dim), seed + 201)
+    a_dst = xavier_uniform(heads, dim, (heads, dim), seed + 202)
+    grad = normal((g.n_nodes, f), seed + 300)
+    return LayerInputs(g, feat, weight, a_src, a_dst, grad, heads, dim, seed + 400)

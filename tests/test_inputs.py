@@ -1,0 +1,56 @@
+"""Host-side checks of the seeded graph builders (no method arithmetic involved)."""
+import numpy as np
+import pytest
+
+import tango_inputs as ti
+
+
+def check_graph(g):
+    N, nnz = g.n_nodes, g.n_edges
+    assert g.in_ptr[0] == 0 and g.in_ptr[-1] == nnz and g.out_ptr[0] == 0 and g.out_ptr[-1] == nnz
+    assert (np.diff(g.in_ptr) >= 1).all() and (np.diff(g.out_ptr) >= 1).all()  # the self-loop
+    dst = g.in_dst().astype(np.int64)
+    src = g.in_src.astype(np.int64)
+    keys = dst * N + src
+    assert (np.diff(keys) > 0).all()  # sorted, no duplicate edges
+    assert np.isin(np.arange(N) * (N + 1), keys).all()  # every self-loop present
+    # out_* is the transpose: same edges, source-major, eid maps back
+    assert np.array_equal(np.sort(g.out_eid), np.arange(nnz))
+    osrc = np.repeat(np.arange(N), np.diff(g.out_ptr))
+    assert np.array_equal(src[g.out_eid], osrc)
+    assert np.array_equal(dst[g.out_eid], g.out_dst)
+    okeys = osrc.astype(np.int64) * N + g.out_dst
+    assert (np.diff(okeys) > 0).all()
+
+
+def test_toy_graph_shape():
+    g = ti.config_graph("toy")
+    assert g.n_nodes == 1024 and g.n_edges == 16384 + 1024
+    check_graph(g)
+
+
+def test_rmat_graph_counts_and_skew():
+    g = ti.rmat_graph(5000, 60000, seed=3)
+    assert g.n_edges == 65000
+    check_graph(g)
+    deg = np.diff(g.in_ptr)
+    assert deg.max() > 20 * np.median(deg)  # power-law skew
+    g2 = ti.rmat_graph(5000, 60000, seed=3)
+    assert np.array_equal(g.in_src, g2.in_src) and np.array_equal(g.out_eid, g2.out_eid)
+    g3 = ti.rmat_graph(5000, 60000, seed=4)
+    assert not np.array_equal(g.in_src, g3.in_src)
+
+
+def test_config2_graph_counts():
+    g = ti.config_graph("gcn_arxiv")
+    assert g.n_nodes == 169343 and g.n_edges == 1166243 + 169343
+    assert np.array_equal(np.sort(g.out_eid), np.arange(g.n_edges))
+
+
+def test_values_are_seeded():
+    a = ti.normal((100, 8), 5)
+    assert a.dtype == np.float32 and np.array_equal(a, ti.normal((100, 8), 5))
+    w = ti.xavier_uniform(64, 64, (64, 64), 6)
+    assert np.abs(w).max() <= np.sqrt(6 / 128)
+    li = ti.layer_inputs("toy")
+    assert li.feat.shape == (1024, 64) and li.weight.shape == (64, 64) and li.a_src.shape == (2, 32)
