@@ -1,0 +1,256 @@
+/*
+ * tango.h -- C ABI of the quantization-aware GNN-layer primitives for AMD
+ * MI355X (gfx950).  Method: "Tango: rethinking quantization for graph neural
+ * network training on GPUs" (SC'23).  Section / equation / figure numbers
+ * below refer to that paper.
+ *
+ * Conventions (all entry points)
+ *  - Every function returns TANGO_OK (0) or a negative tango_status.  Arguments
+ *    are validated on the host before anything is launched; on error nothing
+ *    is launched and no output is touched.
+ *  - Unless marked "host", every pointer is a DEVICE pointer owned by the
+ *    caller.  The library allocates nothing, keeps no state between calls and
+ *    never synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ *    void*, NULL = the default stream) and outputs are valid once the stream
+ *    reaches that point.
+ *  - Scales and abs-max values live in device memory (one float each) so that
+ *    chained calls need no host round trip.  A tensor X with scale s_X
+ *    represents s_X * X_q (symmetric, per tensor, zero point 0; Sec. 2.3).
+ *  - Dense tensors are row-major and contiguous.  Node-feature rows hold
+ *    `heads` blocks of `dim` values, F = heads*dim (Sec. 2.1 step 1).  Edge
+ *    tensors hold `heads` values per edge and are indexed by the edge's
+ *    position in destination-major order (see tango_graph).
+ *  - Indices are int32, n_edges < 2^31; element offsets are formed in 64 bit.
+ *  - `ws`/`ws_bytes`: caller-provided scratch, at least the value returned by
+ *    the matching *_workspace_bytes() query, 256-byte aligned.  Its contents
+ *    on entry do not matter and are undefined on return.
+ *  - `rounding`: TANGO_RN (nearest, ties to even) or TANGO_SR (stochastic
+ *    rounding, Eq. 3).  (seed, stream_id) name the random stream of one
+ *    tensor: element i of the tensor (row-major flat index) uses 16 bits of
+ *    Philox4x32-10(key = seed, counter = (i/8, stream_id)): 32-bit word
+ *    (i%8)/2, low half if i is even, high half if odd.  Results therefore do
+ *    not depend on launch geometry.
+ */
+#ifndef TANGO_H
+#define TANGO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tango_status {
+    TANGO_OK = 0,
+    TANGO_ERR_NULL = -1,          /* a required pointer is NULL */
+    TANGO_ERR_BAD_SHAPE = -2,     /* negative / zero / too large / unsupported size or alignment */
+    TANGO_ERR_BAD_ENUM = -3,      /* unknown rounding, op or direction */
+    TANGO_ERR_UNSUPPORTED = -4,   /* valid but not implemented shape */
+    TANGO_ERR_WORKSPACE = -5,     /* ws is NULL, misaligned or too small */
+    TANGO_ERR_LAUNCH = -6         /* the HIP runtime refused a launch */
+} tango_status;
+
+enum { TANGO_RN = 0, TANGO_SR = 1 };
+enum { TANGO_SDDMM_ADD_LEAKYRELU = 0, TANGO_SDDMM_DOT = 1 };
+enum { TANGO_IN = 0, TANGO_OUT = 1 };
+
+/*
+ * Graph G (Sec. 1: node features H, edge features E, graph G), both
+ * directions.  Destination-major (CSC): the in-edges of node v are positions
+ * in_ptr[v] .. in_ptr[v+1]-1 and in_src[e] is the source of edge e; edge
+ * tensors are indexed by this position e.  Storing edges of one destination
+ * adjacently is what the paper's incidence-matrix formulation buys (Sec. 3.3,
+ * Fig. 5).  Source-major (CSR): out-edges of u are out_ptr[u] .. out_ptr[u+1]-1
+ * with destinations out_dst[j]; out_eid[j] is that edge's destination-major
+ * position.  All arrays are device memory, int32.  The out_* arrays are only
+ * needed by the backward entry points and may be NULL for forward-only use.
+ */
+typedef struct tango_graph {
+    int32_t n_nodes;
+    int64_t n_edges;
+    const int32_t *in_ptr;   /* n_nodes + 1 */
+    const int32_t *in_src;   /* n_edges */
+    const int32_t *out_ptr;  /* n_nodes + 1 */
+    const int32_t *out_dst;  /* n_edges */
+    const int32_t *out_eid;  /* n_edges */
+} tango_graph;
+
+/* Library version (major*10000 + minor*100 + patch) and a static, host string for a status. */
+int tango_version(void);
+const char *tango_status_string(int status);
+
+/* ------------------------------------------------------------------------ */
+/* Quantization (Sec. 2.3 Eq. 1-2 with Z = 0; Sec. 3.2 Eq. 3; Sec. 3.3       */
+/* "Quantization overhead": one abs-max reduction, then multiply + cast).    */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * absmax_out[0] = max_i |x[i]| (0 for n == 0).  x: n floats.
+ */
+int tango_absmax(const float *x, size_t n, float *absmax_out, void *stream);
+
+/*
+ * q[i] = clamp(round(x[i] * inv), -127, 127), inv = 127/absmax (0 if absmax
+ * is 0); scale_out[0] = absmax/127 (1 if absmax is 0).
+ * absmax_in: device float holding max|x| if the producer of x already
+ * computed it (the fused scale computation of Sec. 3.2); NULL = reduce here
+ * (needs ws).  x and q must not overlap.
+ */
+size_t tango_quantize_workspace_bytes(size_t n);
+int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                   const float *absmax_in, int8_t *q, float *scale_out, void *ws, size_t ws_bytes,
+                   void *stream);
+
+/* x[i] = scale[0] * q[i]  (Eq. 2). */
+int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Quantized GEMM (Sec. 3.2 Fig. 3; Sec. 3.3 "GEMM with on-the-fly           */
+/* quantization", Fig. 4).                                                    */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * C (M x N, fp32) = dequantize(A_q . B_q), A (M x K) and B (K x N) fp32.
+ * Both operands are quantized inside the call; their int8 copies A_q (M x K),
+ * B_q (K x N) and scales s_A, s_B are written out for the backward pass
+ * (the cache of Sec. 3.3 "Inter-primitive optimization").  Accumulation is
+ * int32; C = (float)acc * (s_A*s_B); absmax_C[0] = max|C| (the scale
+ * computation fused into the GEMM, Sec. 3.2).  absmax_C may be NULL.
+ * A must be 16-byte aligned.
+ */
+size_t tango_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B, int rounding,
+                uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
+                int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes,
+                void *stream);
+
+/*
+ * Backward of C = A.B from the cached quantized operands (Sec. 3.3): dC
+ * (M x N, fp32) is quantized once (stream_id_dC; absmax_dC_in as in
+ * tango_quantize) into dC_q / s_dC (outputs, kept by the caller), then
+ *   dA (M x K) = (float)(dC_q . B_q^T) * (s_dC*s_B)
+ *   dB (K x N) = (float)(A_q^T . dC_q) * (s_A*s_dC)      (Sec. 3.2: fp32
+ * gradients for the full-precision weight update).  dA or dB may be NULL to
+ * skip that product.
+ */
+size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,
+                    const int8_t *B_q, const float *s_B, const float *dC, int rounding, uint64_t seed,
+                    uint64_t stream_id_dC, const float *absmax_dC_in, int8_t *dC_q, float *s_dC,
+                    float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Attention projections (Sec. 2.1 step 2 and 2'), fp32.                      */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * S[v][h] = sum_d X[v][h][d]*a_src[h][d], D likewise with a_dst.
+ * X: n x (heads*dim); a_src, a_dst: heads x dim; S, D: n x heads.
+ * absmax_S / absmax_D (may be NULL) receive max|S|, max|D|.
+ */
+int tango_head_proj(int64_t n, int heads, int dim, const float *X, const float *a_src,
+                    const float *a_dst, float *S, float *D, float *absmax_S, float *absmax_D,
+                    void *stream);
+
+/*
+ * Step 2' fused with the gradient sum that feeds step 1':
+ *   dX[v][h][d]  = dX_agg[v][h][d] + (dS[v][h]*a_src[h][d] + dD[v][h]*a_dst[h][d])
+ *   da_src[h][d] = sum_v dS[v][h] * (s_X * X_q[v][h][d]),   da_dst likewise with dD
+ * X_q/s_X: the cached quantized H' (n x F int8).  dX may alias dX_agg.
+ * absmax_dX (may be NULL) receives max|dX|.
+ */
+size_t tango_head_proj_bwd_workspace_bytes(int64_t n, int heads, int dim);
+int tango_head_proj_bwd(int64_t n, int heads, int dim, const float *dS, const float *dD,
+                        const float *a_src, const float *a_dst, const int8_t *X_q, const float *s_X,
+                        const float *dX_agg, float *dX, float *absmax_dX, float *da_src,
+                        float *da_dst, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Quantized SDDMM (Sec. 2.1 steps 3 and 5''; Sec. 3.3 "SDDMM with            */
+/* on-the-fly dequantization").                                               */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * op = TANGO_SDDMM_ADD_LEAKYRELU: dim must be 1; X_src, X_dst are n x heads
+ *   int8 (S_q, D_q);  E[e][h] = lrelu(s_src*X_src[src(e)][h] + s_dst*X_dst[dst(e)][h]).
+ * op = TANGO_SDDMM_DOT: X_src, X_dst are n x (heads*dim) int8;
+ *   E[e][h] = (float)(sum_d X_dst[dst(e)][h][d]*X_src[src(e)][h][d]) * (s_dst*s_src);
+ *   `slope` ignored; dim must be a multiple of 4.
+ * E: n_edges x heads fp32.  Uses g->in_ptr, g->in_src.
+ */
+int tango_qsddmm(const tango_graph *g, int op, int heads, int dim, const int8_t *X_src,
+                 const float *s_src, const int8_t *X_dst, const float *s_dst, float slope, float *E,
+                 void *stream);
+
+/*
+ * Backward of TANGO_SDDMM_ADD_LEAKYRELU (Sec. 2.1 steps 3', 3''; Sec. 3.3
+ * "Incidence matrix-based SPMM": with destination-major edge storage dD is a
+ * sum over a contiguous edge segment).  dE: gradient w.r.t. the activated
+ * scores (n_edges x heads).  The LeakyReLU derivative (1 if t > 0 else slope)
+ * uses t recomputed from the quantized S_q (=X_src), D_q (=X_dst).
+ *   dE_pre (may be NULL) = dE * lrelu'(t)
+ *   dD[v][h] = sum over in-edges of v,  dS[u][h] = sum over out-edges of u.
+ * Needs g->out_ptr, g->out_eid for dS.
+ * (The DOT op needs no entry point of its own: its gradients are an SPMM and
+ * an SPMM on the reversed graph.)
+ */
+int tango_qsddmm_bwd(const tango_graph *g, int heads, const int8_t *X_src, const float *s_src,
+                     const int8_t *X_dst, const float *s_dst, float slope, const float *dE,
+                     float *dE_pre, float *dS, float *dD, void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Edge softmax in full precision (Sec. 2.1 steps 4 and 4'; Sec. 3.2          */
+/* "Full precision for the layer before Softmax").                            */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * alpha[e][h] = exp(E[e][h] - m) / sum_{e' -> dst(e)} exp(E[e'][h] - m), m the
+ * maximum over the same in-edges.  absmax_alpha (may be NULL) = max alpha.
+ * alpha may alias E.
+ */
+int tango_edge_softmax(const tango_graph *g, int heads, const float *E, float *alpha,
+                       float *absmax_alpha, void *stream);
+
+/*
+ * dE[e][h] = alpha[e][h] * (dalpha[e][h] - P[dst(e)][h]),
+ * P[v][h] = sum_{e -> v} dalpha[e][h]*alpha[e][h].  dE may alias dalpha.
+ */
+int tango_edge_softmax_bwd(const tango_graph *g, int heads, const float *alpha, const float *dalpha,
+                           float *dE, void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Quantized SPMM (Sec. 2.1 steps 5 and 5'; Sec. 3.3 "Incidence matrix-based  */
+/* adaptive SPMM": node and edge features are both int8, only the result is  */
+/* dequantized).                                                              */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * direction TANGO_IN : out[v][h][:] = (s_w*s_X) * sum_{e=(u->v)} w_q[e][h]*X_q[u][h][:]
+ * direction TANGO_OUT: out[u][h][:] = (s_w*s_X) * sum_{e=(u->v)} w_q[e][h]*X_q[v][h][:]
+ *                      (the same product on the reversed graph; needs out_*).
+ * w_q: n_edges x heads int8 (destination-major positions in both directions);
+ * X_q: n x F int8, F = heads*dim, dim a multiple of 4 and F <= 1024;
+ * out: n x F fp32, 16-byte aligned; absmax_out (may be NULL) = max|out|.
+ * Accumulation is exact int32 (wrap-around beyond 2^31).
+ */
+int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q,
+                const float *s_w, const int8_t *X_q, const float *s_X, float *out, float *absmax_out,
+                void *stream);
+
+/*
+ * Backward of tango_qspmm(direction = TANGO_IN) given the quantized upstream
+ * gradient dOut_q (n x F int8, scale s_dOut), quantized once and shared by
+ * both products (Sec. 3.3):
+ *   dX (n x F fp32, may be NULL)      = SPMM on the reversed graph with w_q (step 5')
+ *   dW (n_edges x heads, may be NULL) = SDDMM-dot of dOut_q[dst] with X_q[src] (step 5'')
+ * absmax_dX may be NULL.
+ */
+int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q, const float *s_w,
+                    const int8_t *X_q, const float *s_X, const int8_t *dOut_q, const float *s_dOut,
+                    float *dX, float *absmax_dX, float *dW, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TANGO_H */

@@ -1,0 +1,142 @@
+// Device and host helpers shared by the kernels of the library (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tango.h"
+
+#define TANGO_WAVE 64
+
+#define TANGO_REQUIRE(cond, err) \
+    do {                         \
+        if (!(cond)) return (err); \
+    } while (0)
+
+// Launch check: never synchronises; reports a refused launch only.
+#define TANGO_LAUNCH_CHECK()                                   \
+    do {                                                       \
+        if (hipGetLastError() != hipSuccess) return TANGO_ERR_LAUNCH; \
+    } while (0)
+
+static inline hipStream_t tango_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+static inline bool tango_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+static inline size_t tango_round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Grid size for a grid-stride kernel: enough workgroups to fill 256 CUs several times over.
+static inline unsigned tango_grid_for(size_t work_items, unsigned per_block, unsigned max_blocks = 256 * 16)
+{
+    size_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return static_cast<unsigned>(b);
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter-based random
+// bits for stochastic rounding (Sec. 3.2 "GPU-accelerated stochastic
+// rounding" asks for a register-resident generator; a counter-based one adds
+// independence from the thread mapping).
+// ---------------------------------------------------------------------------
+struct tango_rng {
+    uint32_t k0, k1;  // key = 64-bit seed
+    uint32_t s0, s1;  // stream id -> counter words 2, 3
+};
+
+__host__ __device__ static inline tango_rng tango_rng_make(uint64_t seed, uint64_t stream_id)
+{
+    tango_rng r;
+    r.k0 = static_cast<uint32_t>(seed);
+    r.k1 = static_cast<uint32_t>(seed >> 32);
+    r.s0 = static_cast<uint32_t>(stream_id);
+    r.s1 = static_cast<uint32_t>(stream_id >> 32);
+    return r;
+}
+
+// The 128-bit block that serves flat elements 8*blk .. 8*blk+7 (16 bits each).
+__device__ static inline uint4 tango_philox_block(const tango_rng &r, uint64_t blk)
+{
+    uint32_t c0 = static_cast<uint32_t>(blk), c1 = static_cast<uint32_t>(blk >> 32), c2 = r.s0, c3 = r.s1;
+    uint32_t k0 = r.k0, k1 = r.k1;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+// 16 random bits of element `lane8` (0..7) of a block.
+__device__ static inline uint32_t tango_bits16(const uint4 &b, int lane8)
+{
+    const uint32_t w = (lane8 & 4) ? ((lane8 & 2) ? b.w : b.z) : ((lane8 & 2) ? b.y : b.x);
+    return (lane8 & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
+// Scale rule (Sec. 2.3, symmetric per-tensor, B = 8): s = absmax/127, inv = 127/absmax.
+__device__ static inline void tango_scale_from_absmax(float absmax, float &s, float &inv)
+{
+    if (absmax > 0.0f) {
+        s = absmax / 127.0f;
+        inv = 127.0f / absmax;
+    } else {
+        s = 1.0f;
+        inv = 0.0f;
+    }
+}
+
+// One element: y = x*inv already formed.  Nearest-even or Eq. 3 with u = bits*2^-16.
+template <int ROUNDING>
+__device__ static inline int tango_round_clamp(float y, uint32_t bits16)
+{
+    int v;
+    if (ROUNDING == TANGO_RN) {
+        v = static_cast<int>(rintf(y));
+    } else {
+        const float f = floorf(y);
+        const float frac = y - f;
+        const float u = static_cast<float>(bits16) * (1.0f / 65536.0f);
+        v = static_cast<int>(f) + (u < frac ? 1 : 0);
+    }
+    return min(127, max(-127, v));
+}
+
+// ---------------------------------------------------------------------------
+// Wave-level reductions (wave64) via cross-lane shuffles.
+// ---------------------------------------------------------------------------
+__device__ static inline float tango_wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ static inline float tango_wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ static inline double tango_wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// max over non-negative floats through their bit patterns (monotone for x >= 0).
+__device__ static inline void tango_atomic_max_nonneg(float *addr, float v)
+{
+    atomicMax(reinterpret_cast<unsigned int *>(addr), __float_as_uint(v));
+}

@@ -1,0 +1,232 @@
+// Per-tensor symmetric int8 quantization (Sec. 2.3 Eq. 1-2 with zero point 0;
+// Sec. 3.2 Eq. 3 for stochastic rounding): abs-max reduction, quantize,
+// dequantize.  All three are pure streaming kernels bound by HBM bandwidth:
+// abs-max reads 4 B/element, quantize reads 4 B and writes 1 B per element.
+#include "internal.hip.h"
+
+namespace {
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// max|x| over n floats into *out (as the bit pattern of a non-negative float; *out must start at 0).
+// VEC = 4: x is 16-byte aligned and float4 loads are used for the body.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, size_t n, float *out)
+{
+    float m = 0.0f;
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    if (VEC == 4) {
+        const size_t n4 = n / 4;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        size_t i = tid;
+        // two independent loads per iteration keep more bytes in flight
+        for (; i + nthr < n4; i += 2 * nthr) {
+            const float4 a = x4[i];
+            const float4 b = x4[i + nthr];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+        }
+        for (; i < n4; i += nthr) {
+            const float4 a = x4[i];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        }
+        for (size_t j = n4 * 4 + tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
+    } else {
+        for (size_t j = tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
+    }
+    m = tango_wave_max(m);
+    __shared__ float part[4];
+    const int wave = threadIdx.x / TANGO_WAVE, lane = threadIdx.x % TANGO_WAVE;
+    if (lane == 0) part[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        if (m > 0.0f) tango_atomic_max_nonneg(out, m);
+    }
+}
+
+// Quantize 8 consecutive elements (one Philox block) held in y[8] = x*inv.
+template <int ROUNDING>
+__device__ inline uint2 quantize8(const float (&y)[8], const tango_rng &rng, uint64_t blk)
+{
+    uint4 b = make_uint4(0, 0, 0, 0);
+    if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, blk);
+    const uint32_t w[4] = {b.x, b.y, b.z, b.w};
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+        const uint32_t byte = static_cast<uint32_t>(tango_round_clamp<ROUNDING>(y[j], bits)) & 0xffu;
+        if (j < 4)
+            lo |= byte << (8 * j);
+        else
+            hi |= byte << (8 * (j - 4));
+    }
+    return make_uint2(lo, hi);
+}
+
+// Vector path: x 16-byte aligned, q 8-byte aligned.  One thread-iteration = 8 elements.
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
+                                                      const float *__restrict__ absmax, tango_rng rng,
+                                                      int8_t *__restrict__ q, float *scale_out)
+{
+    float s, inv;
+    tango_scale_from_absmax(*absmax, s, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+    const size_t n8 = n / 8;
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    uint2 *q8 = reinterpret_cast<uint2 *>(q);
+    for (size_t i = tid; i < n8; i += nthr) {
+        const float4 a = x4[2 * i];
+        const float4 b = x4[2 * i + 1];
+        const float y[8] = {a.x * inv, a.y * inv, a.z * inv, a.w * inv, b.x * inv, b.y * inv, b.z * inv, b.w * inv};
+        q8[i] = quantize8<ROUNDING>(y, rng, i);
+    }
+    // ragged tail: fewer than 8 elements, one thread
+    if (tid == 0 && n8 * 8 < n) {
+        uint4 b = make_uint4(0, 0, 0, 0);
+        if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, n8);
+        for (size_t j = n8 * 8; j < n; ++j)
+            q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(x[j] * inv, tango_bits16(b, static_cast<int>(j & 7))));
+    }
+}
+
+// Scalar path for unaligned pointers: one element per thread-iteration (same results, slower).
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_quantize_scalar(const float *__restrict__ x, size_t n,
+                                                         const float *__restrict__ absmax, tango_rng rng,
+                                                         int8_t *__restrict__ q, float *scale_out)
+{
+    float s, inv;
+    tango_scale_from_absmax(*absmax, s, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t j = tid; j < n; j += nthr) {
+        uint32_t bits = 0;
+        if (ROUNDING == TANGO_SR) bits = tango_bits16(tango_philox_block(rng, j >> 3), static_cast<int>(j & 7));
+        q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(x[j] * inv, bits));
+    }
+}
+
+__global__ __launch_bounds__(256) void k_dequantize(const int8_t *__restrict__ q, size_t n,
+                                                    const float *__restrict__ scale, float *__restrict__ x)
+{
+    const float s = *scale;
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t j = tid; j < n; j += nthr) x[j] = s * static_cast<float>(q[j]);
+}
+
+}  // namespace
+
+// Internal (not part of the ABI): used by the other translation units.
+int tango_fill_u32_async(uint32_t *p, uint32_t v, int n, hipStream_t st)
+{
+    k_fill_u32<<<(n + 63) / 64, 64, 0, st>>>(p, v, n);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int tango_absmax_accumulate_async(const float *x, size_t n, float *out, hipStream_t st)
+{
+    if (n == 0) return TANGO_OK;
+    if (tango_aligned(x, 16))
+        k_absmax<4><<<tango_grid_for(n / 4 + 1, 256 * 2), 256, 0, st>>>(x, n, out);
+    else
+        k_absmax<1><<<tango_grid_for(n, 256 * 4), 256, 0, st>>>(x, n, out);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                                     const float *absmax, int8_t *q, float *scale_out, hipStream_t st)
+{
+    const tango_rng rng = tango_rng_make(seed, stream_id);
+    if (tango_aligned(x, 16) && tango_aligned(q, 8)) {
+        const unsigned grid = tango_grid_for(n / 8 + 1, 256 * 2);
+        if (rounding == TANGO_RN)
+            k_quantize_vec<TANGO_RN><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+        else
+            k_quantize_vec<TANGO_SR><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+    } else {
+        const unsigned grid = tango_grid_for(n + 1, 256 * 8);
+        if (rounding == TANGO_RN)
+            k_quantize_scalar<TANGO_RN><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+        else
+            k_quantize_scalar<TANGO_SR><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+    }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+extern "C" {
+
+int tango_version(void) { return 100; }
+
+const char *tango_status_string(int status)
+{
+    switch (status) {
+        case TANGO_OK: return "ok";
+        case TANGO_ERR_NULL: return "a required pointer is NULL";
+        case TANGO_ERR_BAD_SHAPE: return "bad shape, size or alignment";
+        case TANGO_ERR_BAD_ENUM: return "unknown enum value";
+        case TANGO_ERR_UNSUPPORTED: return "unsupported configuration";
+        case TANGO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TANGO_ERR_LAUNCH: return "kernel launch refused by the HIP runtime";
+        default: return "unknown status";
+    }
+}
+
+int tango_absmax(const float *x, size_t n, float *absmax_out, void *stream)
+{
+    TANGO_REQUIRE(absmax_out != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(n == 0 || x != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(x, 4) && tango_aligned(absmax_out, 4), TANGO_ERR_BAD_SHAPE);
+    hipStream_t st = tango_stream(stream);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_out), 0u, 1, st);
+    if (rc != TANGO_OK) return rc;
+    return tango_absmax_accumulate_async(x, n, absmax_out, st);
+}
+
+size_t tango_quantize_workspace_bytes(size_t) { return 256; }
+
+int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                   const float *absmax_in, int8_t *q, float *scale_out, void *ws, size_t ws_bytes, void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    TANGO_REQUIRE(n == 0 || (x != nullptr && q != nullptr), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(x, 4), TANGO_ERR_BAD_SHAPE);
+    hipStream_t st = tango_stream(stream);
+    const float *am = absmax_in;
+    if (am == nullptr) {
+        TANGO_REQUIRE(ws != nullptr && ws_bytes >= 256 && tango_aligned(ws, 256), TANGO_ERR_WORKSPACE);
+        float *wam = static_cast<float *>(ws);
+        int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(wam), 0u, 1, st);
+        if (rc != TANGO_OK) return rc;
+        rc = tango_absmax_accumulate_async(x, n, wam, st);
+        if (rc != TANGO_OK) return rc;
+        am = wam;
+    }
+    return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, am, q, scale_out, st);
+}
+
+int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream)
+{
+    TANGO_REQUIRE(scale != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(n == 0 || (q != nullptr && x != nullptr), TANGO_ERR_NULL);
+    if (n == 0) return TANGO_OK;
+    k_dequantize<<<tango_grid_for(n, 256 * 8), 256, 0, tango_stream(stream)>>>(q, n, scale, x);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+}  // extern "C"

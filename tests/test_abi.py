@@ -1,0 +1,57 @@
+"""The C-ABI library loads and exports every symbol include/tango.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tango.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tango_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2308_00890_amd import build as b
+
+    if b.is_stale():
+        b.build()
+    return ctypes.CDLL(b.LIB)
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert "tango_quantize" in names and "tango_qspmm_bwd" in names and len(names) >= 19
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_every_symbol():
+    from paper_2308_00890_amd import binding
+
+    assert sorted(binding.SIGNATURES) == declared_symbols()
+    for n in declared_symbols():
+        assert callable(getattr(binding, n)), n
+
+
+def test_version_and_status_strings(lib):
+    lib.tango_status_string.restype = ctypes.c_char_p
+    assert lib.tango_version() >= 100
+    assert lib.tango_status_string(0) == b"ok"
+    for code in range(-6, 0):
+        assert len(lib.tango_status_string(code)) > 3
+
+
+def test_argument_validation_needs_no_gpu(lib):
+    # validation happens on the host before any launch
+    lib.tango_quantize.restype = ctypes.c_int
+    rc = lib.tango_quantize(None, ctypes.c_size_t(8), 7, ctypes.c_uint64(0), ctypes.c_uint64(0), None, None, None, None,
+                            ctypes.c_size_t(0), None)
+    assert rc == -3  # bad rounding enum
+    rc = lib.tango_quantize(None, ctypes.c_size_t(8), 0, ctypes.c_uint64(0), ctypes.c_uint64(0), None, None, None, None,
+                            ctypes.c_size_t(0), None)
+    assert rc == -1  # NULL tensors
