@@ -1,0 +1,487 @@
+// Quantized SPMM (Sec. 2.1 steps 5, 5'; Sec. 3.3 "Incidence matrix-based
+// adaptive SPMM") and quantized SDDMM-dot (Sec. 2.1 step 5''; Sec. 3.3 "SDDMM
+// with on-the-fly dequantization", multiplication case).
+//
+// Work decomposition (both kernels): the edge array of the chosen direction is
+// cut into chunks of CHUNK consecutive edges, one wavefront per chunk, so the
+// load is balanced in edges whatever the degree distribution.  A wave finds
+// the row that holds its first edge by a 64-ary search over the row pointer
+// and then walks the row segments inside its chunk.  A row that lies entirely
+// in one chunk is finished by that wave; a row cut by a chunk boundary is
+// accumulated with int32 atomics (integer addition is associative, so the
+// result does not depend on the order) and dequantized by a small second
+// kernel.
+//
+// Inside a wave, a feature row of F int8 is covered by LPR = F/VEC lanes that
+// load VEC bytes each, so one wave-wide load instruction gathers G = 64/LPR
+// neighbour rows; the G partial sums are combined with cross-lane shuffles.
+//
+// Roofline: both kernels gather F bytes per edge from the int8 node table;
+// HBM-bound when the table exceeds the on-chip caches, else bound by the
+// cache/fabric gather rate.  Algorithmic bytes per edge: 4 (index) + heads
+// (weight) + F (row); per node: 4 (pointer) + 4F (fp32 result).
+#include "internal.hip.h"
+
+namespace {
+
+constexpr int CHUNK = 256;  // edges per wavefront
+constexpr int WAVES_PER_BLOCK = 4;
+
+// Largest r in [0, n) with ptr[r] <= e (ptr non-decreasing, ptr[0] = 0 <= e < ptr[n]).
+// All 64 lanes cooperate: each step probes 64 positions and narrows the range 64-fold.
+__device__ inline int wave_find_row(const int32_t *__restrict__ ptr, int n, int e)
+{
+    const int lane = threadIdx.x % TANGO_WAVE;
+    int lo = 0, hi = n;  // ptr[lo] <= e; hi == n or ptr[hi] > e
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int p = lo + (lane + 1) * step;
+        const bool le = (p < hi) && (ptr[p] <= e);
+        const int cnt = __popcll(__ballot(le));
+        const int nlo = lo + cnt * step;
+        const int nhi = min(hi, lo + (cnt + 1) * step);
+        lo = nlo;
+        hi = nhi;
+    }
+    return lo;
+}
+
+template <int VEC>
+struct vec_bytes;
+template <>
+struct vec_bytes<4> {
+    using type = uint32_t;
+};
+template <>
+struct vec_bytes<8> {
+    using type = uint2;
+};
+template <>
+struct vec_bytes<16> {
+    using type = uint4;
+};
+
+template <int VEC>
+__device__ inline void unpack_words(const typename vec_bytes<VEC>::type &v, uint32_t (&w)[VEC / 4]);
+template <>
+__device__ inline void unpack_words<4>(const uint32_t &v, uint32_t (&w)[1])
+{
+    w[0] = v;
+}
+template <>
+__device__ inline void unpack_words<8>(const uint2 &v, uint32_t (&w)[2])
+{
+    w[0] = v.x;
+    w[1] = v.y;
+}
+template <>
+__device__ inline void unpack_words<16>(const uint4 &v, uint32_t (&w)[4])
+{
+    w[0] = v.x;
+    w[1] = v.y;
+    w[2] = v.z;
+    w[3] = v.w;
+}
+
+__device__ inline int sbyte(uint32_t w, int j) { return static_cast<int>(static_cast<int8_t>(w >> (8 * j))); }
+
+struct spmm_args {
+    int n;                 // rows
+    int64_t nnz;           // edges
+    const int32_t *ptr;    // n+1, row pointer of the chosen direction
+    const int32_t *idx;    // nnz, neighbour of each edge in that direction
+    const int32_t *eid;    // nnz or NULL: position of the edge weight (NULL = the edge's own position)
+    const int8_t *w;       // nnz x heads
+    const int8_t *X;       // n x F
+    const float *s_w, *s_X;
+    float *out;            // n x F (fp32; int32 partial sums while the kernels run)
+    float *absmax;         // or NULL
+    int heads, dim, F;
+};
+
+// True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
+__device__ inline bool row_is_split(int b, int t) { return t > b && (b / CHUNK) != ((t - 1) / CHUNK); }
+
+// Zero the rows that the main kernel reaches through atomics (split rows) or never writes (empty rows).
+__global__ __launch_bounds__(256) void k_spmm_prepare(spmm_args a)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.absmax) *a.absmax = 0.0f;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
+    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+        const int r = static_cast<int>(base) + lane;
+        bool flag = false;
+        if (r < a.n) {
+            const int b = a.ptr[r], t = a.ptr[r + 1];
+            flag = (t == b) || row_is_split(b, t);
+        }
+        unsigned long long mask = __ballot(flag);
+        while (mask) {
+            const int k = __ffsll(static_cast<long long>(mask)) - 1;
+            mask &= mask - 1;
+            float *row = a.out + (base + k) * a.F;
+            for (int c = lane; c < a.F; c += 64) row[c] = 0.0f;
+        }
+    }
+}
+
+// Dequantize the split rows in place (int32 -> fp32) and fold them into the abs-max.
+__global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
+{
+    const float sc = (*a.s_w) * (*a.s_X);
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
+    float m = 0.0f;
+    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+        const int r = static_cast<int>(base) + lane;
+        bool flag = false;
+        if (r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1]);
+        unsigned long long mask = __ballot(flag);
+        while (mask) {
+            const int k = __ffsll(static_cast<long long>(mask)) - 1;
+            mask &= mask - 1;
+            float *row = a.out + (base + k) * a.F;
+            for (int c = lane; c < a.F; c += 64) {
+                const int acc = __float_as_int(row[c]);
+                const float o = static_cast<float>(acc) * sc;
+                row[c] = o;
+                m = fmaxf(m, fabsf(o));
+            }
+        }
+    }
+    if (a.absmax) {
+        m = tango_wave_max(m);
+        if (lane == 0 && m > 0.0f) tango_atomic_max_nonneg(a.absmax, m);
+    }
+}
+
+// One wave per chunk of CHUNK edges.  VEC = bytes of the feature row per lane.
+template <int VEC>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
+{
+    using V = typename vec_bytes<VEC>::type;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    const int64_t c0 = chunk * CHUNK;
+    if (c0 >= a.nnz) return;
+    const int64_t c1 = min(c0 + CHUNK, a.nnz);
+
+    const int LPR = a.F / VEC;          // lanes per feature row
+    const int G = 64 / LPR;             // neighbour rows gathered per wave-wide load (power of two)
+    const int gi = lane / LPR;          // my group (>= G: idle lane)
+    const int li = lane - gi * LPR;     // my position in the row
+    const bool active = gi < G;
+    const int col = li * VEC;           // first of my VEC columns
+    const int h = col / a.dim;          // their head
+    const float sc = (*a.s_w) * (*a.s_X);
+    const int8_t *Xcol = a.X + col;
+
+    int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
+    int maxabs = 0;
+    constexpr int U = 4;  // independent gathers in flight per lane
+
+    for (; r < a.n; ++r) {
+        const int rb = a.ptr[r], rt = a.ptr[r + 1];
+        if (rb >= c1) break;
+        const int sb = max(rb, static_cast<int>(c0)), se = min(rt, static_cast<int>(c1));
+        if (sb >= se) continue;
+        int acc[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0;
+        if (active) {
+            for (int e = sb + gi; e < se; e += G * U) {
+                int wv[U];
+                V xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int ee = e + u * G;
+                    const bool ok = ee < se;
+                    const int ec = ok ? ee : se - 1;
+                    const int nb = a.idx[ec];
+                    const int64_t wp = a.eid ? a.eid[ec] : ec;
+                    wv[u] = ok ? static_cast<int>(a.w[wp * a.heads + h]) : 0;
+                    xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    uint32_t w[VEC / 4];
+                    unpack_words<VEC>(xv[u], w);
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) acc[j] += wv[u] * sbyte(w[j / 4], j % 4);
+                }
+            }
+        }
+        // combine the G groups: afterwards group 0 holds the sums of this row segment
+        for (int off = G / 2; off >= 1; off >>= 1) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += __shfl_down(acc[j], off * LPR, 64);
+        }
+        if (gi == 0) {
+            float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
+            const bool whole = (rb >= c0) && (rt <= c1);
+            if (whole) {
+#pragma unroll
+                for (int j = 0; j < VEC; j += 4) {
+                    float4 o;
+                    o.x = static_cast<float>(acc[j + 0]) * sc;
+                    o.y = static_cast<float>(acc[j + 1]) * sc;
+                    o.z = static_cast<float>(acc[j + 2]) * sc;
+                    o.w = static_cast<float>(acc[j + 3]) * sc;
+                    *reinterpret_cast<float4 *>(orow + j) = o;
+                    maxabs = max(maxabs, max(max(abs(acc[j]), abs(acc[j + 1])), max(abs(acc[j + 2]), abs(acc[j + 3]))));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) atomicAdd(reinterpret_cast<int *>(orow + j), acc[j]);
+            }
+        }
+    }
+    if (a.absmax) {
+        // max|out| over whole rows = (float)max|acc| * sc (conversion and the product are monotone)
+        float m = static_cast<float>(maxabs) * sc;
+        m = tango_wave_max(m);
+        if (lane == 0 && m > 0.0f) tango_atomic_max_nonneg(a.absmax, m);
+    }
+}
+
+struct sddmm_dot_args {
+    int n;
+    int64_t nnz;
+    const int32_t *ptr;   // in_ptr
+    const int32_t *idx;   // in_src
+    const int8_t *Xdst;   // n x F
+    const int8_t *Xsrc;   // n x F
+    const float *s_dst, *s_src;
+    float *out;           // nnz x heads
+    int heads, dim, F;
+};
+
+// out[e][h] = (float)(Xdst[dst(e)][h][:] . Xsrc[src(e)][h][:]) * (s_dst*s_src); one wave per chunk of edges.
+template <int VEC>
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
+{
+    using V = typename vec_bytes<VEC>::type;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    const int64_t c0 = chunk * CHUNK;
+    if (c0 >= a.nnz) return;
+    const int64_t c1 = min(c0 + CHUNK, a.nnz);
+
+    const int LPR = a.F / VEC;
+    const int G = 64 / LPR;
+    const int gi = lane / LPR;
+    const int li = lane - gi * LPR;
+    const bool active = gi < G;
+    const int col = li * VEC;
+    const int h = col / a.dim;
+    const int LPH = a.dim / VEC;  // lanes per head (power of two)
+    const float sc = (*a.s_dst) * (*a.s_src);
+    constexpr int U = 4;
+
+    int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
+    for (; r < a.n; ++r) {
+        const int rb = a.ptr[r], rt = a.ptr[r + 1];
+        if (rb >= c1) break;
+        const int sb = max(rb, static_cast<int>(c0)), se = min(rt, static_cast<int>(c1));
+        if (sb >= se) continue;
+        uint32_t dw[VEC / 4];
+        {
+            const V dv = *reinterpret_cast<const V *>(a.Xdst + static_cast<int64_t>(r) * a.F + (active ? col : 0));
+            unpack_words<VEC>(dv, dw);
+        }
+        // every lane runs the same number of iterations (the shuffles below need all lanes)
+        for (int e0 = sb; e0 < se; e0 += G * U) {
+            int dot[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int ee = e0 + gi + u * G;
+                const int ec = (active && ee < se) ? ee : se - 1;
+                const int nb = a.idx[ec];
+                const V xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
+                uint32_t w[VEC / 4];
+                unpack_words<VEC>(xv, w);
+                int d = 0;
+#pragma unroll
+                for (int j = 0; j < VEC / 4; ++j) d = __builtin_amdgcn_sdot4(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false);
+                dot[u] = d;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                int d = dot[u];
+                for (int off = LPH / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
+                const int ee = e0 + gi + u * G;
+                if (active && ee < se && (li % LPH) == 0) a.out[static_cast<int64_t>(ee) * a.heads + h] = static_cast<float>(d) * sc;
+            }
+        }
+    }
+}
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Bytes of a feature row per lane: aim at ~16 lanes per row.  Every lane's bytes must stay inside one
+// head, the lanes of one row must fit a wave, and the number of row groups per wave must be a power
+// of two (shuffle reduction); SDDMM-dot also needs a power-of-two number of lanes per head.
+// Returns 0 when no width qualifies.
+int pick_vec(int F, int dim, bool pow2_lanes_per_head)
+{
+    int pref[3] = {16, 8, 4};
+    if (F <= 64) { pref[0] = 4; pref[1] = 8; pref[2] = 16; }
+    else if (F <= 128) { pref[0] = 8; pref[1] = 4; pref[2] = 16; }
+    for (int i = 0; i < 3; ++i) {
+        const int vec = pref[i];
+        if (dim % vec != 0 || F % vec != 0) continue;
+        const int lpr = F / vec;
+        if (lpr > 64 || !is_pow2(64 / lpr)) continue;
+        if (pow2_lanes_per_head && !is_pow2(dim / vec)) continue;
+        return vec;
+    }
+    return 0;
+}
+
+int validate_graph_dir(const tango_graph *g, int direction)
+{
+    TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(g->n_nodes > 0 && g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
+    if (direction == TANGO_IN) {
+        TANGO_REQUIRE(g->in_ptr && (g->n_edges == 0 || g->in_src), TANGO_ERR_NULL);
+    } else {
+        TANGO_REQUIRE(g->out_ptr && (g->n_edges == 0 || (g->out_dst && g->out_eid)), TANGO_ERR_NULL);
+    }
+    return TANGO_OK;
+}
+
+int validate_feature_shape(int heads, int dim)
+{
+    TANGO_REQUIRE(heads >= 1 && dim >= 4 && dim % 4 == 0, TANGO_ERR_BAD_SHAPE);
+    const int64_t F = static_cast<int64_t>(heads) * dim;
+    TANGO_REQUIRE(F <= 1024, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(pick_vec(static_cast<int>(F), dim, false) != 0, TANGO_ERR_UNSUPPORTED);
+    return TANGO_OK;
+}
+
+}  // namespace
+
+int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
+                     const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
+{
+    spmm_args a;
+    a.n = g->n_nodes;
+    a.nnz = g->n_edges;
+    a.ptr = direction == TANGO_IN ? g->in_ptr : g->out_ptr;
+    a.idx = direction == TANGO_IN ? g->in_src : g->out_dst;
+    a.eid = direction == TANGO_IN ? nullptr : g->out_eid;
+    a.w = w_q;
+    a.X = X_q;
+    a.s_w = s_w;
+    a.s_X = s_X;
+    a.out = out;
+    a.absmax = absmax_out;
+    a.heads = heads;
+    a.dim = dim;
+    a.F = heads * dim;
+    const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
+    k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
+    TANGO_LAUNCH_CHECK();
+    if (a.nnz > 0) {
+        const int64_t chunks = (a.nnz + CHUNK - 1) / CHUNK;
+        const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        switch (pick_vec(a.F, dim, false)) {
+            case 4: k_spmm<4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            case 8: k_spmm<8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default: k_spmm<16><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        }
+        TANGO_LAUNCH_CHECK();
+        k_spmm_finalize<<<row_blocks, 256, 0, st>>>(a);
+        TANGO_LAUNCH_CHECK();
+    }
+    return TANGO_OK;
+}
+
+int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t *X_dst, const float *s_dst,
+                          const int8_t *X_src, const float *s_src, float *out, hipStream_t st)
+{
+    if (g->n_edges == 0) return TANGO_OK;
+    sddmm_dot_args a;
+    a.n = g->n_nodes;
+    a.nnz = g->n_edges;
+    a.ptr = g->in_ptr;
+    a.idx = g->in_src;
+    a.Xdst = X_dst;
+    a.Xsrc = X_src;
+    a.s_dst = s_dst;
+    a.s_src = s_src;
+    a.out = out;
+    a.heads = heads;
+    a.dim = dim;
+    a.F = heads * dim;
+    const int64_t chunks = (a.nnz + CHUNK - 1) / CHUNK;
+    const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    switch (pick_vec(a.F, dim, true)) {
+        case 4: k_sddmm_dot<4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 8: k_sddmm_dot<8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default: k_sddmm_dot<16><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+    }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int tango_validate_sddmm_dot_shape(int heads, int dim)
+{
+    int rc = validate_feature_shape(heads, dim);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(pick_vec(heads * dim, dim, true) != 0, TANGO_ERR_UNSUPPORTED);
+    return TANGO_OK;
+}
+
+extern "C" {
+
+int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
+                const int8_t *X_q, const float *s_X, float *out, float *absmax_out, void *stream)
+{
+    TANGO_REQUIRE(direction == TANGO_IN || direction == TANGO_OUT, TANGO_ERR_BAD_ENUM);
+    int rc = validate_graph_dir(g, direction);
+    if (rc != TANGO_OK) return rc;
+    rc = validate_feature_shape(heads, dim);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(X_q && s_w && s_X && out && (g->n_edges == 0 || w_q), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
+    return tango_spmm_async(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out, tango_stream(stream));
+}
+
+int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q, const float *s_w, const int8_t *X_q,
+                    const float *s_X, const int8_t *dOut_q, const float *s_dOut, float *dX, float *absmax_dX, float *dW,
+                    void *stream)
+{
+    int rc = validate_graph_dir(g, TANGO_IN);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(dOut_q && s_dOut, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(dOut_q, 16), TANGO_ERR_BAD_SHAPE);
+    hipStream_t st = tango_stream(stream);
+    if (dX) {
+        rc = validate_graph_dir(g, TANGO_OUT);
+        if (rc != TANGO_OK) return rc;
+        rc = validate_feature_shape(heads, dim);
+        if (rc != TANGO_OK) return rc;
+        TANGO_REQUIRE(s_w && (g->n_edges == 0 || w_q), TANGO_ERR_NULL);
+        TANGO_REQUIRE(tango_aligned(dX, 16), TANGO_ERR_BAD_SHAPE);
+    }
+    if (dW) {
+        rc = tango_validate_sddmm_dot_shape(heads, dim);
+        if (rc != TANGO_OK) return rc;
+        TANGO_REQUIRE(X_q && s_X, TANGO_ERR_NULL);
+        TANGO_REQUIRE(tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
+    }
+    if (dX) {
+        rc = tango_spmm_async(g, TANGO_OUT, heads, dim, w_q, s_w, dOut_q, s_dOut, dX, absmax_dX, st);
+        if (rc != TANGO_OK) return rc;
+    }
+    if (dW) {
+        rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dW, st);
+        if (rc != TANGO_OK) return rc;
+    }
+    return TANGO_OK;
+}
+
+}  // extern "C"

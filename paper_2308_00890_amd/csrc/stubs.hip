@@ -8,10 +8,4 @@ int tango_qgemm_bwd(int64_t, int64_t, int64_t, const int8_t *, const float *, co
 int tango_head_proj(int64_t, int, int, const float *, const float *, const float *, float *, float *, float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
 size_t tango_head_proj_bwd_workspace_bytes(int64_t, int, int) { return 256; }
 int tango_head_proj_bwd(int64_t, int, int, const float *, const float *, const float *, const float *, const int8_t *, const float *, const float *, float *, float *, float *, float *, void *, size_t, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_qsddmm(const tango_graph *, int, int, int, const int8_t *, const float *, const int8_t *, const float *, float, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_qsddmm_bwd(const tango_graph *, int, const int8_t *, const float *, const int8_t *, const float *, float, const float *, float *, float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_edge_softmax(const tango_graph *, int, const float *, float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_edge_softmax_bwd(const tango_graph *, int, const float *, const float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_qspmm(const tango_graph *, int, int, int, const int8_t *, const float *, const int8_t *, const float *, float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
-int tango_qspmm_bwd(const tango_graph *, int, int, const int8_t *, const float *, const int8_t *, const float *, const int8_t *, const float *, float *, float *, float *, void *) { return TANGO_ERR_UNSUPPORTED; }
 }
