@@ -1,0 +1,460 @@
+// Quantized GEMM on the int8 matrix cores (Sec. 3.2 Fig. 3; Sec. 3.3 "GEMM with
+// on-the-fly quantization", Fig. 4), forward and backward.
+//
+// What is kept from the paper's design: the fp32 operand is quantized while it
+// is loaded (no separate pass), its int8 copy is written back for the backward
+// pass, accumulation is int32 in registers, the result is dequantized in
+// registers and the abs-max that the next quantization needs is computed in the
+// same kernel.  What differs (the paper tiles for V100 CUDA cores and DP4A):
+// the products run on v_mfma_i32_32x32x32_i8; at GNN shapes (K = 64..602,
+// N = 64..384) the GEMM is bound by HBM traffic of the tall fp32 operand, not
+// by the matrix cores, so a workgroup quantizes a whole 64-row panel of A
+// (all K) into LDS once -- a contiguous, perfectly coalesced stream -- and then
+// sweeps all N columns against the small, cache-resident quantized B.
+//
+// Algorithmic HBM bytes of the forward call per row of A: 4K (abs-max pass)
+// + 4K (read) + K (A_q write) + 4N (C write).
+#include "internal.hip.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 64;     // rows of A per workgroup
+constexpr int BN = 256;    // columns per sweep: 4 waves x 64
+constexpr int KMAX = 2048; // largest reduction length whose 64-row int8 panel fits LDS
+constexpr int LDS_PAD = 16;
+
+struct fused_args {
+    int64_t M;
+    int N, K;        // logical sizes: out is M x N, reduction K
+    int Kp, Np;      // padded: Kp multiple of 32 (BT row length), Np multiple of 64 (BT rows)
+    const float *A;  // M x K fp32
+    const float *absmax_A;
+    tango_rng rng;
+    int8_t *A_q;     // M x K
+    float *s_A;      // out
+    const int8_t *BT;  // Np x Kp, zero padded
+    const float *s_B;
+    float *C;        // M x N
+    float *absmax_C; // or NULL
+};
+
+template <int ROUNDING>
+__device__ inline uint2 quantize8_packed(const float (&y)[8], const tango_rng &rng, uint64_t blk)
+{
+    uint4 b = make_uint4(0, 0, 0, 0);
+    if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, blk);
+    const uint32_t w[4] = {b.x, b.y, b.z, b.w};
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+        const uint32_t byte = static_cast<uint32_t>(tango_round_clamp<ROUNDING>(y[j], bits)) & 0xffu;
+        if (j < 4)
+            lo |= byte << (8 * j);
+        else
+            hi |= byte << (8 * (j - 4));
+    }
+    return make_uint2(lo, hi);
+}
+
+// WL = bytes per LDS write: 4 if K % 4 == 0, 2 if K % 2 == 0, else 1 (pieces never straddle a row then).
+template <int ROUNDING, int WL>
+__global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
+{
+    extern __shared__ __align__(16) int8_t lds[];
+    const int LDK = a.Kp + LDS_PAD;
+    const int tid = threadIdx.x;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * BM;
+    const int rows = static_cast<int>(min(static_cast<int64_t>(BM), a.M - row0));
+
+    // ---- phase 1: stream the panel (a contiguous range of A), quantize, keep it in LDS and write it back
+    float s, inv;
+    tango_scale_from_absmax(*a.absmax_A, s, inv);
+    if (blockIdx.x == 0 && tid == 0) *a.s_A = s;
+    const int64_t flat0 = row0 * a.K;  // multiple of 8 because row0 is a multiple of 64
+    const int cnt = rows * a.K;
+    const int ngroups = (cnt + 7) / 8;
+    const float *Ap = a.A + flat0;
+    int8_t *Aq = a.A_q + flat0;
+    for (int g = tid; g < ngroups; g += 256) {
+        const int f = g * 8;
+        const int valid = min(8, cnt - f);
+        float y[8];
+        if (valid == 8) {
+            const float4 x0 = *reinterpret_cast<const float4 *>(Ap + f);
+            const float4 x1 = *reinterpret_cast<const float4 *>(Ap + f + 4);
+            y[0] = x0.x * inv; y[1] = x0.y * inv; y[2] = x0.z * inv; y[3] = x0.w * inv;
+            y[4] = x1.x * inv; y[5] = x1.y * inv; y[6] = x1.z * inv; y[7] = x1.w * inv;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) y[j] = (j < valid) ? Ap[f + j] * inv : 0.0f;
+        }
+        const uint2 q = quantize8_packed<ROUNDING>(y, a.rng, static_cast<uint64_t>((flat0 + f) >> 3));
+        if (valid == 8) {
+            *reinterpret_cast<uint2 *>(Aq + f) = q;
+        } else {
+            for (int j = 0; j < valid; ++j) Aq[f + j] = static_cast<int8_t>((j < 4 ? q.x >> (8 * j) : q.y >> (8 * (j - 4))) & 0xffu);
+        }
+        int row = f / a.K;
+        int col = f - row * a.K;
+        const uint64_t bits = (static_cast<uint64_t>(q.y) << 32) | q.x;
+#pragma unroll
+        for (int j = 0; j < 8; j += WL) {
+            if (j < valid) {
+                int8_t *dst = lds + row * LDK + col;
+                if (WL == 4)
+                    *reinterpret_cast<uint32_t *>(dst) = static_cast<uint32_t>(bits >> (8 * j));
+                else if (WL == 2)
+                    *reinterpret_cast<uint16_t *>(dst) = static_cast<uint16_t>(bits >> (8 * j));
+                else
+                    *dst = static_cast<int8_t>(bits >> (8 * j));
+                col += WL;
+                if (col >= a.K) {
+                    col -= a.K;
+                    row += 1;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: int8 MFMA sweep over the columns; B^T fragments come straight from the (cached) global copy
+    const int lane = tid % TANGO_WAVE, wave = tid / TANGO_WAVE;
+    const float sc = s * (*a.s_B);
+    const int8_t *ap0 = lds + (lane % 32) * LDK + 16 * (lane / 32);
+    const int8_t *ap1 = ap0 + 32 * LDK;
+    int maxabs = 0;
+    for (int nt = 0; nt < a.Np; nt += BN) {
+        const int col0 = nt + wave * 64;
+        if (col0 >= a.Np) break;
+        v16i acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
+        const int8_t *bp0 = a.BT + static_cast<int64_t>(col0 + lane % 32) * a.Kp + 16 * (lane / 32);
+        const int8_t *bp1 = bp0 + static_cast<int64_t>(32) * a.Kp;
+        v4i b0 = *reinterpret_cast<const v4i *>(bp0);
+        v4i b1 = *reinterpret_cast<const v4i *>(bp1);
+        for (int kk = 0; kk < a.Kp; kk += 32) {
+            const v4i a0 = *reinterpret_cast<const v4i *>(ap0 + kk);
+            const v4i a1 = *reinterpret_cast<const v4i *>(ap1 + kk);
+            const v4i c0 = b0, c1 = b1;
+            if (kk + 32 < a.Kp) {  // prefetch the next B fragments
+                b0 = *reinterpret_cast<const v4i *>(bp0 + kk + 32);
+                b1 = *reinterpret_cast<const v4i *>(bp1 + kk + 32);
+            }
+            acc00 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, c0, acc00, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, c1, acc01, 0, 0, 0);
+            acc10 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, c0, acc10, 0, 0, 0);
+            acc11 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, c1, acc11, 0, 0, 0);
+        }
+        // epilogue: dequantize in registers, store, track the abs-max
+        // (element i of a 32x32 tile: column = lane%32, row = 8*(i/4) + 4*(lane/32) + i%4)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const v16i &acc = t == 0 ? acc00 : (t == 1 ? acc01 : (t == 2 ? acc10 : acc11));
+            const int rb = t / 2, cb = t % 2;
+            const int col = col0 + cb * 32 + lane % 32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                if (r < rows && col < a.N) {
+                    a.C[(row0 + r) * a.N + col] = static_cast<float>(acc[i]) * sc;
+                    maxabs = max(maxabs, abs(acc[i]));
+                }
+            }
+        }
+    }
+    if (a.absmax_C) {
+        float m = static_cast<float>(maxabs) * sc;  // conversion and product are monotone
+        m = tango_wave_max(m);
+        if (lane == 0 && m > 0.0f) tango_atomic_max_nonneg(a.absmax_C, m);
+    }
+}
+
+// B (K x N fp32) -> B_q (K x N int8) and its zero-padded transpose BT (Np x Kp).  B is small: one element per thread.
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_quantize_b(int K, int N, int Kp, const float *__restrict__ B,
+                                                    const float *__restrict__ absmax_B, tango_rng rng,
+                                                    int8_t *__restrict__ B_q, float *s_B, int8_t *__restrict__ BT)
+{
+    float s, inv;
+    tango_scale_from_absmax(*absmax_B, s, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *s_B = s;
+    const int64_t total = static_cast<int64_t>(K) * N;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        uint32_t bits = 0;
+        if (ROUNDING == TANGO_SR) bits = tango_bits16(tango_philox_block(rng, static_cast<uint64_t>(i) >> 3), static_cast<int>(i & 7));
+        const int8_t q = static_cast<int8_t>(tango_round_clamp<ROUNDING>(B[i] * inv, bits));
+        B_q[i] = q;
+        const int k = static_cast<int>(i / N), n = static_cast<int>(i - static_cast<int64_t>(k) * N);
+        BT[static_cast<int64_t>(n) * Kp + k] = q;
+    }
+}
+
+// src (R x C int8) -> dst (Rp x Cp), dst zero-filled beforehand.
+__global__ __launch_bounds__(256) void k_pad_copy_i8(int R, int C, int Cp, const int8_t *__restrict__ src,
+                                                     int8_t *__restrict__ dst)
+{
+    const int64_t total = static_cast<int64_t>(R) * C;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int r = static_cast<int>(i / C), c = static_cast<int>(i - static_cast<int64_t>(r) * C);
+        dst[static_cast<int64_t>(r) * Cp + c] = src[i];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// acc[k][n] += sum_{m in slab} P[m][k] * Q[m][n]  (P: M x K, Q: M x N, both int8 row-major):
+// the weight-gradient product, whose reduction runs over the nodes.  Both
+// operands are read with the reduction index as the slow one, so 4x4 byte
+// blocks are transposed in registers (v_perm_b32) on their way into LDS.
+// Workgroup = 128 x 128 output tile x one slab of rows; partial tiles are added
+// with int32 atomics (exact, order-free).
+// ---------------------------------------------------------------------------
+constexpr int TT = 128;          // output tile edge
+constexpr int MS = 64;           // reduction rows per step
+constexpr int LDM = MS + 16;     // LDS row stride (bytes)
+
+struct unaligned_u32 {
+    uint32_t v;
+} __attribute__((packed, aligned(1)));
+
+// 4 bytes P[row][c0..c0+3] (zero beyond the edges); rows may start at any byte address.
+__device__ inline uint32_t load_quad(const int8_t *__restrict__ base, int64_t row, int64_t nrows, int ld, int c0, int ncols)
+{
+    if (row >= nrows || c0 >= ncols) return 0u;
+    const int8_t *p = base + row * ld + c0;
+    if (c0 + 3 < ncols) return reinterpret_cast<const unaligned_u32 *>(p)->v;
+    uint32_t w = 0;
+    for (int j = 0; j < 4 && c0 + j < ncols; ++j) w |= static_cast<uint32_t>(static_cast<uint8_t>(p[j])) << (8 * j);
+    return w;
+}
+
+__device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3, uint32_t (&t)[4])
+{
+    const uint32_t x01l = __builtin_amdgcn_perm(r1, r0, 0x05010400u);
+    const uint32_t x01h = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
+    const uint32_t x23l = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+    const uint32_t x23h = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+    t[0] = __builtin_amdgcn_perm(x23l, x01l, 0x05040100u);
+    t[1] = __builtin_amdgcn_perm(x23l, x01l, 0x07060302u);
+    t[2] = __builtin_amdgcn_perm(x23h, x01h, 0x05040100u);
+    t[3] = __builtin_amdgcn_perm(x23h, x01h, 0x07060302u);
+}
+
+__global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const int8_t *__restrict__ P,
+                                                 const int8_t *__restrict__ Q, int32_t *acc_out, int64_t slab_rows,
+                                                 int tiles_n)
+{
+    __shared__ __align__(16) int8_t Pt[TT * LDM];
+    __shared__ __align__(16) int8_t Qt[TT * LDM];
+    const int tid = threadIdx.x, lane = tid % TANGO_WAVE, wave = tid / TANGO_WAVE;
+    const int k0 = (blockIdx.x / tiles_n) * TT, n0 = (blockIdx.x % tiles_n) * TT;
+    const int64_t m_begin = static_cast<int64_t>(blockIdx.y) * slab_rows;
+    const int64_t m_end = min(M, m_begin + slab_rows);
+    const int rbase = (wave / 2) * 64, cbase = (wave % 2) * 64;
+    v16i acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
+
+    for (int64_t m0 = m_begin; m0 < m_end; m0 += MS) {
+        // stage: 16 row-quads x 32 column-quads per operand, two blocks per thread per operand
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int bid = tid + 256 * j;
+            const int qa = bid / 32, qb = bid % 32;
+            uint32_t t[4];
+            const int64_t r = m0 + 4 * qa;
+            transpose4x4(load_quad(P, r, m_end, K, k0 + 4 * qb, K), load_quad(P, r + 1, m_end, K, k0 + 4 * qb, K),
+                         load_quad(P, r + 2, m_end, K, k0 + 4 * qb, K), load_quad(P, r + 3, m_end, K, k0 + 4 * qb, K), t);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) *reinterpret_cast<uint32_t *>(Pt + (4 * qb + c) * LDM + 4 * qa) = t[c];
+            transpose4x4(load_quad(Q, r, m_end, N, n0 + 4 * qb, N), load_quad(Q, r + 1, m_end, N, n0 + 4 * qb, N),
+                         load_quad(Q, r + 2, m_end, N, n0 + 4 * qb, N), load_quad(Q, r + 3, m_end, N, n0 + 4 * qb, N), t);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) *reinterpret_cast<uint32_t *>(Qt + (4 * qb + c) * LDM + 4 * qa) = t[c];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < MS; ks += 32) {
+            const v4i a0 = *reinterpret_cast<const v4i *>(Pt + (rbase + lane % 32) * LDM + ks + 16 * (lane / 32));
+            const v4i a1 = *reinterpret_cast<const v4i *>(Pt + (rbase + 32 + lane % 32) * LDM + ks + 16 * (lane / 32));
+            const v4i b0 = *reinterpret_cast<const v4i *>(Qt + (cbase + lane % 32) * LDM + ks + 16 * (lane / 32));
+            const v4i b1 = *reinterpret_cast<const v4i *>(Qt + (cbase + 32 + lane % 32) * LDM + ks + 16 * (lane / 32));
+            acc00 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc00, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b1, acc01, 0, 0, 0);
+            acc10 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b0, acc10, 0, 0, 0);
+            acc11 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc11, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const v16i &acc = t == 0 ? acc00 : (t == 1 ? acc01 : (t == 2 ? acc10 : acc11));
+        const int rb = t / 2, cb = t % 2;
+        const int col = n0 + cbase + cb * 32 + lane % 32;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = k0 + rbase + rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+            if (row < K && col < N && acc[i] != 0) atomicAdd(acc_out + static_cast<int64_t>(row) * N + col, acc[i]);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_dequant_i32(const int32_t *__restrict__ acc, int64_t n, const float *sa,
+                                                     const float *sb, float *__restrict__ out)
+{
+    const float sc = (*sa) * (*sb);
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+        out[i] = static_cast<float>(acc[i]) * sc;
+}
+
+int launch_fused(const fused_args &a, int rounding, hipStream_t st)
+{
+    const size_t lds_bytes = static_cast<size_t>(BM) * (a.Kp + LDS_PAD);
+    const unsigned grid = static_cast<unsigned>((a.M + BM - 1) / BM);
+    const int wl = (a.K % 4 == 0) ? 4 : ((a.K % 2 == 0) ? 2 : 1);
+#define TANGO_FUSED(R, W)                                                                                   \
+    {                                                                                                       \
+        if (lds_bytes > 48 * 1024 &&                                                                        \
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_qgemm_fused<R, W>),                       \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)) != hipSuccess) \
+            return TANGO_ERR_LAUNCH;                                                                        \
+        k_qgemm_fused<R, W><<<grid, 256, lds_bytes, st>>>(a);                                               \
+    }
+    if (rounding == TANGO_RN) {
+        if (wl == 4) TANGO_FUSED(TANGO_RN, 4) else if (wl == 2) TANGO_FUSED(TANGO_RN, 2) else TANGO_FUSED(TANGO_RN, 1)
+    } else {
+        if (wl == 4) TANGO_FUSED(TANGO_SR, 4) else if (wl == 2) TANGO_FUSED(TANGO_SR, 2) else TANGO_FUSED(TANGO_SR, 1)
+    }
+#undef TANGO_FUSED
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int validate_mnk(int64_t M, int64_t N, int64_t K)
+{
+    TANGO_REQUIRE(M >= 1 && N >= 1 && K >= 1, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(M < (int64_t(1) << 31) && N <= 65536 && K <= 65536, TANGO_ERR_BAD_SHAPE);
+    return TANGO_OK;
+}
+
+size_t bt_bytes(int64_t rows, int64_t red)
+{
+    return tango_round_up(static_cast<size_t>(tango_round_up(rows, 64)) * tango_round_up(red, 32), 256);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tango_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (validate_mnk(M, N, K) != TANGO_OK) return 0;
+    return 256 + bt_bytes(N, K);
+}
+
+int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B, int rounding, uint64_t seed,
+                uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A, int8_t *B_q, float *s_B, float *C,
+                float *absmax_C, void *ws, size_t ws_bytes, void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    int rc = validate_mnk(M, N, K);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(K <= KMAX, TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(A && B && A_q && s_A && B_q && s_B && C, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(A, 16) && tango_aligned(A_q, 8) && tango_aligned(B, 4) && tango_aligned(C, 4),
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_qgemm_workspace_bytes(M, N, K), TANGO_ERR_WORKSPACE);
+    hipStream_t st = tango_stream(stream);
+    float *am = static_cast<float *>(ws);  // [0] = absmax A, [1] = absmax B
+    int8_t *BT = static_cast<int8_t *>(ws) + 256;
+    const int Kp = static_cast<int>(tango_round_up(K, 32)), Np = static_cast<int>(tango_round_up(N, 64));
+
+    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(am), 0u, 2, st)) != TANGO_OK) return rc;
+    if (absmax_C && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_C), 0u, 1, st)) != TANGO_OK) return rc;
+    if ((rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
+    if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
+    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, Np * Kp / 4, st)) != TANGO_OK) return rc;
+    const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
+    const unsigned gb = tango_grid_for(static_cast<size_t>(K) * N, 256);
+    if (rounding == TANGO_RN)
+        k_quantize_b<TANGO_RN><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
+    else
+        k_quantize_b<TANGO_SR><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
+    TANGO_LAUNCH_CHECK();
+
+    fused_args a;
+    a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K); a.Kp = Kp; a.Np = Np;
+    a.A = A; a.absmax_A = am; a.rng = tango_rng_make(seed, stream_id_A);
+    a.A_q = A_q; a.s_A = s_A; a.BT = BT; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C;
+    return launch_fused(a, rounding, st);
+}
+
+size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (validate_mnk(M, N, K) != TANGO_OK) return 0;
+    return 256 + bt_bytes(K, N) + tango_round_up(static_cast<size_t>(K) * N * sizeof(int32_t), 256);
+}
+
+int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
+                    const float *s_B, const float *dC, int rounding, uint64_t seed, uint64_t stream_id_dC,
+                    const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, float *dB, void *ws, size_t ws_bytes,
+                    void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    int rc = validate_mnk(M, N, K);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(N <= KMAX, TANGO_ERR_UNSUPPORTED);  // N is the reduction length of the dA product
+    TANGO_REQUIRE(dC && dC_q && s_dC, TANGO_ERR_NULL);
+    TANGO_REQUIRE(!dA || (B_q && s_B), TANGO_ERR_NULL);
+    TANGO_REQUIRE(!dB || (A_q && s_A), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(dC, 16) && tango_aligned(dC_q, 8) && tango_aligned(dA, 4) && tango_aligned(dB, 4),
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_qgemm_bwd_workspace_bytes(M, N, K), TANGO_ERR_WORKSPACE);
+    hipStream_t st = tango_stream(stream);
+    float *am = static_cast<float *>(ws);
+    int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
+    int32_t *acc = reinterpret_cast<int32_t *>(BT + bt_bytes(K, N));
+    const float *amp = absmax_dC_in;
+    if (!amp) {
+        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(am), 0u, 1, st)) != TANGO_OK) return rc;
+        if ((rc = tango_absmax_accumulate_async(dC, static_cast<size_t>(M) * N, am, st)) != TANGO_OK) return rc;
+        amp = am;
+    }
+    if (dA) {
+        // dA = dC_q . B_q^T: the forward kernel with dC in the role of A and B_q (K x N, rows contiguous along
+        // the reduction index n) in the role of the transposed operand.
+        const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));
+        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, Cp * Rp / 4, st)) != TANGO_OK) return rc;
+        k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Rp, B_q, BT);
+        TANGO_LAUNCH_CHECK();
+        fused_args a;
+        a.M = M; a.N = static_cast<int>(K); a.K = static_cast<int>(N); a.Kp = Rp; a.Np = Cp;
+        a.A = dC; a.absmax_A = amp; a.rng = tango_rng_make(seed, stream_id_dC);
+        a.A_q = dC_q; a.s_A = s_dC; a.BT = BT; a.s_B = s_B; a.C = dA; a.absmax_C = nullptr;
+        if ((rc = launch_fused(a, rounding, st)) != TANGO_OK) return rc;
+    } else {
+        if ((rc = tango_quantize_with_absmax_async(dC, static_cast<size_t>(M) * N, rounding, seed, stream_id_dC, amp, dC_q,
+                                                   s_dC, st)) != TANGO_OK)
+            return rc;
+    }
+    if (dB) {
+        // dB = A_q^T . dC_q, reduction over the M rows, split into slabs
+        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, static_cast<int>(K * N), st)) != TANGO_OK) return rc;
+        const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
+        int64_t slabs = 1024 / (tiles_k * tiles_n);
+        if (slabs < 1) slabs = 1;
+        int64_t slab_rows = tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS);
+        slabs = (M + slab_rows - 1) / slab_rows;
+        dim3 grid(static_cast<unsigned>(tiles_k * tiles_n), static_cast<unsigned>(slabs));
+        k_gemm_tn<<<grid, 256, 0, st>>>(M, static_cast<int>(K), static_cast<int>(N), A_q, dC_q, acc, slab_rows, tiles_n);
+        TANGO_LAUNCH_CHECK();
+        k_dequant_i32<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(acc, K * N, s_A, s_dC, dB);
+        TANGO_LAUNCH_CHECK();
+    }
+    return TANGO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,187 @@
+// Attention projections in fp32 (Sec. 2.1 step 2 and step 2').  Both kernels
+// stream an n x F matrix once and are bound by HBM bandwidth:
+//   forward : 4F bytes read per node, 8*heads written;
+//   backward: (4F + F) read and 4F written per node.
+#include "internal.hip.h"
+
+namespace {
+
+// S[p] = X[p, :] . a_src[h, :], D[p] likewise, p = v*heads + h; LPP lanes per (node, head) pair.
+__global__ __launch_bounds__(256) void k_head_proj(int64_t npairs, int heads, int dim, int lpp,
+                                                   const float *__restrict__ X, const float *__restrict__ a_src,
+                                                   const float *__restrict__ a_dst, float *__restrict__ S,
+                                                   float *__restrict__ D, float *absmax_S, float *absmax_D)
+{
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int lg = lane % lpp;
+    const int ppw = 64 / lpp;  // pairs per wave-iteration
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * blockDim.x / TANGO_WAVE;
+    const int q = dim / 4;  // float4 per pair
+    float ms = 0.0f, md = 0.0f;
+    for (int64_t p0 = wave * ppw; p0 < npairs; p0 += nwaves * ppw) {
+        const int64_t p = p0 + lane / lpp;
+        double accs = 0.0, accd = 0.0;
+        if (p < npairs) {
+            const int h = static_cast<int>(p % heads);
+            const float4 *x4 = reinterpret_cast<const float4 *>(X + p * dim);
+            const float4 *as4 = reinterpret_cast<const float4 *>(a_src + static_cast<int64_t>(h) * dim);
+            const float4 *ad4 = reinterpret_cast<const float4 *>(a_dst + static_cast<int64_t>(h) * dim);
+            for (int k = lg; k < q; k += lpp) {
+                const float4 x = x4[k], s = as4[k], d = ad4[k];
+                accs += static_cast<double>(x.x) * s.x + static_cast<double>(x.y) * s.y + static_cast<double>(x.z) * s.z +
+                        static_cast<double>(x.w) * s.w;
+                accd += static_cast<double>(x.x) * d.x + static_cast<double>(x.y) * d.y + static_cast<double>(x.z) * d.z +
+                        static_cast<double>(x.w) * d.w;
+            }
+        }
+        for (int o = lpp / 2; o > 0; o >>= 1) {
+            accs += __shfl_xor(accs, o, 64);
+            accd += __shfl_xor(accd, o, 64);
+        }
+        if (p < npairs && lg == 0) {
+            const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
+            S[p] = fs;
+            D[p] = fd;
+            ms = fmaxf(ms, fabsf(fs));
+            md = fmaxf(md, fabsf(fd));
+        }
+    }
+    ms = tango_wave_max(ms);
+    md = tango_wave_max(md);
+    if (lane == 0) {
+        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
+        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
+    }
+}
+
+// dX = dX_agg + (dS*a_src + dD*a_dst); column sums of dS*(sX*Xq), dD*(sX*Xq) into acc[2F] (double, atomics).
+// Thread <-> one quad of columns; 256/TPR rows per block-iteration.
+__global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int dim, const float *__restrict__ dS,
+                                                       const float *__restrict__ dD, const float *__restrict__ a_src,
+                                                       const float *__restrict__ a_dst, const int8_t *__restrict__ Xq,
+                                                       const float *__restrict__ sX_p, const float *dX_agg, float *dX,
+                                                       float *absmax_dX, double *acc)
+{
+    const int F = heads * dim;
+    const int tpr = F / 4;            // threads per row
+    const int rpb = 256 / tpr;        // rows per block-iteration
+    const int ro = threadIdx.x / tpr;  // my row offset
+    const int c = (threadIdx.x - ro * tpr) * 4;
+    const bool active = ro < rpb;
+    const float sX = *sX_p;
+    double ss[4] = {0, 0, 0, 0}, sd[4] = {0, 0, 0, 0};
+    float m = 0.0f;
+    if (active) {
+        const int h = c / dim;
+        const float4 as = *reinterpret_cast<const float4 *>(a_src + c);
+        const float4 ad = *reinterpret_cast<const float4 *>(a_dst + c);
+        for (int64_t v = static_cast<int64_t>(blockIdx.x) * rpb + ro; v < n; v += static_cast<int64_t>(gridDim.x) * rpb) {
+            const float gs = dS[v * heads + h], gd = dD[v * heads + h];
+            const float4 ag = *reinterpret_cast<const float4 *>(dX_agg + v * F + c);
+            const uint32_t xw = *reinterpret_cast<const uint32_t *>(Xq + v * F + c);
+            float4 o;
+            o.x = ag.x + (gs * as.x + gd * ad.x);
+            o.y = ag.y + (gs * as.y + gd * ad.y);
+            o.z = ag.z + (gs * as.z + gd * ad.z);
+            o.w = ag.w + (gs * as.w + gd * ad.w);
+            *reinterpret_cast<float4 *>(dX + v * F + c) = o;
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(o.x), fabsf(o.y)), fmaxf(fabsf(o.z), fabsf(o.w))));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float x = sX * static_cast<float>(static_cast<int8_t>(xw >> (8 * j)));
+                ss[j] += static_cast<double>(gs) * static_cast<double>(x);
+                sd[j] += static_cast<double>(gd) * static_cast<double>(x);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            atomicAdd(acc + c + j, ss[j]);
+            atomicAdd(acc + F + c + j, sd[j]);
+        }
+    }
+    if (absmax_dX) {
+        m = tango_wave_max(m);
+        if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_dX, m);
+    }
+}
+
+__global__ void k_head_proj_bwd_finish(int F, const double *acc, float *da_src, float *da_dst)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c < F) {
+        da_src[c] = static_cast<float>(acc[c]);
+        da_dst[c] = static_cast<float>(acc[F + c]);
+    }
+}
+
+}  // namespace
+
+int tango_head_proj_async(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst,
+                          float *S, float *D, float *absmax_S, float *absmax_D, hipStream_t st)
+{
+    int rc;
+    if (absmax_S && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 0u, 1, st)) != TANGO_OK) return rc;
+    if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
+    int lpp = 1;
+    while (lpp * 2 <= 64 && lpp * 2 <= dim / 4) lpp *= 2;
+    const int64_t npairs = n * heads;
+    const size_t waves_needed = static_cast<size_t>((npairs + (64 / lpp) - 1) / (64 / lpp));
+    k_head_proj<<<tango_grid_for(waves_needed, 4, 256 * 8), 256, 0, st>>>(npairs, heads, dim, lpp, X, a_src, a_dst, S, D,
+                                                                         absmax_S, absmax_D);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
+                              const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
+                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st)
+{
+    const int F = heads * dim;
+    double *acc = static_cast<double *>(ws);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, 4 * F, st);
+    if (rc != TANGO_OK) return rc;
+    if (absmax_dX && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_dX), 0u, 1, st)) != TANGO_OK) return rc;
+    const int rpb = 256 / (F / 4);
+    k_head_proj_bwd<<<tango_grid_for(static_cast<size_t>((n + rpb - 1) / rpb), 8, 256 * 4), 256, 0, st>>>(
+        n, heads, dim, dS, dD, a_src, a_dst, X_q, s_X, dX_agg, dX, absmax_dX, acc);
+    TANGO_LAUNCH_CHECK();
+    k_head_proj_bwd_finish<<<(F + 255) / 256, 256, 0, st>>>(F, acc, da_src, da_dst);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+extern "C" {
+
+int tango_head_proj(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst, float *S,
+                    float *D, float *absmax_S, float *absmax_D, void *stream)
+{
+    TANGO_REQUIRE(n >= 0 && heads >= 1 && dim >= 4 && dim % 4 == 0, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(a_src && a_dst && (n == 0 || (X && S && D)), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(X, 16) && tango_aligned(a_src, 16) && tango_aligned(a_dst, 16), TANGO_ERR_BAD_SHAPE);
+    return tango_head_proj_async(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D, tango_stream(stream));
+}
+
+size_t tango_head_proj_bwd_workspace_bytes(int64_t, int heads, int dim)
+{
+    return tango_round_up(static_cast<size_t>(2) * heads * dim * sizeof(double), 256);
+}
+
+int tango_head_proj_bwd(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
+                        const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
+                        float *absmax_dX, float *da_src, float *da_dst, void *ws, size_t ws_bytes, void *stream)
+{
+    TANGO_REQUIRE(n >= 0 && heads >= 1 && dim >= 4 && dim % 4 == 0, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(static_cast<int64_t>(heads) * dim <= 1024, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(a_src && a_dst && s_X && da_src && da_dst && (n == 0 || (dS && dD && X_q && dX_agg && dX)),
+                  TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(dX, 16) && tango_aligned(X_q, 4) &&
+                      tango_aligned(a_src, 16) && tango_aligned(a_dst, 16),
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_head_proj_bwd_workspace_bytes(n, heads, dim),
+                  TANGO_ERR_WORKSPACE);
+    return tango_head_proj_bwd_async(n, heads, dim, dS, dD, a_src, a_dst, X_q, s_X, dX_agg, dX, absmax_dX, da_src, da_dst,
+                                     ws, tango_stream(stream));
+}
+
+}  // extern "C"
