@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized GNN-layer hot path on one MI355X.
+
+One "step" = one quantized GAT layer, forward + backward (every abs-max, quantization and dequantization included,
+graph construction excluded), on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_dense|toy|gcn_arxiv] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def spmm_algorithmic_bytes(n, nnz, heads, F):
+    """Per launch of the quantized SPMM: per edge 4 (index) + heads (int8 weight) + F (gathered int8 row);
+    per node 4 (row pointer) + 4F (fp32 result)."""
+    return nnz * (4 + heads + F) + n * (4 + 4 * F)
+
+
+def time_events(torch, fn, iters):
+    """Average milliseconds of fn() over iters launches, HIP events on the current stream."""
+    st = torch.cuda.current_stream()
+    a = torch.cuda.Event(enable_timing=True)
+    b = torch.cuda.Event(enable_timing=True)
+    a.record(st)
+    for _ in range(iters):
+        fn()
+    b.record(st)
+    b.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def cpu_baseline(name, scale_down, slope=0.2):
+    """The CPU oracle, as it stands, on a scaled-down instance of the same workload (same mean degree and widths)."""
+    import oracle as orc
+    import tango_inputs as ti
+
+    li = ti.layer_inputs(name, scale_down=scale_down)
+    g = li.graph
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    if ti.CONFIGS[name]["kind"] == "gcn":
+        w_q, s_w = orc.quantize(ti.gcn_edge_weights(g), orc.SR, li.sr_seed, orc.SID_EW)
+        f = orc.gcn_layer_fwd(g, li.feat, li.weight, w_q, s_w, orc.SR, li.sr_seed)
+        orc.gcn_layer_bwd(g, f, w_q, s_w, li.grad_out, orc.SR, li.sr_seed)
+    else:
+        f = orc.gat_layer_fwd(g, li.feat, li.weight, li.a_src, li.a_dst, slope, orc.SR, li.sr_seed)
+        orc.gat_layer_bwd(g, f, li.a_src, li.a_dst, li.grad_out, slope, orc.SR, li.sr_seed)
+    dt = time.perf_counter() - t0
+    return {
+        "value": dt * 1e3 * scale_down,
+        "unit": "ms per layer fwd+bwd (extrapolated)",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": "oracle layer fwd+bwd on a 1/%d instance (%d nodes, %d edges, same widths and mean degree) took %.2f s; "
+                  "value = that time x %d" % (scale_down, g.n_nodes, g.n_edges, dt, scale_down),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv"])
+    ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-scale-down", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no multi-GPU path exists); use --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2308_00890_amd as T
+    import tango_inputs as ti
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(3)
+    T.load_library()
+    dev = torch.device("cuda:0")
+    name = args.workload
+    cfg = ti.CONFIGS[name]
+    t0 = time.perf_counter()
+    li = ti.layer_inputs(name, scale_down=args.scale_down)
+    g = li.graph
+    log("inputs: %s, %d nodes, %d edges (with self-loops), built in %.1f s" % (name, g.n_nodes, g.n_edges, time.perf_counter() - t0))
+    G = T.Graph.from_host(g, dev)
+    to = lambda a: torch.from_numpy(a).to(dev)
+    slope = 0.2
+    if cfg["kind"] == "gcn":
+        w = to(ti.gcn_edge_weights(g))  # fixed edge weights: inputs of the layer, quantized once outside the timed region
+        w_q = torch.empty(w.shape, dtype=torch.int8, device=dev)
+        s_w = torch.zeros(1, dtype=torch.float32, device=dev)
+        T.tango_quantize(w, T.SR, li.sr_seed, 9, None, w_q, s_w, torch.empty(256, dtype=torch.uint8, device=dev))
+        L = T.GcnLayer(G, to(li.feat), to(li.weight), w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0)
+        step = lambda: (T.tango_gcn_layer_fwd(L), T.tango_gcn_layer_bwd(L))
+        heads, F = 1, cfg["dim"]
+        spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
+    else:
+        L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0)
+        step = lambda: (T.tango_gat_layer_fwd(L), T.tango_gat_layer_bwd(L))
+        heads, F = li.heads, li.heads * li.dim
+        spmm = lambda: T.tango_qspmm(G, T.IN, heads, li.dim, L["alpha_q"], L["s_alpha"], L["Hp_q"], L["s_Hp"], L["out"],
+                                     L["absmax_out"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    log("layer fwd+bwd: %.3f ms/step" % ms_per_step)
+
+    # dominant kernel: the quantized SPMM (one launch = tango_qspmm over the whole graph, as inside the layer)
+    spmm()
+    torch.cuda.synchronize()
+    spmm_ms = time_events(torch, spmm, max(args.steps, 5))
+    alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
+    achieved = alg / (spmm_ms * 1e-3) / 1e9
+    log("qSPMM: %.3f ms/launch, %.1f algorithmic GB/s" % (spmm_ms, achieved))
+
+    out = {
+        "metric": "ms per quantized GAT layer fwd+bwd" if cfg["kind"] == "gat" else "ms per quantized GCN layer fwd+bwd",
+        "value": ms_per_step,
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 operands, int32 accumulation, fp32 softmax/outputs",
+        "data": "synthetic",
+        "config": {
+            "workload": "config %d (%s): %s graph, %d nodes, %d edges incl. self-loops, K_in %d, %d heads x %d, SR"
+            % (cfg["config"], name, cfg["graph"], g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim),
+            "scale_down": args.scale_down,
+        },
+        "roofline": {
+            "kernel": "k_spmm (tango_qspmm, in-edge direction)",
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "algorithmic_bytes_per_launch": alg,
+            "ms_per_launch": spmm_ms,
+        },
+    }
+    if not args.no_cpu_baseline:
+        sd = args.cpu_scale_down or {"gat_dense": 8, "gcn_arxiv": 1, "toy": 1}[name]
+        sd *= args.scale_down
+        log("cpu baseline (oracle) on a 1/%d instance ..." % sd)
+        out["cpu_baseline"] = cpu_baseline(name, sd, slope)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

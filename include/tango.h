@@ -250,6 +250,99 @@ int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q,
                     const int8_t *X_q, const float *s_X, const int8_t *dOut_q, const float *s_dOut,
                     float *dX, float *absmax_dX, float *dW, void *stream);
 
+/* ------------------------------------------------------------------------ */
+/* Whole-layer entry points: the primitives above chained on one stream,     */
+/* with every quantized tensor produced once and reused (Sec. 3.3             */
+/* "Inter-primitive optimization": forward tensors cached for backward, one  */
+/* quantized copy shared by several operators).  They add no arithmetic of   */
+/* their own: each is checkable against the composition of the primitives.   */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Buffers of one GAT layer (Fig. 1).  n = g->n_nodes, nnz = g->n_edges,
+ * F = heads*dim.  All device memory, caller-owned, contiguous.  "out" fields
+ * are written by the call named in brackets and read by later calls.
+ * Random streams: tensor t of layer `layer_id` uses stream_id 16*layer_id + t
+ * with t = 1 H, 2 W, 3 H', 4 S, 5 D, 6 alpha, 7 upstream gradient, 8 dH'.
+ */
+typedef struct tango_gat_layer {
+    const tango_graph *g;
+    int k_in, heads, dim;
+    float slope;            /* LeakyReLU slope */
+    int rounding;
+    uint64_t seed, layer_id;
+    /* parameters and input */
+    const float *H;         /* n x k_in */
+    const float *W;         /* k_in x F */
+    const float *a_src;     /* heads x dim */
+    const float *a_dst;     /* heads x dim */
+    /* forward results and caches [fwd] */
+    int8_t *H_q;  float *s_H;     /* n x k_in */
+    int8_t *W_q;  float *s_W;     /* k_in x F */
+    float *Hp;    float *absmax_Hp; /* n x F: H' = H.W dequantized */
+    int8_t *Hp_q; float *s_Hp;    /* n x F */
+    float *S, *D;                 /* n x heads fp32 (step 2) */
+    int8_t *S_q;  float *s_S;     /* n x heads */
+    int8_t *D_q;  float *s_D;     /* n x heads */
+    float *E;                     /* nnz x heads: activated scores (step 3); may alias alpha */
+    float *alpha;                 /* nnz x heads: softmax output, fp32 (kept for step 4') */
+    int8_t *alpha_q; float *s_alpha; /* nnz x heads */
+    float *out;   float *absmax_out; /* n x F: layer output H^(l) */
+    /* backward input, results and scratch [bwd] */
+    const float *grad_out;        /* n x F */
+    int8_t *g_q;  float *s_g;     /* n x F: quantized upstream gradient */
+    float *dHp;   float *absmax_dHp; /* n x F: dH' = dH'_agg + dH'_att */
+    float *dalpha;                /* nnz x heads: step 5''; overwritten by step 4' (dE) */
+    float *dS, *dD;               /* n x heads */
+    int8_t *dHp_q; float *s_dHp;  /* n x F */
+    float *dW;                    /* k_in x F  (fp32 gradient for the full-precision weight update) */
+    float *dH;                    /* n x k_in, or NULL to skip (first layer) */
+    float *da_src, *da_dst;       /* heads x dim */
+    /* scratch */
+    void *ws;
+    size_t ws_bytes;              /* >= tango_gat_layer_workspace_bytes(...) */
+} tango_gat_layer;
+
+size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim);
+
+/* Steps 1-5 of Fig. 1a: qGEMM, projections, quantize, SDDMM-add, edge softmax, quantize, qSPMM. */
+int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream);
+
+/* Steps 5', 5'', 4', 3', 3'', 2', 1' of Fig. 1b, reading the caches tango_gat_layer_fwd left in *L. */
+int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream);
+
+/*
+ * One GCN layer (Sec. 2.2): H' = H.W (qGEMM), out = (G (.) w) . H' (qSPMM) with
+ * fixed edge weights w already quantized by the caller (w_q: nnz x 1, s_w).
+ * Random streams as in tango_gat_layer.
+ */
+typedef struct tango_gcn_layer {
+    const tango_graph *g;
+    int k_in, f_out;
+    int rounding;
+    uint64_t seed, layer_id;
+    const float *H;          /* n x k_in */
+    const float *W;          /* k_in x f_out */
+    const int8_t *w_q; const float *s_w;  /* nnz edge weights */
+    int8_t *H_q;  float *s_H;
+    int8_t *W_q;  float *s_W;
+    float *Hp;    float *absmax_Hp;   /* n x f_out */
+    int8_t *Hp_q; float *s_Hp;
+    float *out;   float *absmax_out;  /* n x f_out */
+    const float *grad_out;            /* n x f_out */
+    int8_t *g_q;  float *s_g;
+    float *dHp;   float *absmax_dHp;  /* n x f_out */
+    int8_t *dHp_q; float *s_dHp;
+    float *dW;                        /* k_in x f_out */
+    float *dH;                        /* n x k_in or NULL */
+    void *ws;
+    size_t ws_bytes;
+} tango_gcn_layer;
+
+size_t tango_gcn_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int f_out);
+int tango_gcn_layer_fwd(const tango_gcn_layer *L, void *stream);
+int tango_gcn_layer_bwd(const tango_gcn_layer *L, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

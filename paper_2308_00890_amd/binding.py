@@ -284,3 +284,175 @@ def tango_qspmm_bwd(g, heads, dim, w_q, s_w, X_q, s_X, dOut_q, s_dOut, dX, absma
         ),
         "tango_qspmm_bwd",
     )
+
+
+# ------------------------------------------------------------------- whole layers
+class tango_gat_layer(ctypes.Structure):
+    _fields_ = (
+        [("g", _gp), ("k_in", _int), ("heads", _int), ("dim", _int), ("slope", _f32), ("rounding", _int),
+         ("seed", _u64), ("layer_id", _u64)]
+        + [(n, _vp) for n in (
+            "H", "W", "a_src", "a_dst", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "S", "D",
+            "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
+            "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst", "ws")]
+        + [("ws_bytes", _sz)]
+    )
+
+
+class tango_gcn_layer(ctypes.Structure):
+    _fields_ = (
+        [("g", _gp), ("k_in", _int), ("f_out", _int), ("rounding", _int), ("seed", _u64), ("layer_id", _u64)]
+        + [(n, _vp) for n in (
+            "H", "W", "w_q", "s_w", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "out",
+            "absmax_out", "grad_out", "g_q", "s_g", "dHp", "absmax_dHp", "dHp_q", "s_dHp", "dW", "dH", "ws")]
+        + [("ws_bytes", _sz)]
+    )
+
+
+SIGNATURES.update({
+    "tango_gat_layer_workspace_bytes": (_sz, [_i64, _i64, _int, _int, _int]),
+    "tango_gat_layer_fwd": (_int, [ctypes.POINTER(tango_gat_layer), _vp]),
+    "tango_gat_layer_bwd": (_int, [ctypes.POINTER(tango_gat_layer), _vp]),
+    "tango_gcn_layer_workspace_bytes": (_sz, [_i64, _i64, _int, _int]),
+    "tango_gcn_layer_fwd": (_int, [ctypes.POINTER(tango_gcn_layer), _vp]),
+    "tango_gcn_layer_bwd": (_int, [ctypes.POINTER(tango_gcn_layer), _vp]),
+})
+
+
+def tango_gat_layer_workspace_bytes(n_nodes, n_edges, k_in, heads, dim) -> int:
+    return load_library().tango_gat_layer_workspace_bytes(n_nodes, n_edges, k_in, heads, dim)
+
+
+def tango_gcn_layer_workspace_bytes(n_nodes, n_edges, k_in, f_out) -> int:
+    return load_library().tango_gcn_layer_workspace_bytes(n_nodes, n_edges, k_in, f_out)
+
+
+class _LayerBuffers:
+    """Owns the device tensors one layer struct points at (allocation only; no arithmetic)."""
+
+    _struct = None
+    _spec = {}  # field -> (shape fn, dtype)
+
+    def __init__(self):
+        self.t = {}
+        self.c = self._struct()
+
+    def _alloc(self, name, shape, dtype):
+        t = torch.empty(shape, dtype=dtype, device=self.device)
+        self.t[name] = t
+        setattr(self.c, name, t.data_ptr())
+        return t
+
+    def _bind(self, name, tensor, dtype):
+        self.t[name] = tensor
+        setattr(self.c, name, _ptr(tensor, dtype))
+
+    def __getitem__(self, name):
+        return self.t[name]
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+class GatLayer(_LayerBuffers):
+    _struct = tango_gat_layer
+
+    def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
+                 want_dH=True, alias_E_alpha=True):
+        super().__init__()
+        self.device = H.device
+        self.graph = graph
+        n, k_in = H.shape
+        heads, dim = a_src.shape
+        F = heads * dim
+        nnz = graph.n_edges
+        c = self.c
+        c.g = ctypes.pointer(graph.c)
+        c.k_in, c.heads, c.dim, c.slope, c.rounding, c.seed, c.layer_id = k_in, heads, dim, slope, rounding, seed, layer_id
+        f32, i8 = torch.float32, torch.int8
+        for name, tensor in (("H", H), ("W", W), ("a_src", a_src), ("a_dst", a_dst)):
+            self._bind(name, tensor, f32)
+        for name in ("s_H", "s_W", "absmax_Hp", "s_Hp", "s_S", "s_D", "s_alpha", "absmax_out", "s_g", "absmax_dHp", "s_dHp"):
+            self._alloc(name, (1,), f32)
+        self._alloc("H_q", (n, k_in), i8)
+        self._alloc("W_q", (k_in, F), i8)
+        self._alloc("Hp", (n, F), f32)
+        self._alloc("Hp_q", (n, F), i8)
+        for name in ("S", "D", "dS", "dD"):
+            self._alloc(name, (n, heads), f32)
+        self._alloc("S_q", (n, heads), i8)
+        self._alloc("D_q", (n, heads), i8)
+        self._alloc("alpha", (nnz, heads), f32)
+        if alias_E_alpha:
+            self._bind("E", self.t["alpha"], f32)
+        else:
+            self._alloc("E", (nnz, heads), f32)
+        self._alloc("alpha_q", (nnz, heads), i8)
+        self._alloc("out", (n, F), f32)
+        if grad_out is not None:
+            self._bind("grad_out", grad_out, f32)
+            self._alloc("g_q", (n, F), i8)
+            self._alloc("dHp", (n, F), f32)
+            self._alloc("dalpha", (nnz, heads), f32)
+            self._alloc("dHp_q", (n, F), i8)
+            self._alloc("dW", (k_in, F), f32)
+            if want_dH:
+                self._alloc("dH", (n, k_in), f32)
+            self._alloc("da_src", (heads, dim), f32)
+            self._alloc("da_dst", (heads, dim), f32)
+        nbytes = tango_gat_layer_workspace_bytes(n, nnz, k_in, heads, dim)
+        self._alloc("ws", (nbytes,), torch.uint8)
+        c.ws_bytes = nbytes
+
+
+class GcnLayer(_LayerBuffers):
+    _struct = tango_gcn_layer
+
+    def __init__(self, graph: "Graph", H, W, w_q, s_w, grad_out=None, rounding=SR, seed=0, layer_id=0, want_dH=True):
+        super().__init__()
+        self.device = H.device
+        self.graph = graph
+        n, k_in = H.shape
+        f_out = W.shape[1]
+        c = self.c
+        c.g = ctypes.pointer(graph.c)
+        c.k_in, c.f_out, c.rounding, c.seed, c.layer_id = k_in, f_out, rounding, seed, layer_id
+        f32, i8 = torch.float32, torch.int8
+        self._bind("H", H, f32)
+        self._bind("W", W, f32)
+        self._bind("w_q", w_q, i8)
+        self._bind("s_w", s_w, f32)
+        for name in ("s_H", "s_W", "absmax_Hp", "s_Hp", "absmax_out", "s_g", "absmax_dHp", "s_dHp"):
+            self._alloc(name, (1,), f32)
+        self._alloc("H_q", (n, k_in), i8)
+        self._alloc("W_q", (k_in, f_out), i8)
+        self._alloc("Hp", (n, f_out), f32)
+        self._alloc("Hp_q", (n, f_out), i8)
+        self._alloc("out", (n, f_out), f32)
+        if grad_out is not None:
+            self._bind("grad_out", grad_out, f32)
+            self._alloc("g_q", (n, f_out), i8)
+            self._alloc("dHp", (n, f_out), f32)
+            self._alloc("dHp_q", (n, f_out), i8)
+            self._alloc("dW", (k_in, f_out), f32)
+            if want_dH:
+                self._alloc("dH", (n, k_in), f32)
+        nbytes = tango_gcn_layer_workspace_bytes(n, graph.n_edges, k_in, f_out)
+        self._alloc("ws", (nbytes,), torch.uint8)
+        c.ws_bytes = nbytes
+
+
+def tango_gat_layer_fwd(layer: GatLayer):
+    _check(load_library().tango_gat_layer_fwd(layer.ref(), _stream()), "tango_gat_layer_fwd")
+
+
+def tango_gat_layer_bwd(layer: GatLayer):
+    _check(load_library().tango_gat_layer_bwd(layer.ref(), _stream()), "tango_gat_layer_bwd")
+
+
+def tango_gcn_layer_fwd(layer: GcnLayer):
+    _check(load_library().tango_gcn_layer_fwd(layer.ref(), _stream()), "tango_gcn_layer_fwd")
+
+
+def tango_gcn_layer_bwd(layer: GcnLayer):
+    _check(load_library().tango_gcn_layer_bwd(layer.ref(), _stream()), "tango_gcn_layer_bwd")

@@ -1,0 +1,168 @@
+// Whole-layer entry points: the primitives chained on one stream with every
+// quantized tensor produced once and reused (Sec. 3.3 "Inter-primitive
+// optimization").  Host-side sequencing only; all arithmetic is in the kernels
+// of the primitives.
+#include "internal.hip.h"
+
+namespace {
+
+// random-stream ids of the tensors of one layer (layer l uses 16*l + id)
+enum { SID_H = 1, SID_W = 2, SID_HP = 3, SID_S = 4, SID_D = 5, SID_ALPHA = 6, SID_G = 7, SID_DHP = 8 };
+
+// layout of the layer workspace: 256 bytes of scalars, then the largest sub-call workspace
+enum { SC_ABSMAX_S = 0, SC_ABSMAX_D = 1, SC_ABSMAX_ALPHA = 2, SC_ABSMAX_G = 3 };
+
+size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+
+#define TANGO_TRY(expr)             \
+    do {                            \
+        int rc_ = (expr);           \
+        if (rc_ != TANGO_OK) return rc_; \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t, int k_in, int heads, int dim)
+{
+    const int64_t F = static_cast<int64_t>(heads) * dim;
+    const size_t a = tango_qgemm_workspace_bytes(n_nodes, F, k_in);
+    const size_t b = tango_qgemm_bwd_workspace_bytes(n_nodes, F, k_in);
+    const size_t c = tango_head_proj_bwd_workspace_bytes(n_nodes, heads, dim);
+    return 256 + max3(a, b, c);
+}
+
+int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->k_in >= 1 && L->heads >= 1 && L->dim >= 1, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->H && L->W && L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp && L->absmax_Hp &&
+                      L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->E && L->alpha &&
+                      L->alpha_q && L->s_alpha && L->out,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
+    const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_gat_layer_workspace_bytes(n, nnz, L->k_in, L->heads, L->dim),
+                  TANGO_ERR_WORKSPACE);
+    float *sc = static_cast<float *>(L->ws);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+
+    // step 1: H' = H.W, quantize-on-load, cached H_q / W_q, fused abs-max of H'
+    TANGO_TRY(tango_qgemm(n, F, L->k_in, L->H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W, L->H_q, L->s_H,
+                          L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
+    // step 2: S, D in fp32, with their abs-max
+    TANGO_TRY(tango_head_proj(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
+                              sc + SC_ABSMAX_D, stream));
+    // sequential quantization of the tensors the sparse primitives will access randomly (Sec. 3.3)
+    TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_HP, L->absmax_Hp, L->Hp_q,
+                             L->s_Hp, nullptr, 0, stream));
+    TANGO_TRY(tango_quantize(L->S, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_S, sc + SC_ABSMAX_S,
+                             L->S_q, L->s_S, nullptr, 0, stream));
+    TANGO_TRY(tango_quantize(L->D, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_D, sc + SC_ABSMAX_D,
+                             L->D_q, L->s_D, nullptr, 0, stream));
+    // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
+    TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
+                           stream));
+    // step 4: edge softmax in fp32
+    TANGO_TRY(tango_edge_softmax(L->g, L->heads, L->E, L->alpha, sc + SC_ABSMAX_ALPHA, stream));
+    TANGO_TRY(tango_quantize(L->alpha, static_cast<size_t>(nnz * L->heads), L->rounding, L->seed, sid + SID_ALPHA,
+                             sc + SC_ABSMAX_ALPHA, L->alpha_q, L->s_alpha, nullptr, 0, stream));
+    // step 5: quantized SPMM
+    TANGO_TRY(tango_qspmm(L->g, TANGO_IN, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->out,
+                          L->absmax_out, stream));
+    return TANGO_OK;
+}
+
+int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->grad_out && L->g_q && L->s_g && L->dHp && L->absmax_dHp && L->dalpha && L->dS && L->dD && L->dHp_q &&
+                      L->s_dHp && L->dW && L->da_src && L->da_dst,
+                  TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp_q && L->s_Hp && L->S_q && L->s_S &&
+                      L->D_q && L->s_D && L->alpha && L->alpha_q && L->s_alpha,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
+    const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_gat_layer_workspace_bytes(n, nnz, L->k_in, L->heads, L->dim),
+                  TANGO_ERR_WORKSPACE);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+
+    // the upstream gradient is quantized once and shared by steps 5' and 5''
+    TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
+                             L->s_g, sub, sub_bytes, stream));
+    // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
+    TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
+                              nullptr, L->dalpha, stream));
+    // 4': softmax backward, in place over dalpha
+    TANGO_TRY(tango_edge_softmax_bwd(L->g, L->heads, L->alpha, L->dalpha, L->dalpha, stream));
+    // LeakyReLU' and 3', 3'': edge-to-node sums
+    TANGO_TRY(tango_qsddmm_bwd(L->g, L->heads, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->dalpha, nullptr, L->dS, L->dD,
+                               stream));
+    // 2' fused with dH' = dH'_agg + dH'_att and its abs-max
+    TANGO_TRY(tango_head_proj_bwd(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
+                                  L->absmax_dHp, L->da_src, L->da_dst, sub, sub_bytes, stream));
+    // 1': both GEMMs from the cached H_q, W_q
+    TANGO_TRY(tango_qgemm_bwd(n, F, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
+                              L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
+    return TANGO_OK;
+}
+
+size_t tango_gcn_layer_workspace_bytes(int64_t n_nodes, int64_t, int k_in, int f_out)
+{
+    const size_t a = tango_qgemm_workspace_bytes(n_nodes, f_out, k_in);
+    const size_t b = tango_qgemm_bwd_workspace_bytes(n_nodes, f_out, k_in);
+    return 256 + (a > b ? a : b);
+}
+
+int tango_gcn_layer_fwd(const tango_gcn_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->k_in >= 1 && L->f_out >= 4, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->H && L->W && L->w_q && L->s_w && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp && L->absmax_Hp &&
+                      L->Hp_q && L->s_Hp && L->out,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_gcn_layer_workspace_bytes(n, nnz, L->k_in, L->f_out),
+                  TANGO_ERR_WORKSPACE);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+    TANGO_TRY(tango_qgemm(n, L->f_out, L->k_in, L->H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W, L->H_q, L->s_H,
+                          L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
+    TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n) * L->f_out, L->rounding, L->seed, sid + SID_HP, L->absmax_Hp,
+                             L->Hp_q, L->s_Hp, nullptr, 0, stream));
+    TANGO_TRY(tango_qspmm(L->g, TANGO_IN, 1, L->f_out, L->w_q, L->s_w, L->Hp_q, L->s_Hp, L->out, L->absmax_out, stream));
+    return TANGO_OK;
+}
+
+int tango_gcn_layer_bwd(const tango_gcn_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->grad_out && L->g_q && L->s_g && L->dHp && L->absmax_dHp && L->dHp_q && L->s_dHp && L->dW &&
+                      L->w_q && L->s_w && L->H_q && L->s_H && L->W_q && L->s_W,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_gcn_layer_workspace_bytes(n, nnz, L->k_in, L->f_out),
+                  TANGO_ERR_WORKSPACE);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+    TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n) * L->f_out, L->rounding, L->seed, sid + SID_G, nullptr,
+                             L->g_q, L->s_g, sub, sub_bytes, stream));
+    TANGO_TRY(tango_qspmm(L->g, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
+    TANGO_TRY(tango_qgemm_bwd(n, L->f_out, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed,
+                              sid + SID_DHP, L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
+    return TANGO_OK;
+}
+
+}  // extern "C"

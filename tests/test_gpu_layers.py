@@ -1,0 +1,146 @@
+"""GPU parity of the whole-layer entry points (GAT and GCN, forward + backward).
+
+Every stage is compared with the oracle primitive applied to the GPU's own inputs of that stage, so integer
+results stay bit-exact all along the chain even though fp32 intermediates (S, D, alpha, dE ...) may differ from an
+all-oracle run in the last bits.  The all-oracle chain is compared at the end as a whole."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle as orc
+import tango_inputs as ti
+from gpu_util import assert_bit_exact, assert_close, dev, host
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+
+    import paper_2308_00890_amd as tango
+
+    assert torch.cuda.is_available()
+    tango.load_library()
+    return tango
+
+
+def gat_case(name):
+    if name == "toy":  # configuration 1 exactly
+        return ti.layer_inputs("toy"), 0.2
+    if name == "rmat_h4":  # configuration-3 widths on a small skewed graph
+        g = ti.rmat_graph(3000, 60000, seed=21)
+        li = ti.layer_inputs("gat_dense", graph=g, k_in=602)
+        return li, 0.2
+    if name == "rmat_h3":  # configuration-4 widths
+        g = ti.rmat_graph(2000, 30000, seed=22)
+        li = ti.layer_inputs("gat_products", graph=g, k_in=100)
+        return li, 0.2
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
+@pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
+def test_gat_layer_stagewise(T, case, rounding):
+    import torch
+
+    li, slope = gat_case(case)
+    g = li.graph
+    heads = li.heads
+    seed, layer_id = li.sr_seed, 2
+    b = 16 * layer_id
+    G = T.Graph.from_host(g)
+    L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
+                   layer_id, alias_E_alpha=False)
+    T.tango_gat_layer_fwd(L)
+    T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    sc = lambda k: o[k][0]
+
+    # ---- forward, stage by stage
+    r = orc.qgemm(li.feat, li.weight, rounding, seed, b + orc.SID_H, b + orc.SID_W)
+    assert sc("s_H") == r["s_A"] and sc("s_W") == r["s_B"]
+    assert_bit_exact(o["H_q"], r["A_q"], "H_q")
+    assert_bit_exact(o["W_q"], r["B_q"], "W_q")
+    assert_bit_exact(o["Hp"], r["C"], "Hp")
+    assert sc("absmax_Hp") == r["absmax_C"]
+    assert_close(o["S"], orc.head_proj(o["Hp"], li.a_src), "S")
+    assert_close(o["D"], orc.head_proj(o["Hp"], li.a_dst), "D")
+    for name, src, sid, am in (("Hp_q", "Hp", orc.SID_HP, sc("absmax_Hp")), ("S_q", "S", orc.SID_S, None),
+                               ("D_q", "D", orc.SID_D, None)):
+        q, s = orc.quantize(o[src], rounding, seed, b + sid, am=am)
+        assert_bit_exact(o[name], q, name)
+        assert sc("s_" + name[:-2]) == s
+    assert_bit_exact(o["E"], orc.sddmm_add(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope), "E")
+    assert_close(o["alpha"], orc.edge_softmax(g, o["E"]), "alpha")
+    q, s = orc.quantize(o["alpha"], rounding, seed, b + orc.SID_ALPHA)
+    assert_bit_exact(o["alpha_q"], q, "alpha_q")
+    assert sc("s_alpha") == s
+    out, am = orc.spmm_in(g, o["alpha_q"], sc("s_alpha"), o["Hp_q"], sc("s_Hp"))
+    assert_bit_exact(o["out"], out, "out")
+    assert sc("absmax_out") == am
+
+    # ---- backward, stage by stage
+    q, s = orc.quantize(li.grad_out, rounding, seed, b + orc.SID_G)
+    assert_bit_exact(o["g_q"], q, "g_q")
+    assert sc("s_g") == s
+    agg, _ = orc.spmm_rev(g, o["alpha_q"], sc("s_alpha"), o["g_q"], sc("s_g"))
+    dalpha = orc.sddmm_dot(g, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads)
+    assert_close(o["dalpha"], orc.edge_softmax_bwd(g, o["alpha"], dalpha), "dE (softmax backward)")
+    _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, o["dalpha"])
+    assert_close(o["dS"], dS, "dS")
+    assert_close(o["dD"], dD, "dD")
+    dHp, am, da_s, da_d = orc.head_proj_bwd(o["dS"], o["dD"], li.a_src, li.a_dst, o["Hp_q"], sc("s_Hp"), agg)
+    assert_bit_exact(o["dHp"], dHp, "dHp")
+    assert sc("absmax_dHp") == am
+    assert_close(o["da_src"], da_s, "da_src")
+    assert_close(o["da_dst"], da_d, "da_dst")
+    rb = orc.qgemm_bwd(o["H_q"], sc("s_H"), o["W_q"], sc("s_W"), o["dHp"], rounding, seed, b + orc.SID_DHP, am=am)
+    assert_bit_exact(o["dHp_q"], rb["dC_q"], "dHp_q")
+    assert sc("s_dHp") == rb["s_dC"]
+    assert_bit_exact(o["dW"], rb["dB"], "dW")
+    assert_bit_exact(o["dH"], rb["dA"], "dH")
+
+    # ---- the all-oracle chain, as a whole: int8 codes may flip where an fp32 intermediate sits on a rounding
+    # threshold, so this is a closeness check in norm plus a count of differing codes
+    f = orc.gat_layer_fwd(g, li.feat, li.weight, li.a_src, li.a_dst, slope, rounding, seed, layer_id)
+    bw = orc.gat_layer_bwd(g, f, li.a_src, li.a_dst, li.grad_out, slope, rounding, seed, layer_id)
+    rel = lambda a, c: np.linalg.norm(a.astype(np.float64) - c) / max(np.linalg.norm(c), 1e-30)
+    for name, ref in (("out", f["out"]), ("dW", bw["dW"]), ("dH", bw["dH"]), ("da_src", bw["da_src"])):
+        assert rel(o[name], ref) < 2e-2, name
+    for name, ref in (("S_q", f["S_q"]), ("D_q", f["D_q"]), ("alpha_q", f["alpha_q"])):
+        diff = o[name].astype(np.int32) - ref.astype(np.int32)
+        assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-2, name
+
+
+@pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
+def test_gcn_layer_stagewise(T, rounding):
+    import torch
+
+    g = ti.rmat_graph(5000, 40000, seed=23)
+    K, F = 128, 256  # configuration-2 widths
+    H = ti.normal((g.n_nodes, K), 24)
+    W = ti.xavier_uniform(K, F, (K, F), 25)
+    up = ti.normal((g.n_nodes, F), 26)
+    seed, layer_id = 99, 1
+    b = 16 * layer_id
+    w = ti.gcn_edge_weights(g)
+    w_q, s_w = orc.quantize(w, rounding, seed, orc.SID_EW)
+    G = T.Graph.from_host(g)
+    from gpu_util import scalar
+
+    L = T.GcnLayer(G, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id)
+    T.tango_gcn_layer_fwd(L)
+    T.tango_gcn_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    f = orc.gcn_layer_fwd(g, H, W, w_q, s_w, rounding, seed, layer_id)
+    bw = orc.gcn_layer_bwd(g, f, w_q, s_w, up, rounding, seed, layer_id)
+    # every stage is integer-exact given bit-identical inputs, so the whole chain is bit-exact
+    for name in ("H_q", "W_q", "Hp", "Hp_q", "out"):
+        assert_bit_exact(o[name], f[name], name)
+    for name in ("g_q", "dHp", "dHp_q", "dW", "dH"):
+        assert_bit_exact(o[name], bw[name], name)
+    for name, ref in (("s_H", f["s_H"]), ("s_W", f["s_W"]), ("s_Hp", f["s_Hp"]), ("absmax_out", f["absmax_out"]),
+                      ("s_g", bw["s_g"]), ("absmax_dHp", bw["absmax_dHp"]), ("s_dHp", bw["s_dHp"])):
+        assert o[name][0] == ref, name
