@@ -22,9 +22,11 @@
 // (weight) + F (row); per node: 4 (pointer) + 4F (fp32 result).
 #include "internal.hip.h"
 
+#include <type_traits>
+
 namespace {
 
-constexpr int CHUNK = 256;  // edges per wavefront
+constexpr int CHUNK_SHIFT_DEFAULT = 8;  // SDDMM-dot: 256 edges per wavefront
 constexpr int WAVES_PER_BLOCK = 4;
 
 // Largest r in [0, n) with ptr[r] <= e (ptr non-decreasing, ptr[0] = 0 <= e < ptr[n]).
@@ -97,10 +99,11 @@ struct spmm_args {
     float *out;            // n x F (fp32; int32 partial sums while the kernels run)
     float *absmax;         // or NULL
     int heads, dim, F;
+    int chunk_shift;       // log2 of the edges per wavefront
 };
 
 // True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
-__device__ inline bool row_is_split(int b, int t) { return t > b && (b / CHUNK) != ((t - 1) / CHUNK); }
+__device__ inline bool row_is_split(int b, int t, int shift) { return t > b && (b >> shift) != ((t - 1) >> shift); }
 
 // Zero the rows that the main kernel reaches through atomics (split rows) or never writes (empty rows).
 __global__ __launch_bounds__(256) void k_spmm_prepare(spmm_args a)
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(256) void k_spmm_prepare(spmm_args a)
         bool flag = false;
         if (r < a.n) {
             const int b = a.ptr[r], t = a.ptr[r + 1];
-            flag = (t == b) || row_is_split(b, t);
+            flag = (t == b) || row_is_split(b, t, a.chunk_shift);
         }
         unsigned long long mask = __ballot(flag);
         while (mask) {
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
     for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
         const int r = static_cast<int>(base) + lane;
         bool flag = false;
-        if (r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1]);
+        if (r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1], a.chunk_shift);
         unsigned long long mask = __ballot(flag);
         while (mask) {
             const int k = __ffsll(static_cast<long long>(mask)) - 1;
@@ -157,16 +160,31 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
     }
 }
 
-// One wave per chunk of CHUNK edges.  VEC = bytes of the feature row per lane.
-template <int VEC>
+// t[c] = (r0.byte c, r1.byte c, r2.byte c, r3.byte c): 4x4 byte transpose with v_perm_b32.
+__device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3, uint32_t (&t)[4])
+{
+    const uint32_t x01l = __builtin_amdgcn_perm(r1, r0, 0x05010400u);
+    const uint32_t x01h = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
+    const uint32_t x23l = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+    const uint32_t x23h = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+    t[0] = __builtin_amdgcn_perm(x23l, x01l, 0x05040100u);
+    t[1] = __builtin_amdgcn_perm(x23l, x01l, 0x07060302u);
+    t[2] = __builtin_amdgcn_perm(x23h, x01h, 0x05040100u);
+    t[3] = __builtin_amdgcn_perm(x23h, x01h, 0x07060302u);
+}
+
+// One wave per chunk of edges.  VEC = bytes of the feature row per lane; HAS_EID: the weight of edge j of
+// this direction sits at position eid[j] (reversed graph) instead of j.
+template <int VEC, bool HAS_EID>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
 {
     using V = typename vec_bytes<VEC>::type;
+    __shared__ __align__(16) int stage[WAVES_PER_BLOCK][1024];  // one strip of F <= 1024 sums per wave
     const int lane = threadIdx.x % TANGO_WAVE;
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
-    const int64_t c0 = chunk * CHUNK;
+    const int64_t c0 = chunk << a.chunk_shift;
     if (c0 >= a.nnz) return;
-    const int64_t c1 = min(c0 + CHUNK, a.nnz);
+    const int64_t c1 = min(c0 + (int64_t(1) << a.chunk_shift), a.nnz);
 
     const int LPR = a.F / VEC;          // lanes per feature row
     const int G = 64 / LPR;             // neighbour rows gathered per wave-wide load (power of two)
@@ -180,7 +198,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
 
     int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
     int maxabs = 0;
-    constexpr int U = 4;  // independent gathers in flight per lane
+    constexpr int U = 8;  // independent row gathers in flight per lane
 
     for (; r < a.n; ++r) {
         const int rb = a.ptr[r], rt = a.ptr[r + 1];
@@ -190,38 +208,77 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
         int acc[VEC];
 #pragma unroll
         for (int j = 0; j < VEC; ++j) acc[j] = 0;
-        if (active) {
-            for (int e = sb + gi; e < se; e += G * U) {
-                int wv[U];
-                V xv[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int ee = e + u * G;
-                    const bool ok = ee < se;
-                    const int ec = ok ? ee : se - 1;
-                    const int nb = a.idx[ec];
-                    const int64_t wp = a.eid ? a.eid[ec] : ec;
-                    wv[u] = ok ? static_cast<int>(a.w[wp * a.heads + h]) : 0;
-                    xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    uint32_t w[VEC / 4];
-                    unpack_words<VEC>(xv[u], w);
-#pragma unroll
-                    for (int j = 0; j < VEC; ++j) acc[j] += wv[u] * sbyte(w[j / 4], j % 4);
+        // Blocks of 64 edges: lane l first fetches the neighbour index and the packed head weights of edge
+        // base+l (coalesced), then the groups pull (index, weight) pairs out of those registers with
+        // cross-lane reads, so that the row gathers of a block are issued back to back.
+        for (int base = sb; base < se; base += 64) {
+            const int cnt = min(64, se - base);
+            int my_nb = 0;
+            uint32_t my_w0 = 0, my_w1 = 0;
+            if (lane < cnt) {
+                const int e = base + lane;
+                my_nb = a.idx[e];
+                const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
+                for (int hh = 0; hh < a.heads; ++hh) {
+                    const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
+                    if (hh < 4)
+                        my_w0 |= b << (8 * hh);
+                    else
+                        my_w1 |= b << (8 * (hh - 4));
                 }
             }
+            const int steps = (cnt + G - 1) / G;
+            auto batch = [&](int s0, auto uu) {
+                constexpr int UU = decltype(uu)::value;
+                uint32_t wq[UU];
+                V xv[UU];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const int k = (s0 + u) * G + gi;
+                    const bool ok = active && k < cnt;
+                    const int kk = ok ? k : 0;
+                    const int nb = __shfl(my_nb, kk, 64);
+                    uint32_t ww = __shfl(static_cast<int>(my_w0), kk, 64);
+                    if (a.heads > 4) {
+                        const uint32_t w1 = __shfl(static_cast<int>(my_w1), kk, 64);
+                        if (h >= 4) ww = w1;
+                    }
+                    wq[u] = ok ? ((ww >> (8 * (h & 3))) & 0xffu) : 0u;
+                    xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                }
+                // 4 edges at a time: transpose each 4x4 byte block so that one dot4 multiplies one column of
+                // four neighbour rows by the four edge weights
+#pragma unroll
+                for (int u = 0; u < UU; u += 4) {
+                    const uint32_t wpack = wq[u] | (wq[u + 1] << 8) | (wq[u + 2] << 16) | (wq[u + 3] << 24);
+                    uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
+                    unpack_words<VEC>(xv[u], w0);
+                    unpack_words<VEC>(xv[u + 1], w1);
+                    unpack_words<VEC>(xv[u + 2], w2);
+                    unpack_words<VEC>(xv[u + 3], w3);
+#pragma unroll
+                    for (int q = 0; q < VEC / 4; ++q) {
+                        uint32_t t[4];
+                        transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                    }
+                }
+            };
+            int s0 = 0;
+            for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
+            for (; s0 < steps; s0 += 4) batch(s0, std::integral_constant<int, 4>{});
         }
         // combine the G groups: afterwards group 0 holds the sums of this row segment
         for (int off = G / 2; off >= 1; off >>= 1) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] += __shfl_down(acc[j], off * LPR, 64);
         }
-        if (gi == 0) {
-            float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
-            const bool whole = (rb >= c0) && (rt <= c1);
-            if (whole) {
+        const bool whole = (rb >= c0) && (rt <= c1);
+        if (whole) {
+            if (gi == 0) {
+                float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
 #pragma unroll
                 for (int j = 0; j < VEC; j += 4) {
                     float4 o;
@@ -232,10 +289,25 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
                     *reinterpret_cast<float4 *>(orow + j) = o;
                     maxabs = max(maxabs, max(max(abs(acc[j]), abs(acc[j + 1])), max(abs(acc[j + 2]), abs(acc[j + 3]))));
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) atomicAdd(reinterpret_cast<int *>(orow + j), acc[j]);
             }
+        } else {
+            // Row cut by a chunk boundary: int32 atomics.  The sums are first laid out by column in this
+            // wave's LDS strip so that consecutive lanes add to consecutive words (coalesced atomics).
+            int *strip = stage[threadIdx.x / TANGO_WAVE];
+            if (gi == 0) {
+#pragma unroll
+                for (int j = 0; j < VEC; j += 4)
+                    *reinterpret_cast<int4 *>(strip + col + j) = make_int4(acc[j], acc[j + 1], acc[j + 2], acc[j + 3]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            int *orow = reinterpret_cast<int *>(a.out + static_cast<int64_t>(r) * a.F);
+            for (int c = lane; c < a.F; c += 64) {
+                const int v = strip[c];
+                if (v != 0) atomicAdd(orow + c, v);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
     if (a.absmax) {
@@ -265,9 +337,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     using V = typename vec_bytes<VEC>::type;
     const int lane = threadIdx.x % TANGO_WAVE;
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
-    const int64_t c0 = chunk * CHUNK;
+    const int64_t c0 = chunk << CHUNK_SHIFT_DEFAULT;
     if (c0 >= a.nnz) return;
-    const int64_t c1 = min(c0 + CHUNK, a.nnz);
+    const int64_t c1 = min(c0 + (int64_t(1) << CHUNK_SHIFT_DEFAULT), a.nnz);
 
     const int LPR = a.F / VEC;
     const int G = 64 / LPR;
@@ -354,7 +426,7 @@ int validate_graph_dir(const tango_graph *g, int direction)
 
 int validate_feature_shape(int heads, int dim)
 {
-    TANGO_REQUIRE(heads >= 1 && dim >= 4 && dim % 4 == 0, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(heads >= 1 && heads <= 8 && dim >= 4 && dim % 4 == 0, TANGO_ERR_BAD_SHAPE);
     const int64_t F = static_cast<int64_t>(heads) * dim;
     TANGO_REQUIRE(F <= 1024, TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(pick_vec(static_cast<int>(F), dim, false) != 0, TANGO_ERR_UNSUPPORTED);
@@ -381,17 +453,25 @@ int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, co
     a.heads = heads;
     a.dim = dim;
     a.F = heads * dim;
+    // edges per wavefront: large chunks mean fewer rows cut by a boundary (fewer atomics); small graphs
+    // need small chunks to fill 256 CUs
+    a.chunk_shift = 6;
+    if ((a.nnz >> 10) >= 4096) a.chunk_shift = 10;
+    else if ((a.nnz >> 8) >= 4096) a.chunk_shift = 8;
     const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
     k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
     TANGO_LAUNCH_CHECK();
     if (a.nnz > 0) {
-        const int64_t chunks = (a.nnz + CHUNK - 1) / CHUNK;
+        const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
-        switch (pick_vec(a.F, dim, false)) {
-            case 4: k_spmm<4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            case 8: k_spmm<8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            default: k_spmm<16><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        }
+        const int vec = pick_vec(a.F, dim, false);
+#define TANGO_SPMM(V_)                                                           \
+    if (a.eid)                                                                   \
+        k_spmm<V_, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);            \
+    else                                                                         \
+        k_spmm<V_, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+        if (vec == 4) { TANGO_SPMM(4) } else if (vec == 8) { TANGO_SPMM(8) } else { TANGO_SPMM(16) }
+#undef TANGO_SPMM
         TANGO_LAUNCH_CHECK();
         k_spmm_finalize<<<row_blocks, 256, 0, st>>>(a);
         TANGO_LAUNCH_CHECK();
@@ -416,7 +496,7 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     a.heads = heads;
     a.dim = dim;
     a.F = heads * dim;
-    const int64_t chunks = (a.nnz + CHUNK - 1) / CHUNK;
+    const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (pick_vec(a.F, dim, true)) {
         case 4: k_sddmm_dot<4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
