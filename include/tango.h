@@ -251,6 +251,34 @@ int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q,
                     float *dX, float *absmax_dX, float *dW, void *stream);
 
 /* ------------------------------------------------------------------------ */
+/* Fused attention forward (allowed in addition to the primitives, never    */
+/* instead of them): Sec. 2.1 steps 3, 4 and 5 with the fusions of Sec. 3.3   */
+/* -- E and alpha are never written in fp32.                                  */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Equivalent to  E = tango_qsddmm(ADD_LEAKYRELU); alpha = tango_edge_softmax(E);
+ * alpha_q = tango_quantize(alpha); out = tango_qspmm(TANGO_IN, alpha_q, X_q)
+ * up to the summation order of the softmax denominator.  Outputs:
+ *   row_max, row_den (n x heads fp32): per (node, head) maximum activated score and
+ *       sum of exp(E - max) over its in-edges; the backward pass recomputes the
+ *       fp32 alpha from them;
+ *   alpha_q (nnz x heads int8), s_alpha: the quantized attention, cached for backward;
+ *   alpha_dump (nnz x heads fp32) or NULL: the exact fp32 alpha values that were
+ *       quantized (for verification: alpha_q must equal the quantization of this
+ *       tensor bit for bit);
+ *   out (n x F fp32), absmax_out (may be NULL).
+ * ws: at least tango_gat_attention_workspace_bytes() bytes.
+ */
+size_t tango_gat_attention_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads);
+int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8_t *S_q,
+                            const float *s_S, const int8_t *D_q, const float *s_D, float slope,
+                            const int8_t *X_q, const float *s_X, int rounding, uint64_t seed,
+                            uint64_t stream_id_alpha, float *row_max, float *row_den, int8_t *alpha_q,
+                            float *s_alpha, float *alpha_dump, float *out, float *absmax_out, void *ws,
+                            size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------ */
 /* Whole-layer entry points: the primitives above chained on one stream,     */
 /* with every quantized tensor produced once and reused (Sec. 3.3             */
 /* "Inter-primitive optimization": forward tensors cached for backward, one  */

@@ -286,6 +286,32 @@ def tango_qspmm_bwd(g, heads, dim, w_q, s_w, X_q, s_X, dOut_q, s_dOut, dX, absma
     )
 
 
+# ---------------------------------------------------------------- fused attention
+SIGNATURES.update({
+    "tango_gat_attention_workspace_bytes": (_sz, [_i64, _i64, _int]),
+    "tango_gat_attention_fwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64, _vp, _vp,
+                                       _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+})
+
+
+def tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads) -> int:
+    return load_library().tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads)
+
+
+def tango_gat_attention_fwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, rounding, seed, sid_alpha, row_max,
+                            row_den, alpha_q, s_alpha, alpha_dump, out, absmax_out, ws):
+    _check(
+        load_library().tango_gat_attention_fwd(
+            g.ref(), heads, dim, _ptr(S_q, torch.int8), _ptr(s_S, torch.float32), _ptr(D_q, torch.int8),
+            _ptr(s_D, torch.float32), slope, _ptr(X_q, torch.int8), _ptr(s_X, torch.float32), rounding, seed, sid_alpha,
+            _ptr(row_max, torch.float32), _ptr(row_den, torch.float32), _ptr(alpha_q, torch.int8),
+            _ptr(s_alpha, torch.float32), _ptr(alpha_dump, torch.float32), _ptr(out, torch.float32),
+            _ptr(absmax_out, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_gat_attention_fwd",
+    )
+
+
 # ------------------------------------------------------------------- whole layers
 class tango_gat_layer(ctypes.Structure):
     _fields_ = (

@@ -87,6 +87,22 @@ __device__ inline void unpack_words<16>(const uint4 &v, uint32_t (&w)[4])
 
 __device__ inline int sbyte(uint32_t w, int j) { return static_cast<int>(static_cast<int8_t>(w >> (8 * j))); }
 
+// Edge weights computed on the fly (fused attention forward, Sec. 2.1 steps 3-5): alpha of edge (u -> v), head h
+// is exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_max[v][h]) / row_den[v][h], quantized with the abs-max
+// found by the statistics pass.
+struct attn_params {
+    const int8_t *Sq, *Dq;
+    const float *sS, *sD;
+    float slope;
+    const float *row_max, *row_den;  // n x heads
+    const float *absmax_alpha;
+    tango_rng rng;
+    int rounding;
+    int8_t *alpha_q;     // out: nnz x heads
+    float *s_alpha;      // out
+    float *alpha_dump;   // out or NULL: the fp32 alpha that was quantized
+};
+
 struct spmm_args {
     int n;                 // rows
     int64_t nnz;           // edges
@@ -100,6 +116,7 @@ struct spmm_args {
     float *absmax;         // or NULL
     int heads, dim, F;
     int chunk_shift;       // log2 of the edges per wavefront
+    attn_params att;       // used by the ATT instantiations only
 };
 
 // True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
@@ -175,7 +192,7 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 
 // One wave per chunk of edges.  VEC = bytes of the feature row per lane; HAS_EID: the weight of edge j of
 // this direction sits at position eid[j] (reversed graph) instead of j.
-template <int VEC, bool HAS_EID>
+template <int VEC, bool HAS_EID, bool ATT>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
 {
     using V = typename vec_bytes<VEC>::type;
@@ -193,7 +210,16 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
     const bool active = gi < G;
     const int col = li * VEC;           // first of my VEC columns
     const int h = col / a.dim;          // their head
-    const float sc = (*a.s_w) * (*a.s_X);
+    float s_w, inv_w = 0.0f, att_sS = 0.0f, att_sD = 0.0f;
+    if (ATT) {
+        tango_scale_from_absmax(*a.att.absmax_alpha, s_w, inv_w);
+        if (blockIdx.x == 0 && threadIdx.x == 0) *a.att.s_alpha = s_w;
+        att_sS = *a.att.sS;
+        att_sD = *a.att.sD;
+    } else {
+        s_w = *a.s_w;
+    }
+    const float sc = s_w * (*a.s_X);
     const int8_t *Xcol = a.X + col;
 
     int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
@@ -218,13 +244,47 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
             if (lane < cnt) {
                 const int e = base + lane;
                 my_nb = a.idx[e];
-                const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
-                for (int hh = 0; hh < a.heads; ++hh) {
-                    const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
-                    if (hh < 4)
-                        my_w0 |= b << (8 * hh);
-                    else
-                        my_w1 |= b << (8 * (hh - 4));
+                if (ATT) {
+                    // steps 3-4 and the quantization of alpha for this edge, all heads
+                    const int H = a.heads;
+                    const int64_t i0 = static_cast<int64_t>(e) * H;
+                    uint4 blk = make_uint4(0, 0, 0, 0);
+                    uint64_t have = ~uint64_t(0);
+                    for (int hh = 0; hh < H; ++hh) {
+                        const float ts = att_sS * static_cast<float>(a.att.Sq[static_cast<int64_t>(my_nb) * H + hh]);
+                        const float td = att_sD * static_cast<float>(a.att.Dq[static_cast<int64_t>(r) * H + hh]);
+                        const float x = ts + td;
+                        const float ev = x > 0.0f ? x : a.att.slope * x;
+                        const float al = expf(ev - a.att.row_max[static_cast<int64_t>(r) * H + hh]) /
+                                         a.att.row_den[static_cast<int64_t>(r) * H + hh];
+                        if (a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
+                        int q;
+                        if (a.att.rounding == TANGO_SR) {
+                            const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
+                            if (bi != have) {
+                                blk = tango_philox_block(a.att.rng, bi);
+                                have = bi;
+                            }
+                            q = tango_round_clamp<TANGO_SR>(al * inv_w, tango_bits16(blk, static_cast<int>((i0 + hh) & 7)));
+                        } else {
+                            q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
+                        }
+                        a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
+                        const uint32_t b = static_cast<uint32_t>(q) & 0xffu;
+                        if (hh < 4)
+                            my_w0 |= b << (8 * hh);
+                        else
+                            my_w1 |= b << (8 * (hh - 4));
+                    }
+                } else {
+                    const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
+                    for (int hh = 0; hh < a.heads; ++hh) {
+                        const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
+                        if (hh < 4)
+                            my_w0 |= b << (8 * hh);
+                        else
+                            my_w1 |= b << (8 * (hh - 4));
+                    }
                 }
             }
             const int steps = (cnt + G - 1) / G;
@@ -435,10 +495,12 @@ int validate_feature_shape(int heads, int dim)
 
 }  // namespace
 
-int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
-                     const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
+static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
+                       const int8_t *X_q, const float *s_X, float *out, float *absmax_out, const attn_params *att,
+                       hipStream_t st)
 {
     spmm_args a;
+    if (att) a.att = *att;
     a.n = g->n_nodes;
     a.nnz = g->n_edges;
     a.ptr = direction == TANGO_IN ? g->in_ptr : g->out_ptr;
@@ -466,10 +528,12 @@ int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, co
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         const int vec = pick_vec(a.F, dim, false);
 #define TANGO_SPMM(V_)                                                           \
-    if (a.eid)                                                                   \
-        k_spmm<V_, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);            \
+    if (att)                                                                     \
+        k_spmm<V_, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);     \
+    else if (a.eid)                                                              \
+        k_spmm<V_, true, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);     \
     else                                                                         \
-        k_spmm<V_, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+        k_spmm<V_, false, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
         if (vec == 4) { TANGO_SPMM(4) } else if (vec == 8) { TANGO_SPMM(8) } else { TANGO_SPMM(16) }
 #undef TANGO_SPMM
         TANGO_LAUNCH_CHECK();
@@ -478,6 +542,29 @@ int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, co
     }
     return TANGO_OK;
 }
+
+int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
+                     const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
+{
+    return spmm_launch(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out, nullptr, st);
+}
+
+// SPMM over in-edges whose weights are the attention scores computed (and quantized, and stored) on the fly.
+int tango_spmm_attention_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
+                               const int8_t *Dq, const float *sD, float slope, const float *row_max,
+                               const float *row_den, const float *absmax_alpha, int rounding, uint64_t seed,
+                               uint64_t stream_id, int8_t *alpha_q, float *s_alpha, float *alpha_dump,
+                               const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
+{
+    attn_params att;
+    att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
+    att.row_max = row_max; att.row_den = row_den; att.absmax_alpha = absmax_alpha;
+    att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
+    att.alpha_q = alpha_q; att.s_alpha = s_alpha; att.alpha_dump = alpha_dump;
+    return spmm_launch(g, TANGO_IN, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
+}
+
+int tango_validate_spmm_shape(int heads, int dim) { return validate_feature_shape(heads, dim); }
 
 int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t *X_dst, const float *s_dst,
                           const int8_t *X_src, const float *s_src, float *out, hipStream_t st)

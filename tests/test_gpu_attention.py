@@ -1,0 +1,64 @@
+"""GPU parity of the fused attention forward against the oracle's step-by-step composition."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle as orc
+import tango_inputs as ti
+from gpu_util import assert_bit_exact, assert_close, dev, empty, host, scalar, workspace
+from test_gpu_graph_ops import graph, rand_i8
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+
+    import paper_2308_00890_amd as tango
+
+    assert torch.cuda.is_available()
+    tango.load_library()
+    return tango
+
+
+@pytest.mark.parametrize("gname,heads,dim", [("toy", 2, 32), ("rmat", 4, 64), ("rmat", 3, 128), ("sparse", 1, 64),
+                                             ("sparse", 8, 16), ("holes", 2, 32), ("one", 4, 64)])
+@pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
+def test_fused_attention_forward(T, gname, heads, dim, rounding):
+    import torch
+
+    g = graph(gname)
+    G = T.Graph.from_host(g)
+    F = heads * dim
+    Sq, Dq = rand_i8((g.n_nodes, heads), 8), rand_i8((g.n_nodes, heads), 9)
+    Xq = rand_i8((g.n_nodes, F), 10)
+    sS, sD, sX, slope = np.float32(0.021), np.float32(0.013), np.float32(0.017), 0.2
+    seed, sid = 4242, 38
+    row_max, row_den = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    alpha_q = empty((g.n_edges, heads), torch.int8)
+    dump = empty((g.n_edges, heads), torch.float32)
+    s_alpha, am = scalar(-1), scalar(-1)
+    out = empty((g.n_nodes, F), torch.float32)
+    ws = workspace(T.tango_gat_attention_workspace_bytes(g.n_nodes, g.n_edges, heads))
+    T.tango_gat_attention_fwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, dev(Xq), scalar(sX), rounding,
+                              seed, sid, row_max, row_den, alpha_q, s_alpha, dump, out, am, ws)
+    torch.cuda.synchronize()
+    E = orc.sddmm_add(g, Sq, sS, Dq, sD, slope)
+    alpha = orc.edge_softmax(g, E)
+    assert_close(host(dump), alpha, "alpha (fp32 dump)")
+    # the int8 attention is the quantization of exactly those fp32 values
+    q, s = orc.quantize(host(dump), rounding, seed, sid)
+    assert_bit_exact(host(alpha_q), q, "alpha_q")
+    if g.n_edges:
+        assert host(s_alpha)[0] == s
+    want, want_am = orc.spmm_in(g, host(alpha_q), host(s_alpha)[0], Xq, sX)
+    assert_bit_exact(host(out), want, "out")
+    assert host(am)[0] == want_am
+    # row statistics
+    nonempty = np.diff(g.in_ptr) > 0
+    starts = g.in_ptr[:-1][nonempty]
+    if g.n_edges:
+        m = np.maximum.reduceat(E, starts, axis=0)
+        assert_bit_exact(host(row_max)[nonempty], m, "row max")
+        den = np.add.reduceat(np.exp(E.astype(np.float64) - np.repeat(m, np.diff(g.in_ptr)[nonempty], axis=0)), starts, axis=0)
+        assert_close(host(row_den)[nonempty], den, "row denominator")
