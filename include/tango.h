@@ -278,6 +278,23 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
                             float *s_alpha, float *alpha_dump, float *out, float *absmax_out, void *ws,
                             size_t ws_bytes, void *stream);
 
+/*
+ * Backward of tango_gat_attention_fwd (Fig. 1b steps 5', 5'', 4', 3', 3'') from its caches:
+ *   dX_agg (n x F fp32)     = SPMM on the reversed graph of alpha_q and dOut_q (step 5'); absmax_dX may be NULL;
+ *   dalpha (nnz x heads)    = SDDMM-dot of dOut_q[dst] and X_q[src] (step 5''), fp32 scratch that is also an output;
+ *   dD, dS (n x heads fp32) = sums over in-/out-edges of alpha*(dalpha - P)*lrelu'(t) with the fp32 alpha
+ *                             recomputed from S_q, D_q, row_max, row_den exactly as the forward pass computed it
+ *                             (the gradient of the pre-activation scores is never written to memory).
+ * ws: at least tango_gat_attention_bwd_workspace_bytes() bytes.
+ */
+size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads);
+int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q,
+                            const float *s_S, const int8_t *D_q, const float *s_D, float slope,
+                            const float *row_max, const float *row_den, const int8_t *alpha_q,
+                            const float *s_alpha, const int8_t *X_q, const float *s_X,
+                            const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX,
+                            float *dalpha, float *dS, float *dD, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Whole-layer entry points: the primitives above chained on one stream,     */
 /* with every quantized tensor produced once and reused (Sec. 3.3             */
@@ -326,6 +343,12 @@ typedef struct tango_gat_layer {
     float *dW;                    /* k_in x F  (fp32 gradient for the full-precision weight update) */
     float *dH;                    /* n x k_in, or NULL to skip (first layer) */
     float *da_src, *da_dst;       /* heads x dim */
+    /* fused = 1: steps 3-5 and 5'-3'' run through tango_gat_attention_fwd / _bwd.  Then E is unused (may be
+     * NULL), alpha is optional (if not NULL it receives the fp32 attention that was quantized, for
+     * verification), dalpha keeps step 5'' (it is not overwritten), and row_max / row_den (n x heads) are
+     * required.  fused = 0: the primitives are chained one by one and row_max / row_den are unused. */
+    int fused;
+    float *row_max, *row_den;
     /* scratch */
     void *ws;
     size_t ws_bytes;              /* >= tango_gat_layer_workspace_bytes(...) */

@@ -312,6 +312,30 @@ def tango_gat_attention_fwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, 
     )
 
 
+SIGNATURES.update({
+    "tango_gat_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _int]),
+    "tango_gat_attention_bwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32] + [_vp] * 14 + [_sz, _vp]),
+})
+
+
+def tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads) -> int:
+    return load_library().tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads)
+
+
+def tango_gat_attention_bwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_max, row_den, alpha_q, s_alpha, X_q, s_X,
+                            dOut_q, s_dOut, dX_agg, absmax_dX, dalpha, dS, dD, ws):
+    f32, i8 = torch.float32, torch.int8
+    _check(
+        load_library().tango_gat_attention_bwd(
+            g.ref(), heads, dim, _ptr(S_q, i8), _ptr(s_S, f32), _ptr(D_q, i8), _ptr(s_D, f32), slope, _ptr(row_max, f32),
+            _ptr(row_den, f32), _ptr(alpha_q, i8), _ptr(s_alpha, f32), _ptr(X_q, i8), _ptr(s_X, f32), _ptr(dOut_q, i8),
+            _ptr(s_dOut, f32), _ptr(dX_agg, f32), _ptr(absmax_dX, f32), _ptr(dalpha, f32), _ptr(dS, f32), _ptr(dD, f32),
+            _ptr(ws), ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_gat_attention_bwd",
+    )
+
+
 # ------------------------------------------------------------------- whole layers
 class tango_gat_layer(ctypes.Structure):
     _fields_ = (
@@ -320,8 +344,8 @@ class tango_gat_layer(ctypes.Structure):
         + [(n, _vp) for n in (
             "H", "W", "a_src", "a_dst", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "S", "D",
             "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
-            "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst", "ws")]
-        + [("ws_bytes", _sz)]
+            "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst")]
+        + [("fused", _int), ("row_max", _vp), ("row_den", _vp), ("ws", _vp), ("ws_bytes", _sz)]
     )
 
 
@@ -384,7 +408,7 @@ class GatLayer(_LayerBuffers):
     _struct = tango_gat_layer
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
-                 want_dH=True, alias_E_alpha=True):
+                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -408,11 +432,18 @@ class GatLayer(_LayerBuffers):
             self._alloc(name, (n, heads), f32)
         self._alloc("S_q", (n, heads), i8)
         self._alloc("D_q", (n, heads), i8)
-        self._alloc("alpha", (nnz, heads), f32)
-        if alias_E_alpha:
-            self._bind("E", self.t["alpha"], f32)
+        c.fused = 1 if fused else 0
+        if fused:
+            self._alloc("row_max", (n, heads), f32)
+            self._alloc("row_den", (n, heads), f32)
+            if keep_alpha:
+                self._alloc("alpha", (nnz, heads), f32)
         else:
-            self._alloc("E", (nnz, heads), f32)
+            self._alloc("alpha", (nnz, heads), f32)
+            if alias_E_alpha:
+                self._bind("E", self.t["alpha"], f32)
+            else:
+                self._alloc("E", (nnz, heads), f32)
         self._alloc("alpha_q", (nnz, heads), i8)
         self._alloc("out", (n, F), f32)
         if grad_out is not None:

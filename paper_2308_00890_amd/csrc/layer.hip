@@ -30,7 +30,8 @@ size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t, int k_in, int h
     const size_t a = tango_qgemm_workspace_bytes(n_nodes, F, k_in);
     const size_t b = tango_qgemm_bwd_workspace_bytes(n_nodes, F, k_in);
     const size_t c = tango_head_proj_bwd_workspace_bytes(n_nodes, heads, dim);
-    return 256 + max3(a, b, c);
+    const size_t d = tango_gat_attention_bwd_workspace_bytes(n_nodes, 0, heads);
+    return 256 + max3(a, b, c > d ? c : d);
 }
 
 int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
@@ -38,9 +39,10 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
     TANGO_REQUIRE(L->k_in >= 1 && L->heads >= 1 && L->dim >= 1, TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(L->H && L->W && L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp && L->absmax_Hp &&
-                      L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->E && L->alpha &&
-                      L->alpha_q && L->s_alpha && L->out,
+                      L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->alpha_q && L->s_alpha &&
+                      L->out,
                   TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_den) : (L->E && L->alpha), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -64,6 +66,12 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                              L->S_q, L->s_S, nullptr, 0, stream));
     TANGO_TRY(tango_quantize(L->D, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_D, sc + SC_ABSMAX_D,
                              L->D_q, L->s_D, nullptr, 0, stream));
+    if (L->fused) {
+        // steps 3-5 fused: E and alpha never reach memory in fp32
+        return tango_gat_attention_fwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
+                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_max, L->row_den, L->alpha_q,
+                                       L->s_alpha, L->alpha, L->out, L->absmax_out, sub, sub_bytes, stream);
+    }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
                            stream));
@@ -84,8 +92,9 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                       L->s_dHp && L->dW && L->da_src && L->da_dst,
                   TANGO_ERR_NULL);
     TANGO_REQUIRE(L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp_q && L->s_Hp && L->S_q && L->s_S &&
-                      L->D_q && L->s_D && L->alpha && L->alpha_q && L->s_alpha,
+                      L->D_q && L->s_D && L->alpha_q && L->s_alpha,
                   TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_den) : (L->alpha != nullptr), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -98,6 +107,12 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     // the upstream gradient is quantized once and shared by steps 5' and 5''
     TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
                              L->s_g, sub, sub_bytes, stream));
+    if (L->fused) {
+        // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
+        TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_max,
+                                          L->row_den, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
+                                          nullptr, L->dalpha, L->dS, L->dD, sub, sub_bytes, stream));
+    } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
     TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
                               nullptr, L->dalpha, stream));
@@ -106,6 +121,7 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     // LeakyReLU' and 3', 3'': edge-to-node sums
     TANGO_TRY(tango_qsddmm_bwd(L->g, L->heads, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->dalpha, nullptr, L->dS, L->dD,
                                stream));
+    }
     // 2' fused with dH' = dH'_agg + dH'_att and its abs-max
     TANGO_TRY(tango_head_proj_bwd(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
                                   L->absmax_dHp, L->da_src, L->da_dst, sub, sub_bytes, stream));

@@ -388,10 +388,21 @@ struct sddmm_dot_args {
     const float *s_dst, *s_src;
     float *out;           // nnz x heads
     int heads, dim, F;
+    // ATT_BWD instantiations only (rows = source nodes, ptr/idx = out_ptr/out_dst): instead of storing the
+    // dot products, turn each into the gradient of the pre-activation score and sum it per (source, head)
+    const int8_t *Sq, *Dq;
+    const float *sS, *sD;
+    float slope;
+    const float *row_max, *row_den;  // of the destination
+    const double *P;                 // n x heads: sum over in-edges of dalpha*alpha, per destination
+    double *dS_acc;                  // n x heads, zero-initialised
 };
 
 // out[e][h] = (float)(Xdst[dst(e)][h][:] . Xsrc[src(e)][h][:]) * (s_dst*s_src); one wave per chunk of edges.
-template <int VEC>
+// ATT_BWD (step 3' fused with 5'', 4' and LeakyReLU', walking the out-edges of each source u): the dot product
+// of edge (u -> v) is dalpha, alpha is recomputed from S_q[u], D_q[v], row_max[v], row_den[v], and
+// dS_acc[u][h] += alpha*(dalpha - P[v][h]) * lrelu'(t).
+template <int VEC, bool ATT_BWD>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
 {
     using V = typename vec_bytes<VEC>::type;
@@ -423,14 +434,19 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
             const V dv = *reinterpret_cast<const V *>(a.Xdst + static_cast<int64_t>(r) * a.F + (active ? col : 0));
             unpack_words<VEC>(dv, dw);
         }
+        float ts_row = 0.0f;
+        double acc_s = 0.0;
+        if (ATT_BWD) ts_row = (*a.sS) * static_cast<float>(a.Sq[static_cast<int64_t>(r) * a.heads + (active ? h : 0)]);
         // every lane runs the same number of iterations (the shuffles below need all lanes)
         for (int e0 = sb; e0 < se; e0 += G * U) {
             int dot[U];
+            int nbs[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int ee = e0 + gi + u * G;
                 const int ec = (active && ee < se) ? ee : se - 1;
                 const int nb = a.idx[ec];
+                nbs[u] = nb;
                 const V xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
                 uint32_t w[VEC / 4];
                 unpack_words<VEC>(xv, w);
@@ -444,10 +460,34 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                 int d = dot[u];
                 for (int off = LPH / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
                 const int ee = e0 + gi + u * G;
-                if (active && ee < se && (li % LPH) == 0) a.out[static_cast<int64_t>(ee) * a.heads + h] = static_cast<float>(d) * sc;
+                if (active && ee < se && (li % LPH) == 0) {
+                    const float da = static_cast<float>(d) * sc;
+                    if (ATT_BWD) {
+                        const int64_t vh = static_cast<int64_t>(nbs[u]) * a.heads + h;
+                        const float td = (*a.sD) * static_cast<float>(a.Dq[vh]);
+                        const float x = ts_row + td;
+                        const float ev = x > 0.0f ? x : a.slope * x;
+                        const float al = expf(ev - a.row_max[vh]) / a.row_den[vh];
+                        const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - a.P[vh]));
+                        acc_s += static_cast<double>(dE * (x > 0.0f ? 1.0f : a.slope));
+                    } else {
+                        a.out[static_cast<int64_t>(ee) * a.heads + h] = da;
+                    }
+                }
             }
         }
+        if (ATT_BWD) {
+            for (int off = G / 2; off >= 1; off >>= 1) acc_s += __shfl_down(acc_s, off * LPR, 64);
+            if (gi == 0 && (li % LPH) == 0 && acc_s != 0.0) atomicAdd(a.dS_acc + static_cast<int64_t>(r) * a.heads + h, acc_s);
+        }
     }
+}
+
+__global__ __launch_bounds__(256) void k_f64_to_f32(const double *__restrict__ x, int64_t n, float *__restrict__ y)
+{
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+        y[i] = static_cast<float>(x[i]);
 }
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -586,10 +626,50 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (pick_vec(a.F, dim, true)) {
-        case 4: k_sddmm_dot<4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        case 8: k_sddmm_dot<8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        default: k_sddmm_dot<16><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 4: k_sddmm_dot<4, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 8: k_sddmm_dot<8, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default: k_sddmm_dot<16, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
     }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+// dS[u][h] = sum over out-edges (u -> v) of alpha*(dalpha - P[v][h])*lrelu'(t) with dalpha recomputed as the
+// quantized dot product of dOut_q[v] and X_q[u]; dS_acc: n x heads doubles of scratch.
+int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
+                             const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
+                             const float *sD, float slope, const float *row_max, const float *row_den, const double *P,
+                             double *dS_acc, float *dS, hipStream_t st)
+{
+    const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
+    if (rc != TANGO_OK) return rc;
+    if (g->n_edges > 0) {
+        sddmm_dot_args a;
+        a.n = g->n_nodes;
+        a.nnz = g->n_edges;
+        a.ptr = g->out_ptr;
+        a.idx = g->out_dst;
+        a.Xdst = X_q;     // resident row: the source node's features
+        a.Xsrc = dOut_q;  // gathered: the destination's upstream gradient
+        a.s_dst = s_dOut;
+        a.s_src = s_X;
+        a.out = nullptr;
+        a.heads = heads;
+        a.dim = dim;
+        a.F = heads * dim;
+        a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
+        a.row_max = row_max; a.row_den = row_den; a.P = P; a.dS_acc = dS_acc;
+        const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+        const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        switch (pick_vec(a.F, dim, true)) {
+            case 4: k_sddmm_dot<4, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            case 8: k_sddmm_dot<8, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default: k_sddmm_dot<16, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        }
+        TANGO_LAUNCH_CHECK();
+    }
+    k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }

@@ -24,7 +24,7 @@ def T():
 @pytest.mark.parametrize("gname,heads,dim", [("toy", 2, 32), ("rmat", 4, 64), ("rmat", 3, 128), ("sparse", 1, 64),
                                              ("sparse", 8, 16), ("holes", 2, 32), ("one", 4, 64)])
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
-def test_fused_attention_forward(T, gname, heads, dim, rounding):
+def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     import torch
 
     g = graph(gname)
@@ -62,3 +62,25 @@ def test_fused_attention_forward(T, gname, heads, dim, rounding):
         assert_bit_exact(host(row_max)[nonempty], m, "row max")
         den = np.add.reduceat(np.exp(E.astype(np.float64) - np.repeat(m, np.diff(g.in_ptr)[nonempty], axis=0)), starts, axis=0)
         assert_close(host(row_den)[nonempty], den, "row denominator")
+
+    # ---- backward from the caches of the fused forward
+    dOq = rand_i8((g.n_nodes, F), 11)
+    s_dO = np.float32(0.0041)
+    dX = empty((g.n_nodes, F), torch.float32)
+    dal = empty((g.n_edges, heads), torch.float32)
+    dS, dD = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    amx = scalar(-1)
+    wsb = workspace(T.tango_gat_attention_bwd_workspace_bytes(g.n_nodes, g.n_edges, heads))
+    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_max, row_den, alpha_q,
+                              s_alpha, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX, amx, dal, dS, dD, wsb)
+    torch.cuda.synchronize()
+    w_dX, w_am = orc.spmm_rev(g, host(alpha_q), host(s_alpha)[0], dOq, s_dO)
+    assert_bit_exact(host(dX), w_dX, "dX_agg")
+    assert host(amx)[0] == w_am
+    w_dal = orc.sddmm_dot(g, dOq, s_dO, Xq, sX, heads)
+    assert_bit_exact(host(dal), w_dal, "dalpha")
+    # the backward recomputes exactly the fp32 alpha the forward dumped
+    dE_sm = orc.edge_softmax_bwd(g, host(dump), w_dal)
+    _, w_dS, w_dD = orc.sddmm_add_bwd(g, Sq, sS, Dq, sD, slope, dE_sm)
+    assert_close(host(dD), w_dD, "dD")
+    assert_close(host(dS), w_dS, "dS")

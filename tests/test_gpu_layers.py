@@ -40,7 +40,8 @@ def gat_case(name):
 
 @pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
-def test_gat_layer_stagewise(T, case, rounding):
+@pytest.mark.parametrize("fused", [True, False])
+def test_gat_layer_stagewise(T, case, rounding, fused):
     import torch
 
     li, slope = gat_case(case)
@@ -50,7 +51,7 @@ def test_gat_layer_stagewise(T, case, rounding):
     b = 16 * layer_id
     G = T.Graph.from_host(g)
     L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
-                   layer_id, alias_E_alpha=False)
+                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True)
     T.tango_gat_layer_fwd(L)
     T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()
@@ -71,8 +72,10 @@ def test_gat_layer_stagewise(T, case, rounding):
         q, s = orc.quantize(o[src], rounding, seed, b + sid, am=am)
         assert_bit_exact(o[name], q, name)
         assert sc("s_" + name[:-2]) == s
-    assert_bit_exact(o["E"], orc.sddmm_add(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope), "E")
-    assert_close(o["alpha"], orc.edge_softmax(g, o["E"]), "alpha")
+    E = orc.sddmm_add(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope)
+    if not fused:
+        assert_bit_exact(o["E"], E, "E")
+    assert_close(o["alpha"], orc.edge_softmax(g, E), "alpha")
     q, s = orc.quantize(o["alpha"], rounding, seed, b + orc.SID_ALPHA)
     assert_bit_exact(o["alpha_q"], q, "alpha_q")
     assert sc("s_alpha") == s
@@ -86,8 +89,13 @@ def test_gat_layer_stagewise(T, case, rounding):
     assert sc("s_g") == s
     agg, _ = orc.spmm_rev(g, o["alpha_q"], sc("s_alpha"), o["g_q"], sc("s_g"))
     dalpha = orc.sddmm_dot(g, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads)
-    assert_close(o["dalpha"], orc.edge_softmax_bwd(g, o["alpha"], dalpha), "dE (softmax backward)")
-    _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, o["dalpha"])
+    dE_sm = orc.edge_softmax_bwd(g, o["alpha"], dalpha)
+    if fused:  # dalpha is kept, dE is never written
+        assert_bit_exact(o["dalpha"], dalpha, "dalpha")
+        _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, dE_sm)
+    else:  # dalpha was overwritten by dE
+        assert_close(o["dalpha"], dE_sm, "dE (softmax backward)")
+        _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, o["dalpha"])
     assert_close(o["dS"], dS, "dS")
     assert_close(o["dD"], dD, "dD")
     dHp, am, da_s, da_d = orc.head_proj_bwd(o["dS"], o["dD"], li.a_src, li.a_dst, o["Hp_q"], sc("s_Hp"), agg)
