@@ -11,11 +11,12 @@
 // HBM bytes per edge: pass 1 reads 4 (index); pass 2 reads 4 and writes
 // `heads`; the feature-row gathers are as in the plain SPMM.
 #include "internal.hip.h"
+#include "attn_math.hip.h"
 #include "rowwalk.hip.h"
 
 int tango_spmm_attention_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
                                const int8_t *Dq, const float *sD, float slope, const float *row_max,
-                               const float *row_den, const float *absmax_alpha, int rounding, uint64_t seed,
+                               const float *row_rden, const float *absmax_alpha, int rounding, uint64_t seed,
                                uint64_t stream_id, int8_t *alpha_q, float *s_alpha, float *alpha_dump,
                                const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
@@ -26,8 +27,8 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
                           const int8_t *X_src, const float *s_src, float *out, hipStream_t st);
 int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                              const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const float *row_max, const float *row_den, const double *P,
-                             double *dS_acc, float *dS, hipStream_t st);
+                             const float *sD, float slope, const tango_attn_rec *rec, double *dS_acc, float *dS,
+                             hipStream_t st);
 
 namespace {
 
@@ -37,53 +38,48 @@ struct attn_stats_op {
     const int32_t *src;
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
-    float *row_max, *row_den;
+    float *row_max, *row_rden;
     float amax;
-    template <int GS>
-    __device__ void run(int row, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int row, int b, int t, Team tm)
     {
         float td[H], m[H], s[H];
+        int dq[H];
+        tango_load_heads<H>(Dq, row, dq);
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            td[h] = sD * static_cast<float>(Dq[static_cast<int64_t>(row) * H + h]);
+            td[h] = sD * static_cast<float>(dq[h]);
             m[h] = -INFINITY;
             s[h] = 0.0f;
         }
-        for (int e = b + lg; e < t; e += GS) {
-            const int64_t u = src[e];
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
+            int sq[H];
+            tango_load_heads<H>(Sq, src[e], sq);
 #pragma unroll
             for (int h = 0; h < H; ++h) {
-                const float ts = sS * static_cast<float>(Sq[u * H + h]);
-                const float x = ts + td[h];
-                const float ev = x > 0.0f ? x : slope * x;
+                bool pos;
+                const float ev = tango_attn_score(sS * static_cast<float>(sq[h]), td[h], slope, pos);
                 if (ev > m[h]) {
-                    s[h] = s[h] * expf(m[h] - ev) + 1.0f;
+                    s[h] = s[h] * tango_attn_exp(m[h] - ev) + 1.0f;
                     m[h] = ev;
                 } else {
-                    s[h] += expf(ev - m[h]);
+                    s[h] += tango_attn_exp(ev - m[h]);
                 }
             }
         }
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-#pragma unroll
-            for (int o = GS / 2; o > 0; o >>= 1) {
-                const float m2 = __shfl_xor(m[h], o, 64), s2 = __shfl_xor(s[h], o, 64);
-                const float M = fmaxf(m[h], m2);
-                const float f1 = (m[h] == M) ? 1.0f : expf(m[h] - M);
-                const float f2 = (m2 == M) ? 1.0f : expf(m2 - M);
-                s[h] = s[h] * f1 + s2 * f2;
-                m[h] = M;
-            }
+            tm.merge_ms(m[h], s[h]);
             if (t > b) {
-                if (lg == 0) {
+                const float rden = 1.0f / s[h];
+                if (tm.rank == 0) {
                     row_max[static_cast<int64_t>(row) * H + h] = m[h];
-                    row_den[static_cast<int64_t>(row) * H + h] = s[h];
+                    row_rden[static_cast<int64_t>(row) * H + h] = rden;
                 }
-                amax = fmaxf(amax, 1.0f / s[h]);
-            } else if (lg == 0) {
+                amax = fmaxf(amax, rden);  // the largest alpha of the row is exp(0)*rden
+            } else if (tm.rank == 0) {
                 row_max[static_cast<int64_t>(row) * H + h] = 0.0f;
-                row_den[static_cast<int64_t>(row) * H + h] = 1.0f;
+                row_rden[static_cast<int64_t>(row) * H + h] = 1.0f;
             }
         }
     }
@@ -91,12 +87,26 @@ struct attn_stats_op {
 
 template <int H, int GROUP>
 __global__ __launch_bounds__(256) void k_attn_stats(int n, const int32_t *ptr, attn_stats_op<H> op, const float *sS,
-                                                    const float *sD, float *absmax_alpha)
+                                                    const float *sD, float *absmax_alpha, int *huge)
 {
     op.sS = *sS;
     op.sD = *sD;
     op.amax = 0.0f;
-    walk_rows<GROUP>(ptr, n, op);
+    walk_rows<GROUP>(ptr, n, op, huge);
+    const float m = tango_wave_max(op.amax);
+    if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
+}
+
+template <int H>
+__global__ __launch_bounds__(TEAM_BLOCK_THREADS) void k_attn_stats_huge(const int32_t *ptr, attn_stats_op<H> op,
+                                                                        const float *sS, const float *sD,
+                                                                        float *absmax_alpha, const int *huge)
+{
+    __shared__ double scratch[2 * TEAM_BLOCK_THREADS / 64];
+    op.sS = *sS;
+    op.sD = *sD;
+    op.amax = 0.0f;
+    walk_huge_rows(ptr, huge, op, scratch);
     const float m = tango_wave_max(op.amax);
     if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
 }
@@ -108,56 +118,62 @@ struct attn_bwd_dst_op {
     const int32_t *src;
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
-    const float *row_max, *row_den, *dalpha;
-    double *P;
+    const float *row_max, *row_rden, *dalpha;
+    tango_attn_rec *rec;
     float *dD;
-    template <int GS>
-    __device__ void run(int row, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int row, int b, int t, Team tm)
     {
-        float td[H], m[H], den[H];
+        float td[H], m[H], rden[H];
         double p[H], acc[H];
+        int dq[H];
+        tango_load_heads<H>(Dq, row, dq);
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            td[h] = sD * static_cast<float>(Dq[static_cast<int64_t>(row) * H + h]);
+            td[h] = sD * static_cast<float>(dq[h]);
             m[h] = row_max[static_cast<int64_t>(row) * H + h];
-            den[h] = row_den[static_cast<int64_t>(row) * H + h];
+            rden[h] = row_rden[static_cast<int64_t>(row) * H + h];
             p[h] = 0.0;
             acc[h] = 0.0;
         }
-        for (int e = b + lg; e < t; e += GS) {
-            const int64_t u = src[e];
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
+            int sq[H];
+            tango_load_heads<H>(Sq, src[e], sq);
             float d[H];
             load_h<H>(dalpha + static_cast<int64_t>(e) * H, d);
 #pragma unroll
             for (int h = 0; h < H; ++h) {
-                const float ts = sS * static_cast<float>(Sq[u * H + h]);
-                const float x = ts + td[h];
-                const float ev = x > 0.0f ? x : slope * x;
-                const float al = expf(ev - m[h]) / den[h];
+                bool pos;
+                const float ev = tango_attn_score(sS * static_cast<float>(sq[h]), td[h], slope, pos);
+                const float al = tango_attn_alpha(ev, m[h], rden[h]);
                 p[h] += static_cast<double>(d[h]) * static_cast<double>(al);
             }
         }
 #pragma unroll
-        for (int h = 0; h < H; ++h) p[h] = group_sum<GS>(p[h]);
-        for (int e = b + lg; e < t; e += GS) {
-            const int64_t u = src[e];
+        for (int h = 0; h < H; ++h) p[h] = tm.sum(p[h]);
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
+            int sq[H];
+            tango_load_heads<H>(Sq, src[e], sq);
             float d[H];
             load_h<H>(dalpha + static_cast<int64_t>(e) * H, d);
 #pragma unroll
             for (int h = 0; h < H; ++h) {
-                const float ts = sS * static_cast<float>(Sq[u * H + h]);
-                const float x = ts + td[h];
-                const float ev = x > 0.0f ? x : slope * x;
-                const float al = expf(ev - m[h]) / den[h];
+                bool pos;
+                const float ev = tango_attn_score(sS * static_cast<float>(sq[h]), td[h], slope, pos);
+                const float al = tango_attn_alpha(ev, m[h], rden[h]);
                 const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(d[h]) - p[h]));
-                acc[h] += static_cast<double>(dE * (x > 0.0f ? 1.0f : slope));
+                acc[h] += static_cast<double>(dE * (pos ? 1.0f : slope));
             }
         }
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            const double sacc = group_sum<GS>(acc[h]);
-            if (lg == 0) {
-                P[static_cast<int64_t>(row) * H + h] = p[h];
+            const double sacc = tm.sum(acc[h]);
+            if (tm.rank == 0) {
+                tango_attn_rec rc;
+                rc.P = p[h];
+                rc.row_max = m[h];
+                rc.row_rden = rden[h];
+                rec[static_cast<int64_t>(row) * H + h] = rc;
                 dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(sacc);
             }
         }
@@ -166,26 +182,40 @@ struct attn_bwd_dst_op {
 
 template <int H, int GROUP>
 __global__ __launch_bounds__(256) void k_attn_bwd_dst(int n, const int32_t *ptr, attn_bwd_dst_op<H> op, const float *sS,
-                                                      const float *sD)
+                                                      const float *sD, int *huge)
 {
     op.sS = *sS;
     op.sD = *sD;
-    walk_rows<GROUP>(ptr, n, op);
+    walk_rows<GROUP>(ptr, n, op, huge);
+}
+
+template <int H>
+__global__ __launch_bounds__(TEAM_BLOCK_THREADS) void k_attn_bwd_dst_huge(const int32_t *ptr, attn_bwd_dst_op<H> op,
+                                                                          const float *sS, const float *sD,
+                                                                          const int *huge)
+{
+    __shared__ double scratch[2 * TEAM_BLOCK_THREADS / 64];
+    op.sS = *sS;
+    op.sD = *sD;
+    walk_huge_rows(ptr, huge, op, scratch);
 }
 
 }  // namespace
 
 int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const float *row_max, const float *row_den,
-                             const float *dalpha, double *P, float *dD, hipStream_t st)
+                             const float *sD, float slope, const float *row_max, const float *row_rden,
+                             const float *dalpha, tango_attn_rec *rec, float *dD, int *huge, hipStream_t st)
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
     const unsigned grid = row_grid(n);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st);
+    if (rc != TANGO_OK) return rc;
 #define CALL(HH)                                                                                            \
     {                                                                                                       \
-        attn_bwd_dst_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_den, dalpha, P, dD};        \
-        k_attn_bwd_dst<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD);                          \
+        attn_bwd_dst_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_rden, dalpha, rec, dD};        \
+        k_attn_bwd_dst<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, huge);                    \
+        k_attn_bwd_dst_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, huge);      \
     }
     TANGO_DISPATCH_H(heads, grp, CALL)
 #undef CALL
@@ -194,18 +224,20 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
 }
 
 int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                           const float *sD, float slope, float *row_max, float *row_den, float *absmax_alpha,
-                           hipStream_t st)
+                           const float *sD, float slope, float *row_max, float *row_rden, float *absmax_alpha,
+                           int *huge, hipStream_t st)
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
     const unsigned grid = row_grid(n);
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
-#define CALL(HH)                                                                                   \
-    {                                                                                              \
-        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_den, 0.f};           \
-        k_attn_stats<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha);     \
+    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st)) != TANGO_OK) return rc;
+#define CALL(HH)                                                                                             \
+    {                                                                                                        \
+        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_rden, 0.f};                    \
+        k_attn_stats<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge);         \
+        k_attn_stats_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, absmax_alpha, huge); \
     }
     TANGO_DISPATCH_H(heads, grp, CALL)
 #undef CALL
@@ -215,11 +247,11 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
 
 extern "C" {
 
-size_t tango_gat_attention_workspace_bytes(int64_t, int64_t, int) { return 256; }
+size_t tango_gat_attention_workspace_bytes(int64_t, int64_t n_edges, int) { return 256 + huge_list_bytes(n_edges); }
 
 int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                             const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
-                            int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_max, float *row_den,
+                            int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_max, float *row_rden,
                             int8_t *alpha_q, float *s_alpha, float *alpha_dump, float *out, float *absmax_out, void *ws,
                             size_t ws_bytes, void *stream)
 {
@@ -230,31 +262,35 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
     TANGO_REQUIRE(heads_supported(heads), TANGO_ERR_UNSUPPORTED);
     int rc = tango_validate_spmm_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(S_q && s_S && D_q && s_D && X_q && s_X && row_max && row_den && s_alpha && out &&
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && X_q && s_X && row_max && row_rden && s_alpha && out &&
                       (g->n_edges == 0 || alpha_q),
                   TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
-    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= 256, TANGO_ERR_WORKSPACE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
+                      ws_bytes >= tango_gat_attention_workspace_bytes(g->n_nodes, g->n_edges, heads),
+                  TANGO_ERR_WORKSPACE);
+    TANGO_REQUIRE(tango_aligned(S_q, heads == 3 ? 1 : heads) && tango_aligned(D_q, heads == 3 ? 1 : heads), TANGO_ERR_BAD_SHAPE);
     hipStream_t st = tango_stream(stream);
     float *absmax_alpha = static_cast<float *>(ws);
+    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256);
     if (g->n_edges == 0) {  // no edge: the scale of an empty tensor is 1
         rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(s_alpha), 0x3f800000u, 1, st);
         if (rc != TANGO_OK) return rc;
     }
-    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_den, absmax_alpha, st);
+    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_rden, absmax_alpha, huge, st);
     if (rc != TANGO_OK) return rc;
-    return tango_spmm_attention_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_max, row_den, absmax_alpha, rounding,
+    return tango_spmm_attention_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_max, row_rden, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, st);
 }
 
-size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t, int heads)
+size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads)
 {
-    // P and the dS accumulator: n x heads doubles each
-    return 256 + 2 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256);
+    // per (node, head): a 16-byte record (P, row_max, row_rden) and a double dS accumulator; then the list of hub rows
+    return 256 + 3 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
 }
 
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
-                            const int8_t *D_q, const float *s_D, float slope, const float *row_max, const float *row_den,
+                            const int8_t *D_q, const float *s_D, float slope, const float *row_max, const float *row_rden,
                             const int8_t *alpha_q, const float *s_alpha, const int8_t *X_q, const float *s_X,
                             const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
                             float *dS, float *dD, void *ws, size_t ws_bytes, void *stream)
@@ -265,7 +301,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     TANGO_REQUIRE(heads_supported(heads), TANGO_ERR_UNSUPPORTED);
     int rc = tango_validate_sddmm_dot_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_max && row_den && s_alpha && X_q && s_X && dOut_q && s_dOut && dX_agg &&
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_max && row_rden && s_alpha && X_q && s_X && dOut_q && s_dOut && dX_agg &&
                       dS && dD && (g->n_edges == 0 || (alpha_q && dalpha)),
                   TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) &&
@@ -276,8 +312,9 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                   TANGO_ERR_WORKSPACE);
     hipStream_t st = tango_stream(stream);
     const size_t nh_bytes = tango_round_up(static_cast<size_t>(g->n_nodes) * heads * sizeof(double), 256);
-    double *P = reinterpret_cast<double *>(static_cast<char *>(ws) + 256);
-    double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + nh_bytes);
+    tango_attn_rec *rec = reinterpret_cast<tango_attn_rec *>(static_cast<char *>(ws) + 256);
+    double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 2 * nh_bytes);
+    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
     // 5': SPMM on the reversed graph with the cached int8 attention
     rc = tango_spmm_async(g, TANGO_OUT, heads, dim, alpha_q, s_alpha, dOut_q, s_dOut, dX_agg, absmax_dX, st);
     if (rc != TANGO_OK) return rc;
@@ -285,10 +322,9 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);
     if (rc != TANGO_OK) return rc;
     // 4' and 3'' over in-edges, then 3' over out-edges
-    rc = tango_attn_bwd_dst_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_den, dalpha, P, dD, st);
+    rc = tango_attn_bwd_dst_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_rden, dalpha, rec, dD, huge, st);
     if (rc != TANGO_OK) return rc;
-    return tango_attn_bwd_src_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_max, row_den, P,
-                                    dS_acc, dS, st);
+    return tango_attn_bwd_src_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, rec, dS_acc, dS, st);
 }
 
 }  // extern "C"

@@ -1,0 +1,72 @@
+// The attention arithmetic shared by every kernel of the fused path, so that the forward pass, the
+// statistics pass and both backward passes form bit-identical fp32 values (Sec. 2.1 steps 3 and 4):
+//   t     = s_S*S_q[u][h] + s_D*D_q[v][h]          (two fp32 products, one fp32 sum)
+//   E     = t > 0 ? t : slope*t                    (LeakyReLU)
+//   alpha = exp(E - row_max) * row_rden            (row_rden = 1 / sum exp(E - row_max), one division per row)
+// exp is the hardware exponential (v_exp_f32 on x*log2(e)); its relative error, about 1e-7*(1+|x|), is far
+// inside the fp32 tolerance of the softmax.
+#pragma once
+
+#include "internal.hip.h"
+
+__device__ static inline float tango_attn_exp(float x) { return __expf(x); }
+
+__device__ static inline float tango_attn_score(float ts, float td, float slope, bool &positive)
+{
+    const float x = ts + td;
+    positive = x > 0.0f;
+    return positive ? x : slope * x;
+}
+
+__device__ static inline float tango_attn_alpha(float ev, float row_max, float row_rden)
+{
+    return tango_attn_exp(ev - row_max) * row_rden;
+}
+
+// The `heads` int8 values of one node (heads <= 8) as sign-extended ints; one vector load when heads is 2, 4 or 8
+// (the table must then be aligned to `heads` bytes).
+template <int H>
+__device__ static inline void tango_load_heads(const int8_t *__restrict__ table, int64_t node, int (&v)[H])
+{
+    const int8_t *p = table + node * H;
+    if constexpr (H == 4) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) v[h] = static_cast<int>(static_cast<int8_t>(w >> (8 * h)));
+    } else if constexpr (H == 2) {
+        const uint16_t w = *reinterpret_cast<const uint16_t *>(p);
+        v[0] = static_cast<int>(static_cast<int8_t>(w & 0xff));
+        v[1] = static_cast<int>(static_cast<int8_t>(w >> 8));
+    } else if constexpr (H == 8) {
+        const uint2 w = *reinterpret_cast<const uint2 *>(p);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            v[h] = static_cast<int>(static_cast<int8_t>(w.x >> (8 * h)));
+            v[4 + h] = static_cast<int>(static_cast<int8_t>(w.y >> (8 * h)));
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < H; ++h) v[h] = static_cast<int>(p[h]);
+    }
+}
+
+// Same with a run-time head count (heads <= 8).
+__device__ static inline void tango_load_heads_rt(const int8_t *__restrict__ table, int64_t node, int heads, int (&v)[8])
+{
+    const int8_t *p = table + node * heads;
+    if (heads == 4) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) v[h] = static_cast<int>(static_cast<int8_t>(w >> (8 * h)));
+    } else {
+        for (int h = 0; h < heads; ++h) v[h] = static_cast<int>(p[h]);
+    }
+}
+
+// Per (destination, head) record gathered by the source-side backward pass: one 16-byte load instead of three
+// scattered ones, and the records of all heads of a node share a cache line.
+struct __attribute__((aligned(16))) tango_attn_rec {
+    double P;        // sum over the in-edges of dalpha*alpha
+    float row_max;
+    float row_rden;
+};

@@ -20,13 +20,13 @@ struct sddmm_add_op {
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
     float *E;
-    template <int GS>
-    __device__ void run(int row, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int row, int b, int t, Team tm)
     {
         float td[H];
 #pragma unroll
         for (int h = 0; h < H; ++h) td[h] = sD * static_cast<float>(Dq[static_cast<int64_t>(row) * H + h]);
-        for (int e = b + lg; e < t; e += GS) {
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             const int64_t u = src[e];
             float v[H];
 #pragma unroll
@@ -57,8 +57,8 @@ struct sddmm_add_bwd_dst_op {
     float sS, sD, slope;
     const float *dE;
     float *dEpre, *dD;
-    template <int GS>
-    __device__ void run(int row, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int row, int b, int t, Team tm)
     {
         float td[H];
         double acc[H];
@@ -67,7 +67,7 @@ struct sddmm_add_bwd_dst_op {
             td[h] = sD * static_cast<float>(Dq[static_cast<int64_t>(row) * H + h]);
             acc[h] = 0.0;
         }
-        for (int e = b + lg; e < t; e += GS) {
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             const int64_t u = src[e];
             float g[H];
             load_h<H>(dE + static_cast<int64_t>(e) * H, g);
@@ -82,8 +82,8 @@ struct sddmm_add_bwd_dst_op {
         }
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            const double s = group_sum<GS>(acc[h]);
-            if (lg == 0) dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(s);
+            const double s = tm.sum(acc[h]);
+            if (tm.rank == 0) dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(s);
         }
     }
 };
@@ -105,8 +105,8 @@ struct sddmm_add_bwd_src_op {
     float sS, sD, slope;
     const float *dE;
     float *dS;
-    template <int GS>
-    __device__ void run(int row, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int row, int b, int t, Team tm)
     {
         float ts[H];
         double acc[H];
@@ -115,7 +115,7 @@ struct sddmm_add_bwd_src_op {
             ts[h] = sS * static_cast<float>(Sq[static_cast<int64_t>(row) * H + h]);
             acc[h] = 0.0;
         }
-        for (int j = b + lg; j < t; j += GS) {
+        for (int j = b + tm.rank; j < t; j += tm.size()) {
             const int64_t v = dst[j];
             const int64_t e = eid[j];
             float g[H];
@@ -129,8 +129,8 @@ struct sddmm_add_bwd_src_op {
         }
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            const double s = group_sum<GS>(acc[h]);
-            if (lg == 0) dS[static_cast<int64_t>(row) * H + h] = static_cast<float>(s);
+            const double s = tm.sum(acc[h]);
+            if (tm.rank == 0) dS[static_cast<int64_t>(row) * H + h] = static_cast<float>(s);
         }
     }
 };
@@ -150,8 +150,8 @@ struct softmax_op {
     const float *E;
     float *alpha;
     float amax;
-    template <int GS>
-    __device__ void run(int /*row*/, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int /*row*/, int b, int t, Team tm)
     {
         float m[H], s[H];
 #pragma unroll
@@ -159,23 +159,23 @@ struct softmax_op {
             m[h] = -INFINITY;
             s[h] = 0.0f;
         }
-        for (int e = b + lg; e < t; e += GS) {
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             float v[H];
             load_h<H>(E + static_cast<int64_t>(e) * H, v);
 #pragma unroll
             for (int h = 0; h < H; ++h) m[h] = fmaxf(m[h], v[h]);
         }
 #pragma unroll
-        for (int h = 0; h < H; ++h) m[h] = group_max<GS>(m[h]);
-        for (int e = b + lg; e < t; e += GS) {
+        for (int h = 0; h < H; ++h) m[h] = tm.max(m[h]);
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             float v[H];
             load_h<H>(E + static_cast<int64_t>(e) * H, v);
 #pragma unroll
             for (int h = 0; h < H; ++h) s[h] += expf(v[h] - m[h]);
         }
 #pragma unroll
-        for (int h = 0; h < H; ++h) s[h] = group_sum<GS>(s[h]);
-        for (int e = b + lg; e < t; e += GS) {
+        for (int h = 0; h < H; ++h) s[h] = tm.sum(s[h]);
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             float v[H];
             load_h<H>(E + static_cast<int64_t>(e) * H, v);
 #pragma unroll
@@ -203,13 +203,13 @@ template <int H>
 struct softmax_bwd_op {
     const float *alpha, *dalpha;
     float *dE;
-    template <int GS>
-    __device__ void run(int /*row*/, int b, int t, int lg)
+    template <class Team>
+    __device__ void run(int /*row*/, int b, int t, Team tm)
     {
         double P[H];
 #pragma unroll
         for (int h = 0; h < H; ++h) P[h] = 0.0;
-        for (int e = b + lg; e < t; e += GS) {
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             float a[H], d[H];
             load_h<H>(alpha + static_cast<int64_t>(e) * H, a);
             load_h<H>(dalpha + static_cast<int64_t>(e) * H, d);
@@ -217,8 +217,8 @@ struct softmax_bwd_op {
             for (int h = 0; h < H; ++h) P[h] += static_cast<double>(d[h]) * static_cast<double>(a[h]);
         }
 #pragma unroll
-        for (int h = 0; h < H; ++h) P[h] = group_sum<GS>(P[h]);
-        for (int e = b + lg; e < t; e += GS) {
+        for (int h = 0; h < H; ++h) P[h] = tm.sum(P[h]);
+        for (int e = b + tm.rank; e < t; e += tm.size()) {
             float a[H], d[H], o[H];
             load_h<H>(alpha + static_cast<int64_t>(e) * H, a);
             load_h<H>(dalpha + static_cast<int64_t>(e) * H, d);

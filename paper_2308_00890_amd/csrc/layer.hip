@@ -24,14 +24,15 @@ size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b 
 
 extern "C" {
 
-size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t, int k_in, int heads, int dim)
+size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim)
 {
     const int64_t F = static_cast<int64_t>(heads) * dim;
     const size_t a = tango_qgemm_workspace_bytes(n_nodes, F, k_in);
     const size_t b = tango_qgemm_bwd_workspace_bytes(n_nodes, F, k_in);
     const size_t c = tango_head_proj_bwd_workspace_bytes(n_nodes, heads, dim);
-    const size_t d = tango_gat_attention_bwd_workspace_bytes(n_nodes, 0, heads);
-    return 256 + max3(a, b, c > d ? c : d);
+    const size_t d = tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads);
+    const size_t e = tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads);
+    return 256 + max3(a, b, max3(c, d, e));
 }
 
 int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
@@ -42,7 +43,7 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                       L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->alpha_q && L->s_alpha &&
                       L->out,
                   TANGO_ERR_NULL);
-    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_den) : (L->E && L->alpha), TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_rden) : (L->E && L->alpha), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -69,7 +70,7 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     if (L->fused) {
         // steps 3-5 fused: E and alpha never reach memory in fp32
         return tango_gat_attention_fwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
-                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_max, L->row_den, L->alpha_q,
+                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_max, L->row_rden, L->alpha_q,
                                        L->s_alpha, L->alpha, L->out, L->absmax_out, sub, sub_bytes, stream);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
@@ -94,7 +95,7 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     TANGO_REQUIRE(L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp_q && L->s_Hp && L->S_q && L->s_S &&
                       L->D_q && L->s_D && L->alpha_q && L->s_alpha,
                   TANGO_ERR_NULL);
-    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_den) : (L->alpha != nullptr), TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_rden) : (L->alpha != nullptr), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -110,7 +111,7 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     if (L->fused) {
         // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
         TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_max,
-                                          L->row_den, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
+                                          L->row_rden, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
                                           nullptr, L->dalpha, L->dS, L->dD, sub, sub_bytes, stream));
     } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)

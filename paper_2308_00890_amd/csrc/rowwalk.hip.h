@@ -35,31 +35,113 @@ __device__ inline void store_h(float *p, const float (&v)[H])
     }
 }
 
+// A team = the lanes (or threads) that share one row.  lane_team<GS>: GS consecutive lanes of a wave,
+// reductions by cross-lane shuffles.  block_team: every thread of the workgroup, reductions through LDS
+// (deterministic: partial results are combined in wave order).
 template <int GS>
-__device__ inline float group_max(float v)
-{
+struct lane_team {
+    int rank;
+    __device__ int size() const { return GS; }
+    __device__ float max(float v) const
+    {
 #pragma unroll
-    for (int o = GS / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-template <int GS>
-__device__ inline float group_sum(float v)
-{
+        for (int o = GS / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+        return v;
+    }
+    __device__ float sum(float v) const
+    {
 #pragma unroll
-    for (int o = GS / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-template <int GS>
-__device__ inline double group_sum(double v)
-{
+        for (int o = GS / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        return v;
+    }
+    __device__ double sum(double v) const
+    {
 #pragma unroll
-    for (int o = GS / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
+        for (int o = GS / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        return v;
+    }
+    // combine online-softmax states (maximum m, sum s of exp(x - m))
+    __device__ void merge_ms(float &m, float &s) const
+    {
+#pragma unroll
+        for (int o = GS / 2; o > 0; o >>= 1) {
+            const float m2 = __shfl_xor(m, o, 64), s2 = __shfl_xor(s, o, 64);
+            const float M = fmaxf(m, m2);
+            const float f1 = (m == M) ? 1.0f : __expf(m - M);
+            const float f2 = (m2 == M) ? 1.0f : __expf(m2 - M);
+            s = s * f1 + s2 * f2;
+            m = M;
+        }
+    }
+};
 
-// Hand rows to lane groups: op.run<GS>(row, begin, end, lane_in_group) is called by all GS lanes of a group.
+constexpr int TEAM_BLOCK_THREADS = 1024;
+
+struct block_team {
+    int rank;
+    double *scratch;  // 2 * (blockDim.x / 64) doubles of LDS
+    __device__ int size() const { return blockDim.x; }
+    __device__ double sum(double v) const
+    {
+        const lane_team<64> w{0};
+        v = w.sum(v);
+        const int nw = blockDim.x / 64;
+        if (threadIdx.x % 64 == 0) scratch[threadIdx.x / 64] = v;
+        __syncthreads();
+        double t = 0.0;
+        for (int i = 0; i < nw; ++i) t += scratch[i];
+        __syncthreads();
+        return t;
+    }
+    __device__ float sum(float v) const { return static_cast<float>(sum(static_cast<double>(v))); }
+    __device__ float max(float v) const
+    {
+        const lane_team<64> w{0};
+        v = w.max(v);
+        const int nw = blockDim.x / 64;
+        if (threadIdx.x % 64 == 0) scratch[threadIdx.x / 64] = static_cast<double>(v);
+        __syncthreads();
+        float t = static_cast<float>(scratch[0]);
+        for (int i = 1; i < nw; ++i) t = fmaxf(t, static_cast<float>(scratch[i]));
+        __syncthreads();
+        return t;
+    }
+    __device__ void merge_ms(float &m, float &s) const
+    {
+        const lane_team<64> w{0};
+        w.merge_ms(m, s);
+        const int nw = blockDim.x / 64;
+        if (threadIdx.x % 64 == 0) {
+            scratch[2 * (threadIdx.x / 64)] = static_cast<double>(m);
+            scratch[2 * (threadIdx.x / 64) + 1] = static_cast<double>(s);
+        }
+        __syncthreads();
+        float M = static_cast<float>(scratch[0]), S = static_cast<float>(scratch[1]);
+        for (int i = 1; i < nw; ++i) {
+            const float m2 = static_cast<float>(scratch[2 * i]), s2 = static_cast<float>(scratch[2 * i + 1]);
+            const float MM = fmaxf(M, m2);
+            const float f1 = (M == MM) ? 1.0f : __expf(M - MM);
+            const float f2 = (m2 == MM) ? 1.0f : __expf(m2 - MM);
+            S = S * f1 + s2 * f2;
+            M = MM;
+        }
+        __syncthreads();
+        m = M;
+        s = S;
+    }
+};
+
+// Rows longer than this are not processed by one wave but appended to a list and handled by whole
+// workgroups in a second kernel (hub rows would otherwise serialise the tail of the launch).
+constexpr int HUGE_ROW = 4096;
+
+inline size_t huge_list_bytes(int64_t nnz) { return tango_round_up(static_cast<size_t>(nnz / HUGE_ROW + 2) * sizeof(int), 256); }
+
+// Hand rows to lane teams: op.run(row, begin, end, team) is called by all lanes of the team.
+// huge: NULL, or a list (huge[0] = count, zero-initialised; huge[1..] = rows) that receives rows longer than
+// HUGE_ROW instead of processing them here.
 template <int GROUP, class Op>
-__device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op)
+__device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op, int *huge = nullptr)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
@@ -72,24 +154,41 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op)
             b = ptr[r];
             t = ptr[r + 1];
         }
-        const int is_long = (GROUP == 64) ? 1 : ((t - b) > 16 * GROUP ? 1 : 0);
+        int is_long = (GROUP == 64) ? 1 : ((t - b) > 16 * GROUP ? 1 : 0);
+        if (huge && r < n && (t - b) > HUGE_ROW) {
+            huge[1 + atomicAdd(huge, 1)] = r;
+            is_long = 2;  // neither a group nor this wave processes it
+        }
         if (GROUP < 64) {
             for (int k = 0; k < GROUP; ++k) {
                 const int src = k * RPI + lane / GROUP;
                 const int rb = __shfl(b, src, 64), rt = __shfl(t, src, 64), lg = __shfl(is_long, src, 64);
                 const int row = static_cast<int>(base) + src;
-                if (row < n && !lg) op.template run<GROUP>(row, rb, rt, lane % GROUP);
+                if (row < n && !lg) op.run(row, rb, rt, lane_team<GROUP>{lane % GROUP});
             }
         }
-        unsigned long long mask = __ballot(r < n && is_long);
+        unsigned long long mask = __ballot(r < n && is_long == 1);
         while (mask) {
             const int k = __ffsll(static_cast<long long>(mask)) - 1;
             mask &= mask - 1;
             const int rb = __shfl(b, k, 64), rt = __shfl(t, k, 64);
-            op.template run<64>(static_cast<int>(base) + k, rb, rt, lane);
+            op.run(static_cast<int>(base) + k, rb, rt, lane_team<64>{lane});
         }
     }
 }
+
+// Second kernel body: one workgroup per listed row.
+template <class Op>
+__device__ inline void walk_huge_rows(const int32_t *__restrict__ ptr, const int *huge, Op &op, double *scratch)
+{
+    const int count = huge[0];
+    for (int i = blockIdx.x; i < count; i += gridDim.x) {
+        const int row = huge[1 + i];
+        op.run(row, ptr[row], ptr[row + 1], block_team{static_cast<int>(threadIdx.x), scratch});
+    }
+}
+
+constexpr unsigned HUGE_GRID = 2048;
 
 inline int pick_group(int n, int64_t nnz)
 {

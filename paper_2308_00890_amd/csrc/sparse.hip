@@ -21,6 +21,7 @@
 // cache/fabric gather rate.  Algorithmic bytes per edge: 4 (index) + heads
 // (weight) + F (row); per node: 4 (pointer) + 4F (fp32 result).
 #include "internal.hip.h"
+#include "attn_math.hip.h"
 
 #include <type_traits>
 
@@ -88,13 +89,13 @@ __device__ inline void unpack_words<16>(const uint4 &v, uint32_t (&w)[4])
 __device__ inline int sbyte(uint32_t w, int j) { return static_cast<int>(static_cast<int8_t>(w >> (8 * j))); }
 
 // Edge weights computed on the fly (fused attention forward, Sec. 2.1 steps 3-5): alpha of edge (u -> v), head h
-// is exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_max[v][h]) / row_den[v][h], quantized with the abs-max
+// is exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_max[v][h]) / row_rden[v][h], quantized with the abs-max
 // found by the statistics pass.
 struct attn_params {
     const int8_t *Sq, *Dq;
     const float *sS, *sD;
     float slope;
-    const float *row_max, *row_den;  // n x heads
+    const float *row_max, *row_rden;  // n x heads
     const float *absmax_alpha;
     tango_rng rng;
     int rounding;
@@ -250,13 +251,15 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
                     const int64_t i0 = static_cast<int64_t>(e) * H;
                     uint4 blk = make_uint4(0, 0, 0, 0);
                     uint64_t have = ~uint64_t(0);
+                    int sq[8], dq[8];
+                    tango_load_heads_rt(a.att.Sq, my_nb, H, sq);
+                    tango_load_heads_rt(a.att.Dq, r, H, dq);
                     for (int hh = 0; hh < H; ++hh) {
-                        const float ts = att_sS * static_cast<float>(a.att.Sq[static_cast<int64_t>(my_nb) * H + hh]);
-                        const float td = att_sD * static_cast<float>(a.att.Dq[static_cast<int64_t>(r) * H + hh]);
-                        const float x = ts + td;
-                        const float ev = x > 0.0f ? x : a.att.slope * x;
-                        const float al = expf(ev - a.att.row_max[static_cast<int64_t>(r) * H + hh]) /
-                                         a.att.row_den[static_cast<int64_t>(r) * H + hh];
+                        bool pos;
+                        const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
+                                                          a.att.slope, pos);
+                        const float al = tango_attn_alpha(ev, a.att.row_max[static_cast<int64_t>(r) * H + hh],
+                                                          a.att.row_rden[static_cast<int64_t>(r) * H + hh]);
                         if (a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
                         int q;
                         if (a.att.rounding == TANGO_SR) {
@@ -393,25 +396,30 @@ struct sddmm_dot_args {
     const int8_t *Sq, *Dq;
     const float *sS, *sD;
     float slope;
-    const float *row_max, *row_den;  // of the destination
-    const double *P;                 // n x heads: sum over in-edges of dalpha*alpha, per destination
+    const tango_attn_rec *rec;       // n x heads: (P, row_max, row_rden) of the destination
     double *dS_acc;                  // n x heads, zero-initialised
 };
 
 // out[e][h] = (float)(Xdst[dst(e)][h][:] . Xsrc[src(e)][h][:]) * (s_dst*s_src); one wave per chunk of edges.
 // ATT_BWD (step 3' fused with 5'', 4' and LeakyReLU', walking the out-edges of each source u): the dot product
-// of edge (u -> v) is dalpha, alpha is recomputed from S_q[u], D_q[v], row_max[v], row_den[v], and
+// of edge (u -> v) is dalpha, alpha is recomputed from S_q[u], D_q[v], row_max[v], row_rden[v], and
 // dS_acc[u][h] += alpha*(dalpha - P[v][h]) * lrelu'(t).
 template <int VEC, bool ATT_BWD>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
 {
     using V = typename vec_bytes<VEC>::type;
+    // per wave: the dot products of a block of 64 edges (edge-major, heads <= 8) and the neighbours of those edges
+    __shared__ int dots[WAVES_PER_BLOCK][64 * 8];
+    __shared__ int nbl[WAVES_PER_BLOCK][64];
+    __shared__ double red[WAVES_PER_BLOCK][64];
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    const int wv = threadIdx.x / TANGO_WAVE;
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
     const int64_t c0 = chunk << CHUNK_SHIFT_DEFAULT;
     if (c0 >= a.nnz) return;
     const int64_t c1 = min(c0 + (int64_t(1) << CHUNK_SHIFT_DEFAULT), a.nnz);
 
+    const int H = a.heads;
     const int LPR = a.F / VEC;
     const int G = 64 / LPR;
     const int gi = lane / LPR;
@@ -421,7 +429,18 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     const int h = col / a.dim;
     const int LPH = a.dim / VEC;  // lanes per head (power of two)
     const float sc = (*a.s_dst) * (*a.s_src);
-    constexpr int U = 4;
+    constexpr int U = 8;
+    // epilogue mapping: lane l < S handles the (edge, head) pairs l, l+S, l+2S, ... of a block, S a multiple of
+    // the head count so that a lane always sees the same head
+    const int S = (64 / H) * H;
+    const int eh = lane % H;       // my head in the epilogue
+    const int ek0 = lane / H;      // my first edge of a block
+    const int ekstep = S / H;
+    float sS = 0.0f, sD = 0.0f;
+    if (ATT_BWD) {
+        sS = *a.sS;
+        sD = *a.sD;
+    }
 
     int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
     for (; r < a.n; ++r) {
@@ -436,49 +455,75 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
         }
         float ts_row = 0.0f;
         double acc_s = 0.0;
-        if (ATT_BWD) ts_row = (*a.sS) * static_cast<float>(a.Sq[static_cast<int64_t>(r) * a.heads + (active ? h : 0)]);
-        // every lane runs the same number of iterations (the shuffles below need all lanes)
-        for (int e0 = sb; e0 < se; e0 += G * U) {
-            int dot[U];
-            int nbs[U];
+        if (ATT_BWD && lane < S) ts_row = sS * static_cast<float>(a.Sq[static_cast<int64_t>(r) * H + eh]);
+        for (int base = sb; base < se; base += 64) {
+            const int cnt = min(64, se - base);
+            int my_nb = 0;
+            if (lane < cnt) my_nb = a.idx[base + lane];
+            if (ATT_BWD) nbl[wv][lane] = my_nb;
+            const int steps = (cnt + G - 1) / G;
+            auto batch = [&](int s0, auto uu) {
+                constexpr int UU = decltype(uu)::value;
+                int dot[UU];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int ee = e0 + gi + u * G;
-                const int ec = (active && ee < se) ? ee : se - 1;
-                const int nb = a.idx[ec];
-                nbs[u] = nb;
-                const V xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
-                uint32_t w[VEC / 4];
-                unpack_words<VEC>(xv, w);
-                int d = 0;
+                for (int u = 0; u < UU; ++u) {
+                    const int k = (s0 + u) * G + gi;
+                    const bool ok = active && k < cnt;
+                    const int nb = __shfl(my_nb, ok ? k : 0, 64);
+                    const V xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
+                    uint32_t w[VEC / 4];
+                    unpack_words<VEC>(xv, w);
+                    int d = 0;
 #pragma unroll
-                for (int j = 0; j < VEC / 4; ++j) d = __builtin_amdgcn_sdot4(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false);
-                dot[u] = d;
-            }
+                    for (int j = 0; j < VEC / 4; ++j)
+                        d = __builtin_amdgcn_sdot4(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false);
+                    dot[u] = d;
+                }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int d = dot[u];
-                for (int off = LPH / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
-                const int ee = e0 + gi + u * G;
-                if (active && ee < se && (li % LPH) == 0) {
-                    const float da = static_cast<float>(d) * sc;
+                for (int u = 0; u < UU; ++u) {
+                    int d = dot[u];
+                    for (int off = LPH / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
+                    const int k = (s0 + u) * G + gi;
+                    if (active && k < cnt && (li % LPH) == 0) dots[wv][k * H + h] = d;
+                }
+            };
+            int s0 = 0;
+            for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
+            for (; s0 < steps; s0 += 2) batch(s0, std::integral_constant<int, 2>{});
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // epilogue at full lane occupancy: one (edge, head) pair per lane and step
+            if (lane < S) {
+                for (int k = ek0; k < cnt; k += ekstep) {
+                    const float da = static_cast<float>(dots[wv][k * H + eh]) * sc;
                     if (ATT_BWD) {
-                        const int64_t vh = static_cast<int64_t>(nbs[u]) * a.heads + h;
-                        const float td = (*a.sD) * static_cast<float>(a.Dq[vh]);
-                        const float x = ts_row + td;
-                        const float ev = x > 0.0f ? x : a.slope * x;
-                        const float al = expf(ev - a.row_max[vh]) / a.row_den[vh];
-                        const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - a.P[vh]));
-                        acc_s += static_cast<double>(dE * (x > 0.0f ? 1.0f : a.slope));
+                        const int64_t vh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
+                        bool pos;
+                        const float ev = tango_attn_score(ts_row, sD * static_cast<float>(a.Dq[vh]), a.slope, pos);
+                        const tango_attn_rec rc = a.rec[vh];
+                        const float al = tango_attn_alpha(ev, rc.row_max, rc.row_rden);
+                        const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
+                        acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
                     } else {
-                        a.out[static_cast<int64_t>(ee) * a.heads + h] = da;
+                        a.out[(static_cast<int64_t>(base) + k) * H + eh] = da;
                     }
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
         if (ATT_BWD) {
-            for (int off = G / 2; off >= 1; off >>= 1) acc_s += __shfl_down(acc_s, off * LPR, 64);
-            if (gi == 0 && (li % LPH) == 0 && acc_s != 0.0) atomicAdd(a.dS_acc + static_cast<int64_t>(r) * a.heads + h, acc_s);
+            // sum the lanes that share a head (lanes eh, eh+H, ...), in lane order
+            red[wv][lane] = (lane < S) ? acc_s : 0.0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < H) {
+                double t = 0.0;
+                for (int l = lane; l < S; l += H) t += red[wv][l];
+                if (t != 0.0) atomicAdd(a.dS_acc + static_cast<int64_t>(r) * H + lane, t);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -592,13 +637,13 @@ int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, co
 // SPMM over in-edges whose weights are the attention scores computed (and quantized, and stored) on the fly.
 int tango_spmm_attention_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
                                const int8_t *Dq, const float *sD, float slope, const float *row_max,
-                               const float *row_den, const float *absmax_alpha, int rounding, uint64_t seed,
+                               const float *row_rden, const float *absmax_alpha, int rounding, uint64_t seed,
                                uint64_t stream_id, int8_t *alpha_q, float *s_alpha, float *alpha_dump,
                                const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
 {
     attn_params att;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
-    att.row_max = row_max; att.row_den = row_den; att.absmax_alpha = absmax_alpha;
+    att.row_max = row_max; att.row_rden = row_rden; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = alpha_q; att.s_alpha = s_alpha; att.alpha_dump = alpha_dump;
     return spmm_launch(g, TANGO_IN, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
@@ -638,8 +683,8 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
 // quantized dot product of dOut_q[v] and X_q[u]; dS_acc: n x heads doubles of scratch.
 int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                              const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const float *row_max, const float *row_den, const double *P,
-                             double *dS_acc, float *dS, hipStream_t st)
+                             const float *sD, float slope, const tango_attn_rec *rec, double *dS_acc, float *dS,
+                             hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
@@ -659,7 +704,7 @@ int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int
         a.dim = dim;
         a.F = heads * dim;
         a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
-        a.row_max = row_max; a.row_den = row_den; a.P = P; a.dS_acc = dS_acc;
+        a.rec = rec; a.dS_acc = dS_acc;
         const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         switch (pick_vec(a.F, dim, true)) {

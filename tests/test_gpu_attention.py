@@ -34,14 +34,14 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     Xq = rand_i8((g.n_nodes, F), 10)
     sS, sD, sX, slope = np.float32(0.021), np.float32(0.013), np.float32(0.017), 0.2
     seed, sid = 4242, 38
-    row_max, row_den = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    row_max, row_rden = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
     alpha_q = empty((g.n_edges, heads), torch.int8)
     dump = empty((g.n_edges, heads), torch.float32)
     s_alpha, am = scalar(-1), scalar(-1)
     out = empty((g.n_nodes, F), torch.float32)
     ws = workspace(T.tango_gat_attention_workspace_bytes(g.n_nodes, g.n_edges, heads))
     T.tango_gat_attention_fwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, dev(Xq), scalar(sX), rounding,
-                              seed, sid, row_max, row_den, alpha_q, s_alpha, dump, out, am, ws)
+                              seed, sid, row_max, row_rden, alpha_q, s_alpha, dump, out, am, ws)
     torch.cuda.synchronize()
     E = orc.sddmm_add(g, Sq, sS, Dq, sD, slope)
     alpha = orc.edge_softmax(g, E)
@@ -61,7 +61,7 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
         m = np.maximum.reduceat(E, starts, axis=0)
         assert_bit_exact(host(row_max)[nonempty], m, "row max")
         den = np.add.reduceat(np.exp(E.astype(np.float64) - np.repeat(m, np.diff(g.in_ptr)[nonempty], axis=0)), starts, axis=0)
-        assert_close(host(row_den)[nonempty], den, "row denominator")
+        assert_close(host(row_rden)[nonempty], 1.0 / den, "reciprocal row denominator")
 
     # ---- backward from the caches of the fused forward
     dOq = rand_i8((g.n_nodes, F), 11)
@@ -71,7 +71,7 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     dS, dD = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
     amx = scalar(-1)
     wsb = workspace(T.tango_gat_attention_bwd_workspace_bytes(g.n_nodes, g.n_edges, heads))
-    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_max, row_den, alpha_q,
+    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_max, row_rden, alpha_q,
                               s_alpha, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX, amx, dal, dS, dD, wsb)
     torch.cuda.synchronize()
     w_dX, w_am = orc.spmm_rev(g, host(alpha_q), host(s_alpha)[0], dOq, s_dO)
