@@ -105,13 +105,15 @@ def scale_from_absmax(am):
     return np.float32(s.value), np.float32(inv.value)
 
 
-def quantize(x, rounding: int = SR, seed: int = 0, stream: int = 0, am=None):
-    """Returns (q int8 same shape, scale fp32).  ``am`` overrides the abs-max (a cached one)."""
+def quantize(x, rounding: int = SR, seed: int = 0, stream: int = 0, am=None, first: int = 0):
+    """Returns (q int8 same shape, scale fp32).  ``am`` overrides the abs-max (a cached one, or that of the
+    whole tensor when ``x`` is a window of it starting at flat element ``first``)."""
     x = _c(x, np.float32)
     if am is None:
         am = absmax(x)
     q = np.empty(x.shape, np.int8)
-    _L().orc_quantize(_p(x), ctypes.c_size_t(x.size), _f32(float(am)), ctypes.c_int(rounding), _u64(seed), _u64(stream), _p(q))
+    _L().orc_quantize(_p(x), ctypes.c_size_t(x.size), _u64(first), _f32(float(am)), ctypes.c_int(rounding), _u64(seed),
+                      _u64(stream), _p(q))
     return q, scale_from_absmax(am)[0]
 
 

@@ -108,8 +108,11 @@ void orc_scale_from_absmax(float absmax, float *s, float *inv)
  * rounding 0: nearest, ties to even.
  * rounding 1: stochastic (Eq. 3): floor(y) + 1 with probability y - floor(y),
  *             realised as u < frac with u = bits16 * 2^-16.
+ * x[0..n) are elements first .. first+n-1 of the tensor (first = 0 for a whole
+ * tensor; a window of a large tensor can be checked on its own).
  */
-void orc_quantize(const float *x, size_t n, float absmax, int rounding, uint64_t seed, uint64_t stream, int8_t *q)
+void orc_quantize(const float *x, size_t n, uint64_t first, float absmax, int rounding, uint64_t seed, uint64_t stream,
+                  int8_t *q)
 {
     float s, inv;
     orc_scale_from_absmax(absmax, &s, &inv);
@@ -122,7 +125,7 @@ void orc_quantize(const float *x, size_t n, float absmax, int rounding, uint64_t
         } else {
             float f = floorf(y);
             float frac = y - f;
-            float u = (float)orc_sr_bits16(seed, stream, (uint64_t)i) * (1.0f / 65536.0f);
+            float u = (float)orc_sr_bits16(seed, stream, first + (uint64_t)i) * (1.0f / 65536.0f);
             v = (int)f + (u < frac ? 1 : 0);
         }
         if (v > 127) v = 127;

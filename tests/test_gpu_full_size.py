@@ -1,0 +1,144 @@
+"""GPU parity at BASELINE sizes, in the launch configuration bench.py times (fused GAT layer, SR).
+
+The oracle cannot run a whole layer at these sizes in test time, so every stage is checked on sampled outputs that
+the oracle computes one by one from the GPU's own inputs of that stage: sampled rows of the GEMMs, sampled elements
+of every quantization, sampled destination rows (all their in-edges) of the forward attention + SPMM, sampled source
+rows (all their out-edges) of the reverse SPMM and dS, sampled edges of the SDDMM-dot."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle as orc
+import tango_inputs as ti
+from gpu_util import assert_bit_exact, assert_close, dev, host
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+
+    import paper_2308_00890_amd as tango
+
+    assert torch.cuda.is_available()
+    tango.load_library()
+    return tango
+
+
+def subgraph(g, eids):
+    """Graph on the same nodes holding only the edges at destination-major positions `eids` (sorted)."""
+    eids = np.sort(np.asarray(eids, dtype=np.int64))
+    dst = (np.searchsorted(g.in_ptr, eids, side="right") - 1).astype(np.uint64)
+    src = g.in_src[eids].astype(np.uint64)
+    return ti.graph_from_keys(g.n_nodes, (dst << np.uint64(32)) | src), eids
+
+
+def in_edges_of(g, rows):
+    return np.concatenate([np.arange(g.in_ptr[v], g.in_ptr[v + 1], dtype=np.int64) for v in rows])
+
+
+def out_edges_of(g, rows):
+    return np.concatenate([g.out_eid[g.out_ptr[u] : g.out_ptr[u + 1]].astype(np.int64) for u in rows])
+
+
+def sample_rows(g, rng, k, ptr):
+    """k rows: the longest one, a few long ones and random ones (bounded total edge count)."""
+    deg = np.diff(ptr)
+    order = np.argsort(deg)
+    rows = {int(order[-1]), int(order[-2]), int(order[len(order) // 2]), int(order[0])}
+    while len(rows) < k:
+        rows.add(int(rng.integers(0, g.n_nodes)))
+    return sorted(rows)
+
+
+def check_quantized(name, x, q, s, rounding, seed, sid, rng, am=None):
+    """Sampled windows (the first and last elements and random aligned and unaligned places) of q = Q(x)."""
+    x = x.ravel()
+    q = q.ravel()
+    if am is None:
+        am = np.abs(x).max()
+    assert s == orc.scale_from_absmax(np.float32(am))[0], name
+    n = x.size
+    starts = np.unique(np.concatenate([[0, max(0, n - 100)], rng.integers(0, max(1, n - 100), 300)]))
+    for st in starts:
+        en = min(n, int(st) + 100)
+        want, _ = orc.quantize(x[st:en], rounding, seed, sid, am=am, first=int(st))
+        assert_bit_exact(q[st:en], want, "%s window at %d" % (name, st))
+
+
+@pytest.mark.parametrize("name", ["gat_dense", "gat_products"])
+def test_full_size_gat_layer_sampled(T, name):
+    import torch
+
+    li = ti.layer_inputs(name)
+    g = li.graph
+    heads, dim = li.heads, li.dim
+    F = heads * dim
+    seed, slope, rounding = li.sr_seed, 0.2, orc.SR
+    G = T.Graph.from_host(g)
+    L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed, 0,
+                   fused=True, keep_alpha=True)
+    T.tango_gat_layer_fwd(L)
+    T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    del L
+    torch.cuda.empty_cache()
+    sc = lambda k: o[k][0]
+    rng = np.random.default_rng(5)
+
+    # ---- quantizations (sampled blocks) and the GEMM (sampled rows)
+    check_quantized("H_q", li.feat, o["H_q"], sc("s_H"), rounding, seed, orc.SID_H, rng)
+    check_quantized("W_q", li.weight, o["W_q"], sc("s_W"), rounding, seed, orc.SID_W, rng)
+    rows = np.sort(rng.choice(g.n_nodes, 96, replace=False))
+    C, _ = orc.dequant_i32(orc.igemm(o["H_q"][rows], o["W_q"]), sc("s_H"), sc("s_W"))
+    assert_bit_exact(o["Hp"][rows], C, "Hp rows")
+    assert sc("absmax_Hp") == np.abs(o["Hp"]).max()
+    assert_close(o["S"][rows], orc.head_proj(o["Hp"][rows], li.a_src), "S rows")
+    assert_close(o["D"][rows], orc.head_proj(o["Hp"][rows], li.a_dst), "D rows")
+    check_quantized("Hp_q", o["Hp"], o["Hp_q"], sc("s_Hp"), rounding, seed, orc.SID_HP, rng)
+    check_quantized("S_q", o["S"], o["S_q"], sc("s_S"), rounding, seed, orc.SID_S, rng)
+    check_quantized("D_q", o["D"], o["D_q"], sc("s_D"), rounding, seed, orc.SID_D, rng)
+
+    # ---- forward attention: the streaming stages over the whole graph, the F-wide SPMM on sampled rows
+    E = orc.sddmm_add(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope)
+    assert_close(o["alpha"], orc.edge_softmax(g, E), "alpha")
+    del E
+    check_quantized("alpha_q", o["alpha"], o["alpha_q"], sc("s_alpha"), rounding, seed, orc.SID_ALPHA, rng)
+    vrows = sample_rows(g, rng, 24, g.in_ptr)
+    sub, eids = subgraph(g, in_edges_of(g, vrows))
+    want, _ = orc.spmm_in(sub, o["alpha_q"][eids], sc("s_alpha"), o["Hp_q"], sc("s_Hp"))
+    assert_bit_exact(o["out"][vrows], want[vrows], "out rows")
+    assert sc("absmax_out") == np.abs(o["out"]).max()
+
+    # ---- backward
+    check_quantized("g_q", li.grad_out, o["g_q"], sc("s_g"), rounding, seed, orc.SID_G, rng)
+    dal = orc.sddmm_dot(sub, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads)
+    assert_bit_exact(o["dalpha"][eids], dal, "dalpha on sampled rows (all their in-edges)")
+    erand = np.sort(rng.choice(g.n_edges, 20000, replace=False))
+    sube, _ = subgraph(g, erand)
+    assert_bit_exact(o["dalpha"][erand], orc.sddmm_dot(sube, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads),
+                     "dalpha on sampled edges")
+    dE_sm = orc.edge_softmax_bwd(g, o["alpha"], o["dalpha"])
+    _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, dE_sm)
+    del dE_sm
+    assert_close(o["dD"], dD, "dD")
+    assert_close(o["dS"], dS, "dS")
+
+    urows = sample_rows(g, rng, 24, g.out_ptr)
+    sub2, eids2 = subgraph(g, out_edges_of(g, urows))
+    agg, _ = orc.spmm_rev(sub2, o["alpha_q"][eids2], sc("s_alpha"), o["g_q"], sc("s_g"))
+    dHp, _, _, _ = orc.head_proj_bwd(o["dS"][urows], o["dD"][urows], li.a_src, li.a_dst, o["Hp_q"][urows], sc("s_Hp"), agg[urows])
+    assert_bit_exact(o["dHp"][urows], dHp, "dHp rows")
+    assert sc("absmax_dHp") == np.abs(o["dHp"]).max()
+    check_quantized("dHp_q", o["dHp"], o["dHp_q"], sc("s_dHp"), rounding, seed, orc.SID_DHP, rng, am=sc("absmax_dHp"))
+    dH, _ = orc.dequant_i32(orc.igemm(o["dHp_q"][rows], o["W_q"], transB=True), sc("s_dHp"), sc("s_W"))
+    assert_bit_exact(o["dH"][rows], dH, "dH rows")
+    # dW: sampled rows of the K_in x F result, each a reduction over every node
+    krows = np.sort(rng.choice(li.feat.shape[1], 6, replace=False))
+    dW, _ = orc.dequant_i32(orc.igemm(np.ascontiguousarray(o["H_q"][:, krows]), o["dHp_q"], transA=True), sc("s_H"), sc("s_dHp"))
+    assert_bit_exact(o["dW"][krows], dW, "dW rows")
+    # da_src / da_dst: column sums over every node
+    X = (sc("s_Hp") * o["Hp_q"].astype(np.float32)).astype(np.float64).reshape(g.n_nodes, heads, dim)
+    assert_close(o["da_src"], np.einsum("vh,vhd->hd", o["dS"].astype(np.float64), X), "da_src", rtol=1e-5, atol=1e-5)
+    assert_close(o["da_dst"], np.einsum("vh,vhd->hd", o["dD"].astype(np.float64), X), "da_dst", rtol=1e-5, atol=1e-5)

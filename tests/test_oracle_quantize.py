@@ -154,3 +154,13 @@ def test_dequantize_is_scale_times_code():
     q = np.arange(-127, 128, dtype=np.int8)
     x = orc.dequantize(q, np.float32(0.037))
     assert np.array_equal(x, np.float32(0.037) * q.astype(np.float32))
+
+
+def test_window_of_a_tensor_quantizes_like_the_whole():
+    x = _x(5000, 9)
+    am = orc.absmax(x)
+    for mode in (orc.RN, orc.SR):
+        full, _ = orc.quantize(x, mode, seed=12, stream=5)
+        for a, b in ((0, 17), (1003, 1100), (4990, 5000)):
+            part, _ = orc.quantize(x[a:b], mode, seed=12, stream=5, am=am, first=a)
+            assert np.array_equal(part, full[a:b])
