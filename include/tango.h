@@ -262,11 +262,12 @@ int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q,
  * up to the summation order of the softmax denominator and the last bits of exp
  * (the hardware exponential is used).  S_q and D_q must be aligned to `heads` bytes
  * when heads is 2, 4 or 8.  Outputs:
- *   row_max, row_rden (n x heads fp32): per (node, head) maximum activated score and
- *       reciprocal of the sum of exp(E - max) over its in-edges, so that
- *       alpha = exp(E - row_max) * row_rden; the backward pass recomputes the fp32
- *       alpha from them;
- *   alpha_q (nnz x heads int8), s_alpha: the quantized attention, cached for backward;
+ *   row_lse (n x heads fp32): per (node, head) the logarithm of the sum of exp(E) over
+ *       its in-edges, so that alpha = exp(E - row_lse); the backward pass recomputes the
+ *       fp32 alpha from it;
+ *   alpha_q (nnz x heads int8) or NULL: the quantized attention; s_alpha, absmax_alpha:
+ *       its scale and abs-max (the backward pass can recompute the identical codes from
+ *       S_q, D_q, row_lse, absmax_alpha and the random stream, so caching alpha_q is optional);
  *   alpha_dump (nnz x heads fp32) or NULL: the exact fp32 alpha values that were
  *       quantized (for verification: alpha_q must equal the quantization of this
  *       tensor bit for bit);
@@ -277,24 +278,28 @@ size_t tango_gat_attention_workspace_bytes(int64_t n_nodes, int64_t n_edges, int
 int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8_t *S_q,
                             const float *s_S, const int8_t *D_q, const float *s_D, float slope,
                             const int8_t *X_q, const float *s_X, int rounding, uint64_t seed,
-                            uint64_t stream_id_alpha, float *row_max, float *row_rden, int8_t *alpha_q,
-                            float *s_alpha, float *alpha_dump, float *out, float *absmax_out, void *ws,
-                            size_t ws_bytes, void *stream);
+                            uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q, float *s_alpha,
+                            float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
+                            void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Backward of tango_gat_attention_fwd (Fig. 1b steps 5', 5'', 4', 3', 3'') from its caches:
- *   dX_agg (n x F fp32)     = SPMM on the reversed graph of alpha_q and dOut_q (step 5'); absmax_dX may be NULL;
+ *   dX_agg (n x F fp32)     = SPMM on the reversed graph of alpha_q and dOut_q (step 5'); absmax_dX may be NULL.
+ *                             alpha_q = NULL: its codes are recomputed on the fly (same rounding, seed, stream id
+ *                             as the forward call), which replaces one random 4-byte read per edge by reads of
+ *                             the small cache-resident S_q, D_q, row_lse tables;
  *   dalpha (nnz x heads)    = SDDMM-dot of dOut_q[dst] and X_q[src] (step 5''), fp32 scratch that is also an output;
  *   dD, dS (n x heads fp32) = sums over in-/out-edges of alpha*(dalpha - P)*lrelu'(t) with the fp32 alpha
- *                             recomputed from S_q, D_q, row_max, row_rden exactly as the forward pass computed it
+ *                             recomputed from S_q, D_q, row_lse exactly as the forward pass computed it
  *                             (the gradient of the pre-activation scores is never written to memory).
  * ws: at least tango_gat_attention_bwd_workspace_bytes() bytes.
  */
 size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads);
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q,
                             const float *s_S, const int8_t *D_q, const float *s_D, float slope,
-                            const float *row_max, const float *row_rden, const int8_t *alpha_q,
-                            const float *s_alpha, const int8_t *X_q, const float *s_X,
+                            const float *row_lse, const int8_t *alpha_q, const float *s_alpha,
+                            const float *absmax_alpha, int rounding, uint64_t seed,
+                            uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
                             const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX,
                             float *dalpha, float *dS, float *dD, void *ws, size_t ws_bytes, void *stream);
 
@@ -348,10 +353,12 @@ typedef struct tango_gat_layer {
     float *da_src, *da_dst;       /* heads x dim */
     /* fused = 1: steps 3-5 and 5'-3'' run through tango_gat_attention_fwd / _bwd.  Then E is unused (may be
      * NULL), alpha is optional (if not NULL it receives the fp32 attention that was quantized, for
-     * verification), dalpha keeps step 5'' (it is not overwritten), and row_max / row_rden (n x heads) are
-     * required.  fused = 0: the primitives are chained one by one and row_max / row_rden are unused. */
+     * verification), alpha_q is optional (NULL: the backward pass recomputes its codes), dalpha keeps step
+     * 5'' (it is not overwritten), and row_lse (n x heads) and absmax_alpha are required.
+     * fused = 0: the primitives are chained one by one and row_lse / absmax_alpha are unused. */
     int fused;
-    float *row_max, *row_rden;
+    float *row_lse;
+    float *absmax_alpha;
     /* scratch */
     void *ws;
     size_t ws_bytes;              /* >= tango_gat_layer_workspace_bytes(...) */

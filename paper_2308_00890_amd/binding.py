@@ -289,8 +289,8 @@ def tango_qspmm_bwd(g, heads, dim, w_q, s_w, X_q, s_X, dOut_q, s_dOut, dX, absma
 # ---------------------------------------------------------------- fused attention
 SIGNATURES.update({
     "tango_gat_attention_workspace_bytes": (_sz, [_i64, _i64, _int]),
-    "tango_gat_attention_fwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64, _vp, _vp,
-                                       _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "tango_gat_attention_fwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _int, _u64, _u64] + [_vp] * 8
+                                + [_sz, _vp]),
 })
 
 
@@ -298,14 +298,14 @@ def tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads) -> int:
     return load_library().tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads)
 
 
-def tango_gat_attention_fwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, rounding, seed, sid_alpha, row_max,
-                            row_rden, alpha_q, s_alpha, alpha_dump, out, absmax_out, ws):
+def tango_gat_attention_fwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, rounding, seed, sid_alpha, row_lse,
+                            alpha_q, s_alpha, absmax_alpha, alpha_dump, out, absmax_out, ws):
     _check(
         load_library().tango_gat_attention_fwd(
             g.ref(), heads, dim, _ptr(S_q, torch.int8), _ptr(s_S, torch.float32), _ptr(D_q, torch.int8),
             _ptr(s_D, torch.float32), slope, _ptr(X_q, torch.int8), _ptr(s_X, torch.float32), rounding, seed, sid_alpha,
-            _ptr(row_max, torch.float32), _ptr(row_rden, torch.float32), _ptr(alpha_q, torch.int8),
-            _ptr(s_alpha, torch.float32), _ptr(alpha_dump, torch.float32), _ptr(out, torch.float32),
+            _ptr(row_lse, torch.float32), _ptr(alpha_q, torch.int8), _ptr(s_alpha, torch.float32),
+            _ptr(absmax_alpha, torch.float32), _ptr(alpha_dump, torch.float32), _ptr(out, torch.float32),
             _ptr(absmax_out, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream(),
         ),
         "tango_gat_attention_fwd",
@@ -314,7 +314,8 @@ def tango_gat_attention_fwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, 
 
 SIGNATURES.update({
     "tango_gat_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _int]),
-    "tango_gat_attention_bwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32] + [_vp] * 14 + [_sz, _vp]),
+    "tango_gat_attention_bwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _int, _u64, _u64]
+                                + [_vp] * 10 + [_sz, _vp]),
 })
 
 
@@ -322,13 +323,14 @@ def tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads) -> int:
     return load_library().tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads)
 
 
-def tango_gat_attention_bwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_max, row_rden, alpha_q, s_alpha, X_q, s_X,
-                            dOut_q, s_dOut, dX_agg, absmax_dX, dalpha, dS, dD, ws):
+def tango_gat_attention_bwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, alpha_q, s_alpha, absmax_alpha, rounding,
+                            seed, sid_alpha, X_q, s_X, dOut_q, s_dOut, dX_agg, absmax_dX, dalpha, dS, dD, ws):
     f32, i8 = torch.float32, torch.int8
     _check(
         load_library().tango_gat_attention_bwd(
-            g.ref(), heads, dim, _ptr(S_q, i8), _ptr(s_S, f32), _ptr(D_q, i8), _ptr(s_D, f32), slope, _ptr(row_max, f32),
-            _ptr(row_rden, f32), _ptr(alpha_q, i8), _ptr(s_alpha, f32), _ptr(X_q, i8), _ptr(s_X, f32), _ptr(dOut_q, i8),
+            g.ref(), heads, dim, _ptr(S_q, i8), _ptr(s_S, f32), _ptr(D_q, i8), _ptr(s_D, f32), slope, _ptr(row_lse, f32),
+            _ptr(alpha_q, i8), _ptr(s_alpha, f32), _ptr(absmax_alpha, f32), rounding, seed, sid_alpha, _ptr(X_q, i8),
+            _ptr(s_X, f32), _ptr(dOut_q, i8),
             _ptr(s_dOut, f32), _ptr(dX_agg, f32), _ptr(absmax_dX, f32), _ptr(dalpha, f32), _ptr(dS, f32), _ptr(dD, f32),
             _ptr(ws), ws.numel() * ws.element_size(), _stream(),
         ),
@@ -345,7 +347,7 @@ class tango_gat_layer(ctypes.Structure):
             "H", "W", "a_src", "a_dst", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "S", "D",
             "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
             "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst")]
-        + [("fused", _int), ("row_max", _vp), ("row_rden", _vp), ("ws", _vp), ("ws_bytes", _sz)]
+        + [("fused", _int), ("row_lse", _vp), ("absmax_alpha", _vp), ("ws", _vp), ("ws_bytes", _sz)]
     )
 
 
@@ -408,7 +410,7 @@ class GatLayer(_LayerBuffers):
     _struct = tango_gat_layer
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
-                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False):
+                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -434,17 +436,19 @@ class GatLayer(_LayerBuffers):
         self._alloc("D_q", (n, heads), i8)
         c.fused = 1 if fused else 0
         if fused:
-            self._alloc("row_max", (n, heads), f32)
-            self._alloc("row_rden", (n, heads), f32)
+            self._alloc("row_lse", (n, heads), f32)
+            self._alloc("absmax_alpha", (1,), f32)
             if keep_alpha:
                 self._alloc("alpha", (nnz, heads), f32)
+            if keep_alpha_q:
+                self._alloc("alpha_q", (nnz, heads), i8)
         else:
             self._alloc("alpha", (nnz, heads), f32)
             if alias_E_alpha:
                 self._bind("E", self.t["alpha"], f32)
             else:
                 self._alloc("E", (nnz, heads), f32)
-        self._alloc("alpha_q", (nnz, heads), i8)
+            self._alloc("alpha_q", (nnz, heads), i8)
         self._alloc("out", (n, F), f32)
         if grad_out is not None:
             self._bind("grad_out", grad_out, f32)

@@ -14,11 +14,11 @@
 #include "attn_math.hip.h"
 #include "rowwalk.hip.h"
 
-int tango_spmm_attention_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
-                               const int8_t *Dq, const float *sD, float slope, const float *row_max,
-                               const float *row_rden, const float *absmax_alpha, int rounding, uint64_t seed,
-                               uint64_t stream_id, int8_t *alpha_q, float *s_alpha, float *alpha_dump,
-                               const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st);
+int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *Sq,
+                               const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
+                               const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
+                               int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
+                               float *out, float *absmax_out, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -38,7 +38,7 @@ struct attn_stats_op {
     const int32_t *src;
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
-    float *row_max, *row_rden;
+    float *row_lse;
     float amax;
     template <class Team>
     __device__ void run(int row, int b, int t, Team tm)
@@ -71,15 +71,11 @@ struct attn_stats_op {
         for (int h = 0; h < H; ++h) {
             tm.merge_ms(m[h], s[h]);
             if (t > b) {
-                const float rden = 1.0f / s[h];
-                if (tm.rank == 0) {
-                    row_max[static_cast<int64_t>(row) * H + h] = m[h];
-                    row_rden[static_cast<int64_t>(row) * H + h] = rden;
-                }
-                amax = fmaxf(amax, rden);  // the largest alpha of the row is exp(0)*rden
+                const float lse = m[h] + logf(s[h]);
+                if (tm.rank == 0) row_lse[static_cast<int64_t>(row) * H + h] = lse;
+                amax = fmaxf(amax, tango_attn_alpha(m[h], lse));  // the largest alpha of the row: its maximum score
             } else if (tm.rank == 0) {
-                row_max[static_cast<int64_t>(row) * H + h] = 0.0f;
-                row_rden[static_cast<int64_t>(row) * H + h] = 1.0f;
+                row_lse[static_cast<int64_t>(row) * H + h] = 0.0f;
             }
         }
     }
@@ -118,21 +114,20 @@ struct attn_bwd_dst_op {
     const int32_t *src;
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
-    const float *row_max, *row_rden, *dalpha;
+    const float *row_lse, *dalpha;
     tango_attn_rec *rec;
     float *dD;
     template <class Team>
     __device__ void run(int row, int b, int t, Team tm)
     {
-        float td[H], m[H], rden[H];
+        float td[H], lse[H];
         double p[H], acc[H];
         int dq[H];
         tango_load_heads<H>(Dq, row, dq);
 #pragma unroll
         for (int h = 0; h < H; ++h) {
             td[h] = sD * static_cast<float>(dq[h]);
-            m[h] = row_max[static_cast<int64_t>(row) * H + h];
-            rden[h] = row_rden[static_cast<int64_t>(row) * H + h];
+            lse[h] = row_lse[static_cast<int64_t>(row) * H + h];
             p[h] = 0.0;
             acc[h] = 0.0;
         }
@@ -145,7 +140,7 @@ struct attn_bwd_dst_op {
             for (int h = 0; h < H; ++h) {
                 bool pos;
                 const float ev = tango_attn_score(sS * static_cast<float>(sq[h]), td[h], slope, pos);
-                const float al = tango_attn_alpha(ev, m[h], rden[h]);
+                const float al = tango_attn_alpha(ev, lse[h]);
                 p[h] += static_cast<double>(d[h]) * static_cast<double>(al);
             }
         }
@@ -160,7 +155,7 @@ struct attn_bwd_dst_op {
             for (int h = 0; h < H; ++h) {
                 bool pos;
                 const float ev = tango_attn_score(sS * static_cast<float>(sq[h]), td[h], slope, pos);
-                const float al = tango_attn_alpha(ev, m[h], rden[h]);
+                const float al = tango_attn_alpha(ev, lse[h]);
                 const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(d[h]) - p[h]));
                 acc[h] += static_cast<double>(dE * (pos ? 1.0f : slope));
             }
@@ -171,8 +166,8 @@ struct attn_bwd_dst_op {
             if (tm.rank == 0) {
                 tango_attn_rec rc;
                 rc.P = p[h];
-                rc.row_max = m[h];
-                rc.row_rden = rden[h];
+                rc.row_lse = lse[h];
+                rc.unused = 0.0f;
                 rec[static_cast<int64_t>(row) * H + h] = rc;
                 dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(sacc);
             }
@@ -203,7 +198,7 @@ __global__ __launch_bounds__(TEAM_BLOCK_THREADS) void k_attn_bwd_dst_huge(const 
 }  // namespace
 
 int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const float *row_max, const float *row_rden,
+                             const float *sD, float slope, const float *row_lse,
                              const float *dalpha, tango_attn_rec *rec, float *dD, int *huge, hipStream_t st)
 {
     const int n = g->n_nodes;
@@ -213,7 +208,7 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
     if (rc != TANGO_OK) return rc;
 #define CALL(HH)                                                                                            \
     {                                                                                                       \
-        attn_bwd_dst_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_rden, dalpha, rec, dD};        \
+        attn_bwd_dst_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, dalpha, rec, dD};        \
         k_attn_bwd_dst<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, huge);                    \
         k_attn_bwd_dst_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, huge);      \
     }
@@ -224,7 +219,7 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
 }
 
 int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                           const float *sD, float slope, float *row_max, float *row_rden, float *absmax_alpha,
+                           const float *sD, float slope, float *row_lse, float *absmax_alpha,
                            int *huge, hipStream_t st)
 {
     const int n = g->n_nodes;
@@ -235,7 +230,7 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
     if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st)) != TANGO_OK) return rc;
 #define CALL(HH)                                                                                             \
     {                                                                                                        \
-        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_max, row_rden, 0.f};                    \
+        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f};                    \
         k_attn_stats<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge);         \
         k_attn_stats_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, absmax_alpha, huge); \
     }
@@ -251,9 +246,9 @@ size_t tango_gat_attention_workspace_bytes(int64_t, int64_t n_edges, int) { retu
 
 int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                             const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
-                            int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_max, float *row_rden,
-                            int8_t *alpha_q, float *s_alpha, float *alpha_dump, float *out, float *absmax_out, void *ws,
-                            size_t ws_bytes, void *stream)
+                            int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
+                            float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
+                            void *ws, size_t ws_bytes, void *stream)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -262,51 +257,51 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
     TANGO_REQUIRE(heads_supported(heads), TANGO_ERR_UNSUPPORTED);
     int rc = tango_validate_spmm_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(S_q && s_S && D_q && s_D && X_q && s_X && row_max && row_rden && s_alpha && out &&
-                      (g->n_edges == 0 || alpha_q),
-                  TANGO_ERR_NULL);
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && X_q && s_X && row_lse && s_alpha && absmax_alpha && out, TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
                       ws_bytes >= tango_gat_attention_workspace_bytes(g->n_nodes, g->n_edges, heads),
                   TANGO_ERR_WORKSPACE);
     TANGO_REQUIRE(tango_aligned(S_q, heads == 3 ? 1 : heads) && tango_aligned(D_q, heads == 3 ? 1 : heads), TANGO_ERR_BAD_SHAPE);
     hipStream_t st = tango_stream(stream);
-    float *absmax_alpha = static_cast<float *>(ws);
     int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256);
     if (g->n_edges == 0) {  // no edge: the scale of an empty tensor is 1
         rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(s_alpha), 0x3f800000u, 1, st);
         if (rc != TANGO_OK) return rc;
     }
-    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_rden, absmax_alpha, huge, st);
+    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, huge, st);
     if (rc != TANGO_OK) return rc;
-    return tango_spmm_attention_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_max, row_rden, absmax_alpha, rounding,
+    return tango_spmm_attention_async(g, TANGO_IN, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, st);
 }
 
 size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads)
 {
-    // per (node, head): a 16-byte record (P, row_max, row_rden) and a double dS accumulator; then the list of hub rows
+    // per (node, head): a 16-byte record (P, row_lse) and a double dS accumulator; then the list of hub rows
     return 256 + 3 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
 }
 
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
-                            const int8_t *D_q, const float *s_D, float slope, const float *row_max, const float *row_rden,
-                            const int8_t *alpha_q, const float *s_alpha, const int8_t *X_q, const float *s_X,
-                            const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
-                            float *dS, float *dD, void *ws, size_t ws_bytes, void *stream)
+                            const int8_t *D_q, const float *s_D, float slope, const float *row_lse, const int8_t *alpha_q,
+                            const float *s_alpha, const float *absmax_alpha, int rounding, uint64_t seed,
+                            uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X, const int8_t *dOut_q,
+                            const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha, float *dS, float *dD,
+                            void *ws, size_t ws_bytes, void *stream)
 {
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
     TANGO_REQUIRE(g->n_nodes > 0 && g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(g->in_ptr && g->out_ptr && (g->n_edges == 0 || (g->in_src && g->out_dst && g->out_eid)), TANGO_ERR_NULL);
     TANGO_REQUIRE(heads_supported(heads), TANGO_ERR_UNSUPPORTED);
     int rc = tango_validate_sddmm_dot_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_max && row_rden && s_alpha && X_q && s_X && dOut_q && s_dOut && dX_agg &&
-                      dS && dD && (g->n_edges == 0 || (alpha_q && dalpha)),
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && s_alpha && absmax_alpha && X_q && s_X && dOut_q && s_dOut &&
+                      dX_agg && dS && dD && (g->n_edges == 0 || dalpha),
                   TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) &&
                       tango_aligned(dalpha, 16),
                   TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(tango_aligned(S_q, heads == 3 ? 1 : heads) && tango_aligned(D_q, heads == 3 ? 1 : heads), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
                       ws_bytes >= tango_gat_attention_bwd_workspace_bytes(g->n_nodes, g->n_edges, heads),
                   TANGO_ERR_WORKSPACE);
@@ -315,14 +310,20 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     tango_attn_rec *rec = reinterpret_cast<tango_attn_rec *>(static_cast<char *>(ws) + 256);
     double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 2 * nh_bytes);
     int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
-    // 5': SPMM on the reversed graph with the cached int8 attention
-    rc = tango_spmm_async(g, TANGO_OUT, heads, dim, alpha_q, s_alpha, dOut_q, s_dOut, dX_agg, absmax_dX, st);
+    // 5': SPMM on the reversed graph.  With a cached alpha_q its codes are read through the edge-id map (a random
+    // 4-byte access per edge); without, the identical codes are recomputed from the cache-resident S_q, D_q, row_lse.
+    if (alpha_q)
+        rc = tango_spmm_async(g, TANGO_OUT, heads, dim, alpha_q, s_alpha, dOut_q, s_dOut, dX_agg, absmax_dX, st);
+    else
+        rc = tango_spmm_attention_async(g, TANGO_OUT, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
+                                        seed, stream_id_alpha, nullptr, const_cast<float *>(s_alpha), nullptr, dOut_q,
+                                        s_dOut, dX_agg, absmax_dX, st);
     if (rc != TANGO_OK) return rc;
     // 5'': dalpha, the only fp32 edge tensor of the backward pass
     rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);
     if (rc != TANGO_OK) return rc;
     // 4' and 3'' over in-edges, then 3' over out-edges
-    rc = tango_attn_bwd_dst_async(g, heads, S_q, s_S, D_q, s_D, slope, row_max, row_rden, dalpha, rec, dD, huge, st);
+    rc = tango_attn_bwd_dst_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, dalpha, rec, dD, huge, st);
     if (rc != TANGO_OK) return rc;
     return tango_attn_bwd_src_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, rec, dS_acc, dS, st);
 }

@@ -2,7 +2,7 @@
 // statistics pass and both backward passes form bit-identical fp32 values (Sec. 2.1 steps 3 and 4):
 //   t     = s_S*S_q[u][h] + s_D*D_q[v][h]          (two fp32 products, one fp32 sum)
 //   E     = t > 0 ? t : slope*t                    (LeakyReLU)
-//   alpha = exp(E - row_max) * row_rden            (row_rden = 1 / sum exp(E - row_max), one division per row)
+//   alpha = exp(E - row_lse)                       (row_lse = log of the row's sum of exp(E): max + log(sum exp(E - max)))
 // exp is the hardware exponential (v_exp_f32 on x*log2(e)); its relative error, about 1e-7*(1+|x|), is far
 // inside the fp32 tolerance of the softmax.
 #pragma once
@@ -18,10 +18,7 @@ __device__ static inline float tango_attn_score(float ts, float td, float slope,
     return positive ? x : slope * x;
 }
 
-__device__ static inline float tango_attn_alpha(float ev, float row_max, float row_rden)
-{
-    return tango_attn_exp(ev - row_max) * row_rden;
-}
+__device__ static inline float tango_attn_alpha(float ev, float row_lse) { return tango_attn_exp(ev - row_lse); }
 
 // The `heads` int8 values of one node (heads <= 8) as sign-extended ints; one vector load when heads is 2, 4 or 8
 // (the table must then be aligned to `heads` bytes).
@@ -67,6 +64,6 @@ __device__ static inline void tango_load_heads_rt(const int8_t *__restrict__ tab
 // scattered ones, and the records of all heads of a node share a cache line.
 struct __attribute__((aligned(16))) tango_attn_rec {
     double P;        // sum over the in-edges of dalpha*alpha
-    float row_max;
-    float row_rden;
+    float row_lse;
+    float unused;
 };

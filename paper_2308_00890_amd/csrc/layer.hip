@@ -40,10 +40,9 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
     TANGO_REQUIRE(L->k_in >= 1 && L->heads >= 1 && L->dim >= 1, TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(L->H && L->W && L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp && L->absmax_Hp &&
-                      L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->alpha_q && L->s_alpha &&
-                      L->out,
+                      L->Hp_q && L->s_Hp && L->S && L->D && L->S_q && L->s_S && L->D_q && L->s_D && L->s_alpha && L->out,
                   TANGO_ERR_NULL);
-    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_rden) : (L->E && L->alpha), TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_lse && L->absmax_alpha) : (L->E && L->alpha && L->alpha_q), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -70,8 +69,8 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     if (L->fused) {
         // steps 3-5 fused: E and alpha never reach memory in fp32
         return tango_gat_attention_fwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
-                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_max, L->row_rden, L->alpha_q,
-                                       L->s_alpha, L->alpha, L->out, L->absmax_out, sub, sub_bytes, stream);
+                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
+                                       L->absmax_alpha, L->alpha, L->out, L->absmax_out, sub, sub_bytes, stream);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -93,9 +92,9 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                       L->s_dHp && L->dW && L->da_src && L->da_dst,
                   TANGO_ERR_NULL);
     TANGO_REQUIRE(L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp_q && L->s_Hp && L->S_q && L->s_S &&
-                      L->D_q && L->s_D && L->alpha_q && L->s_alpha,
+                      L->D_q && L->s_D && L->s_alpha,
                   TANGO_ERR_NULL);
-    TANGO_REQUIRE(L->fused ? (L->row_max && L->row_rden) : (L->alpha != nullptr), TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->fused ? (L->row_lse && L->absmax_alpha) : (L->alpha && L->alpha_q), TANGO_ERR_NULL);
     const int64_t n = L->g->n_nodes, nnz = L->g->n_edges;
     const int64_t F = static_cast<int64_t>(L->heads) * L->dim;
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
@@ -110,9 +109,10 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                              L->s_g, sub, sub_bytes, stream));
     if (L->fused) {
         // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
-        TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_max,
-                                          L->row_rden, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
-                                          nullptr, L->dalpha, L->dS, L->dD, sub, sub_bytes, stream));
+        TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,
+                                          L->alpha_q, L->s_alpha, L->absmax_alpha, L->rounding, L->seed, sid + SID_ALPHA,
+                                          L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp, nullptr, L->dalpha, L->dS, L->dD, sub,
+                                          sub_bytes, stream));
     } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
     TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,

@@ -88,21 +88,24 @@ __device__ inline void unpack_words<16>(const uint4 &v, uint32_t (&w)[4])
 
 __device__ inline int sbyte(uint32_t w, int j) { return static_cast<int>(static_cast<int8_t>(w >> (8 * j))); }
 
-// Edge weights computed on the fly (fused attention forward, Sec. 2.1 steps 3-5): alpha of edge (u -> v), head h
-// is exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_max[v][h]) / row_rden[v][h], quantized with the abs-max
-// found by the statistics pass.
+// Edge weights computed on the fly (fused attention, Sec. 2.1 steps 3-5): alpha of edge (u -> v), head h is
+// exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_lse[v][h]), quantized with the abs-max found by the statistics
+// pass; the random bits of stochastic rounding belong to the edge's destination-major position, so the forward
+// pass (walking in-edges) and the backward pass (walking out-edges) form identical int8 codes.
 struct attn_params {
     const int8_t *Sq, *Dq;
     const float *sS, *sD;
     float slope;
-    const float *row_max, *row_rden;  // n x heads
+    const float *row_lse;  // n x heads, of the destination
     const float *absmax_alpha;
     tango_rng rng;
     int rounding;
-    int8_t *alpha_q;     // out: nnz x heads
-    float *s_alpha;      // out
-    float *alpha_dump;   // out or NULL: the fp32 alpha that was quantized
+    int8_t *alpha_q;     // forward: out, nnz x heads (or NULL)
+    float *s_alpha;      // forward: out
+    float *alpha_dump;   // forward: out or NULL, the fp32 alpha that was quantized
 };
+
+enum { W_LOAD = 0, W_ATT_FWD = 1, W_ATT_REV = 2 };
 
 struct spmm_args {
     int n;                 // rows
@@ -193,7 +196,7 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 
 // One wave per chunk of edges.  VEC = bytes of the feature row per lane; HAS_EID: the weight of edge j of
 // this direction sits at position eid[j] (reversed graph) instead of j.
-template <int VEC, bool HAS_EID, bool ATT>
+template <int VEC, bool HAS_EID, int WMODE>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
 {
     using V = typename vec_bytes<VEC>::type;
@@ -211,10 +214,11 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
     const bool active = gi < G;
     const int col = li * VEC;           // first of my VEC columns
     const int h = col / a.dim;          // their head
+    constexpr bool ATT = WMODE != W_LOAD;
     float s_w, inv_w = 0.0f, att_sS = 0.0f, att_sD = 0.0f;
     if (ATT) {
         tango_scale_from_absmax(*a.att.absmax_alpha, s_w, inv_w);
-        if (blockIdx.x == 0 && threadIdx.x == 0) *a.att.s_alpha = s_w;
+        if (WMODE == W_ATT_FWD && blockIdx.x == 0 && threadIdx.x == 0) *a.att.s_alpha = s_w;
         att_sS = *a.att.sS;
         att_sD = *a.att.sD;
     } else {
@@ -246,21 +250,24 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
                 const int e = base + lane;
                 my_nb = a.idx[e];
                 if (ATT) {
-                    // steps 3-4 and the quantization of alpha for this edge, all heads
+                    // steps 3-4 and the quantization of alpha for this edge, all heads.  Forward: this row is the
+                    // destination, the neighbour the source; reverse: the other way round, and the edge's
+                    // destination-major position (for the random bits) comes from eid.
                     const int H = a.heads;
-                    const int64_t i0 = static_cast<int64_t>(e) * H;
+                    const int64_t src_node = (WMODE == W_ATT_FWD) ? my_nb : r;
+                    const int64_t dst_node = (WMODE == W_ATT_FWD) ? r : my_nb;
+                    const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(a.eid[e])) * H;
                     uint4 blk = make_uint4(0, 0, 0, 0);
                     uint64_t have = ~uint64_t(0);
                     int sq[8], dq[8];
-                    tango_load_heads_rt(a.att.Sq, my_nb, H, sq);
-                    tango_load_heads_rt(a.att.Dq, r, H, dq);
+                    tango_load_heads_rt(a.att.Sq, src_node, H, sq);
+                    tango_load_heads_rt(a.att.Dq, dst_node, H, dq);
                     for (int hh = 0; hh < H; ++hh) {
                         bool pos;
                         const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
                                                           a.att.slope, pos);
-                        const float al = tango_attn_alpha(ev, a.att.row_max[static_cast<int64_t>(r) * H + hh],
-                                                          a.att.row_rden[static_cast<int64_t>(r) * H + hh]);
-                        if (a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
+                        const float al = tango_attn_alpha(ev, a.att.row_lse[dst_node * H + hh]);
+                        if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
                         int q;
                         if (a.att.rounding == TANGO_SR) {
                             const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
                         } else {
                             q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
                         }
-                        a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
+                        if (WMODE == W_ATT_FWD && a.att.alpha_q) a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
                         const uint32_t b = static_cast<uint32_t>(q) & 0xffu;
                         if (hh < 4)
                             my_w0 |= b << (8 * hh);
@@ -396,7 +403,7 @@ struct sddmm_dot_args {
     const int8_t *Sq, *Dq;
     const float *sS, *sD;
     float slope;
-    const tango_attn_rec *rec;       // n x heads: (P, row_max, row_rden) of the destination
+    const tango_attn_rec *rec;       // n x heads: (P, row_lse) of the destination
     double *dS_acc;                  // n x heads, zero-initialised
 };
 
@@ -501,7 +508,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                         bool pos;
                         const float ev = tango_attn_score(ts_row, sD * static_cast<float>(a.Dq[vh]), a.slope, pos);
                         const tango_attn_rec rc = a.rec[vh];
-                        const float al = tango_attn_alpha(ev, rc.row_max, rc.row_rden);
+                        const float al = tango_attn_alpha(ev, rc.row_lse);
                         const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
                         acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
                     } else {
@@ -612,13 +619,15 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
         const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         const int vec = pick_vec(a.F, dim, false);
-#define TANGO_SPMM(V_)                                                           \
-    if (att)                                                                     \
-        k_spmm<V_, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);     \
-    else if (a.eid)                                                              \
-        k_spmm<V_, true, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);     \
-    else                                                                         \
-        k_spmm<V_, false, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+#define TANGO_SPMM(V_)                                                                  \
+    if (att && a.eid)                                                                   \
+        k_spmm<V_, true, W_ATT_REV><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);        \
+    else if (att)                                                                       \
+        k_spmm<V_, false, W_ATT_FWD><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);       \
+    else if (a.eid)                                                                     \
+        k_spmm<V_, true, W_LOAD><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);           \
+    else                                                                                \
+        k_spmm<V_, false, W_LOAD><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
         if (vec == 4) { TANGO_SPMM(4) } else if (vec == 8) { TANGO_SPMM(8) } else { TANGO_SPMM(16) }
 #undef TANGO_SPMM
         TANGO_LAUNCH_CHECK();
@@ -634,19 +643,21 @@ int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, co
     return spmm_launch(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out, nullptr, st);
 }
 
-// SPMM over in-edges whose weights are the attention scores computed (and quantized, and stored) on the fly.
-int tango_spmm_attention_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
-                               const int8_t *Dq, const float *sD, float slope, const float *row_max,
-                               const float *row_rden, const float *absmax_alpha, int rounding, uint64_t seed,
-                               uint64_t stream_id, int8_t *alpha_q, float *s_alpha, float *alpha_dump,
-                               const int8_t *X_q, const float *s_X, float *out, float *absmax_out, hipStream_t st)
+// SPMM whose weights are the attention scores computed (and quantized) on the fly.  direction TANGO_IN: forward
+// (step 5), also stores alpha_q / s_alpha / alpha_dump.  direction TANGO_OUT: step 5' on the reversed graph; the
+// same int8 codes are recomputed, nothing is stored, s_alpha is read.
+int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *Sq,
+                               const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
+                               const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
+                               int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
+                               float *out, float *absmax_out, hipStream_t st)
 {
     attn_params att;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
-    att.row_max = row_max; att.row_rden = row_rden; att.absmax_alpha = absmax_alpha;
+    att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = alpha_q; att.s_alpha = s_alpha; att.alpha_dump = alpha_dump;
-    return spmm_launch(g, TANGO_IN, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
+    return spmm_launch(g, direction, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
 }
 
 int tango_validate_spmm_shape(int heads, int dim) { return validate_feature_shape(heads, dim); }

@@ -34,14 +34,15 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     Xq = rand_i8((g.n_nodes, F), 10)
     sS, sD, sX, slope = np.float32(0.021), np.float32(0.013), np.float32(0.017), 0.2
     seed, sid = 4242, 38
-    row_max, row_rden = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    row_lse = empty((g.n_nodes, heads), torch.float32)
+    am_alpha = scalar(-1)
     alpha_q = empty((g.n_edges, heads), torch.int8)
     dump = empty((g.n_edges, heads), torch.float32)
     s_alpha, am = scalar(-1), scalar(-1)
     out = empty((g.n_nodes, F), torch.float32)
     ws = workspace(T.tango_gat_attention_workspace_bytes(g.n_nodes, g.n_edges, heads))
     T.tango_gat_attention_fwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, dev(Xq), scalar(sX), rounding,
-                              seed, sid, row_max, row_rden, alpha_q, s_alpha, dump, out, am, ws)
+                              seed, sid, row_lse, alpha_q, s_alpha, am_alpha, dump, out, am, ws)
     torch.cuda.synchronize()
     E = orc.sddmm_add(g, Sq, sS, Dq, sD, slope)
     alpha = orc.edge_softmax(g, E)
@@ -54,14 +55,14 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     want, want_am = orc.spmm_in(g, host(alpha_q), host(s_alpha)[0], Xq, sX)
     assert_bit_exact(host(out), want, "out")
     assert host(am)[0] == want_am
-    # row statistics
+    # row statistics: log-sum-exp of the activated scores
     nonempty = np.diff(g.in_ptr) > 0
     starts = g.in_ptr[:-1][nonempty]
     if g.n_edges:
-        m = np.maximum.reduceat(E, starts, axis=0)
-        assert_bit_exact(host(row_max)[nonempty], m, "row max")
+        m = np.maximum.reduceat(E, starts, axis=0).astype(np.float64)
         den = np.add.reduceat(np.exp(E.astype(np.float64) - np.repeat(m, np.diff(g.in_ptr)[nonempty], axis=0)), starts, axis=0)
-        assert_close(host(row_rden)[nonempty], 1.0 / den, "reciprocal row denominator")
+        assert_close(host(row_lse)[nonempty], m + np.log(den), "row log-sum-exp", rtol=1e-6, atol=1e-6)
+        assert host(am_alpha)[0] == host(dump).max()
 
     # ---- backward from the caches of the fused forward
     dOq = rand_i8((g.n_nodes, F), 11)
@@ -71,9 +72,20 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     dS, dD = empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
     amx = scalar(-1)
     wsb = workspace(T.tango_gat_attention_bwd_workspace_bytes(g.n_nodes, g.n_edges, heads))
-    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_max, row_rden, alpha_q,
-                              s_alpha, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX, amx, dal, dS, dD, wsb)
+    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_lse, alpha_q, s_alpha,
+                              am_alpha, rounding, seed, sid, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX, amx, dal, dS, dD,
+                              wsb)
     torch.cuda.synchronize()
+    # without the cached alpha_q the reverse SPMM recomputes the same int8 codes
+    dX2 = empty((g.n_nodes, F), torch.float32)
+    amx2 = scalar(-1)
+    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_lse, None, s_alpha,
+                              am_alpha, rounding, seed, sid, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX2, amx2,
+                              empty((g.n_edges, heads), torch.float32), empty((g.n_nodes, heads), torch.float32),
+                              empty((g.n_nodes, heads), torch.float32), wsb)
+    torch.cuda.synchronize()
+    assert_bit_exact(host(dX2), host(dX), "dX_agg with recomputed attention codes")
+    assert host(amx2)[0] == host(amx)[0]
     w_dX, w_am = orc.spmm_rev(g, host(alpha_q), host(s_alpha)[0], dOq, s_dO)
     assert_bit_exact(host(dX), w_dX, "dX_agg")
     assert host(amx)[0] == w_am

@@ -77,7 +77,7 @@ def test_full_size_gat_layer_sampled(T, name):
     seed, slope, rounding = li.sr_seed, 0.2, orc.SR
     G = T.Graph.from_host(g)
     L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed, 0,
-                   fused=True, keep_alpha=True)
+                   fused=True, keep_alpha=True, keep_alpha_q=True)
     T.tango_gat_layer_fwd(L)
     T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()

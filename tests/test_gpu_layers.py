@@ -51,7 +51,7 @@ def test_gat_layer_stagewise(T, case, rounding, fused):
     b = 16 * layer_id
     G = T.Graph.from_host(g)
     L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
-                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True)
+                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True, keep_alpha_q=True)
     T.tango_gat_layer_fwd(L)
     T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()
@@ -119,6 +119,24 @@ def test_gat_layer_stagewise(T, case, rounding, fused):
     for name, ref in (("S_q", f["S_q"]), ("D_q", f["D_q"]), ("alpha_q", f["alpha_q"])):
         diff = o[name].astype(np.int32) - ref.astype(np.int32)
         assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-2, name
+
+
+def test_fused_gat_layer_without_edge_caches(T):
+    """The production launch (what bench.py times) keeps neither alpha nor alpha_q: same results, bit for bit."""
+    import torch
+
+    li, slope = gat_case("rmat_h4")
+    G = T.Graph.from_host(li.graph)
+    args = (G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, orc.SR, li.sr_seed, 1)
+    A = T.GatLayer(*args, fused=True, keep_alpha=True, keep_alpha_q=True)
+    B = T.GatLayer(*args, fused=True)
+    for L in (A, B):
+        T.tango_gat_layer_fwd(L)
+        T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    assert "alpha_q" not in B.t and "alpha" not in B.t
+    for name in ("out", "dHp", "dS", "dD", "dW", "dH", "da_src", "da_dst", "dalpha"):
+        assert_bit_exact(host(B[name]), host(A[name]), name)
 
 
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
