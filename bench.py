@@ -31,6 +31,19 @@ def spmm_algorithmic_bytes(n, nnz, heads, F):
     return nnz * (4 + heads + F) + n * (4 + 4 * F)
 
 
+def rev_attention_spmm_algorithmic_bytes(n, nnz, heads, F):
+    """Per launch of the reverse SPMM with recomputed attention codes (step 5'): per edge 4 (neighbour index)
+    + 4 (edge id, for the random bits) + F (gathered int8 gradient row) + heads (D_q of the neighbour)
+    + 4*heads (its row_lse); per node 4 (row pointer) + heads (S_q) + 4F (fp32 result)."""
+    return nnz * (8 + F + 5 * heads) + n * (4 + heads + 4 * F)
+
+
+# HBM-side traffic of the dominant kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this file, scaled by a 1 GiB copy kernel (FETCH_SIZE reads half the copied bytes, WRITE_SIZE all of them); see
+# profiles/.  Keyed by workload; None where no counter run has been recorded.
+MEASURED_TRAFFIC = {"gat_dense": 29.0e9}  # profiles/gat_dense_hbm_traffic.md, k_spmm<16, true, 2>
+
+
 def time_events(torch, fn, iters):
     """Average milliseconds of fn() over iters launches, HIP events on the current stream."""
     st = torch.cuda.current_stream()
@@ -80,6 +93,8 @@ def main():
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale-down", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy three times (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no multi-GPU path exists); use --gpus 1")
@@ -96,6 +111,14 @@ def main():
         sys.exit(3)
     T.load_library()
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        log("copied 3 x %d bytes" % (a.numel() * 4))
+        return
     name = args.workload
     cfg = ti.CONFIGS[name]
     t0 = time.perf_counter()
@@ -114,12 +137,19 @@ def main():
         step = lambda: (T.tango_gcn_layer_fwd(L), T.tango_gcn_layer_bwd(L))
         heads, F = 1, cfg["dim"]
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
+        spmm_name = "k_spmm<16, false, 0> (tango_qspmm, in-edge direction)"
+        alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     else:
         L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0)
         step = lambda: (T.tango_gat_layer_fwd(L), T.tango_gat_layer_bwd(L))
         heads, F = li.heads, li.heads * li.dim
-        spmm = lambda: T.tango_qspmm(G, T.IN, heads, li.dim, L["alpha_q"], L["s_alpha"], L["Hp_q"], L["s_Hp"], L["out"],
-                                     L["absmax_out"])
+        # the kernel with the largest share of the step: the reverse SPMM (step 5') with recomputed attention codes,
+        # launched exactly as inside tango_gat_layer_bwd (dalpha = dS = dD = None: step 5' only)
+        spmm = lambda: T.tango_gat_attention_bwd(G, heads, li.dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
+                                                 None, L["s_alpha"], L["absmax_alpha"], T.SR, li.sr_seed, 6, L["Hp_q"],
+                                                 L["s_Hp"], L["g_q"], L["s_g"], L["dHp"], None, None, None, None, L["ws"])
+        spmm_name = "k_spmm<16, true, 2> (reverse SPMM with recomputed attention codes, step 5')"
+        alg = rev_attention_spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
 
     for _ in range(args.warmup):
         step()
@@ -131,13 +161,13 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     log("layer fwd+bwd: %.3f ms/step" % ms_per_step)
 
-    # dominant kernel: the quantized SPMM (one launch = tango_qspmm over the whole graph, as inside the layer)
+    # dominant kernel, timed with HIP events on the stream it is launched on (the step above left every input it
+    # needs in place); the two small helper kernels around it (row zeroing, split-row dequantize) are included
     spmm()
     torch.cuda.synchronize()
     spmm_ms = time_events(torch, spmm, max(args.steps, 5))
-    alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     achieved = alg / (spmm_ms * 1e-3) / 1e9
-    log("qSPMM: %.3f ms/launch, %.1f algorithmic GB/s" % (spmm_ms, achieved))
+    log("%s: %.3f ms/launch, %.1f algorithmic GB/s" % (spmm_name, spmm_ms, achieved))
 
     out = {
         "metric": "ms per quantized GAT layer fwd+bwd" if cfg["kind"] == "gat" else "ms per quantized GCN layer fwd+bwd",
@@ -158,13 +188,13 @@ def main():
             "scale_down": args.scale_down,
         },
         "roofline": {
-            "kernel": "k_spmm (tango_qspmm, in-edge direction)",
+            "kernel": spmm_name,
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC.get(name) if args.scale_down == 1 else None,
             "algorithmic_bytes_per_launch": alg,
             "ms_per_launch": spmm_ms,
         },

@@ -292,6 +292,7 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
  *   dD, dS (n x heads fp32) = sums over in-/out-edges of alpha*(dalpha - P)*lrelu'(t) with the fp32 alpha
  *                             recomputed from S_q, D_q, row_lse exactly as the forward pass computed it
  *                             (the gradient of the pre-activation scores is never written to memory).
+ *                             dalpha, dS and dD may all three be NULL: then only step 5' runs.
  * ws: at least tango_gat_attention_bwd_workspace_bytes() bytes.
  */
 size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads);

@@ -296,8 +296,10 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     int rc = tango_validate_sddmm_dot_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
     TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && s_alpha && absmax_alpha && X_q && s_X && dOut_q && s_dOut &&
-                      dX_agg && dS && dD && (g->n_edges == 0 || dalpha),
+                      dX_agg,
                   TANGO_ERR_NULL);
+    const bool edge_part = dalpha || dS || dD;  // all three or none
+    TANGO_REQUIRE(!edge_part || (dS && dD && (g->n_edges == 0 || dalpha)), TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) &&
                       tango_aligned(dalpha, 16),
                   TANGO_ERR_BAD_SHAPE);
@@ -318,7 +320,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
         rc = tango_spmm_attention_async(g, TANGO_OUT, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                         seed, stream_id_alpha, nullptr, const_cast<float *>(s_alpha), nullptr, dOut_q,
                                         s_dOut, dX_agg, absmax_dX, st);
-    if (rc != TANGO_OK) return rc;
+    if (rc != TANGO_OK || !edge_part) return rc;
     // 5'': dalpha, the only fp32 edge tensor of the backward pass
     rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);
     if (rc != TANGO_OK) return rc;
