@@ -55,3 +55,33 @@ def test_argument_validation_needs_no_gpu(lib):
     rc = lib.tango_quantize(None, ctypes.c_size_t(8), 0, ctypes.c_uint64(0), ctypes.c_uint64(0), None, None, None, None,
                             ctypes.c_size_t(0), None)
     assert rc == -1  # NULL tensors
+
+
+def test_layer_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors of tango_gat_layer / tango_gcn_layer / tango_graph have the C compiler's sizes and offsets."""
+    import subprocess
+
+    from paper_2308_00890_amd import binding
+
+    src = tmp_path / "layout.c"
+    fields = {
+        "tango_graph": ["n_nodes", "n_edges", "in_ptr", "out_eid"],
+        "tango_gat_layer": ["g", "slope", "seed", "H", "absmax_Hp", "alpha_q", "grad_out", "dalpha", "da_dst", "fused",
+                            "row_lse", "absmax_alpha", "ws", "ws_bytes"],
+        "tango_gcn_layer": ["g", "f_out", "seed", "w_q", "Hp", "grad_out", "dH", "ws", "ws_bytes"],
+    }
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "tango.h"', "int main(void){"]
+    for st, fs in fields.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (st, st))
+        for f in fs:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (st, f, st, f))
+    lines.append("return 0;}")
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = dict(l.split() for l in subprocess.check_output([str(exe)]).decode().splitlines())
+    for st, fs in fields.items():
+        cls = getattr(binding, st)
+        assert int(out[st]) == ctypes.sizeof(cls), st
+        for f in fs:
+            assert int(out["%s.%s" % (st, f)]) == getattr(cls, f).offset, (st, f)
