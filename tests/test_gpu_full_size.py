@@ -142,3 +142,86 @@ def test_full_size_gat_layer_sampled(T, name):
     X = (sc("s_Hp") * o["Hp_q"].astype(np.float32)).astype(np.float64).reshape(g.n_nodes, heads, dim)
     assert_close(o["da_src"], np.einsum("vh,vhd->hd", o["dS"].astype(np.float64), X), "da_src", rtol=1e-5, atol=1e-5)
     assert_close(o["da_dst"], np.einsum("vh,vhd->hd", o["dD"].astype(np.float64), X), "da_dst", rtol=1e-5, atol=1e-5)
+
+
+def test_full_size_gcn_layer_config2(T):
+    """Configuration 2 at full size: every stage of the GCN layer is integer-exact, so the whole oracle chain is run."""
+    import torch
+
+    from gpu_util import scalar
+
+    li = ti.layer_inputs("gcn_arxiv")
+    g = li.graph
+    seed = li.sr_seed
+    w_q, s_w = orc.quantize(ti.gcn_edge_weights(g), orc.SR, seed, orc.SID_EW)
+    G = T.Graph.from_host(g)
+    L = T.GcnLayer(G, dev(li.feat), dev(li.weight), dev(w_q), scalar(s_w), dev(li.grad_out), orc.SR, seed, 0)
+    T.tango_gcn_layer_fwd(L)
+    T.tango_gcn_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    f = orc.gcn_layer_fwd(g, li.feat, li.weight, w_q, s_w, orc.SR, seed, 0)
+    bw = orc.gcn_layer_bwd(g, f, w_q, s_w, li.grad_out, orc.SR, seed, 0)
+    for name in ("H_q", "W_q", "Hp", "Hp_q", "out"):
+        assert_bit_exact(o[name], f[name], name)
+    for name in ("g_q", "dHp", "dHp_q", "dW", "dH"):
+        assert_bit_exact(o[name], bw[name], name)
+    assert o["absmax_out"][0] == f["absmax_out"] and o["s_dHp"][0] == bw["s_dHp"]
+
+
+@pytest.mark.parametrize("F", [32, 64, 128, 256, 512])
+def test_full_size_primitive_sweep_config5(T, F):
+    """Configuration 5 (scale-22 R-MAT, mean degree 16): qSPMM in both directions and qSDDMM-dot, sampled rows."""
+    import torch
+
+    from gpu_util import empty, scalar
+
+    g = _sweep_graph()
+    G = _sweep_graph_dev(T)
+    rng = np.random.default_rng(F)
+    w = rng.integers(-127, 128, size=(g.n_edges, 1), dtype=np.int8)
+    X = rng.integers(-127, 128, size=(g.n_nodes, F), dtype=np.int8)
+    Y = rng.integers(-127, 128, size=(g.n_nodes, F), dtype=np.int8)
+    sw, sx, sy = np.float32(1 / 127), np.float32(0.02), np.float32(0.003)
+    Xd, Yd, wd = dev(X), dev(Y), dev(w)
+    out = empty((g.n_nodes, F), torch.float32)
+    am = scalar(-1)
+    T.tango_qspmm(G, T.IN, 1, F, wd, scalar(sw), Xd, scalar(sx), out, am)
+    torch.cuda.synchronize()
+    o_in, am_in = host(out), host(am)[0]
+    T.tango_qspmm(G, T.OUT, 1, F, wd, scalar(sw), Yd, scalar(sy), out, am)
+    torch.cuda.synchronize()
+    o_out, am_out = host(out), host(am)[0]
+    E = empty((g.n_edges, 1), torch.float32)
+    T.tango_qsddmm(G, T.SDDMM_DOT, 1, F, Xd, scalar(sx), Yd, scalar(sy), 0.0, E)
+    torch.cuda.synchronize()
+    e_dot = host(E)
+    del Xd, Yd, wd, out, E
+    torch.cuda.empty_cache()
+
+    vrows = sample_rows(g, rng, 200, g.in_ptr)
+    sub, eids = subgraph(g, in_edges_of(g, vrows))
+    want, _ = orc.spmm_in(sub, w[eids], sw, X, sx)
+    assert_bit_exact(o_in[vrows], want[vrows], "spmm in rows")
+    assert am_in == np.abs(o_in).max()
+    assert_bit_exact(e_dot[eids], orc.sddmm_dot(sub, Y, sy, X, sx, 1), "sddmm-dot on sampled rows")
+    urows = sample_rows(g, rng, 200, g.out_ptr)
+    sub2, eids2 = subgraph(g, out_edges_of(g, urows))
+    want2, _ = orc.spmm_rev(sub2, w[eids2], sw, Y, sy)
+    assert_bit_exact(o_out[urows], want2[urows], "spmm out rows")
+    assert am_out == np.abs(o_out).max()
+
+
+_sweep = {}
+
+
+def _sweep_graph():
+    if "g" not in _sweep:
+        _sweep["g"] = ti.config_graph("sweep22")
+    return _sweep["g"]
+
+
+def _sweep_graph_dev(T):
+    if "G" not in _sweep:
+        _sweep["G"] = T.Graph.from_host(_sweep_graph())
+    return _sweep["G"]
