@@ -305,6 +305,25 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                             float *dalpha, float *dS, float *dD, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------ */
+/* Full-precision twins of the two gather-bound primitives, for measuring     */
+/* what quantization buys on the same graph (Sec. 3.3: the random accesses    */
+/* hit a 4x smaller table).  Not part of the quantized path.                  */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * out (n x F fp32) = SPMM of fp32 edge weights w (nnz x heads, destination-major positions) and fp32 features
+ * X (n x F); direction as in tango_qspmm.  Sums are formed in fp32 (order not fixed for rows longer than 1,024
+ * edges).  F = heads*dim must be a power of two <= 256 with dim a power of two >= 4, or a multiple of 256 with
+ * heads == 1.  X, out 16-byte aligned.
+ */
+int tango_spmm_f32(const tango_graph *g, int direction, int heads, int dim, const float *w, const float *X,
+                   float *out, void *stream);
+
+/* E[e][h] = X_dst[dst(e)][h][:] . X_src[src(e)][h][:] in fp32; shapes as above. */
+int tango_sddmm_dot_f32(const tango_graph *g, int heads, int dim, const float *X_src, const float *X_dst,
+                        float *E, void *stream);
+
+/* ------------------------------------------------------------------------ */
 /* Whole-layer entry points: the primitives above chained on one stream,     */
 /* with every quantized tensor produced once and reused (Sec. 3.3             */
 /* "Inter-primitive optimization": forward tensors cached for backward, one  */

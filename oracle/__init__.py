@@ -60,6 +60,8 @@ def _L():
             "orc_sddmm_add_bwd",
             "orc_edge_softmax",
             "orc_edge_softmax_bwd",
+            "orc_spmm_f32",
+            "orc_sddmm_dot_f32",
         ):
             getattr(lib, name).restype = None
         _lib = lib
@@ -273,6 +275,29 @@ def spmm_in(g, w_q, s_w, X_q, s_X, want_acc: bool = False):
 def spmm_rev(g, w_q, s_w, Y_q, s_Y, want_acc: bool = False):
     """out[u] = sum over out-edges (u->v) of w[e] * Y[v]; returns (out, absmax[, acc])."""
     return _spmm(_L().orc_spmm_rev, g, w_q, s_w, Y_q, s_Y, want_acc)
+
+
+def spmm_f32(g, w, X, reverse: bool = False) -> np.ndarray:
+    """fp32 twin of the SPMM: out[v] = sum over in-edges of w[e]*X[src] (reverse: out[u] = sum over out-edges of w[e]*X[dst])."""
+    w = _c(w, np.float32)
+    X = _c(X, np.float32)
+    heads = w.shape[1]
+    F = X.shape[1]
+    out = np.empty((g.n_nodes, F), np.float32)
+    _L().orc_spmm_f32(_i64(g.n_nodes), _p(g.in_ptr), _p(g.in_src), ctypes.c_int(heads), ctypes.c_int(F // heads), _p(w), _p(X),
+                      ctypes.c_int(1 if reverse else 0), _p(out))
+    return out
+
+
+def sddmm_dot_f32(g, X_dst, X_src, heads: int) -> np.ndarray:
+    """fp32 twin of the SDDMM-dot: out[e][h] = X_dst[dst(e)][h] . X_src[src(e)][h]."""
+    X_dst = _c(X_dst, np.float32)
+    X_src = _c(X_src, np.float32)
+    F = X_dst.shape[1]
+    out = np.empty((g.n_edges, heads), np.float32)
+    _L().orc_sddmm_dot_f32(_i64(g.n_nodes), _p(g.in_ptr), _p(g.in_src), ctypes.c_int(heads), ctypes.c_int(F // heads),
+                           _p(X_dst), _p(X_src), _p(out))
+    return out
 
 
 def head_proj_bwd(dS, dD, a_src, a_dst, X_q, s_X, dX_agg):

@@ -431,3 +431,45 @@ float orc_head_proj_bwd(int64_t n, int heads, int dim, const float *dS, const fl
     free(ad);
     return m;
 }
+
+/* ------------------------------------------------------------------ */
+/* Full-precision twins (the non-quantized primitives the quantized    */
+/* ones are compared with, Sec. 2.1 steps 5 and 5''): same products in  */
+/* fp32 storage, sums in fp64, one fp32 rounding.                       */
+/* ------------------------------------------------------------------ */
+void orc_spmm_f32(int64_t n, const int32_t *in_ptr, const int32_t *in_src, int heads, int dim, const float *w,
+                  const float *X, int reverse, float *out)
+{
+    size_t F = (size_t)heads * dim;
+    double *acc = (double *)calloc((size_t)n * F, sizeof(double));
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < (int64_t)F; ++c) {
+        int h = (int)(c / dim);
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t e = in_ptr[v]; e < in_ptr[v + 1]; ++e) {
+                int64_t u = in_src[e];
+                if (reverse)
+                    acc[u * F + c] += (double)w[e * heads + h] * (double)X[v * F + c];
+                else
+                    acc[v * F + c] += (double)w[e * heads + h] * (double)X[u * F + c];
+            }
+    }
+    for (size_t i = 0; i < (size_t)n * F; ++i) out[i] = (float)acc[i];
+    free(acc);
+}
+
+void orc_sddmm_dot_f32(int64_t n, const int32_t *in_ptr, const int32_t *in_src, int heads, int dim, const float *Xdst,
+                       const float *Xsrc, float *out)
+{
+    size_t F = (size_t)heads * dim;
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t e = in_ptr[v]; e < in_ptr[v + 1]; ++e) {
+            int64_t u = in_src[e];
+            for (int h = 0; h < heads; ++h) {
+                double t = 0.0;
+                for (int d = 0; d < dim; ++d) t += (double)Xdst[v * F + h * dim + d] * (double)Xsrc[u * F + h * dim + d];
+                out[e * heads + h] = (float)t;
+            }
+        }
+}

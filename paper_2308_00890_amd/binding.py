@@ -338,6 +338,24 @@ def tango_gat_attention_bwd(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, a
     )
 
 
+SIGNATURES.update({
+    "tango_spmm_f32": (_int, [_gp, _int, _int, _int, _vp, _vp, _vp, _vp]),
+    "tango_sddmm_dot_f32": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp]),
+})
+
+
+def tango_spmm_f32(g, direction, heads, dim, w, X, out):
+    f32 = torch.float32
+    _check(load_library().tango_spmm_f32(g.ref(), direction, heads, dim, _ptr(w, f32), _ptr(X, f32), _ptr(out, f32), _stream()),
+           "tango_spmm_f32")
+
+
+def tango_sddmm_dot_f32(g, heads, dim, X_src, X_dst, E):
+    f32 = torch.float32
+    _check(load_library().tango_sddmm_dot_f32(g.ref(), heads, dim, _ptr(X_src, f32), _ptr(X_dst, f32), _ptr(E, f32), _stream()),
+           "tango_sddmm_dot_f32")
+
+
 # ------------------------------------------------------------------- whole layers
 class tango_gat_layer(ctypes.Structure):
     _fields_ = (

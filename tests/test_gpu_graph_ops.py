@@ -188,3 +188,30 @@ def test_unsupported_shapes_are_refused(T):
     with pytest.raises(T.TangoError):  # bad direction
         T.tango_qspmm(G, 7, 2, 32, dev(rand_i8((g.n_edges, 2), 1)), scalar(1), dev(rand_i8((g.n_nodes, 64), 2)), scalar(1),
                       empty((g.n_nodes, 64), torch.float32), None)
+
+
+@pytest.mark.parametrize("gname,heads,dim", [("toy", 2, 32), ("rmat", 4, 64), ("rmat", 1, 256), ("sparse", 1, 32),
+                                             ("sparse", 1, 128), ("sparse", 1, 512), ("holes", 2, 16), ("one", 1, 64)])
+def test_fp32_twins(T, gname, heads, dim):
+    """The full-precision comparison kernels against fp64-accumulating CPU versions (fp32 sums: 1e-5 relative to the
+    largest term magnitude of a row, which for N(0,1) inputs and the longest rows here is covered by atol 2e-4)."""
+    import torch
+
+    g = graph(gname)
+    G = T.Graph.from_host(g)
+    F = heads * dim
+    w = ti.normal((g.n_edges, heads), 31)
+    X = ti.normal((g.n_nodes, F), 32)
+    Y = ti.normal((g.n_nodes, F), 33)
+    out = empty((g.n_nodes, F), torch.float32)
+    out.fill_(float("nan"))
+    T.tango_spmm_f32(G, T.IN, heads, dim, dev(w), dev(X), out)
+    torch.cuda.synchronize()
+    assert_close(host(out), orc.spmm_f32(g, w, X), "spmm f32 in", rtol=1e-5, atol=2e-4)
+    T.tango_spmm_f32(G, T.OUT, heads, dim, dev(w), dev(Y), out)
+    torch.cuda.synchronize()
+    assert_close(host(out), orc.spmm_f32(g, w, Y, reverse=True), "spmm f32 out", rtol=1e-5, atol=2e-4)
+    E = empty((g.n_edges, heads), torch.float32)
+    T.tango_sddmm_dot_f32(G, heads, dim, dev(X), dev(Y), E)
+    torch.cuda.synchronize()
+    assert_close(host(E), orc.sddmm_dot_f32(g, Y, X, heads), "sddmm-dot f32", rtol=1e-5, atol=2e-5)

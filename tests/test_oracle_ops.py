@@ -294,6 +294,23 @@ def test_spmm_rev_paper_value(paper):
     assert np.allclose(out[1], ex["dHp_v1"], atol=0.011 + float(sg))
 
 
+def test_fp32_twins_dense_definitions():
+    g = small_graph(40, 260, 17)
+    heads, dim = 2, 4
+    rng = np.random.default_rng(18)
+    w = rng.standard_normal((g.n_edges, heads)).astype(np.float32)
+    X = rng.standard_normal((g.n_nodes, heads * dim)).astype(np.float32)
+    Y = rng.standard_normal((g.n_nodes, heads * dim)).astype(np.float32)
+    Wd = to_dense(g, w.astype(np.float64))
+    X3 = X.reshape(-1, heads, dim).astype(np.float64)
+    Y3 = Y.reshape(-1, heads, dim).astype(np.float64)
+    assert np.array_equal(orc.spmm_f32(g, w, X), np.einsum("hvu,uhd->vhd", Wd, X3).reshape(g.n_nodes, -1).astype(np.float32))
+    assert np.array_equal(orc.spmm_f32(g, w, Y, reverse=True),
+                          np.einsum("hvu,vhd->uhd", Wd, Y3).reshape(g.n_nodes, -1).astype(np.float32))
+    dense = np.einsum("vhd,uhd->hvu", Y3, X3) * mask(g)[None]
+    assert np.array_equal(orc.sddmm_dot_f32(g, Y, X, heads), from_dense(g, dense).astype(np.float32))
+
+
 # ---------------------------------------------------- SDDMM-add backward / sums
 def test_sddmm_add_bwd_dense_definition():
     g = small_graph()
