@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv"])
+    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products"])
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale-down", type=int, default=0)
@@ -139,6 +139,37 @@ def main():
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
         spmm_name = "k_spmm<16, false, 0> (tango_qspmm, in-edge direction)"
         alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
+    elif name == "gat_products":
+        # configuration 4: three stacked GAT layers (K_in 100 -> 384 -> 384 -> 384), ReLU between them; one step =
+        # forward through all three, then backward through all three
+        F = li.heads * li.dim
+        heads = li.heads
+        grads = [torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev) for _ in range(3)]
+        grads[2].copy_(to(li.grad_out))
+        acts = [to(li.feat)] + [torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev) for _ in range(2)]
+        layers = []
+        for i in range(3):
+            k = li.feat.shape[1] if i == 0 else F
+            W = to(ti.xavier_uniform(k, F, (k, F), li.sr_seed + 10 + i))
+            layers.append(T.GatLayer(G, acts[i], W, to(li.a_src), to(li.a_dst), grads[i], slope, T.SR, li.sr_seed, i,
+                                     want_dH=(i > 0)))
+
+        def step():
+            for i in range(3):
+                T.tango_gat_layer_fwd(layers[i])
+                if i < 2:
+                    T.tango_relu(layers[i]["out"], acts[i + 1])
+            for i in (2, 1, 0):
+                T.tango_gat_layer_bwd(layers[i])
+                if i > 0:
+                    T.tango_relu_bwd(layers[i - 1]["out"], layers[i]["dH"], grads[i - 1])
+
+        L = layers[2]
+        spmm = lambda: T.tango_gat_attention_bwd(G, heads, li.dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
+                                                 None, L["s_alpha"], L["absmax_alpha"], T.SR, li.sr_seed, 16 * 2 + 6, L["Hp_q"],
+                                                 L["s_Hp"], L["g_q"], L["s_g"], L["dHp"], None, None, None, None, L["ws"])
+        spmm_name = "k_spmm<16, true, 2> (reverse SPMM with recomputed attention codes, step 5')"
+        alg = rev_attention_spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     else:
         L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0)
         step = lambda: (T.tango_gat_layer_fwd(L), T.tango_gat_layer_bwd(L))
@@ -170,7 +201,8 @@ def main():
     log("%s: %.3f ms/launch, %.1f algorithmic GB/s" % (spmm_name, spmm_ms, achieved))
 
     out = {
-        "metric": "ms per quantized GAT layer fwd+bwd" if cfg["kind"] == "gat" else "ms per quantized GCN layer fwd+bwd",
+        "metric": ("ms per 3 stacked quantized GAT layers fwd+bwd" if name == "gat_products" else
+                   "ms per quantized GAT layer fwd+bwd" if cfg["kind"] == "gat" else "ms per quantized GCN layer fwd+bwd"),
         "value": ms_per_step,
         "unit": "ms",
         "n_gpus": 1,
@@ -200,6 +232,10 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
+        if name == "gat_products":
+            log("no CPU baseline leg for the 3-layer workload")
+            print(json.dumps(out), flush=True)
+            return
         sd = args.cpu_scale_down or {"gat_dense": 8, "gcn_arxiv": 1, "toy": 1}[name]
         sd *= args.scale_down
         log("cpu baseline (oracle) on a 1/%d instance ..." % sd)

@@ -105,6 +105,14 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
 /* x[i] = scale[0] * q[i]  (Eq. 2). */
 int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream);
 
+/*
+ * Activation between stacked layers (the paper's models are 2-3 layers deep, Sec. 4.1; it does not name the
+ * activation, ReLU is used): y = max(x, 0), absmax_y (may be NULL) = max y; dx = x > 0 ? dy : 0.
+ * y may alias x; dx may alias dy.
+ */
+int tango_relu(const float *x, size_t n, float *y, float *absmax_y, void *stream);
+int tango_relu_bwd(const float *x, const float *dy, size_t n, float *dx, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Quantized GEMM (Sec. 3.2 Fig. 3; Sec. 3.3 "GEMM with on-the-fly           */
 /* quantization", Fig. 4).                                                    */

@@ -163,6 +163,22 @@ def tango_dequantize(q, scale, x):
                                            _ptr(x, torch.float32), _stream()), "tango_dequantize")
 
 
+SIGNATURES.update({
+    "tango_relu": (_int, [_vp, _sz, _vp, _vp, _vp]),
+    "tango_relu_bwd": (_int, [_vp, _vp, _sz, _vp, _vp]),
+})
+
+
+def tango_relu(x, y, absmax_y=None):
+    _check(load_library().tango_relu(_ptr(x, torch.float32), x.numel(), _ptr(y, torch.float32), _ptr(absmax_y, torch.float32),
+                                     _stream()), "tango_relu")
+
+
+def tango_relu_bwd(x, dy, dx):
+    _check(load_library().tango_relu_bwd(_ptr(x, torch.float32), _ptr(dy, torch.float32), x.numel(), _ptr(dx, torch.float32),
+                                         _stream()), "tango_relu_bwd")
+
+
 # ----------------------------------------------------------------------------- GEMM
 def tango_qgemm_workspace_bytes(M, N, K) -> int:
     return load_library().tango_qgemm_workspace_bytes(M, N, K)

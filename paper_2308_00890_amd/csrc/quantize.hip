@@ -126,6 +126,32 @@ __global__ __launch_bounds__(256) void k_dequantize(const int8_t *__restrict__ q
     for (size_t j = tid; j < n; j += nthr) x[j] = s * static_cast<float>(q[j]);
 }
 
+// y = max(x, 0) and, optionally, max|y| (the abs-max the next layer's quantization needs)
+__global__ __launch_bounds__(256) void k_relu(const float *__restrict__ x, size_t n, float *__restrict__ y, float *absmax)
+{
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    float m = 0.0f;
+    for (size_t i = tid; i < n; i += nthr) {
+        const float v = fmaxf(x[i], 0.0f);
+        y[i] = v;
+        m = fmaxf(m, v);
+    }
+    if (absmax) {
+        m = tango_wave_max(m);
+        if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax, m);
+    }
+}
+
+// dx = x > 0 ? dy : 0
+__global__ __launch_bounds__(256) void k_relu_bwd(const float *__restrict__ x, const float *__restrict__ dy, size_t n,
+                                                  float *__restrict__ dx)
+{
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = tid; i < n; i += nthr) dx[i] = x[i] > 0.0f ? dy[i] : 0.0f;
+}
+
 }  // namespace
 
 // Internal (not part of the ABI): used by the other translation units.
@@ -217,6 +243,29 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
         am = wam;
     }
     return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, am, q, scale_out, st);
+}
+
+int tango_relu(const float *x, size_t n, float *y, float *absmax_y, void *stream)
+{
+    TANGO_REQUIRE(n == 0 || (x != nullptr && y != nullptr), TANGO_ERR_NULL);
+    hipStream_t st = tango_stream(stream);
+    if (absmax_y) {
+        int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_y), 0u, 1, st);
+        if (rc != TANGO_OK) return rc;
+    }
+    if (n == 0) return TANGO_OK;
+    k_relu<<<tango_grid_for(n, 256 * 4), 256, 0, st>>>(x, n, y, absmax_y);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+int tango_relu_bwd(const float *x, const float *dy, size_t n, float *dx, void *stream)
+{
+    TANGO_REQUIRE(n == 0 || (x != nullptr && dy != nullptr && dx != nullptr), TANGO_ERR_NULL);
+    if (n == 0) return TANGO_OK;
+    k_relu_bwd<<<tango_grid_for(n, 256 * 4), 256, 0, tango_stream(stream)>>>(x, dy, n, dx);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
 }
 
 int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream)

@@ -38,35 +38,22 @@ def gat_case(name):
     raise KeyError(name)
 
 
-@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
-@pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
-@pytest.mark.parametrize("fused", [True, False])
-def test_gat_layer_stagewise(T, case, rounding, fused):
-    import torch
-
-    li, slope = gat_case(case)
-    g = li.graph
-    heads = li.heads
-    seed, layer_id = li.sr_seed, 2
+def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding, seed, layer_id, fused, chain=True):
+    """Stage-by-stage check of one GAT layer's device tensors `o` (host copies) against the oracle primitives applied
+    to the GPU's own inputs of each stage."""
+    heads = a_src.shape[0]
     b = 16 * layer_id
-    G = T.Graph.from_host(g)
-    L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
-                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True, keep_alpha_q=True)
-    T.tango_gat_layer_fwd(L)
-    T.tango_gat_layer_bwd(L)
-    torch.cuda.synchronize()
-    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
     sc = lambda k: o[k][0]
 
     # ---- forward, stage by stage
-    r = orc.qgemm(li.feat, li.weight, rounding, seed, b + orc.SID_H, b + orc.SID_W)
+    r = orc.qgemm(feat, weight, rounding, seed, b + orc.SID_H, b + orc.SID_W)
     assert sc("s_H") == r["s_A"] and sc("s_W") == r["s_B"]
     assert_bit_exact(o["H_q"], r["A_q"], "H_q")
     assert_bit_exact(o["W_q"], r["B_q"], "W_q")
     assert_bit_exact(o["Hp"], r["C"], "Hp")
     assert sc("absmax_Hp") == r["absmax_C"]
-    assert_close(o["S"], orc.head_proj(o["Hp"], li.a_src), "S")
-    assert_close(o["D"], orc.head_proj(o["Hp"], li.a_dst), "D")
+    assert_close(o["S"], orc.head_proj(o["Hp"], a_src), "S")
+    assert_close(o["D"], orc.head_proj(o["Hp"], a_dst), "D")
     for name, src, sid, am in (("Hp_q", "Hp", orc.SID_HP, sc("absmax_Hp")), ("S_q", "S", orc.SID_S, None),
                                ("D_q", "D", orc.SID_D, None)):
         q, s = orc.quantize(o[src], rounding, seed, b + sid, am=am)
@@ -84,7 +71,7 @@ def test_gat_layer_stagewise(T, case, rounding, fused):
     assert sc("absmax_out") == am
 
     # ---- backward, stage by stage
-    q, s = orc.quantize(li.grad_out, rounding, seed, b + orc.SID_G)
+    q, s = orc.quantize(grad_out, rounding, seed, b + orc.SID_G)
     assert_bit_exact(o["g_q"], q, "g_q")
     assert sc("s_g") == s
     agg, _ = orc.spmm_rev(g, o["alpha_q"], sc("s_alpha"), o["g_q"], sc("s_g"))
@@ -98,7 +85,7 @@ def test_gat_layer_stagewise(T, case, rounding, fused):
         _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, o["dalpha"])
     assert_close(o["dS"], dS, "dS")
     assert_close(o["dD"], dD, "dD")
-    dHp, am, da_s, da_d = orc.head_proj_bwd(o["dS"], o["dD"], li.a_src, li.a_dst, o["Hp_q"], sc("s_Hp"), agg)
+    dHp, am, da_s, da_d = orc.head_proj_bwd(o["dS"], o["dD"], a_src, a_dst, o["Hp_q"], sc("s_Hp"), agg)
     assert_bit_exact(o["dHp"], dHp, "dHp")
     assert sc("absmax_dHp") == am
     assert_close(o["da_src"], da_s, "da_src")
@@ -109,16 +96,85 @@ def test_gat_layer_stagewise(T, case, rounding, fused):
     assert_bit_exact(o["dW"], rb["dB"], "dW")
     assert_bit_exact(o["dH"], rb["dA"], "dH")
 
+    if not chain:
+        return
     # ---- the all-oracle chain, as a whole: int8 codes may flip where an fp32 intermediate sits on a rounding
     # threshold, so this is a closeness check in norm plus a count of differing codes
-    f = orc.gat_layer_fwd(g, li.feat, li.weight, li.a_src, li.a_dst, slope, rounding, seed, layer_id)
-    bw = orc.gat_layer_bwd(g, f, li.a_src, li.a_dst, li.grad_out, slope, rounding, seed, layer_id)
+    f = orc.gat_layer_fwd(g, feat, weight, a_src, a_dst, slope, rounding, seed, layer_id)
+    bw = orc.gat_layer_bwd(g, f, a_src, a_dst, grad_out, slope, rounding, seed, layer_id)
     rel = lambda a, c: np.linalg.norm(a.astype(np.float64) - c) / max(np.linalg.norm(c), 1e-30)
     for name, ref in (("out", f["out"]), ("dW", bw["dW"]), ("dH", bw["dH"]), ("da_src", bw["da_src"])):
         assert rel(o[name], ref) < 2e-2, name
     for name, ref in (("S_q", f["S_q"]), ("D_q", f["D_q"]), ("alpha_q", f["alpha_q"])):
         diff = o[name].astype(np.int32) - ref.astype(np.int32)
         assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-2, name
+
+
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
+@pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
+@pytest.mark.parametrize("fused", [True, False])
+def test_gat_layer_stagewise(T, case, rounding, fused):
+    import torch
+
+    li, slope = gat_case(case)
+    g = li.graph
+    seed, layer_id = li.sr_seed, 2
+    G = T.Graph.from_host(g)
+    L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
+                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True, keep_alpha_q=True)
+    T.tango_gat_layer_fwd(L)
+    T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    verify_gat_layer(o, g, li.feat, li.weight, li.a_src, li.a_dst, li.grad_out, slope, rounding, seed, layer_id, fused)
+
+
+def test_three_layer_gat_chain(T):
+    """Configuration-4 shape (K_in 100 -> 3 x 128 -> 3 x 128 -> 3 x 128) on a small skewed graph: three fused layers with
+    ReLU between them, forward through all three and backward through all three; each layer is verified stage by
+    stage on its own device inputs (the previous layer's activated output, the next layer's masked input gradient)."""
+    import torch
+
+    g = ti.rmat_graph(2500, 40000, seed=31)
+    heads, dim, widths = 3, 128, [100, 384, 384]
+    F = heads * dim
+    seed, slope = 777, 0.2
+    G = T.Graph.from_host(g)
+    x0 = ti.normal((g.n_nodes, widths[0]), 32)
+    up = ti.normal((g.n_nodes, F), 33)
+    params = [(ti.xavier_uniform(k, F, (k, F), 40 + i), ti.xavier_uniform(heads, dim, (heads, dim), 50 + i),
+               ti.xavier_uniform(heads, dim, (heads, dim), 60 + i)) for i, k in enumerate(widths)]
+    feats = [dev(x0)]
+    grads = [torch.empty((g.n_nodes, F), dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    grads[2].copy_(dev(up))
+    layers = []
+    for i in range(3):
+        W, a_s, a_d = params[i]
+        L = T.GatLayer(G, feats[i], dev(W), dev(a_s), dev(a_d), grads[i], slope, orc.SR, seed, i, fused=True, keep_alpha=True,
+                       keep_alpha_q=True)
+        T.tango_gat_layer_fwd(L)
+        layers.append(L)
+        if i < 2:
+            act = torch.empty_like(L["out"])
+            T.tango_relu(L["out"], act)
+            feats.append(act)
+    for i in (2, 1, 0):
+        T.tango_gat_layer_bwd(layers[i])
+        if i > 0:  # gradient w.r.t. the previous layer's pre-activation output
+            T.tango_relu_bwd(layers[i - 1]["out"], layers[i]["dH"], grads[i - 1])
+    torch.cuda.synchronize()
+    for i in range(3):
+        o = {k: host(v) for k, v in layers[i].t.items() if k != "ws"}
+        W, a_s, a_d = params[i]
+        feat = host(feats[i])
+        gout = host(grads[i])
+        if i > 0:
+            prev_out = host(layers[i - 1]["out"])
+            assert_bit_exact(feat, np.maximum(prev_out, 0), "relu")
+        if i < 2:
+            assert_bit_exact(gout, np.where(host(layers[i]["out"]) > 0, host(layers[i + 1]["dH"]), 0).astype(np.float32),
+                             "relu backward")
+        verify_gat_layer(o, g, feat, W, a_s, a_d, gout, slope, orc.SR, seed, i, True, chain=False)
 
 
 def test_fused_gat_layer_without_edge_caches(T):
