@@ -106,6 +106,19 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
 int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream);
 
 /*
+ * Quantization-error metric and bit-count rule (Sec. 3.2 Eq. 4): for each candidate bit count B (2..8, at most 4
+ * candidates, host array) error_out[c] = mean_i |(x_i - xq_i) / (x_i + xq_i + 0.0005)| (device doubles), xq the grid
+ * point of the B-bit symmetric per-tensor quantizer (codes in +-(2^(B-1)-1), scale absmax/(2^(B-1)-1), rounding and
+ * random stream as in tango_quantize).  bits_out (device int, may be NULL) receives the first candidate whose
+ * error is below `threshold` (the paper uses 0.3 on the first layer's output in the first epoch), else the last
+ * candidate.  absmax_in as in tango_quantize.  ws: tango_error_x_workspace_bytes() bytes.
+ */
+size_t tango_error_x_workspace_bytes(void);
+int tango_error_x(const float *x, size_t n, const int *candidate_bits /* host */, int n_candidates, float threshold,
+                  int rounding, uint64_t seed, uint64_t stream_id, const float *absmax_in, double *error_out,
+                  int *bits_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Activation between stacked layers (the paper's models are 2-3 layers deep, Sec. 4.1; it does not name the
  * activation, ReLU is used): y = max(x, 0), absmax_y (may be NULL) = max y; dx = x > 0 ? dy : 0.
  * y may alias x; dx may alias dy.

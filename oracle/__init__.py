@@ -50,6 +50,7 @@ def _L():
         lib.orc_spmm_in.restype = ctypes.c_int64
         lib.orc_spmm_rev.restype = ctypes.c_int64
         lib.orc_head_proj_bwd.restype = ctypes.c_float
+        lib.orc_error_x.restype = ctypes.c_double
         for name in (
             "orc_philox4x32_10",
             "orc_scale_from_absmax",
@@ -117,6 +118,23 @@ def quantize(x, rounding: int = SR, seed: int = 0, stream: int = 0, am=None, fir
     _L().orc_quantize(_p(x), ctypes.c_size_t(x.size), _u64(first), _f32(float(am)), ctypes.c_int(rounding), _u64(seed),
                       _u64(stream), _p(q))
     return q, scale_from_absmax(am)[0]
+
+
+def error_x(x, bits: int, rounding: int = SR, seed: int = 0, stream: int = 0) -> float:
+    """Quantization-error metric of Eq. 4 for a B-bit symmetric per-tensor quantizer."""
+    x = _c(x, np.float32)
+    return float(_L().orc_error_x(_p(x), ctypes.c_size_t(x.size), ctypes.c_int(bits), _f32(float(absmax(x))),
+                                  ctypes.c_int(rounding), _u64(seed), _u64(stream)))
+
+
+def select_bits(x, candidates=(4, 6, 8), threshold: float = 0.3, rounding: int = SR, seed: int = 0, stream: int = 0):
+    """Smallest candidate bit count whose Error_X is below the threshold (the largest candidate if none is);
+    returns (bits, [Error_X per candidate])."""
+    errs = [error_x(x, b, rounding, seed, stream) for b in candidates]
+    for b, e in zip(candidates, errs):
+        if e < threshold:
+            return b, errs
+    return candidates[-1], errs
 
 
 def dequantize(q, s) -> np.ndarray:

@@ -473,3 +473,38 @@ void orc_sddmm_dot_f32(int64_t n, const int32_t *in_ptr, const int32_t *in_src, 
             }
         }
 }
+
+/* ------------------------------------------------------------------ */
+/* Quantization-error metric and bit-count rule (Sec. 3.2, Eq. 4).      */
+/* Error_X = mean_i | (X_i - X_i,Quant) / (X_i + X_i,Quant + eps) |,     */
+/* eps = 0.0005, X_i,Quant the grid point s*q_i of a B-bit symmetric     */
+/* quantizer (codes in +-(2^(B-1)-1), same scale/rounding rules as the   */
+/* 8-bit one).  Terms and their sum in fp64.                              */
+/* ------------------------------------------------------------------ */
+double orc_error_x(const float *x, size_t n, int bits, float absmax, int rounding, uint64_t seed, uint64_t stream)
+{
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    float s = 1.0f, inv = 0.0f;
+    if (absmax > 0.0f) {
+        s = absmax / qmax;
+        inv = qmax / absmax;
+    }
+    double sum = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        float y = x[i] * inv;
+        float v;
+        if (rounding == 0) {
+            v = rintf(y);
+        } else {
+            float f = floorf(y);
+            float frac = y - f;
+            float u = (float)orc_sr_bits16(seed, stream, (uint64_t)i) * (1.0f / 65536.0f);
+            v = f + (u < frac ? 1.0f : 0.0f);
+        }
+        if (v > qmax) v = qmax;
+        if (v < -qmax) v = -qmax;
+        float xq = s * v;
+        sum += fabs(((double)x[i] - (double)xq) / ((double)x[i] + (double)xq + 0.0005));
+    }
+    return n ? sum / (double)n : 0.0;
+}

@@ -169,6 +169,28 @@ SIGNATURES.update({
 })
 
 
+SIGNATURES.update({
+    "tango_error_x_workspace_bytes": (_sz, []),
+    "tango_error_x": (_int, [_vp, _sz, ctypes.POINTER(ctypes.c_int), _int, _f32, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
+})
+
+
+def tango_error_x_workspace_bytes() -> int:
+    return load_library().tango_error_x_workspace_bytes()
+
+
+def tango_error_x(x, candidate_bits, threshold, rounding, seed, stream_id, absmax_in, error_out, bits_out, ws):
+    cand = (ctypes.c_int * len(candidate_bits))(*candidate_bits)
+    _check(
+        load_library().tango_error_x(
+            _ptr(x, torch.float32), x.numel(), cand, len(candidate_bits), threshold, rounding, seed, stream_id,
+            _ptr(absmax_in, torch.float32), _ptr(error_out, torch.float64), _ptr(bits_out, torch.int32), _ptr(ws),
+            ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_error_x",
+    )
+
+
 def tango_relu(x, y, absmax_y=None):
     _check(load_library().tango_relu(_ptr(x, torch.float32), x.numel(), _ptr(y, torch.float32), _ptr(absmax_y, torch.float32),
                                      _stream()), "tango_relu")

@@ -152,6 +152,81 @@ __global__ __launch_bounds__(256) void k_relu_bwd(const float *__restrict__ x, c
     for (size_t i = tid; i < n; i += nthr) dx[i] = x[i] > 0.0f ? dy[i] : 0.0f;
 }
 
+// Error_X (Sec. 3.2 Eq. 4) of up to MAX_CAND bit counts in one pass: sums[c] += |x - xq| / |x + xq + eps| with xq
+// the grid point of a bits[c]-bit symmetric quantizer.  One element per thread-iteration; fp64 sums.
+constexpr int MAX_CAND = 4;
+struct error_x_cands {
+    int n;
+    int bits[MAX_CAND];
+};
+
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_error_x(const float *__restrict__ x, size_t n, const float *__restrict__ absmax,
+                                                 tango_rng rng, error_x_cands cands, double *sums)
+{
+    const float am = *absmax;
+    float s[MAX_CAND], inv[MAX_CAND], qmax[MAX_CAND];
+    double acc[MAX_CAND];
+#pragma unroll
+    for (int c = 0; c < MAX_CAND; ++c) {
+        qmax[c] = static_cast<float>((1 << ((c < cands.n ? cands.bits[c] : 8) - 1)) - 1);
+        s[c] = am > 0.0f ? am / qmax[c] : 1.0f;
+        inv[c] = am > 0.0f ? qmax[c] / am : 0.0f;
+        acc[c] = 0.0;
+    }
+    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = tid; i < n; i += nthr) {
+        const float xv = x[i];
+        float u = 0.0f;
+        if (ROUNDING == TANGO_SR)
+            u = static_cast<float>(tango_bits16(tango_philox_block(rng, static_cast<uint64_t>(i) >> 3), static_cast<int>(i & 7))) *
+                (1.0f / 65536.0f);
+#pragma unroll
+        for (int c = 0; c < MAX_CAND; ++c) {
+            if (c < cands.n) {
+                const float y = xv * inv[c];
+                float v;
+                if (ROUNDING == TANGO_RN) {
+                    v = rintf(y);
+                } else {
+                    const float f = floorf(y);
+                    v = f + (u < (y - f) ? 1.0f : 0.0f);
+                }
+                v = fminf(qmax[c], fmaxf(-qmax[c], v));
+                const float xq = s[c] * v;
+                acc[c] += fabs((static_cast<double>(xv) - static_cast<double>(xq)) /
+                               (static_cast<double>(xv) + static_cast<double>(xq) + 0.0005));
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < MAX_CAND; ++c) {
+        if (c < cands.n) {
+            const double t = tango_wave_sum(acc[c]);
+            if (threadIdx.x % TANGO_WAVE == 0 && t != 0.0) atomicAdd(sums + c, t);
+        }
+    }
+}
+
+// error[c] = sums[c]/n; *chosen = the first candidate below the threshold, else the last one
+__global__ void k_error_x_finish(error_x_cands cands, size_t n, float threshold, const double *sums, double *error,
+                                 int *chosen)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int pick = cands.bits[cands.n - 1];
+    bool found = false;
+    for (int c = 0; c < cands.n; ++c) {
+        const double e = n ? sums[c] / static_cast<double>(n) : 0.0;
+        error[c] = e;
+        if (!found && e < static_cast<double>(threshold)) {
+            pick = cands.bits[c];
+            found = true;
+        }
+    }
+    if (chosen) *chosen = pick;
+}
+
 }  // namespace
 
 // Internal (not part of the ABI): used by the other translation units.
@@ -243,6 +318,48 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
         am = wam;
     }
     return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, am, q, scale_out, st);
+}
+
+size_t tango_error_x_workspace_bytes(void) { return 512; }
+
+int tango_error_x(const float *x, size_t n, const int *candidate_bits, int n_candidates, float threshold, int rounding,
+                  uint64_t seed, uint64_t stream_id, const float *absmax_in, double *error_out, int *bits_out, void *ws,
+                  size_t ws_bytes, void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    TANGO_REQUIRE(candidate_bits && error_out && (n == 0 || x), TANGO_ERR_NULL);
+    TANGO_REQUIRE(n_candidates >= 1 && n_candidates <= MAX_CAND, TANGO_ERR_BAD_SHAPE);
+    error_x_cands cands;
+    cands.n = n_candidates;
+    for (int c = 0; c < MAX_CAND; ++c) cands.bits[c] = 8;
+    for (int c = 0; c < n_candidates; ++c) {
+        TANGO_REQUIRE(candidate_bits[c] >= 2 && candidate_bits[c] <= 8, TANGO_ERR_BAD_SHAPE);
+        cands.bits[c] = candidate_bits[c];
+    }
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_error_x_workspace_bytes(), TANGO_ERR_WORKSPACE);
+    hipStream_t st = tango_stream(stream);
+    double *sums = static_cast<double *>(ws);               // MAX_CAND doubles
+    float *wam = reinterpret_cast<float *>(static_cast<char *>(ws) + 256);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(sums), 0u, 2 * MAX_CAND, st);
+    if (rc != TANGO_OK) return rc;
+    const float *am = absmax_in;
+    if (!am) {
+        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(wam), 0u, 1, st)) != TANGO_OK) return rc;
+        if ((rc = tango_absmax_accumulate_async(x, n, wam, st)) != TANGO_OK) return rc;
+        am = wam;
+    }
+    const tango_rng rng = tango_rng_make(seed, stream_id);
+    if (n > 0) {
+        const unsigned grid = tango_grid_for(n, 256 * 4);
+        if (rounding == TANGO_RN)
+            k_error_x<TANGO_RN><<<grid, 256, 0, st>>>(x, n, am, rng, cands, sums);
+        else
+            k_error_x<TANGO_SR><<<grid, 256, 0, st>>>(x, n, am, rng, cands, sums);
+        TANGO_LAUNCH_CHECK();
+    }
+    k_error_x_finish<<<1, 64, 0, st>>>(cands, n, threshold, sums, error_out, bits_out);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
 }
 
 int tango_relu(const float *x, size_t n, float *y, float *absmax_y, void *stream)

@@ -102,3 +102,24 @@ def test_bad_arguments_are_refused(T):
         T.tango_quantize(x, 5, 0, 0, None, q, s, workspace(256))  # bad rounding
     with pytest.raises(T.TangoError):
         T.tango_quantize(x, orc.SR, 0, 0, None, q, s, None)  # needs a workspace for the reduction
+
+
+@pytest.mark.parametrize("rounding", [orc.RN, orc.SR])
+def test_error_x_and_bit_count_rule(T, rounding):
+    import torch
+
+    x = ti.normal((200003,), 91)
+    cands = (4, 6, 8)
+    err = empty((3,), torch.float64)
+    bits = empty((1,), torch.int32)
+    ws = workspace(T.tango_error_x_workspace_bytes())
+    T.tango_error_x(dev(x), cands, 0.3, rounding, 17, 5, None, err, bits, ws)
+    torch.cuda.synchronize()
+    want_bits, want = orc.select_bits(x, cands, 0.3, rounding, 17, 5)
+    got = host(err)
+    assert np.allclose(got, want, rtol=1e-9, atol=1e-12), (got, want)
+    assert int(host(bits)[0]) == want_bits
+    # an exactly representable tensor has zero error at 8 bits
+    T.tango_error_x(dev(np.arange(-127, 128, dtype=np.float32)), (8,), 0.3, rounding, 1, 1, None, err, bits, ws)
+    torch.cuda.synchronize()
+    assert host(err)[0] == 0.0 and int(host(bits)[0]) == 8

@@ -164,3 +164,37 @@ def test_window_of_a_tensor_quantizes_like_the_whole():
         for a, b in ((0, 17), (1003, 1100), (4990, 5000)):
             part, _ = orc.quantize(x[a:b], mode, seed=12, stream=5, am=am, first=a)
             assert np.array_equal(part, full[a:b])
+
+
+def test_error_x_closed_forms_and_range():
+    # exactly representable tensor: no rounding error
+    x = np.arange(-127, 128, dtype=np.float32)
+    assert orc.error_x(x, 8, orc.RN) == 0.0 and orc.error_x(x, 8, orc.SR, 3, 4) == 0.0
+    # one hand-computed case, B = 8, absmax 127 -> s = 1: 63.25 -> 63, 10.5 -> 10 (ties to even), 127 -> 127
+    x = np.array([127.0, 63.25, 10.5], np.float32)
+    want = (0.0 + 0.25 / (63.25 + 63 + 0.0005) + 0.5 / (10.5 + 10 + 0.0005)) / 3
+    assert abs(orc.error_x(x, 8, orc.RN) - want) < 1e-12
+    # B = 4: codes in [-7, 7], s = 127/7
+    s = np.float32(127.0) / np.float32(7.0)
+    inv = np.float32(7.0) / np.float32(127.0)
+    q = np.rint(x * inv)
+    xq = (s * q).astype(np.float64)
+    want4 = np.mean(np.abs((x - xq) / (x + xq + 0.0005)))
+    assert abs(orc.error_x(x, 4, orc.RN) - want4) < 1e-12
+    # range and monotonicity in the bit count on Gaussian data
+    g = _x(100000, 21)
+    errs = [orc.error_x(g, b, orc.RN) for b in (2, 4, 6, 8)]
+    assert all(0.0 <= e <= 1.0 for e in errs)
+    assert errs[0] > errs[1] > errs[2] > errs[3]
+    # elements that round to zero contribute |x/(x+eps)| ~ 1
+    tiny = np.array([1.0] + [1e-3] * 99, np.float32)
+    assert orc.error_x(tiny, 4, orc.RN) > 0.6
+
+
+def test_bit_count_rule():
+    g = _x(50000, 22)
+    bits, errs = orc.select_bits(g, (4, 6, 8), 0.3, orc.RN)
+    assert errs[0] > errs[1] > errs[2]
+    assert bits == next((b for b, e in zip((4, 6, 8), errs) if e < 0.3), 8)
+    assert orc.select_bits(g, (4, 6, 8), 0.0, orc.RN)[0] == 8  # nothing qualifies: the widest
+    assert orc.select_bits(g, (4, 6, 8), 2.0, orc.RN)[0] == 4  # everything qualifies: the narrowest
