@@ -161,6 +161,19 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
                     uint64_t stream_id_dC, const float *absmax_dC_in, int8_t *dC_q, float *s_dC,
                     float *dA, float *dB, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * The quantized product alone (Sec. 3.2 Fig. 3: int8 operands, int32
+ * accumulation, one fp32 factor), for operands that are already int8 and
+ * for shapes wide enough that the matrix cores, not HBM, are the bound:
+ *   C[m][n] (M x N, fp32) = (float)(sum_k A_q[m][k] * BT_q[n][k]) * (s_A*s_B)
+ * A_q: M x K, BT_q: N x K (the right operand transposed), both row-major
+ * with K contiguous, device, 16-byte aligned; K % 16 == 0 (else
+ * TANGO_ERR_UNSUPPORTED); K <= 2^17 keeps the int32 accumulator exact.
+ * absmax_C (may be NULL) = max|C|.  No workspace.
+ */
+int tango_qgemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,
+                   const int8_t *BT_q, const float *s_B, float *C, float *absmax_C, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Attention projections (Sec. 2.1 step 2 and 2'), fp32.                      */
 /* ------------------------------------------------------------------------ */

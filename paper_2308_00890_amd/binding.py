@@ -53,6 +53,7 @@ SIGNATURES = {
     "tango_dequantize": (_int, [_vp, _sz, _vp, _vp, _vp]),
     "tango_qgemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qgemm_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm_bwd": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _int, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_head_proj": (_int, [_i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -218,6 +219,20 @@ def tango_qgemm(A, B, rounding, seed, sid_A, sid_B, A_q, s_A, B_q, s_B, C, absma
             _ptr(C, torch.float32), _ptr(absmax_C, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream(),
         ),
         "tango_qgemm",
+    )
+
+
+def tango_qgemm_i8(A_q, s_A, BT_q, s_B, C, absmax_C):
+    M, K = A_q.shape
+    N, K2 = BT_q.shape
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise TangoError("shape mismatch")
+    _check(
+        load_library().tango_qgemm_i8(
+            M, N, K, _ptr(A_q, torch.int8), _ptr(s_A, torch.float32), _ptr(BT_q, torch.int8), _ptr(s_B, torch.float32),
+            _ptr(C, torch.float32), _ptr(absmax_C, torch.float32), _stream(),
+        ),
+        "tango_qgemm_i8",
     )
 
 

@@ -88,6 +88,31 @@ def test_qgemm_backward(T, M, K, N):
     assert_bit_exact(host(dB2), r["dB"], "dB (alone)")
 
 
+# (M, K, N) for the tiled int8 kernel: one tile, ragged M and N, K not a multiple of the 64-deep step, several tiles
+I8_SHAPES = [(256, 64, 256), (300, 80, 130), (1, 16, 1), (515, 1040, 777), (1024, 4096, 512), (257, 48, 513)]
+
+
+@pytest.mark.parametrize("M,K,N", I8_SHAPES)
+def test_qgemm_i8(T, M, K, N):
+    import torch
+
+    rng = np.random.default_rng(M * 7 + K)
+    A_q = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    BT_q = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+    if K >= 1040:  # saturated rows: the largest accumulator magnitude the shape allows
+        A_q[0, :], BT_q[0, :] = 127, -127
+    sA, sB = np.float32(0.0173), np.float32(0.0009)
+    C = empty((M, N), torch.float32)
+    C.fill_(float("nan"))
+    am = scalar(-1)
+    T.tango_qgemm_i8(dev(A_q), scalar(sA), dev(BT_q), scalar(sB), C, am)
+    torch.cuda.synchronize()
+    acc = orc.igemm(A_q, BT_q, transB=True)
+    want, want_am = orc.dequant_i32(acc, sA, sB)
+    assert_bit_exact(host(C), want, "C")
+    assert host(am)[0] == want_am
+
+
 PROJ_SHAPES = [(1024, 2, 32), (1001, 4, 64), (333, 3, 128), (500, 1, 256), (70, 8, 16), (17, 1, 1024), (5, 2, 4)]
 
 
@@ -132,3 +157,6 @@ def test_gemm_bad_arguments(T):
     with pytest.raises(T.TangoError):  # workspace too small
         T.tango_qgemm(A, A, orc.SR, 0, 1, 2, empty((8, 8), torch.int8), scalar(), empty((8, 8), torch.int8), scalar(),
                       empty((8, 8), torch.float32), None, workspace(256))
+    with pytest.raises(T.TangoError):  # K not a multiple of 16
+        T.tango_qgemm_i8(empty((8, 8), torch.int8), scalar(), empty((8, 8), torch.int8), scalar(), empty((8, 8), torch.float32),
+                         None)
