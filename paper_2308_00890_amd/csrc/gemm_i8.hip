@@ -170,23 +170,42 @@ __global__ __launch_bounds__(256) void k_gemm_i8(i8gemm_args a)
         step(R0, s + 1, ic<1>{}, std::true_type{});
     }
 
-    // epilogue: dequantize, store, abs-max (element r of a 32x32 tile: column lane%32, row 8*(r/4) + 4*(lane/32) + r%4)
+    // epilogue: dequantize, store, abs-max (element r of a 32x32 tile: column lane%32, row 8*(r/4) + 4*(lane/32) + r%4).
     const float sc = (*a.s_A) * (*a.s_B);
     int maxabs = 0;
+    const int col0 = n0 + wn + lane % 32;
+    const int64_t row0 = m0 + wm + (lane / 32) * 4;
+    if (m0 + TM <= a.M && n0 + TN <= a.N && a.N < (1 << 22)) {
+        // interior tile: no guards; every address is a wave-uniform pointer plus one 32-bit lane offset
+        float *ct = a.C + (m0 + wm) * a.N + (n0 + wn);
+        const unsigned lane_off = static_cast<unsigned>((lane / 32) * 4 * a.N + lane % 32);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = n0 + wn + j * 32 + lane % 32;
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm + i * 32 + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
-                if (row < a.M && col < a.N) {
-                    a.C[row * a.N + col] = static_cast<float>(acc[i][j][r]) * sc;
+                for (int r = 0; r < 16; ++r) {
+                    float *cu = ct + static_cast<int64_t>(i * 32 + (r / 4) * 8 + (r % 4)) * a.N + j * 32;
+                    cu[lane_off] = static_cast<float>(acc[i][j][r]) * sc;
                     maxabs = max(maxabs, abs(acc[i][j][r]));
+                    if (r % 4 == 3) __builtin_amdgcn_sched_barrier(0);  // keep the register footprint of this part small
+                }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = col0 + j * 32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = row0 + i * 32 + (r / 4) * 8 + (r % 4);
+                    if (row < a.M && col < a.N) {
+                        a.C[row * a.N + col] = static_cast<float>(acc[i][j][r]) * sc;
+                        maxabs = max(maxabs, abs(acc[i][j][r]));
+                    }
                 }
             }
-        }
+    }
     if (a.absmax_C) {
         float m = static_cast<float>(maxabs) * sc;
         m = tango_wave_max(m);
