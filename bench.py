@@ -4,7 +4,7 @@
 One "step" = one quantized GAT layer, forward + backward (every abs-max, quantization and dequantization included,
 graph construction excluded), on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_dense|toy|gcn_arxiv] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_dense|toy|gcn_arxiv|gat_products|qgemm_i8] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -19,6 +19,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+MFMA_I8_PEAK_TOPS = 5000.0  # MI355X dense int8 matrix-core rate, published
 
 
 def log(*a):
@@ -84,12 +85,98 @@ def cpu_baseline(name, scale_down, slope=0.2):
     }
 
 
+def bench_qgemm_i8(args, torch, T, dev):
+    """The int8-input quantized GEMM on a compute-bound shape that is NOT one of the paper's workloads (their GEMMs are
+    HBM-bound): shows what the matrix-core main loop reaches.  One step = one tango_qgemm_i8 call, abs-max included."""
+    import numpy as np
+
+    M, N, K = (int(x) for x in args.gemm_shape.split(","))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2308008900)
+    A = torch.randint(-127, 128, (M, K), dtype=torch.int8, device=dev, generator=gen)
+    BT = torch.randint(-127, 128, (N, K), dtype=torch.int8, device=dev, generator=gen)
+    sA = torch.full((1,), 0.01, dtype=torch.float32, device=dev)
+    sB = torch.full((1,), 0.02, dtype=torch.float32, device=dev)
+    C = torch.empty((M, N), dtype=torch.float32, device=dev)
+    am = torch.zeros(1, dtype=torch.float32, device=dev)
+    step = lambda: T.tango_qgemm_i8(A, sA, BT, sB, C, am)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = time_events(torch, step, max(args.steps, 5))
+    ops = 2.0 * M * N * K
+    tops = ops / (kernel_ms * 1e-3) / 1e12
+    log("tango_qgemm_i8 %dx%dx%d: %.3f ms/step wall, %.3f ms/launch (events), %.1f TOP/s" % (M, N, K, ms_per_step, kernel_ms, tops))
+    # the rate the matrix cores sustain from registers alone, constant and random operand bytes
+    ws = torch.empty(T.tango_mfma_i8_rate_workspace_bytes(), dtype=torch.uint8, device=dev)
+    ceiling = {}
+    for label, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        cal_ops = [0.0]
+
+        def cal():
+            cal_ops[0] = T.tango_mfma_i8_rate_launch(20000, rnd, ws)
+
+        cal()
+        torch.cuda.synchronize()
+        cal_ms = time_events(torch, cal, 5)
+        ceiling[label] = cal_ops[0] / (cal_ms * 1e-3) / 1e12
+        log("register-only MFMA loop, %s: %.1f TOP/s" % (label, ceiling[label]))
+    out = {
+        "metric": "int8 quantized GEMM throughput (int8 in, int32 accumulate, fp32 out + abs-max)",
+        "value": ops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 operands, int32 accumulation, fp32 output",
+        "data": "synthetic",
+        "config": {"workload": "tango_qgemm_i8 M=%d N=%d K=%d, uniform random int8 operands; a compute-bound shape outside "
+                               "the paper's configurations" % (M, N, K)},
+        "roofline": {
+            "kernel": "k_gemm_i8",
+            "bound": "mfma",
+            "achieved": tops,
+            "peak": MFMA_I8_PEAK_TOPS,
+            "unit": "TOP/s",
+            "frac": tops / MFMA_I8_PEAK_TOPS,
+            "traffic": None,
+            "ms_per_launch": kernel_ms,
+            "measured_register_only_mfma_rate": ceiling,
+            "frac_of_measured_rate_random_operands": tops / ceiling["random_operands"],
+        },
+    }
+    if not args.no_cpu_baseline:
+        import oracle as orc
+
+        m, n, k = min(M, 4096), min(N, 4096), min(K, 8192)  # about 15 s of the oracle on 8 cores
+        rng = np.random.default_rng(1)
+        a = rng.integers(-127, 128, size=(m, k), dtype=np.int8)
+        b = rng.integers(-127, 128, size=(n, k), dtype=np.int8)
+        t0 = time.perf_counter()
+        acc = orc.igemm(a, b, transB=True)
+        orc.dequant_i32(acc, 0.01, 0.02)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * m * n * k / dt / 1e12, "unit": "TOP/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle", "sample": "oracle igemm + dequantize on %dx%dx%d, %.1f s" % (m, n, k, dt)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products"])
+    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products", "qgemm_i8"])
+    ap.add_argument("--gemm-shape", default="8192,8192,8192", help="M,N,K of the qgemm_i8 workload")
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale-down", type=int, default=0)
@@ -120,6 +207,9 @@ def main():
         log("copied 3 x %d bytes" % (a.numel() * 4))
         return
     name = args.workload
+    if name == "qgemm_i8":
+        bench_qgemm_i8(args, torch, T, dev)
+        return
     cfg = ti.CONFIGS[name]
     t0 = time.perf_counter()
     li = ti.layer_inputs(name, scale_down=args.scale_down)

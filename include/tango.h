@@ -174,6 +174,20 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
 int tango_qgemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,
                    const int8_t *BT_q, const float *s_B, float *C, float *absmax_C, void *stream);
 
+/*
+ * Measurement aid (not a step of the method; for callers that report the
+ * matrix-core roofline of tango_qgemm_i8): launches 256 workgroups x 4 waves
+ * that each issue 8*iters independent v_mfma_i32_32x32x32_i8 from registers.
+ * random_operands != 0 fills the operand registers with pseudo-random bytes
+ * (realistic switching activity; the chip then runs power-limited), 0 with
+ * constant bytes.  *ops (host) receives the int8 operation count (2 per MAC)
+ * of the launch; the caller times it.  ws: device scratch of
+ * tango_mfma_i8_rate_workspace_bytes().
+ */
+size_t tango_mfma_i8_rate_workspace_bytes(void);
+int tango_mfma_i8_rate_launch(int iters, int random_operands, void *ws, size_t ws_bytes, double *ops,
+                              void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Attention projections (Sec. 2.1 step 2 and 2'), fp32.                      */
 /* ------------------------------------------------------------------------ */

@@ -54,6 +54,8 @@ SIGNATURES = {
     "tango_qgemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "tango_mfma_i8_rate_workspace_bytes": (_sz, []),
+    "tango_mfma_i8_rate_launch": (_int, [_int, _int, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
     "tango_qgemm_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm_bwd": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _int, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_head_proj": (_int, [_i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -234,6 +236,18 @@ def tango_qgemm_i8(A_q, s_A, BT_q, s_B, C, absmax_C):
         ),
         "tango_qgemm_i8",
     )
+
+
+def tango_mfma_i8_rate_workspace_bytes() -> int:
+    return load_library().tango_mfma_i8_rate_workspace_bytes()
+
+
+def tango_mfma_i8_rate_launch(iters, random_operands, ws) -> float:
+    """Enqueues the register-only int8 MFMA loop; returns its operation count (the caller times the launch)."""
+    ops = ctypes.c_double(0.0)
+    _check(load_library().tango_mfma_i8_rate_launch(iters, int(bool(random_operands)), _ptr(ws), ws.numel() * ws.element_size(),
+                                                    ctypes.byref(ops), _stream()), "tango_mfma_i8_rate_launch")
+    return ops.value
 
 
 def tango_qgemm_bwd_workspace_bytes(M, N, K) -> int:

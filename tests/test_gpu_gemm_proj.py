@@ -113,6 +113,17 @@ def test_qgemm_i8(T, M, K, N):
     assert host(am)[0] == want_am
 
 
+def test_mfma_rate_measurement_aid(T):
+    import torch
+
+    ws = workspace(T.tango_mfma_i8_rate_workspace_bytes())
+    ops = T.tango_mfma_i8_rate_launch(10, 1, ws)
+    torch.cuda.synchronize()
+    assert ops == 2.0 * 32 * 32 * 32 * 8 * 10 * 256 * 4
+    with pytest.raises(T.TangoError):
+        T.tango_mfma_i8_rate_launch(10, 1, workspace(16))
+
+
 PROJ_SHAPES = [(1024, 2, 32), (1001, 4, 64), (333, 3, 128), (500, 1, 256), (70, 8, 16), (17, 1, 1024), (5, 2, 4)]
 
 
