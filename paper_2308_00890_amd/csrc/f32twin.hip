@@ -66,7 +66,8 @@ template <bool HAS_EID>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm_f32(spmm_f32_args a)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    // readfirstlane: tells the compiler that the wave index, hence the chunk and the row walk, is wave-uniform
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));
     const int64_t c0 = chunk << CHUNK_SHIFT;
     if (c0 >= a.nnz) return;
     const int64_t c1 = min(c0 + (int64_t(1) << CHUNK_SHIFT), a.nnz);
@@ -150,7 +151,8 @@ template <int DUMMY>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot_f32(sddmm_f32_args a)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    // readfirstlane: tells the compiler that the wave index, hence the chunk and the row walk, is wave-uniform
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));
     const int64_t c0 = chunk << CHUNK_SHIFT;
     if (c0 >= a.nnz) return;
     const int64_t c1 = min(c0 + (int64_t(1) << CHUNK_SHIFT), a.nnz);

@@ -144,7 +144,9 @@ template <int GROUP, class Op>
 __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op, int *huge = nullptr)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    // readfirstlane / readlane: the wave index and the bounds of a row taken by the whole wave are wave-uniform, and
+    // saying so keeps them (and the loops over a row's edges) in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>((blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE));
     const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
     constexpr int RPI = 64 / GROUP;  // rows per wave-iteration
     for (int64_t base = static_cast<int64_t>(wave) * 64; base < n; base += static_cast<int64_t>(nwaves) * 64) {
@@ -171,7 +173,7 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op,
         while (mask) {
             const int k = __ffsll(static_cast<long long>(mask)) - 1;
             mask &= mask - 1;
-            const int rb = __shfl(b, k, 64), rt = __shfl(t, k, 64);
+            const int rb = __builtin_amdgcn_readlane(b, k), rt = __builtin_amdgcn_readlane(t, k);
             op.run(static_cast<int>(base) + k, rb, rt, lane_team<64>{lane});
         }
     }

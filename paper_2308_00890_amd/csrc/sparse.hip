@@ -201,12 +201,15 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 // One wave per chunk of edges.  VEC = bytes of the feature row per lane; HAS_EID: the weight of edge j of
 // this direction sits at position eid[j] (reversed graph) instead of j.
 template <int VEC, bool HAS_EID, int WMODE>
-__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 0 ? 5 : 4))) void k_spmm(spmm_args a)
 {
     using V = typename vec_bytes<VEC>::type;
     __shared__ __align__(16) int stage[WAVES_PER_BLOCK][1024];  // one strip of F <= 1024 sums per wave
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + threadIdx.x / TANGO_WAVE;
+    // the wave index goes through readfirstlane so that the compiler knows it (and everything derived from it: the
+    // chunk, the row walk, the loop bounds) is wave-uniform and keeps it in scalar registers
+    const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));
+    const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
     const int64_t c0 = chunk << a.chunk_shift;
     if (c0 >= a.nnz) return;
     const int64_t c1 = min(c0 + (int64_t(1) << a.chunk_shift), a.nnz);
@@ -231,125 +234,46 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
     const float sc = s_w * (*a.s_X);
     const int8_t *Xcol = a.X + col;
 
-    int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
+    // The chunk is walked in blocks of 64 consecutive edges, whatever rows they belong to: lane l of a block first
+    // fetches the neighbour index and the packed head weights of edge base+l (coalesced; in the attention modes it
+    // computes them), so that these loads and the attention arithmetic are paid once per 64 edges even when rows
+    // are short.  Then the row segments inside the block are processed one after the other: the groups pull
+    // (index, weight) pairs out of those registers with cross-lane reads and issue the row gathers back to back.
+    const int c0i = static_cast<int>(c0), c1i = static_cast<int>(c1);
     int maxabs = 0;
     constexpr int U = 8;  // independent row gathers in flight per lane
+    constexpr int NO_END = 0x7fffffff;
 
-    for (; r < a.n; ++r) {
-        const int rb = a.ptr[r], rt = a.ptr[r + 1];
-        if (rb >= c1) break;
-        const int sb = max(rb, static_cast<int>(c0)), se = min(rt, static_cast<int>(c1));
-        if (sb >= se || (rt - rb) <= a.short_max) continue;
-        int acc[VEC];
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] = 0;
-        // Blocks of 64 edges: lane l first fetches the neighbour index and the packed head weights of edge
-        // base+l (coalesced), then the groups pull (index, weight) pairs out of those registers with
-        // cross-lane reads, so that the row gathers of a block are issued back to back.
-        for (int base = sb; base < se; base += 64) {
-            const int cnt = min(64, se - base);
-            int my_nb = 0;
-            uint32_t my_w0 = 0, my_w1 = 0;
-            if (lane < cnt) {
-                const int e = base + lane;
-                my_nb = a.idx[e];
-                if (ATT) {
-                    // steps 3-4 and the quantization of alpha for this edge, all heads.  Forward: this row is the
-                    // destination, the neighbour the source; reverse: the other way round, and the edge's
-                    // destination-major position (for the random bits) comes from eid.
-                    const int H = a.heads;
-                    const int64_t src_node = (WMODE == W_ATT_FWD) ? my_nb : r;
-                    const int64_t dst_node = (WMODE == W_ATT_FWD) ? r : my_nb;
-                    const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(a.eid[e])) * H;
-                    uint4 blk = make_uint4(0, 0, 0, 0);
-                    uint64_t have = ~uint64_t(0);
-                    int sq[8], dq[8];
-                    tango_load_heads_rt(a.att.Sq, src_node, H, sq);
-                    tango_load_heads_rt(a.att.Dq, dst_node, H, dq);
-                    for (int hh = 0; hh < H; ++hh) {
-                        bool pos;
-                        const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
-                                                          a.att.slope, pos);
-                        const float al = tango_attn_alpha(ev, a.att.row_lse[dst_node * H + hh]);
-                        if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
-                        int q;
-                        if (a.att.rounding == TANGO_SR) {
-                            const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
-                            if (bi != have) {
-                                blk = tango_philox_block(a.att.rng, bi);
-                                have = bi;
-                            }
-                            q = tango_round_clamp<TANGO_SR>(al * inv_w, tango_bits16(blk, static_cast<int>((i0 + hh) & 7)));
-                        } else {
-                            q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
-                        }
-                        if (WMODE == W_ATT_FWD && a.att.alpha_q) a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
-                        const uint32_t b = static_cast<uint32_t>(q) & 0xffu;
-                        if (hh < 4)
-                            my_w0 |= b << (8 * hh);
-                        else
-                            my_w1 |= b << (8 * (hh - 4));
-                    }
-                } else {
-                    const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
-                    for (int hh = 0; hh < a.heads; ++hh) {
-                        const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
-                        if (hh < 4)
-                            my_w0 |= b << (8 * hh);
-                        else
-                            my_w1 |= b << (8 * (hh - 4));
-                    }
-                }
+    // rows: cur_r = the non-empty row that holds edge `pos`; cur_rt = its end; row ends of rows win_r0 .. win_r0+63
+    // sit in the lanes of win_end
+    int cur_r = wave_find_row(a.ptr, a.n, c0i);
+    int open_rb = a.ptr[cur_r];  // start of the row being accumulated
+    int win_r0 = cur_r;
+    int win_end = (win_r0 + lane < a.n) ? a.ptr[win_r0 + lane + 1] : NO_END;
+    int cur_rt = __builtin_amdgcn_readlane(win_end, 0);  // readlane: the result is wave-uniform (scalar registers)
+    auto next_row = [&]() {  // advance cur_r to the next non-empty row (or to n)
+        const int was = cur_rt;
+        do {
+            ++cur_r;
+            if (cur_r - win_r0 >= 64) {
+                win_r0 = cur_r;
+                win_end = (win_r0 + lane < a.n) ? a.ptr[win_r0 + lane + 1] : NO_END;
             }
-            const int steps = (cnt + G - 1) / G;
-            auto batch = [&](int s0, auto uu) {
-                constexpr int UU = decltype(uu)::value;
-                uint32_t wq[UU];
-                V xv[UU];
+            cur_rt = __builtin_amdgcn_readlane(win_end, cur_r - win_r0);
+        } while (cur_rt == was);
+    };
+
+    int acc[VEC];
 #pragma unroll
-                for (int u = 0; u < UU; ++u) {
-                    const int k = (s0 + u) * G + gi;
-                    const bool ok = active && k < cnt;
-                    const int kk = ok ? k : 0;
-                    const int nb = __shfl(my_nb, kk, 64);
-                    uint32_t ww = __shfl(static_cast<int>(my_w0), kk, 64);
-                    if (a.heads > 4) {
-                        const uint32_t w1 = __shfl(static_cast<int>(my_w1), kk, 64);
-                        if (h >= 4) ww = w1;
-                    }
-                    wq[u] = ok ? ((ww >> (8 * (h & 3))) & 0xffu) : 0u;
-                    xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
-                }
-                // 4 edges at a time: transpose each 4x4 byte block so that one dot4 multiplies one column of
-                // four neighbour rows by the four edge weights
-#pragma unroll
-                for (int u = 0; u < UU; u += 4) {
-                    const uint32_t wpack = wq[u] | (wq[u + 1] << 8) | (wq[u + 2] << 16) | (wq[u + 3] << 24);
-                    uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
-                    unpack_words<VEC>(xv[u], w0);
-                    unpack_words<VEC>(xv[u + 1], w1);
-                    unpack_words<VEC>(xv[u + 2], w2);
-                    unpack_words<VEC>(xv[u + 3], w3);
-#pragma unroll
-                    for (int q = 0; q < VEC / 4; ++q) {
-                        uint32_t t[4];
-                        transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
-                    }
-                }
-            };
-            int s0 = 0;
-            for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
-            for (; s0 < steps; s0 += 4) batch(s0, std::integral_constant<int, 4>{});
-        }
+    for (int j = 0; j < VEC; ++j) acc[j] = 0;
+    bool pending = false;  // acc holds sums of the open row
+
+    auto finish_row = [&](int r, bool whole) {
         // combine the G groups: afterwards group 0 holds the sums of this row segment
         for (int off = G / 2; off >= 1; off >>= 1) {
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] += __shfl_down(acc[j], off * LPR, 64);
         }
-        const bool whole = (rb >= c0) && (rt <= c1);
         if (whole) {
             if (gi == 0) {
                 float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
@@ -367,7 +291,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
         } else {
             // Row cut by a chunk boundary: int32 atomics.  The sums are first laid out by column in this
             // wave's LDS strip so that consecutive lanes add to consecutive words (coalesced atomics).
-            int *strip = stage[threadIdx.x / TANGO_WAVE];
+            int *strip = stage[wv];
             if (gi == 0) {
 #pragma unroll
                 for (int j = 0; j < VEC; j += 4)
@@ -383,7 +307,138 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_spmm(spmm_args a)
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
         }
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc[j] = 0;
+        pending = false;
+    };
+
+    for (int base = c0i; base < c1i; base += 64) {
+        const int cnt = min(64, c1i - base);
+        // pass 1 over the rows of this block: every lane learns the row of its edge and where that row ends
+        // (seg_r, seg_rt: the walker's state at the start of the block, replayed by pass 2)
+        const int seg_r = cur_r, seg_rt = cur_rt;
+        int my_row = cur_r, my_rt = cur_rt;
+        for (int k = 0; k < cnt;) {
+            const int k1 = min(cur_rt - base, cnt);
+            if (lane >= k && lane < k1) {
+                my_row = cur_r;
+                my_rt = cur_rt;
+            }
+            k = k1;
+            if (cur_rt <= base + cnt) next_row();
+        }
+        int my_nb = 0;
+        uint32_t my_w0 = 0, my_w1 = 0;
+        if (lane < cnt) {
+            const int e = base + lane;
+            my_nb = a.idx[e];
+            if (ATT) {
+                // steps 3-4 and the quantization of alpha for this edge, all heads.  Forward: the row is the
+                // destination, the neighbour the source; reverse: the other way round, and the edge's
+                // destination-major position (for the random bits) comes from eid.
+                const int H = a.heads;
+                const int64_t src_node = (WMODE == W_ATT_FWD) ? my_nb : my_row;
+                const int64_t dst_node = (WMODE == W_ATT_FWD) ? my_row : my_nb;
+                const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(a.eid[e])) * H;
+                uint4 blk = make_uint4(0, 0, 0, 0);
+                uint64_t have = ~uint64_t(0);
+                int sq[8], dq[8];
+                tango_load_heads_rt(a.att.Sq, src_node, H, sq);
+                tango_load_heads_rt(a.att.Dq, dst_node, H, dq);
+                for (int hh = 0; hh < H; ++hh) {
+                    bool pos;
+                    const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
+                                                      a.att.slope, pos);
+                    const float al = tango_attn_alpha(ev, a.att.row_lse[dst_node * H + hh]);
+                    if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
+                    int q;
+                    if (a.att.rounding == TANGO_SR) {
+                        const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
+                        if (bi != have) {
+                            blk = tango_philox_block(a.att.rng, bi);
+                            have = bi;
+                        }
+                        q = tango_round_clamp<TANGO_SR>(al * inv_w, tango_bits16(blk, static_cast<int>((i0 + hh) & 7)));
+                    } else {
+                        q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
+                    }
+                    if (WMODE == W_ATT_FWD && a.att.alpha_q) a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
+                    const uint32_t b = static_cast<uint32_t>(q) & 0xffu;
+                    if (hh < 4)
+                        my_w0 |= b << (8 * hh);
+                    else
+                        my_w1 |= b << (8 * (hh - 4));
+                }
+            } else {
+                const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
+                for (int hh = 0; hh < a.heads; ++hh) {
+                    const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
+                    if (hh < 4)
+                        my_w0 |= b << (8 * hh);
+                    else
+                        my_w1 |= b << (8 * (hh - 4));
+                }
+            }
+        }
+        // pass 2: the row segments [k0, k1) of the block
+        for (int k0 = 0; k0 < cnt;) {
+            const int r = (k0 == 0) ? seg_r : __builtin_amdgcn_readlane(my_row, k0);
+            const int rt = (k0 == 0) ? seg_rt : __builtin_amdgcn_readlane(my_rt, k0);
+            const int k1 = min(rt - base, cnt);
+            const int len = k1 - k0;
+            if (rt - open_rb > a.short_max) {
+                const int steps = (len + G - 1) / G;
+                auto batch = [&](int s0, auto uu) {
+                    constexpr int UU = decltype(uu)::value;
+                    uint32_t wq[UU];
+                    V xv[UU];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) {
+                        const int k = (s0 + u) * G + gi;
+                        const bool ok = active && k < len;
+                        const int kk = ok ? k0 + k : 0;
+                        const int nb = __shfl(my_nb, kk, 64);
+                        uint32_t ww = __shfl(static_cast<int>(my_w0), kk, 64);
+                        if (a.heads > 4) {
+                            const uint32_t w1 = __shfl(static_cast<int>(my_w1), kk, 64);
+                            if (h >= 4) ww = w1;
+                        }
+                        wq[u] = ok ? ((ww >> (8 * (h & 3))) & 0xffu) : 0u;
+                        xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                    }
+                    // 4 edges at a time: transpose each 4x4 byte block so that one dot4 multiplies one column of
+                    // four neighbour rows by the four edge weights
+#pragma unroll
+                    for (int u = 0; u < UU; u += 4) {
+                        const uint32_t wpack = wq[u] | (wq[u + 1] << 8) | (wq[u + 2] << 16) | (wq[u + 3] << 24);
+                        uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
+                        unpack_words<VEC>(xv[u], w0);
+                        unpack_words<VEC>(xv[u + 1], w1);
+                        unpack_words<VEC>(xv[u + 2], w2);
+                        unpack_words<VEC>(xv[u + 3], w3);
+#pragma unroll
+                        for (int q = 0; q < VEC / 4; ++q) {
+                            uint32_t t[4];
+                            transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                        }
+                    }
+                };
+                int s0 = 0;
+                for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
+                for (; s0 < steps; s0 += 4) batch(s0, std::integral_constant<int, 4>{});
+                pending = true;
+            }
+            if (base + k1 == rt) {  // the row ends here
+                if (pending) finish_row(r, open_rb >= c0i);
+                open_rb = rt;
+            }
+            k0 = k1;
+        }
     }
+    if (pending) finish_row(cur_r, false);  // the last row continues in the next chunk
     if (a.absmax) {
         // max|out| over whole rows = (float)max|acc| * sc (conversion and the product are monotone)
         float m = static_cast<float>(maxabs) * sc;
@@ -508,7 +563,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     __shared__ int nbl[WAVES_PER_BLOCK][64];
     __shared__ double red[WAVES_PER_BLOCK][64];
     const int lane = threadIdx.x % TANGO_WAVE;
-    const int wv = threadIdx.x / TANGO_WAVE;
+    const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));  // wave-uniform, see k_spmm
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
     const int64_t c0 = chunk << CHUNK_SHIFT_DEFAULT;
     if (c0 >= a.nnz) return;
