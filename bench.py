@@ -179,6 +179,8 @@ def main():
     ap.add_argument("--gemm-shape", default="8192,8192,8192", help="M,N,K of the qgemm_i8 workload")
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hipgraph", action="store_true",
+                    help="record one step into a HIP graph and time replays (same kernels; for the launch-bound small workloads)")
     ap.add_argument("--cpu-scale-down", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -272,6 +274,13 @@ def main():
         spmm_name = "k_spmm<16, true, 2> (reverse SPMM with recomputed attention codes, step 5')"
         alg = rev_attention_spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
 
+    if args.hipgraph:
+        step()  # everything allocated and warm before the capture
+        torch.cuda.synchronize()
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hip_graph):
+            step()
+        step = hip_graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -280,7 +289,7 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    log("layer fwd+bwd: %.3f ms/step" % ms_per_step)
+    log("layer fwd+bwd: %.3f ms/step%s" % (ms_per_step, " (HIP graph replay)" if args.hipgraph else ""))
 
     # dominant kernel, timed with HIP events on the stream it is launched on (the step above left every input it
     # needs in place); the two small helper kernels around it (row zeroing, split-row dequantize) are included
@@ -308,6 +317,7 @@ def main():
             "workload": "config %d (%s): %s graph, %d nodes, %d edges incl. self-loops, K_in %d, %d heads x %d, SR"
             % (cfg["config"], name, cfg["graph"], g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim),
             "scale_down": args.scale_down,
+            "launch": "hip graph replay" if args.hipgraph else "eager",
         },
         "roofline": {
             "kernel": spmm_name,
