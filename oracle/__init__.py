@@ -63,6 +63,9 @@ def _L():
             "orc_edge_softmax_bwd",
             "orc_spmm_f32",
             "orc_sddmm_dot_f32",
+            "orc_quantize_bits",
+            "orc_pack_int4",
+            "orc_unpack_int4",
         ):
             getattr(lib, name).restype = None
         _lib = lib
@@ -118,6 +121,35 @@ def quantize(x, rounding: int = SR, seed: int = 0, stream: int = 0, am=None, fir
     _L().orc_quantize(_p(x), ctypes.c_size_t(x.size), _u64(first), _f32(float(am)), ctypes.c_int(rounding), _u64(seed),
                       _u64(stream), _p(q))
     return q, scale_from_absmax(am)[0]
+
+
+def quantize_bits(x, bits: int, rounding: int = SR, seed: int = 0, stream: int = 0, am=None, first: int = 0):
+    """B-bit quantizer: (codes int8 in +-(2^(B-1)-1), scale fp32 = absmax/qmax)."""
+    x = _c(x, np.float32)
+    if am is None:
+        am = absmax(x)
+    q = np.empty(x.shape, np.int8)
+    _L().orc_quantize_bits(_p(x), ctypes.c_size_t(x.size), _u64(first), _f32(float(am)), ctypes.c_int(bits), ctypes.c_int(rounding),
+                           _u64(seed), _u64(stream), _p(q))
+    qmax = np.float32((1 << (bits - 1)) - 1)
+    s = np.float32(am) / qmax if am > 0 else np.float32(1.0)
+    return q, np.float32(s)
+
+
+def pack_int4(q) -> np.ndarray:
+    """Two 4-bit codes per byte along the last axis (even element in the low nibble)."""
+    q = _c(q, np.int8)
+    assert q.shape[-1] % 2 == 0
+    p = np.empty(q.shape[:-1] + (q.shape[-1] // 2,), np.uint8)
+    _L().orc_pack_int4(_p(q), ctypes.c_size_t(q.size), _p(p))
+    return p
+
+
+def unpack_int4(p) -> np.ndarray:
+    p = _c(p, np.uint8)
+    q = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), np.int8)
+    _L().orc_unpack_int4(_p(p), ctypes.c_size_t(q.size), _p(q))
+    return q
 
 
 def error_x(x, bits: int, rounding: int = SR, seed: int = 0, stream: int = 0) -> float:

@@ -134,6 +134,57 @@ void orc_quantize(const float *x, size_t n, uint64_t first, float absmax, int ro
     }
 }
 
+/*
+ * B-bit variant of the quantizer (Sec. 3.2 bit-count rule; Sec. 4 "Speed impact
+ * for # of quantization bits", INT4): codes in +-(2^(B-1)-1), s = absmax/qmax,
+ * inv = qmax/absmax, same rounding rules and the same random bits per element
+ * as the 8-bit one.  One code per int8; B = 8 is orc_quantize.
+ */
+void orc_quantize_bits(const float *x, size_t n, uint64_t first, float absmax, int bits, int rounding, uint64_t seed,
+                       uint64_t stream, int8_t *q)
+{
+    const int qmax = (1 << (bits - 1)) - 1;
+    float s = 1.0f, inv = 0.0f;
+    if (absmax > 0.0f) {
+        s = absmax / (float)qmax;
+        inv = (float)qmax / absmax;
+    }
+    (void)s;
+    for (size_t i = 0; i < n; ++i) {
+        float y = x[i] * inv;
+        int v;
+        if (rounding == 0) {
+            v = (int)rintf(y);
+        } else {
+            float f = floorf(y);
+            float frac = y - f;
+            float u = (float)orc_sr_bits16(seed, stream, first + (uint64_t)i) * (1.0f / 65536.0f);
+            v = (int)f + (u < frac ? 1 : 0);
+        }
+        if (v > qmax) v = qmax;
+        if (v < -qmax) v = -qmax;
+        q[i] = (int8_t)v;
+    }
+}
+
+/*
+ * Packed 4-bit storage: byte j holds element 2j in its low nibble and element
+ * 2j+1 in its high nibble, each as a 4-bit two's-complement number; n even.
+ */
+void orc_pack_int4(const int8_t *q, size_t n, uint8_t *p)
+{
+    for (size_t j = 0; j < n / 2; ++j) p[j] = (uint8_t)(((unsigned)q[2 * j] & 0xFu) | (((unsigned)q[2 * j + 1] & 0xFu) << 4));
+}
+
+void orc_unpack_int4(const uint8_t *p, size_t n, int8_t *q)
+{
+    for (size_t j = 0; j < n / 2; ++j) {
+        int lo = p[j] & 0xF, hi = p[j] >> 4;
+        q[2 * j] = (int8_t)(lo >= 8 ? lo - 16 : lo);
+        q[2 * j + 1] = (int8_t)(hi >= 8 ? hi - 16 : hi);
+    }
+}
+
 /* x_i = s * q_i (Eq. 2 with Z = 0). */
 void orc_dequantize(const int8_t *q, size_t n, float s, float *x)
 {

@@ -198,3 +198,46 @@ def test_bit_count_rule():
     assert bits == next((b for b, e in zip((4, 6, 8), errs) if e < 0.3), 8)
     assert orc.select_bits(g, (4, 6, 8), 0.0, orc.RN)[0] == 8  # nothing qualifies: the widest
     assert orc.select_bits(g, (4, 6, 8), 2.0, orc.RN)[0] == 4  # everything qualifies: the narrowest
+
+
+def test_bit_parameterised_quantizer():
+    x = _x(20000, 31)
+    # B = 8 is the 8-bit quantizer, bit for bit, in both rounding modes
+    for mode in (orc.RN, orc.SR):
+        q8, s8 = orc.quantize(x, mode, seed=4, stream=2)
+        qb, sb = orc.quantize_bits(x, 8, mode, seed=4, stream=2)
+        assert np.array_equal(q8, qb) and s8 == sb
+    # B = 4: codes in [-7, 7], s = absmax/7, nearest rounding within s/2, extreme element at +-7
+    q4, s4 = orc.quantize_bits(x, 4, orc.RN)
+    assert s4 == orc.absmax(x) / np.float32(7.0)
+    assert q4.min() == -7 or q4.max() == 7
+    assert q4.min() >= -7 and q4.max() <= 7
+    assert np.abs(s4.astype(np.float64) * q4 - x.astype(np.float64)).max() <= 0.5 * float(s4) * (1 + 1e-5)
+    # hand-computed: absmax 7 -> inv = 1: 2.5 -> 2 (ties to even), 3.5 -> 4, -6.6 -> -7, 0.49 -> 0
+    q, s = orc.quantize_bits(np.array([7.0, 2.5, 3.5, -6.6, 0.49], np.float32), 4, orc.RN)
+    assert s == 1.0 and list(q) == [7, 2, 4, -7, 0]
+    # stochastic: floor or floor + 1, unbiased, same random bits as the 8-bit quantizer (same index -> same u)
+    q4s, _ = orc.quantize_bits(x, 4, orc.SR, seed=9, stream=3)
+    inv = np.float32(7.0) / orc.absmax(x)
+    f = np.floor(x * inv)
+    d = q4s.astype(np.float32) - np.clip(f, -7, 7)
+    assert set(np.unique(d)).issubset({0.0, 1.0})
+    err = float(s4) * q4s.astype(np.float64) - x.astype(np.float64)
+    assert abs(err.mean()) < 4 * float(s4) / (2 * np.sqrt(x.size))
+    y = np.full(100000, 3.25, np.float32)
+    y[0] = 7.0
+    up4 = (orc.quantize_bits(y, 4, orc.SR, seed=99, stream=1)[0][1:] == 4)
+    y8 = np.full(100000, 3.25, np.float32)
+    y8[0] = 127.0
+    up8 = (orc.quantize(y8, orc.SR, seed=99, stream=1)[0][1:] == 4)
+    assert np.array_equal(up4, up8)  # identical fractions, identical random bits -> identical decisions
+
+
+def test_int4_packing():
+    q = np.array([[-7, 3, 0, -1], [7, -8 + 1, 5, 2]], np.int8)
+    p = orc.pack_int4(q)
+    assert p.shape == (2, 2) and p.dtype == np.uint8
+    assert p[0, 0] == ((3 << 4) | (-7 & 0xF)) and p[0, 1] == ((0xF << 4) | 0)
+    assert np.array_equal(orc.unpack_int4(p), q)
+    r = np.random.default_rng(0).integers(-7, 8, size=(37, 64), dtype=np.int8)
+    assert np.array_equal(orc.unpack_int4(orc.pack_int4(r)), r)
