@@ -353,6 +353,42 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                             float *dalpha, float *dS, float *dD, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------ */
+/* 4-bit operands (Sec. 4 "Speed impact for # of quantization bits").         */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * The quantizer of tango_quantize with codes in [-7, 7] (s = absmax/7,
+ * inv = 7/absmax; same rounding rules, same random bits per element),
+ * stored packed: byte j of q4 holds element 2j in its low nibble and 2j+1 in
+ * its high nibble, each a 4-bit two's-complement number.  n even; x 16-byte,
+ * q4 4-byte aligned; q4 has n/2 bytes.  absmax_in / ws as in tango_quantize.
+ */
+int tango_quantize_i4(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                      const float *absmax_in, uint8_t *q4, float *scale_out, void *ws, size_t ws_bytes,
+                      void *stream);
+
+/*
+ * tango_qspmm with a packed 4-bit feature table X_q4 (n x heads*dim/2 bytes,
+ * layout of tango_quantize_i4 along each row); the edge weights w_q stay
+ * int8.  Halves the gathered bytes per edge.  The paper measures no INT4
+ * SPMM (its baselines have none); this is the same operation as steps 5 / 5'
+ * on the narrower table.  dim % 8 == 0; heads*dim <= 1024; exact while every
+ * |integer sum| < 2^27.  Other arguments as in tango_qspmm.
+ */
+int tango_qspmm_i4(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q,
+                   const float *s_w, const uint8_t *X_q4, const float *s_X, float *out, float *absmax_out,
+                   void *stream);
+
+/*
+ * SDDMM, dot-product case (step 5''), with both node tables packed 4-bit:
+ * E[e][h] = (float)(sum_d X_dst4[dst(e)][h][d] * X_src4[src(e)][h][d]) * (s_dst*s_src),
+ * E: nnz x heads fp32 in destination-major edge order.  dim % 8 == 0;
+ * heads*dim <= 2048; tables 16-byte aligned.
+ */
+int tango_qsddmm_dot_i4(const tango_graph *g, int heads, int dim, const uint8_t *X_src4, const float *s_src,
+                        const uint8_t *X_dst4, const float *s_dst, float *E, void *stream);
+
+/* ------------------------------------------------------------------------ */
 /* Full-precision twins of the two gather-bound primitives, for measuring     */
 /* what quantization buys on the same graph (Sec. 3.3: the random accesses    */
 /* hit a 4x smaller table).  Not part of the quantized path.                  */

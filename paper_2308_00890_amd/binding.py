@@ -56,6 +56,9 @@ SIGNATURES = {
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_mfma_i8_rate_workspace_bytes": (_sz, []),
     "tango_mfma_i8_rate_launch": (_int, [_int, _int, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
+    "tango_quantize_i4": (_int, [_vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "tango_qspmm_i4": (_int, [_gp, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "tango_qsddmm_dot_i4": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qgemm_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm_bwd": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _int, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_head_proj": (_int, [_i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -339,6 +342,36 @@ def tango_qspmm(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out):
             _ptr(s_X, torch.float32), _ptr(out, torch.float32), _ptr(absmax_out, torch.float32), _stream(),
         ),
         "tango_qspmm",
+    )
+
+
+def tango_quantize_i4(x, rounding, seed, stream_id, absmax_in, q4, scale_out, ws):
+    _check(
+        load_library().tango_quantize_i4(
+            _ptr(x, torch.float32), x.numel(), rounding, seed, stream_id, _ptr(absmax_in, torch.float32), _ptr(q4, torch.uint8),
+            _ptr(scale_out, torch.float32), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_quantize_i4",
+    )
+
+
+def tango_qspmm_i4(g, direction, heads, dim, w_q, s_w, X_q4, s_X, out, absmax_out):
+    _check(
+        load_library().tango_qspmm_i4(
+            g.ref(), direction, heads, dim, _ptr(w_q, torch.int8), _ptr(s_w, torch.float32), _ptr(X_q4, torch.uint8),
+            _ptr(s_X, torch.float32), _ptr(out, torch.float32), _ptr(absmax_out, torch.float32), _stream(),
+        ),
+        "tango_qspmm_i4",
+    )
+
+
+def tango_qsddmm_dot_i4(g, heads, dim, X_src4, s_src, X_dst4, s_dst, E):
+    _check(
+        load_library().tango_qsddmm_dot_i4(
+            g.ref(), heads, dim, _ptr(X_src4, torch.uint8), _ptr(s_src, torch.float32), _ptr(X_dst4, torch.uint8),
+            _ptr(s_dst, torch.float32), _ptr(E, torch.float32), _stream(),
+        ),
+        "tango_qsddmm_dot_i4",
     )
 
 

@@ -200,9 +200,13 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 
 // One wave per chunk of edges.  VEC = bytes of the feature row per lane; HAS_EID: the weight of edge j of
 // this direction sits at position eid[j] (reversed graph) instead of j.
-template <int VEC, bool HAS_EID, int WMODE>
+// X4: the feature table holds packed 4-bit codes (two columns per byte, even column in the low nibble); a.F and
+// a.dim still count columns.  The nibbles are used in place as (code * 16) in an int8, so the int32 sums carry a
+// factor 16 that is shifted out (exactly) when a row is finished: exact while |sum| < 2^27.
+template <int VEC, bool HAS_EID, int WMODE, bool X4 = false>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 0 ? 5 : 4))) void k_spmm(spmm_args a)
 {
+    constexpr int CPL = X4 ? 2 * VEC : VEC;  // columns per lane
     using V = typename vec_bytes<VEC>::type;
     __shared__ __align__(16) int stage[WAVES_PER_BLOCK][1024];  // one strip of F <= 1024 sums per wave
     const int lane = threadIdx.x % TANGO_WAVE;
@@ -214,13 +218,14 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     if (c0 >= a.nnz) return;
     const int64_t c1 = min(c0 + (int64_t(1) << a.chunk_shift), a.nnz);
 
-    const int LPR = a.F / VEC;          // lanes per feature row
+    const int LPR = a.F / CPL;          // lanes per feature row
     const int G = 64 / LPR;             // neighbour rows gathered per wave-wide load (power of two)
     const int gi = lane / LPR;          // my group (>= G: idle lane)
     const int li = lane - gi * LPR;     // my position in the row
     const bool active = gi < G;
-    const int col = li * VEC;           // first of my VEC columns
+    const int col = li * CPL;           // first of my CPL columns
     const int h = col / a.dim;          // their head
+    const int row_bytes = X4 ? a.F / 2 : a.F;
     constexpr bool ATT = WMODE != W_LOAD;
     float s_w, inv_w = 0.0f, att_sS = 0.0f, att_sD = 0.0f;
     if (ATT) {
@@ -232,7 +237,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         s_w = *a.s_w;
     }
     const float sc = s_w * (*a.s_X);
-    const int8_t *Xcol = a.X + col;
+    const int8_t *Xcol = a.X + li * VEC;
 
     // The chunk is walked in blocks of 64 consecutive edges, whatever rows they belong to: lane l of a block first
     // fetches the neighbour index and the packed head weights of edge base+l (coalesced; in the attention modes it
@@ -263,22 +268,26 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         } while (cur_rt == was);
     };
 
-    int acc[VEC];
+    int acc[CPL];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0;
+    for (int j = 0; j < CPL; ++j) acc[j] = 0;
     bool pending = false;  // acc holds sums of the open row
 
     auto finish_row = [&](int r, bool whole) {
         // combine the G groups: afterwards group 0 holds the sums of this row segment
         for (int off = G / 2; off >= 1; off >>= 1) {
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] += __shfl_down(acc[j], off * LPR, 64);
+            for (int j = 0; j < CPL; ++j) acc[j] += __shfl_down(acc[j], off * LPR, 64);
+        }
+        if (X4) {
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) acc[j] >>= 4;  // exact: every term is a multiple of 16
         }
         if (whole) {
             if (gi == 0) {
                 float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
 #pragma unroll
-                for (int j = 0; j < VEC; j += 4) {
+                for (int j = 0; j < CPL; j += 4) {
                     float4 o;
                     o.x = static_cast<float>(acc[j + 0]) * sc;
                     o.y = static_cast<float>(acc[j + 1]) * sc;
@@ -294,7 +303,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             int *strip = stage[wv];
             if (gi == 0) {
 #pragma unroll
-                for (int j = 0; j < VEC; j += 4)
+                for (int j = 0; j < CPL; j += 4)
                     *reinterpret_cast<int4 *>(strip + col + j) = make_int4(acc[j], acc[j + 1], acc[j + 2], acc[j + 3]);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -308,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             __builtin_amdgcn_wave_barrier();
         }
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc[j] = 0;
+        for (int j = 0; j < CPL; ++j) acc[j] = 0;
         pending = false;
     };
 
@@ -404,7 +413,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                             if (h >= 4) ww = w1;
                         }
                         wq[u] = ok ? ((ww >> (8 * (h & 3))) & 0xffu) : 0u;
-                        xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                        xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * row_bytes);
                     }
                     // 4 edges at a time: transpose each 4x4 byte block so that one dot4 multiplies one column of
                     // four neighbour rows by the four edge weights
@@ -419,10 +428,26 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
 #pragma unroll
                         for (int q = 0; q < VEC / 4; ++q) {
                             uint32_t t[4];
-                            transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+                            if (X4) {
+                                // byte c of a word = columns 2c (low nibble) and 2c+1 (high nibble): split into two words
+                                // of (code * 16) bytes and treat each like an int8 word
+                                constexpr uint32_t HI = 0xf0f0f0f0u;
+                                transpose4x4((w0[q] << 4) & HI, (w1[q] << 4) & HI, (w2[q] << 4) & HI, (w3[q] << 4) & HI, t);
 #pragma unroll
-                            for (int c = 0; c < 4; ++c)
-                                acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                                for (int c = 0; c < 4; ++c)
+                                    acc[8 * q + 2 * c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack),
+                                                                                acc[8 * q + 2 * c], false);
+                                transpose4x4(w0[q] & HI, w1[q] & HI, w2[q] & HI, w3[q] & HI, t);
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    acc[8 * q + 2 * c + 1] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack),
+                                                                                    acc[8 * q + 2 * c + 1], false);
+                            } else {
+                                transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+#pragma unroll
+                                for (int c = 0; c < 4; ++c)
+                                    acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                            }
                         }
                     }
                 };
@@ -554,7 +579,9 @@ struct sddmm_dot_args {
 // ATT_BWD (step 3' fused with 5'', 4' and LeakyReLU', walking the out-edges of each source u): the dot product
 // of edge (u -> v) is dalpha, alpha is recomputed from S_q[u], D_q[v], row_max[v], row_rden[v], and
 // dS_acc[u][h] += alpha*(dalpha - P[v][h]) * lrelu'(t).
-template <int VEC, bool ATT_BWD>
+// I4: both tables hold packed 4-bit codes; a.F and a.dim then count bytes (two columns each) and the products come
+// from v_dot8_i32_i4.
+template <int VEC, bool ATT_BWD, bool I4 = false>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
 {
     using V = typename vec_bytes<VEC>::type;
@@ -626,7 +653,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                     int d = 0;
 #pragma unroll
                     for (int j = 0; j < VEC / 4; ++j)
-                        d = __builtin_amdgcn_sdot4(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false);
+                        d = I4 ? __builtin_amdgcn_sdot8(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false)
+                               : __builtin_amdgcn_sdot4(static_cast<int>(dw[j]), static_cast<int>(w[j]), d, false);
                     dot[u] = d;
                 }
 #pragma unroll
@@ -707,6 +735,21 @@ int pick_vec(int F, int dim, bool pow2_lanes_per_head)
     return 0;
 }
 
+// Packed 4-bit rows (F/2 bytes): bytes per lane for the SPMM, 8 or 4 (16 or 8 columns per lane, all in one head,
+// lanes per row dividing 64); 0 when neither fits.
+int pick_vec_i4(int F, int dim)
+{
+    const int pref[2] = {F <= 128 ? 4 : 8, F <= 128 ? 8 : 4};
+    for (int i = 0; i < 2; ++i) {
+        const int cpl = 2 * pref[i];
+        if (dim % cpl != 0 || F % cpl != 0) continue;
+        const int lpr = F / cpl;
+        if (lpr > 64 || !is_pow2(64 / lpr)) continue;
+        return pref[i];
+    }
+    return 0;
+}
+
 int validate_graph_dir(const tango_graph *g, int direction)
 {
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -732,7 +775,7 @@ int validate_feature_shape(int heads, int dim)
 
 static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
                        const int8_t *X_q, const float *s_X, float *out, float *absmax_out, const attn_params *att,
-                       hipStream_t st)
+                       hipStream_t st, bool x4 = false)
 {
     spmm_args a;
     if (att) a.att = *att;
@@ -757,7 +800,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     else if ((a.nnz >> 8) >= 4096) a.chunk_shift = 8;
     // low mean degree, weights at the edge's own position, rows of at most two cache lines: rows of up to 64
     // edges go to the group-per-row kernel (measured: 3-20 % faster there, slower elsewhere)
-    a.short_max = (!att && !a.eid && a.F <= 256 && a.n > 0 && a.nnz / a.n <= 20) ? 64 : 0;
+    a.short_max = (!x4 && !att && !a.eid && a.F <= 256 && a.n > 0 && a.nnz / a.n <= 20) ? 64 : 0;
     const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
     k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
     TANGO_LAUNCH_CHECK();
@@ -776,6 +819,20 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     if (a.nnz > 0) {
         const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        if (x4) {  // packed 4-bit table, plain weights
+            const int vec = pick_vec_i4(a.F, dim);
+            if (vec == 4) {
+                if (a.eid) k_spmm<4, true, W_LOAD, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+                else k_spmm<4, false, W_LOAD, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            } else {
+                if (a.eid) k_spmm<8, true, W_LOAD, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+                else k_spmm<8, false, W_LOAD, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            }
+            TANGO_LAUNCH_CHECK();
+            k_spmm_finalize<<<row_blocks, 256, 0, st>>>(a);
+            TANGO_LAUNCH_CHECK();
+            return TANGO_OK;
+        }
         const int vec = pick_vec(a.F, dim, false);
 #define TANGO_SPMM(V_)                                                                  \
     if (att && a.eid)                                                                   \
@@ -909,6 +966,58 @@ int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const i
     TANGO_REQUIRE(X_q && s_w && s_X && out && (g->n_edges == 0 || w_q), TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
     return tango_spmm_async(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out, tango_stream(stream));
+}
+
+int tango_qspmm_i4(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
+                   const uint8_t *X_q4, const float *s_X, float *out, float *absmax_out, void *stream)
+{
+    TANGO_REQUIRE(direction == TANGO_IN || direction == TANGO_OUT, TANGO_ERR_BAD_ENUM);
+    int rc = validate_graph_dir(g, direction);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(heads >= 1 && heads <= 8 && dim >= 8 && dim % 8 == 0 && static_cast<int64_t>(heads) * dim <= 1024,
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(pick_vec_i4(heads * dim, dim) != 0, TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(X_q4 && s_w && s_X && out && (g->n_edges == 0 || w_q), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q4, 16), TANGO_ERR_BAD_SHAPE);
+    return spmm_launch(g, direction, heads, dim, w_q, s_w, reinterpret_cast<const int8_t *>(X_q4), s_X, out, absmax_out,
+                       nullptr, tango_stream(stream), true);
+}
+
+int tango_qsddmm_dot_i4(const tango_graph *g, int heads, int dim, const uint8_t *X_src4, const float *s_src,
+                        const uint8_t *X_dst4, const float *s_dst, float *E, void *stream)
+{
+    int rc = validate_graph_dir(g, TANGO_IN);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(heads >= 1 && heads <= 8 && dim >= 8 && dim % 8 == 0 && static_cast<int64_t>(heads) * dim <= 2048,
+                  TANGO_ERR_BAD_SHAPE);
+    const int vec = pick_vec(heads * dim / 2, dim / 2, true);  // in bytes of the packed rows
+    TANGO_REQUIRE(vec != 0, TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(X_src4 && X_dst4 && s_src && s_dst && (g->n_edges == 0 || E), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(X_src4, 16) && tango_aligned(X_dst4, 16), TANGO_ERR_BAD_SHAPE);
+    if (g->n_edges == 0) return TANGO_OK;
+    hipStream_t st = tango_stream(stream);
+    sddmm_dot_args a;
+    a.n = g->n_nodes;
+    a.nnz = g->n_edges;
+    a.ptr = g->in_ptr;
+    a.idx = g->in_src;
+    a.Xdst = reinterpret_cast<const int8_t *>(X_dst4);
+    a.Xsrc = reinterpret_cast<const int8_t *>(X_src4);
+    a.s_dst = s_dst;
+    a.s_src = s_src;
+    a.out = E;
+    a.heads = heads;
+    a.dim = dim / 2;
+    a.F = heads * dim / 2;
+    const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+    const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+    switch (vec) {
+        case 4: k_sddmm_dot<4, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 8: k_sddmm_dot<8, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default: k_sddmm_dot<16, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+    }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
 }
 
 int tango_qspmm_bwd(const tango_graph *g, int heads, int dim, const int8_t *w_q, const float *s_w, const int8_t *X_q,
