@@ -19,6 +19,12 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
                                float *out, float *absmax_out, hipStream_t st);
+int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
+                                      const int8_t *Dq, const float *sD, float slope, const float *row_lse,
+                                      const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
+                                      const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
+                                      const float *s_X, const tango_attn_rec *rec, double *dS_acc, float *out,
+                                      float *absmax_out, float *dS, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -312,6 +318,17 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     tango_attn_rec *rec = reinterpret_cast<tango_attn_rec *>(static_cast<char *>(ws) + 256);
     double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 2 * nh_bytes);
     int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
+    if (edge_part && !alpha_q) {
+        // 5'' over in-edges (dalpha, the only fp32 edge tensor of the backward pass), 4' and 3'' over in-edges, then
+        // 5' and 3' together in one walk over the out-edges: both need the rows dOut_q[v] of every out-edge (u -> v)
+        rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);
+        if (rc != TANGO_OK) return rc;
+        rc = tango_attn_bwd_dst_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, dalpha, rec, dD, huge, st);
+        if (rc != TANGO_OK) return rc;
+        return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
+                                                 stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
+                                                 absmax_dX, dS, st);
+    }
     // 5': SPMM on the reversed graph.  With a cached alpha_q its codes are read through the edge-id map (a random
     // 4-byte access per edge); without, the identical codes are recomputed from the cache-resident S_q, D_q, row_lse.
     if (alpha_q)

@@ -114,6 +114,20 @@ __device__ static inline int tango_round_clamp(float y, uint32_t bits16)
 // ---------------------------------------------------------------------------
 // Wave-level reductions (wave64) via cross-lane shuffles.
 // ---------------------------------------------------------------------------
+// Sum over aligned groups of n adjacent lanes (n a power of two), result in every lane of the group.  Up to 16
+// lanes the partner values come through DPP modifiers of VALU moves (quad permutes, then mirrored halves and rows -
+// after the earlier steps all lanes of a half hold the same value, so a mirror is as good as an xor); only wider
+// groups use LDS-pipe shuffles.  Must be called by all 64 lanes.
+__device__ static inline int tango_group_sum(int d, int n)
+{
+    if (n >= 2) d += __builtin_amdgcn_update_dpp(0, d, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    if (n >= 4) d += __builtin_amdgcn_update_dpp(0, d, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    if (n >= 8) d += __builtin_amdgcn_update_dpp(0, d, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    if (n >= 16) d += __builtin_amdgcn_update_dpp(0, d, 0x140, 0xF, 0xF, true);  // row_mirror
+    for (int off = 16; off < n; off <<= 1) d += __shfl_xor(d, off, 64);
+    return d;
+}
+
 __device__ static inline float tango_wave_max(float v)
 {
 #pragma unroll

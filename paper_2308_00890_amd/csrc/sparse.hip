@@ -103,6 +103,11 @@ struct attn_params {
     int8_t *alpha_q;     // forward: out, nnz x heads (or NULL)
     float *s_alpha;      // forward: out
     float *alpha_dump;   // forward: out or NULL, the fp32 alpha that was quantized
+    // reverse pass fused with step 3' (DS instantiations): the gathered rows also give dalpha of every out-edge
+    const int8_t *Xrow;            // n x F: the table of the row side (H'_q of the source)
+    const float *s_Xrow;
+    const tango_attn_rec *rec;     // n x heads: (P, row_lse) of the destination
+    double *dS_acc;                // n x heads, zero-initialised
 };
 
 enum { W_LOAD = 0, W_ATT_FWD = 1, W_ATT_REV = 2 };
@@ -203,10 +208,18 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 // X4: the feature table holds packed 4-bit codes (two columns per byte, even column in the low nibble); a.F and
 // a.dim still count columns.  The nibbles are used in place as (code * 16) in an int8, so the int32 sums carry a
 // factor 16 that is shifted out (exactly) when a row is finished: exact while |sum| < 2^27.
-template <int VEC, bool HAS_EID, int WMODE, bool X4 = false>
+// DS (reverse attention mode only; Sec. 2.1 steps 5', 5'', 4', 3' in one walk over the out-edges of each source u):
+// the row of dOut_q[v] gathered for 5' is also multiplied with the resident row X_q[u], which is dalpha of edge
+// (u -> v); with alpha (already recomputed for the edge weight), P[v] and the sign of the pre-activation this gives
+// dE, summed into dS_acc[u][h] - the second gather pass over the same rows that a separate SDDMM would need is gone.
+template <int VEC, bool HAS_EID, int WMODE, bool X4 = false, bool DS = false>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 0 ? 5 : 4))) void k_spmm(spmm_args a)
 {
     constexpr int CPL = X4 ? 2 * VEC : VEC;  // columns per lane
+    static_assert(!DS || (WMODE == W_ATT_REV && !X4), "the fused dS path belongs to the reverse attention mode");
+    // DS: per wave, the dot products and the fp32 alpha of the current block of 64 edges, [edge][head], heads <= 8
+    __shared__ int dots_s[DS ? WAVES_PER_BLOCK : 1][DS ? 64 * 8 : 1];
+    __shared__ float alf_s[DS ? WAVES_PER_BLOCK : 1][DS ? 64 * 8 : 1];
     using V = typename vec_bytes<VEC>::type;
     __shared__ __align__(16) int stage[WAVES_PER_BLOCK][1024];  // one strip of F <= 1024 sums per wave
     const int lane = threadIdx.x % TANGO_WAVE;
@@ -238,6 +251,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     }
     const float sc = s_w * (*a.s_X);
     const int8_t *Xcol = a.X + li * VEC;
+    const int LPH = a.dim / VEC;  // DS: lanes per head (a power of two)
+    float sc_dot = 0.0f;
+    if (DS) sc_dot = (*a.s_X) * (*a.att.s_Xrow);
 
     // The chunk is walked in blocks of 64 consecutive edges, whatever rows they belong to: lane l of a block first
     // fetches the neighbour index and the packed head weights of edge base+l (coalesced; in the attention modes it
@@ -338,6 +354,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         }
         int my_nb = 0;
         uint32_t my_w0 = 0, my_w1 = 0;
+        uint32_t pos_mask = 0;  // DS: bit h = the pre-activation score of my edge, head h, is positive
         if (lane < cnt) {
             const int e = base + lane;
             my_nb = a.idx[e];
@@ -359,6 +376,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                     const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
                                                       a.att.slope, pos);
                     const float al = tango_attn_alpha(ev, a.att.row_lse[dst_node * H + hh]);
+                    if (DS) {
+                        alf_s[wv][lane * H + hh] = al;
+                        pos_mask |= (pos ? 1u : 0u) << hh;
+                    }
                     if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
                     int q;
                     if (a.att.rounding == TANGO_SR) {
@@ -395,6 +416,11 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             const int rt = (k0 == 0) ? seg_rt : __builtin_amdgcn_readlane(my_rt, k0);
             const int k1 = min(rt - base, cnt);
             const int len = k1 - k0;
+            uint32_t dw[VEC / 4];  // DS: my columns of the resident row X_q[r]
+            if (DS) {
+                const V dv = *reinterpret_cast<const V *>(a.att.Xrow + static_cast<int64_t>(r) * a.F + (active ? col : 0));
+                unpack_words<VEC>(dv, dw);
+            }
             if (rt - open_rb > a.short_max) {
                 const int steps = (len + G - 1) / G;
                 auto batch = [&](int s0, auto uu) {
@@ -425,6 +451,24 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         unpack_words<VEC>(xv[u + 1], w1);
                         unpack_words<VEC>(xv[u + 2], w2);
                         unpack_words<VEC>(xv[u + 3], w3);
+                        if (DS) {
+                            // dalpha of the four edges: my columns' share of the dot product with the resident row,
+                            // summed over the lanes of my head, left in LDS as [edge of the block][head]
+                            int d4[4] = {0, 0, 0, 0};
+#pragma unroll
+                            for (int q = 0; q < VEC / 4; ++q) {
+                                d4[0] = __builtin_amdgcn_sdot4(static_cast<int>(dw[q]), static_cast<int>(w0[q]), d4[0], false);
+                                d4[1] = __builtin_amdgcn_sdot4(static_cast<int>(dw[q]), static_cast<int>(w1[q]), d4[1], false);
+                                d4[2] = __builtin_amdgcn_sdot4(static_cast<int>(dw[q]), static_cast<int>(w2[q]), d4[2], false);
+                                d4[3] = __builtin_amdgcn_sdot4(static_cast<int>(dw[q]), static_cast<int>(w3[q]), d4[3], false);
+                            }
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const int d = tango_group_sum(d4[v], LPH);
+                                const int k = (s0 + u + v) * G + gi;
+                                if (active && k < len && (li % LPH) == 0) dots_s[wv][(k0 + k) * a.heads + h] = d;
+                            }
+                        }
 #pragma unroll
                         for (int q = 0; q < VEC / 4; ++q) {
                             uint32_t t[4];
@@ -461,6 +505,34 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 open_rb = rt;
             }
             k0 = k1;
+        }
+        if (DS) {
+            // step 4', LeakyReLU' and step 3' for the 64 edges of the block, one edge per lane: dE = alpha*(dalpha - P),
+            // times the slope where the score was not positive, summed per (row segment, head) in fp64
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int H = a.heads;
+            for (int hh = 0; hh < H; ++hh) {
+                double contrib = 0.0;
+                if (lane < cnt) {
+                    const float da = static_cast<float>(dots_s[wv][lane * H + hh]) * sc_dot;
+                    const tango_attn_rec rc = a.att.rec[static_cast<int64_t>(my_nb) * H + hh];
+                    const float al = alf_s[wv][lane * H + hh];
+                    const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
+                    contrib = static_cast<double>(dE * (((pos_mask >> hh) & 1u) ? 1.0f : a.att.slope));
+                }
+                for (int k0 = 0; k0 < cnt;) {
+                    const int r = __builtin_amdgcn_readlane(my_row, k0);
+                    const int k1 = min(__builtin_amdgcn_readlane(my_rt, k0) - base, cnt);
+                    double v = (lane >= k0 && lane < k1) ? contrib : 0.0;
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+                    if (lane == 0 && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(r) * H + hh, v);
+                    k0 = k1;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
     if (pending) finish_row(cur_r, false);  // the last row continues in the next chunk
@@ -659,8 +731,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                 }
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
-                    int d = dot[u];
-                    for (int off = LPH / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off, 64);
+                    const int d = tango_group_sum(dot[u], LPH);
                     const int k = (s0 + u) * G + gi;
                     if (active && k < cnt && (li % LPH) == 0) dots[wv][k * H + h] = d;
                 }
@@ -833,6 +904,17 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
             TANGO_LAUNCH_CHECK();
             return TANGO_OK;
         }
+        if (att && att->rec) {  // reverse attention SPMM fused with step 3'
+            switch (pick_vec(a.F, dim, true)) {
+                case 4: k_spmm<4, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+                case 8: k_spmm<8, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+                default: k_spmm<16, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            }
+            TANGO_LAUNCH_CHECK();
+            k_spmm_finalize<<<row_blocks, 256, 0, st>>>(a);
+            TANGO_LAUNCH_CHECK();
+            return TANGO_OK;
+        }
         const int vec = pick_vec(a.F, dim, false);
 #define TANGO_SPMM(V_)                                                                  \
     if (att && a.eid)                                                                   \
@@ -872,7 +954,34 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = alpha_q; att.s_alpha = s_alpha; att.alpha_dump = alpha_dump;
+    att.Xrow = nullptr; att.s_Xrow = nullptr; att.rec = nullptr; att.dS_acc = nullptr;
     return spmm_launch(g, direction, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
+}
+
+// Steps 5' and 3' in one walk over the out-edges (attention codes recomputed): out = the reverse SPMM of dOut_q,
+// dS[u][h] = sum over out-edges of dE.  rec holds (P, row_lse) per (destination, head); dS_acc: n x heads doubles
+// of scratch.  heads*dim must also satisfy the SDDMM-dot shape rule (power-of-two lanes per head).
+int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
+                                      const int8_t *Dq, const float *sD, float slope, const float *row_lse,
+                                      const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
+                                      const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
+                                      const float *s_X, const tango_attn_rec *rec, double *dS_acc, float *out,
+                                      float *absmax_out, float *dS, hipStream_t st)
+{
+    const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
+    if (rc != TANGO_OK) return rc;
+    attn_params att;
+    att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
+    att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
+    att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
+    att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
+    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc;
+    rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st);
+    if (rc != TANGO_OK) return rc;
+    k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
 }
 
 int tango_validate_spmm_shape(int heads, int dim) { return validate_feature_shape(heads, dim); }
