@@ -336,7 +336,12 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
  *                             alpha_q = NULL: its codes are recomputed on the fly (same rounding, seed, stream id
  *                             as the forward call), which replaces one random 4-byte read per edge by reads of
  *                             the small cache-resident S_q, D_q, row_lse tables;
- *   dalpha (nnz x heads)    = SDDMM-dot of dOut_q[dst] and X_q[src] (step 5''), fp32 scratch that is also an output;
+ *   dalpha (nnz x heads)    = SDDMM-dot of dOut_q[dst] and X_q[src] (step 5''), fp32 scratch that is also an output.
+ *                             With alpha_q = NULL it may be NULL while dS and dD are given: then no edge tensor is
+ *                             written at all - one walk over the in-edges forms P and dD from three running sums
+ *                             per (node, head) (dD = B - P*C with P = sum alpha*dalpha, B = sum alpha*dalpha*s,
+ *                             C = sum alpha*s, s = 1 or the slope by the sign of the score; fp64), and one walk
+ *                             over the out-edges forms dX_agg and dS together;
  *   dD, dS (n x heads fp32) = sums over in-/out-edges of alpha*(dalpha - P)*lrelu'(t) with the fp32 alpha
  *                             recomputed from S_q, D_q, row_lse exactly as the forward pass computed it
  *                             (the gradient of the pre-activation scores is never written to memory).
@@ -449,7 +454,8 @@ typedef struct tango_gat_layer {
     const float *grad_out;        /* n x F */
     int8_t *g_q;  float *s_g;     /* n x F: quantized upstream gradient */
     float *dHp;   float *absmax_dHp; /* n x F: dH' = dH'_agg + dH'_att */
-    float *dalpha;                /* nnz x heads: step 5''; overwritten by step 4' (dE) */
+    float *dalpha;                /* nnz x heads: step 5''; overwritten by step 4' (dE); with fused = 1 and
+                                     alpha_q = NULL it may be NULL (nothing is stored per edge) */
     float *dS, *dD;               /* n x heads */
     int8_t *dHp_q; float *s_dHp;  /* n x F */
     float *dW;                    /* k_in x F  (fp32 gradient for the full-precision weight update) */

@@ -528,7 +528,7 @@ class GatLayer(_LayerBuffers):
     _struct = tango_gat_layer
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
-                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False):
+                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False, keep_dalpha=False):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -572,7 +572,8 @@ class GatLayer(_LayerBuffers):
             self._bind("grad_out", grad_out, f32)
             self._alloc("g_q", (n, F), i8)
             self._alloc("dHp", (n, F), f32)
-            self._alloc("dalpha", (nnz, heads), f32)
+            if keep_dalpha or not fused or keep_alpha_q:
+                self._alloc("dalpha", (nnz, heads), f32)
             self._alloc("dHp_q", (n, F), i8)
             self._alloc("dW", (k_in, F), f32)
             if want_dH:

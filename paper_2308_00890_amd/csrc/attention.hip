@@ -25,6 +25,10 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
                                       const float *s_X, const tango_attn_rec *rec, double *dS_acc, float *out,
                                       float *absmax_out, float *dS, hipStream_t st);
+int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
+                                   const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
+                                   const float *sD, float slope, const float *row_lse, double *stats, tango_attn_rec *rec,
+                                   float *dD, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -283,8 +287,9 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
 
 size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads)
 {
-    // per (node, head): a 16-byte record (P, row_lse) and a double dS accumulator; then the list of hub rows
-    return 256 + 3 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
+    // per (node, head): a 16-byte record (P, row_lse), a double dS accumulator and three running sums; then the list
+    // of hub rows
+    return 256 + 6 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
 }
 
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
@@ -304,8 +309,9 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && s_alpha && absmax_alpha && X_q && s_X && dOut_q && s_dOut &&
                       dX_agg,
                   TANGO_ERR_NULL);
-    const bool edge_part = dalpha || dS || dD;  // all three or none
-    TANGO_REQUIRE(!edge_part || (dS && dD && (g->n_edges == 0 || dalpha)), TANGO_ERR_NULL);
+    const bool edge_part = dalpha || dS || dD;
+    TANGO_REQUIRE(!edge_part || (dS && dD), TANGO_ERR_NULL);
+    TANGO_REQUIRE(!(alpha_q && edge_part && g->n_edges > 0 && !dalpha), TANGO_ERR_NULL);  // the cached-codes path keeps dalpha
     TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) &&
                       tango_aligned(dalpha, 16),
                   TANGO_ERR_BAD_SHAPE);
@@ -317,7 +323,17 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     const size_t nh_bytes = tango_round_up(static_cast<size_t>(g->n_nodes) * heads * sizeof(double), 256);
     tango_attn_rec *rec = reinterpret_cast<tango_attn_rec *>(static_cast<char *>(ws) + 256);
     double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 2 * nh_bytes);
-    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
+    double *stats = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
+    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 6 * nh_bytes);
+    if (edge_part && !alpha_q && !dalpha) {
+        // no edge tensor at all: 5'', 4', 3'' in one walk over the in-edges, then 5' and 3' in one walk over the out-edges
+        rc = tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse, stats,
+                                            rec, dD, st);
+        if (rc != TANGO_OK) return rc;
+        return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
+                                                 stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
+                                                 absmax_dX, dS, st);
+    }
     if (edge_part && !alpha_q) {
         // 5'' over in-edges (dalpha, the only fp32 edge tensor of the backward pass), 4' and 3'' over in-edges, then
         // 5' and 3' together in one walk over the out-edges: both need the rows dOut_q[v] of every out-edge (u -> v)

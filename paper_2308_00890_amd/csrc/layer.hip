@@ -88,9 +88,10 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
 int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
 {
     TANGO_REQUIRE(L && L->g, TANGO_ERR_NULL);
-    TANGO_REQUIRE(L->grad_out && L->g_q && L->s_g && L->dHp && L->absmax_dHp && L->dalpha && L->dS && L->dD && L->dHp_q &&
+    TANGO_REQUIRE(L->grad_out && L->g_q && L->s_g && L->dHp && L->absmax_dHp && L->dS && L->dD && L->dHp_q &&
                       L->s_dHp && L->dW && L->da_src && L->da_dst,
                   TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->dalpha || (L->fused && !L->alpha_q) || L->g->n_edges == 0, TANGO_ERR_NULL);
     TANGO_REQUIRE(L->a_src && L->a_dst && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp_q && L->s_Hp && L->S_q && L->s_S &&
                       L->D_q && L->s_D && L->s_alpha,
                   TANGO_ERR_NULL);

@@ -645,22 +645,33 @@ struct sddmm_dot_args {
     float slope;
     const tango_attn_rec *rec;       // n x heads: (P, row_lse) of the destination
     double *dS_acc;                  // n x heads, zero-initialised
+    // DOT_DST instantiations only (rows = destination nodes): three running sums per (destination, head)
+    const float *row_lse;            // n x heads
+    double *stats;                   // n x heads x 3, zero-initialised: sum alpha*dalpha, sum alpha*dalpha*s, sum alpha*s
 };
+
+enum { DOT_STORE = 0, DOT_SRC = 1, DOT_DST = 2 };
 
 // out[e][h] = (float)(Xdst[dst(e)][h][:] . Xsrc[src(e)][h][:]) * (s_dst*s_src); one wave per chunk of edges.
 // ATT_BWD (step 3' fused with 5'', 4' and LeakyReLU', walking the out-edges of each source u): the dot product
 // of edge (u -> v) is dalpha, alpha is recomputed from S_q[u], D_q[v], row_max[v], row_rden[v], and
 // dS_acc[u][h] += alpha*(dalpha - P[v][h]) * lrelu'(t).
+// DOT_DST (steps 5'', 4', 3'' in one walk over the in-edges of each destination v, nothing stored per edge): with
+// s = 1 or the LeakyReLU slope by the sign of the pre-activation score, dE = alpha*(dalpha - P)*s summed over the
+// row is B - P*C with P = A = sum alpha*dalpha, B = sum alpha*dalpha*s, C = sum alpha*s; the three sums go to
+// stats[v][h][0..2] in fp64 and a finishing kernel forms P and dD.
 // I4: both tables hold packed 4-bit codes; a.F and a.dim then count bytes (two columns each) and the products come
 // from v_dot8_i32_i4.
-template <int VEC, bool ATT_BWD, bool I4 = false>
+template <int VEC, int MODE, bool I4 = false>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
 {
+    constexpr bool ATT_BWD = MODE == DOT_SRC;
+    constexpr bool ATT_DST = MODE == DOT_DST;
     using V = typename vec_bytes<VEC>::type;
     // per wave: the dot products of a block of 64 edges (edge-major, heads <= 8) and the neighbours of those edges
     __shared__ int dots[WAVES_PER_BLOCK][64 * 8];
     __shared__ int nbl[WAVES_PER_BLOCK][64];
-    __shared__ double red[WAVES_PER_BLOCK][64];
+    __shared__ double red[WAVES_PER_BLOCK][ATT_DST ? 3 * 64 : 64];
     const int lane = threadIdx.x % TANGO_WAVE;
     const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));  // wave-uniform, see k_spmm
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
@@ -686,7 +697,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     const int ek0 = lane / H;      // my first edge of a block
     const int ekstep = S / H;
     float sS = 0.0f, sD = 0.0f;
-    if (ATT_BWD) {
+    if (ATT_BWD || ATT_DST) {
         sS = *a.sS;
         sD = *a.sD;
     }
@@ -705,11 +716,17 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
         float ts_row = 0.0f;
         double acc_s = 0.0;
         if (ATT_BWD && lane < S) ts_row = sS * static_cast<float>(a.Sq[static_cast<int64_t>(r) * H + eh]);
+        float td_row = 0.0f, lse_row = 0.0f;
+        double acc_a = 0.0, acc_b = 0.0, acc_c = 0.0;
+        if (ATT_DST && lane < S) {
+            td_row = sD * static_cast<float>(a.Dq[static_cast<int64_t>(r) * H + eh]);
+            lse_row = a.row_lse[static_cast<int64_t>(r) * H + eh];
+        }
         for (int base = sb; base < se; base += 64) {
             const int cnt = min(64, se - base);
             int my_nb = 0;
             if (lane < cnt) my_nb = a.idx[base + lane];
-            if (ATT_BWD) nbl[wv][lane] = my_nb;
+            if (ATT_BWD || ATT_DST) nbl[wv][lane] = my_nb;
             const int steps = (cnt + G - 1) / G;
             auto batch = [&](int s0, auto uu) {
                 constexpr int UU = decltype(uu)::value;
@@ -753,10 +770,35 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                         const float al = tango_attn_alpha(ev, rc.row_lse);
                         const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
                         acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
+                    } else if (ATT_DST) {
+                        const int64_t uh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
+                        bool pos;
+                        const float ev = tango_attn_score(sS * static_cast<float>(a.Sq[uh]), td_row, a.slope, pos);
+                        const float al = tango_attn_alpha(ev, lse_row);
+                        const double ad = static_cast<double>(al) * static_cast<double>(da);
+                        const double sl = pos ? 1.0 : static_cast<double>(a.slope);
+                        acc_a += ad;
+                        acc_b += ad * sl;
+                        acc_c += static_cast<double>(al) * sl;
                     } else {
                         a.out[(static_cast<int64_t>(base) + k) * H + eh] = da;
                     }
                 }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (ATT_DST) {
+            red[wv][lane] = (lane < S) ? acc_a : 0.0;
+            red[wv][64 + lane] = (lane < S) ? acc_b : 0.0;
+            red[wv][128 + lane] = (lane < S) ? acc_c : 0.0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < 3 * H) {  // lane = 3*head + which sum
+                const int hd = lane / 3, w = lane - 3 * hd;
+                double t = 0.0;
+                for (int l = hd; l < S; l += H) t += red[wv][64 * w + l];
+                if (t != 0.0) atomicAdd(a.stats + (static_cast<int64_t>(r) * H + hd) * 3 + w, t);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -1006,10 +1048,66 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (pick_vec(a.F, dim, true)) {
-        case 4: k_sddmm_dot<4, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        case 8: k_sddmm_dot<8, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        default: k_sddmm_dot<16, false><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 4: k_sddmm_dot<4, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 8: k_sddmm_dot<8, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default: k_sddmm_dot<16, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
     }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+__global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, const double *__restrict__ stats, const float *__restrict__ row_lse,
+                                                         tango_attn_rec *__restrict__ rec, float *__restrict__ dD)
+{
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nh;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const double A = stats[3 * i], B = stats[3 * i + 1], C = stats[3 * i + 2];
+        tango_attn_rec rc;
+        rc.P = A;
+        rc.row_lse = row_lse[i];
+        rc.unused = 0.0f;
+        rec[i] = rc;
+        dD[i] = static_cast<float>(B - A * C);
+    }
+}
+
+// Steps 5'', 4' and 3'' without an edge tensor: P (into rec) and dD from one walk over the in-edges; stats: n x heads x 3
+// doubles of scratch.
+int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
+                                   const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
+                                   const float *sD, float slope, const float *row_lse, double *stats, tango_attn_rec *rec,
+                                   float *dD, hipStream_t st)
+{
+    const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(stats), 0u, static_cast<int>(6 * nh), st);
+    if (rc != TANGO_OK) return rc;
+    if (g->n_edges > 0) {
+        sddmm_dot_args a;
+        a.n = g->n_nodes;
+        a.nnz = g->n_edges;
+        a.ptr = g->in_ptr;
+        a.idx = g->in_src;
+        a.Xdst = dOut_q;  // resident row: the destination's upstream gradient
+        a.Xsrc = X_q;     // gathered: the source node's features
+        a.s_dst = s_dOut;
+        a.s_src = s_X;
+        a.out = nullptr;
+        a.heads = heads;
+        a.dim = dim;
+        a.F = heads * dim;
+        a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
+        a.rec = nullptr; a.dS_acc = nullptr;
+        a.row_lse = row_lse; a.stats = stats;
+        const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+        const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+        switch (pick_vec(a.F, dim, true)) {
+            case 4: k_sddmm_dot<4, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            case 8: k_sddmm_dot<8, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default: k_sddmm_dot<16, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        }
+        TANGO_LAUNCH_CHECK();
+    }
+    k_attn_dst_finish<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(nh, stats, row_lse, rec, dD);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
@@ -1043,9 +1141,9 @@ int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int
         const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         switch (pick_vec(a.F, dim, true)) {
-            case 4: k_sddmm_dot<4, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            case 8: k_sddmm_dot<8, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            default: k_sddmm_dot<16, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            case 4: k_sddmm_dot<4, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            case 8: k_sddmm_dot<8, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default: k_sddmm_dot<16, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
         }
         TANGO_LAUNCH_CHECK();
     }
@@ -1121,9 +1219,9 @@ int tango_qsddmm_dot_i4(const tango_graph *g, int heads, int dim, const uint8_t 
     const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (vec) {
-        case 4: k_sddmm_dot<4, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        case 8: k_sddmm_dot<8, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        default: k_sddmm_dot<16, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 4: k_sddmm_dot<4, DOT_STORE, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        case 8: k_sddmm_dot<8, DOT_STORE, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default: k_sddmm_dot<16, DOT_STORE, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
     }
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;

@@ -64,7 +64,10 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
         assert_bit_exact(o["E"], E, "E")
     assert_close(o["alpha"], orc.edge_softmax(g, E), "alpha")
     q, s = orc.quantize(o["alpha"], rounding, seed, b + orc.SID_ALPHA)
-    assert_bit_exact(o["alpha_q"], q, "alpha_q")
+    if "alpha_q" in o:
+        assert_bit_exact(o["alpha_q"], q, "alpha_q")
+    else:  # the codes exist only inside the kernels: use the oracle's codes of the GPU's own alpha from here on
+        o = dict(o, alpha_q=q)
     assert sc("s_alpha") == s
     out, am = orc.spmm_in(g, o["alpha_q"], sc("s_alpha"), o["Hp_q"], sc("s_Hp"))
     assert_bit_exact(o["out"], out, "out")
@@ -77,8 +80,9 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
     agg, _ = orc.spmm_rev(g, o["alpha_q"], sc("s_alpha"), o["g_q"], sc("s_g"))
     dalpha = orc.sddmm_dot(g, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads)
     dE_sm = orc.edge_softmax_bwd(g, o["alpha"], dalpha)
-    if fused:  # dalpha is kept, dE is never written
-        assert_bit_exact(o["dalpha"], dalpha, "dalpha")
+    if fused:  # dE is never written; dalpha is kept unless nothing at all is stored per edge
+        if "dalpha" in o:
+            assert_bit_exact(o["dalpha"], dalpha, "dalpha")
         _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, dE_sm)
     else:  # dalpha was overwritten by dE
         assert_close(o["dalpha"], dE_sm, "dE (softmax backward)")
@@ -112,16 +116,22 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
 
 @pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
-@pytest.mark.parametrize("fused", [True, False])
-def test_gat_layer_stagewise(T, case, rounding, fused):
+@pytest.mark.parametrize("mode", ["fused, nothing stored per edge", "fused, edge caches kept", "primitive by primitive"])
+def test_gat_layer_stagewise(T, case, rounding, mode):
+    """Three ways through the layer: the production launch (what bench.py times: neither alpha_q nor dalpha exist, the
+    backward pass recomputes the codes and forms the edge sums in two fused walks; alpha is dumped for this check only),
+    the fused entry points with cached alpha_q and a stored dalpha, and the chain of primitives."""
     import torch
 
     li, slope = gat_case(case)
     g = li.graph
     seed, layer_id = li.sr_seed, 2
     G = T.Graph.from_host(g)
+    fused = mode != "primitive by primitive"
+    cached = mode != "fused, nothing stored per edge"
     L = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed,
-                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True, keep_alpha_q=True)
+                   layer_id, alias_E_alpha=False, fused=fused, keep_alpha=True, keep_alpha_q=cached, keep_dalpha=cached)
+    assert cached or ("alpha_q" not in L.t and "dalpha" not in L.t)
     T.tango_gat_layer_fwd(L)
     T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()
@@ -190,9 +200,18 @@ def test_fused_gat_layer_without_edge_caches(T):
         T.tango_gat_layer_fwd(L)
         T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()
-    assert "alpha_q" not in B.t and "alpha" not in B.t
-    for name in ("out", "dHp", "dS", "dD", "dW", "dH", "da_src", "da_dst", "dalpha"):
+    assert "alpha_q" not in B.t and "alpha" not in B.t and "dalpha" not in B.t
+    for name in ("out", "g_q"):
         assert_bit_exact(host(B[name]), host(A[name]), name)
+    # the edge sums are formed in a different order (and dD as B - P*C): equal within the fp32 tolerance; what is
+    # quantized from them may then differ by one code in a few places
+    for name in ("dS", "dD", "dHp"):
+        assert_close(host(B[name]), host(A[name]), name)
+    diff = host(B["dHp_q"]).astype(np.int32) - host(A["dHp_q"]).astype(np.int32)
+    assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-3
+    rel = lambda x, y: np.linalg.norm(x.astype(np.float64) - y) / np.linalg.norm(y)
+    for name in ("dW", "dH", "da_src", "da_dst"):  # sums over all nodes of the above (cancelling terms): in norm
+        assert rel(host(B[name]), host(A[name]).astype(np.float64)) < 1e-3, name
 
 
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
