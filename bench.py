@@ -39,10 +39,37 @@ def rev_attention_spmm_algorithmic_bytes(n, nnz, heads, F):
     return nnz * (8 + F + 5 * heads) + n * (4 + heads + 4 * F)
 
 
+def attention_bwd_src_algorithmic_bytes(n, nnz, heads, F):
+    """Per launch of the source-side walk of the attention backward (steps 5' and 3' together, attention codes
+    recomputed): per edge 4 (neighbour index) + 4 (edge id, for the random bits) + F (gathered int8 gradient row) and,
+    per head, 1 (D_q of the neighbour) + 4 (its row_lse) + 8 (its P); per node 4 (row pointer) + heads (S_q) + F (its
+    own int8 feature row) + 4F (fp32 dX_agg) + 4*heads (fp32 dS)."""
+    return nnz * (8 + F + 13 * heads) + n * (4 + heads + 5 * F + 4 * heads)
+
+
 # HBM-side traffic of the dominant kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by a 1 GiB copy kernel (FETCH_SIZE reads half the copied bytes, WRITE_SIZE all of them); see
 # profiles/.  Keyed by workload; None where no counter run has been recorded.
-MEASURED_TRAFFIC = {"gat_dense": 29.0e9}  # profiles/gat_dense_hbm_traffic.md, k_spmm<16, true, 2>
+MEASURED_TRAFFIC = {"gat_dense": None}  # profiles/gat_dense_hbm_traffic.md, k_spmm<16, true, 2, false, true>
+
+
+def attention_bwd_src_launch(torch, T, G, L, heads, dim, slope, seed, sid_alpha):
+    """A closure that launches tango_gat_attention_bwd_src on the tensors a finished layer step left in place (the
+    destination-side half is run once here to fill the P table it reads), and the name of its main kernel."""
+    n = L["dS"].shape[0]
+    dev = L["dS"].device
+    u8 = lambda nbytes: torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
+    rec = u8(T.tango_gat_attention_bwd_rec_bytes(n, heads))
+    ws_d = u8(T.tango_gat_attention_bwd_dst_workspace_bytes(n, heads))
+    ws_s = u8(T.tango_gat_attention_bwd_src_workspace_bytes(n, heads))
+    dD = torch.empty_like(L["dD"])
+    dS = torch.empty_like(L["dS"])
+    T.tango_gat_attention_bwd_dst(G, heads, dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"], L["Hp_q"], L["s_Hp"],
+                                  L["g_q"], L["s_g"], rec, dD, ws_d)
+    fn = lambda: T.tango_gat_attention_bwd_src(G, heads, dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
+                                               L["s_alpha"], L["absmax_alpha"], T.SR, seed, sid_alpha, L["Hp_q"], L["s_Hp"],
+                                               L["g_q"], L["s_g"], rec, L["dHp"], None, dS, ws_s)
+    return fn, "k_spmm<16, true, 2, false, true> (attention backward, source side: steps 5' and 3' in one walk over the out-edges)"
 
 
 def time_events(torch, fn, iters):
@@ -257,22 +284,16 @@ def main():
                     T.tango_relu_bwd(layers[i - 1]["out"], layers[i]["dH"], grads[i - 1])
 
         L = layers[2]
-        spmm = lambda: T.tango_gat_attention_bwd(G, heads, li.dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
-                                                 None, L["s_alpha"], L["absmax_alpha"], T.SR, li.sr_seed, 16 * 2 + 6, L["Hp_q"],
-                                                 L["s_Hp"], L["g_q"], L["s_g"], L["dHp"], None, None, None, None, L["ws"])
-        spmm_name = "k_spmm<16, true, 2> (reverse SPMM with recomputed attention codes, step 5')"
-        alg = rev_attention_spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
+        spmm, spmm_name = attention_bwd_src_launch(torch, T, G, L, heads, li.dim, slope, li.sr_seed, 16 * 2 + 6)
+        alg = attention_bwd_src_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     else:
         L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0)
         step = lambda: (T.tango_gat_layer_fwd(L), T.tango_gat_layer_bwd(L))
         heads, F = li.heads, li.heads * li.dim
-        # the kernel with the largest share of the step: the reverse SPMM (step 5') with recomputed attention codes,
-        # launched exactly as inside tango_gat_layer_bwd (dalpha = dS = dD = None: step 5' only)
-        spmm = lambda: T.tango_gat_attention_bwd(G, heads, li.dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
-                                                 None, L["s_alpha"], L["absmax_alpha"], T.SR, li.sr_seed, 6, L["Hp_q"],
-                                                 L["s_Hp"], L["g_q"], L["s_g"], L["dHp"], None, None, None, None, L["ws"])
-        spmm_name = "k_spmm<16, true, 2> (reverse SPMM with recomputed attention codes, step 5')"
-        alg = rev_attention_spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
+        # the kernel with the largest share of the step: the source-side walk of the attention backward (steps 5' and 3'
+        # together, attention codes recomputed), launched with the arguments tango_gat_layer_bwd gives it
+        spmm, spmm_name = attention_bwd_src_launch(torch, T, G, L, heads, li.dim, slope, li.sr_seed, 6)
+        alg = attention_bwd_src_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
 
     if args.hipgraph:
         step()  # everything allocated and warm before the capture
@@ -292,7 +313,7 @@ def main():
     log("layer fwd+bwd: %.3f ms/step%s" % (ms_per_step, " (HIP graph replay)" if args.hipgraph else ""))
 
     # dominant kernel, timed with HIP events on the stream it is launched on (the step above left every input it
-    # needs in place); the two small helper kernels around it (row zeroing, split-row dequantize) are included
+    # needs in place); the small helper kernels around it (zeroing, split-row dequantize, fp64 -> fp32) are included
     spmm()
     torch.cuda.synchronize()
     spmm_ms = time_events(torch, spmm, max(args.steps, 5))

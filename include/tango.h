@@ -357,6 +357,31 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                             const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX,
                             float *dalpha, float *dS, float *dD, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * The two halves of tango_gat_attention_bwd's no-edge-tensor path as calls of their own (the whole call is their
+ * composition):
+ *   _dst: one walk over the in-edges of every destination v (steps 5'', 4', 3''): dD (n x heads fp32) and, in `rec`
+ *         (device, tango_gat_attention_bwd_rec_bytes() bytes, 16-byte aligned; an opaque table of 16 bytes per
+ *         (node, head): P as fp64 and row_lse), what the other half needs;
+ *   _src: one walk over the out-edges of every source u (steps 5' and 3'): dX_agg (n x F fp32, absmax_dX may be
+ *         NULL) and dS (n x heads fp32), with the int8 attention codes recomputed as in tango_gat_attention_bwd.
+ * ws: device scratch of the matching _workspace_bytes(), 256-byte aligned.  Other arguments as in
+ * tango_gat_attention_bwd.
+ */
+size_t tango_gat_attention_bwd_rec_bytes(int64_t n_nodes, int heads);
+size_t tango_gat_attention_bwd_dst_workspace_bytes(int64_t n_nodes, int heads);
+size_t tango_gat_attention_bwd_src_workspace_bytes(int64_t n_nodes, int heads);
+int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                const int8_t *D_q, const float *s_D, float slope, const float *row_lse,
+                                const int8_t *X_q, const float *s_X, const int8_t *dOut_q, const float *s_dOut,
+                                void *rec, float *dD, void *ws, size_t ws_bytes, void *stream);
+int tango_gat_attention_bwd_src(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                const int8_t *D_q, const float *s_D, float slope, const float *row_lse,
+                                const float *s_alpha, const float *absmax_alpha, int rounding, uint64_t seed,
+                                uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
+                                const int8_t *dOut_q, const float *s_dOut, const void *rec, float *dX_agg,
+                                float *absmax_dX, float *dS, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* 4-bit operands (Sec. 4 "Speed impact for # of quantization bits").         */
 /* ------------------------------------------------------------------------ */

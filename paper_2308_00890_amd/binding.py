@@ -56,6 +56,13 @@ SIGNATURES = {
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_mfma_i8_rate_workspace_bytes": (_sz, []),
     "tango_mfma_i8_rate_launch": (_int, [_int, _int, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
+    "tango_gat_attention_bwd_rec_bytes": (_sz, [_i64, _int]),
+    "tango_gat_attention_bwd_dst_workspace_bytes": (_sz, [_i64, _int]),
+    "tango_gat_attention_bwd_src_workspace_bytes": (_sz, [_i64, _int]),
+    "tango_gat_attention_bwd_dst": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                           _vp, _sz, _vp]),
+    "tango_gat_attention_bwd_src": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _int, _u64, _u64,
+                                           _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_quantize_i4": (_int, [_vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_qspmm_i4": (_int, [_gp, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qsddmm_dot_i4": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -342,6 +349,44 @@ def tango_qspmm(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out):
             _ptr(s_X, torch.float32), _ptr(out, torch.float32), _ptr(absmax_out, torch.float32), _stream(),
         ),
         "tango_qspmm",
+    )
+
+
+def tango_gat_attention_bwd_rec_bytes(n_nodes, heads) -> int:
+    return load_library().tango_gat_attention_bwd_rec_bytes(n_nodes, heads)
+
+
+def tango_gat_attention_bwd_dst_workspace_bytes(n_nodes, heads) -> int:
+    return load_library().tango_gat_attention_bwd_dst_workspace_bytes(n_nodes, heads)
+
+
+def tango_gat_attention_bwd_src_workspace_bytes(n_nodes, heads) -> int:
+    return load_library().tango_gat_attention_bwd_src_workspace_bytes(n_nodes, heads)
+
+
+def tango_gat_attention_bwd_dst(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, X_q, s_X, dOut_q, s_dOut, rec, dD, ws):
+    f32, i8 = torch.float32, torch.int8
+    _check(
+        load_library().tango_gat_attention_bwd_dst(
+            g.ref(), heads, dim, _ptr(S_q, i8), _ptr(s_S, f32), _ptr(D_q, i8), _ptr(s_D, f32), slope, _ptr(row_lse, f32),
+            _ptr(X_q, i8), _ptr(s_X, f32), _ptr(dOut_q, i8), _ptr(s_dOut, f32), _ptr(rec), _ptr(dD, f32), _ptr(ws),
+            ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_gat_attention_bwd_dst",
+    )
+
+
+def tango_gat_attention_bwd_src(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, s_alpha, absmax_alpha, rounding, seed,
+                                sid_alpha, X_q, s_X, dOut_q, s_dOut, rec, dX_agg, absmax_dX, dS, ws):
+    f32, i8 = torch.float32, torch.int8
+    _check(
+        load_library().tango_gat_attention_bwd_src(
+            g.ref(), heads, dim, _ptr(S_q, i8), _ptr(s_S, f32), _ptr(D_q, i8), _ptr(s_D, f32), slope, _ptr(row_lse, f32),
+            _ptr(s_alpha, f32), _ptr(absmax_alpha, f32), rounding, seed, sid_alpha, _ptr(X_q, i8), _ptr(s_X, f32),
+            _ptr(dOut_q, i8), _ptr(s_dOut, f32), _ptr(rec), _ptr(dX_agg, f32), _ptr(absmax_dX, f32), _ptr(dS, f32), _ptr(ws),
+            ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_gat_attention_bwd_src",
     )
 
 

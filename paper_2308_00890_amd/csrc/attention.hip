@@ -292,6 +292,69 @@ size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges,
     return 256 + 6 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
 }
 
+size_t tango_gat_attention_bwd_rec_bytes(int64_t n_nodes, int heads)
+{
+    return tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(tango_attn_rec), 256);
+}
+
+size_t tango_gat_attention_bwd_dst_workspace_bytes(int64_t n_nodes, int heads)
+{
+    return 3 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256);
+}
+
+size_t tango_gat_attention_bwd_src_workspace_bytes(int64_t n_nodes, int heads)
+{
+    return tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256);
+}
+
+static int attention_bwd_common_checks(const tango_graph *g, int heads, int dim)
+{
+    TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(g->n_nodes > 0 && g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(g->in_ptr && g->out_ptr && (g->n_edges == 0 || (g->in_src && g->out_dst && g->out_eid)), TANGO_ERR_NULL);
+    TANGO_REQUIRE(heads_supported(heads), TANGO_ERR_UNSUPPORTED);
+    return tango_validate_sddmm_dot_shape(heads, dim);
+}
+
+int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                const int8_t *D_q, const float *s_D, float slope, const float *row_lse, const int8_t *X_q,
+                                const float *s_X, const int8_t *dOut_q, const float *s_dOut, void *rec, float *dD, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    int rc = attention_bwd_common_checks(g, heads, dim);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && X_q && s_X && dOut_q && s_dOut && rec && dD, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) && tango_aligned(rec, 16), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
+                  TANGO_ERR_WORKSPACE);
+    return tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse,
+                                          static_cast<double *>(ws), static_cast<tango_attn_rec *>(rec), dD,
+                                          tango_stream(stream));
+}
+
+int tango_gat_attention_bwd_src(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                const int8_t *D_q, const float *s_D, float slope, const float *row_lse, const float *s_alpha,
+                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id_alpha,
+                                const int8_t *X_q, const float *s_X, const int8_t *dOut_q, const float *s_dOut,
+                                const void *rec, float *dX_agg, float *absmax_dX, float *dS, void *ws, size_t ws_bytes,
+                                void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    int rc = attention_bwd_common_checks(g, heads, dim);
+    if (rc != TANGO_OK) return rc;
+    TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && s_alpha && absmax_alpha && X_q && s_X && dOut_q && s_dOut && rec &&
+                      dX_agg && dS,
+                  TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) && tango_aligned(rec, 16) && tango_aligned(dX_agg, 16),
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_src_workspace_bytes(g->n_nodes, heads),
+                  TANGO_ERR_WORKSPACE);
+    return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
+                                             stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X,
+                                             static_cast<const tango_attn_rec *>(rec), static_cast<double *>(ws), dX_agg,
+                                             absmax_dX, dS, tango_stream(stream));
+}
+
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                             const int8_t *D_q, const float *s_D, float slope, const float *row_lse, const int8_t *alpha_q,
                             const float *s_alpha, const float *absmax_alpha, int rounding, uint64_t seed,

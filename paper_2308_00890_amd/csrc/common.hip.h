@@ -77,10 +77,13 @@ __device__ static inline uint4 tango_philox_block(const tango_rng &r, uint64_t b
 }
 
 // 16 random bits of element `lane8` (0..7) of a block.
-__device__ static inline uint32_t tango_bits16(const uint4 &b, int lane8)
+__device__ static inline uint32_t tango_bits16(const uint4 b, int lane8)
 {
-    const uint32_t w = (lane8 & 4) ? ((lane8 & 2) ? b.w : b.z) : ((lane8 & 2) ? b.y : b.x);
-    return (lane8 & 1) ? (w >> 16) : (w & 0xffffu);
+    // two selects and one 64-bit shift (written without any indexing so that the block stays in registers)
+    const uint32_t lo = (lane8 & 4) ? b.z : b.x;
+    const uint32_t hi = (lane8 & 4) ? b.w : b.y;
+    const uint64_t half = (static_cast<uint64_t>(hi) << 32) | lo;
+    return static_cast<uint32_t>(half >> (16 * (lane8 & 3))) & 0xffffu;
 }
 
 // Scale rule (Sec. 2.3, symmetric per-tensor, B = 8): s = absmax/127, inv = 127/absmax.

@@ -371,11 +371,15 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 int sq[8], dq[8];
                 tango_load_heads_rt(a.att.Sq, src_node, H, sq);
                 tango_load_heads_rt(a.att.Dq, dst_node, H, dq);
-                for (int hh = 0; hh < H; ++hh) {
+#pragma unroll
+                for (int hh = 0; hh < 8; ++hh) {  // constant trip count: sq/dq stay in registers
+                    if (hh >= H) break;
                     bool pos;
                     const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
                                                       a.att.slope, pos);
-                    const float al = tango_attn_alpha(ev, a.att.row_lse[dst_node * H + hh]);
+                    // DS: row_lse comes from the record that the epilogue reads again for P (one table, one cache line)
+                    const float lse = DS ? a.att.rec[dst_node * H + hh].row_lse : a.att.row_lse[dst_node * H + hh];
+                    const float al = tango_attn_alpha(ev, lse);
                     if (DS) {
                         alf_s[wv][lane * H + hh] = al;
                         pos_mask |= (pos ? 1u : 0u) << hh;

@@ -96,3 +96,28 @@ def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     _, w_dS, w_dD = orc.sddmm_add_bwd(g, Sq, sS, Dq, sD, slope, dE_sm)
     assert_close(host(dD), w_dD, "dD")
     assert_close(host(dS), w_dS, "dS")
+
+    # ---- no edge tensor at all (dalpha = None): two fused walks; and the same as its two halves called separately
+    dX3, dS3, dD3 = empty((g.n_nodes, F), torch.float32), empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    for t in (dX3, dS3, dD3):
+        t.fill_(float("nan"))
+    amx3 = scalar(-1)
+    T.tango_gat_attention_bwd(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_lse, None, s_alpha,
+                              am_alpha, rounding, seed, sid, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), dX3, amx3, None, dS3, dD3,
+                              wsb)
+    torch.cuda.synchronize()
+    assert_bit_exact(host(dX3), w_dX, "dX_agg (no edge tensor)")
+    assert host(amx3)[0] == w_am
+    assert_close(host(dD3), w_dD, "dD (no edge tensor)")
+    assert_close(host(dS3), w_dS, "dS (no edge tensor)")
+    rec = workspace(T.tango_gat_attention_bwd_rec_bytes(g.n_nodes, heads))
+    dX4, dS4, dD4 = empty((g.n_nodes, F), torch.float32), empty((g.n_nodes, heads), torch.float32), empty((g.n_nodes, heads), torch.float32)
+    T.tango_gat_attention_bwd_dst(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_lse, dev(Xq), scalar(sX),
+                                  dev(dOq), scalar(s_dO), rec, dD4, workspace(T.tango_gat_attention_bwd_dst_workspace_bytes(g.n_nodes, heads)))
+    T.tango_gat_attention_bwd_src(G, heads, dim, dev(Sq), scalar(sS), dev(Dq), scalar(sD), slope, row_lse, s_alpha, am_alpha,
+                                  rounding, seed, sid, dev(Xq), scalar(sX), dev(dOq), scalar(s_dO), rec, dX4, None, dS4,
+                                  workspace(T.tango_gat_attention_bwd_src_workspace_bytes(g.n_nodes, heads)))
+    torch.cuda.synchronize()
+    assert_bit_exact(host(dX4), w_dX, "dX_agg (halves)")
+    assert_close(host(dD4), w_dD, "dD (halves)")
+    assert_close(host(dS4), w_dS, "dS (halves)")
