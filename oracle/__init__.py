@@ -51,6 +51,8 @@ def _L():
         lib.orc_spmm_rev.restype = ctypes.c_int64
         lib.orc_head_proj_bwd.restype = ctypes.c_float
         lib.orc_error_x.restype = ctypes.c_double
+        lib.orc_splitmix64.restype = ctypes.c_uint64
+        lib.orc_xoshiro256pp_next.restype = ctypes.c_uint64
         for name in (
             "orc_philox4x32_10",
             "orc_scale_from_absmax",
@@ -64,6 +66,7 @@ def _L():
             "orc_spmm_f32",
             "orc_sddmm_dot_f32",
             "orc_quantize_bits",
+            "orc_quantize_xoshiro",
             "orc_pack_int4",
             "orc_unpack_int4",
         ):
@@ -150,6 +153,27 @@ def unpack_int4(p) -> np.ndarray:
     q = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), np.int8)
     _L().orc_unpack_int4(_p(p), ctypes.c_size_t(q.size), _p(q))
     return q
+
+
+def xoshiro256pp(state, count: int):
+    """`count` outputs of xoshiro256++ from the four-word state (list of ints)."""
+    st = (ctypes.c_uint64 * 4)(*state)
+    return [int(_L().orc_xoshiro256pp_next(st)) for _ in range(count)]
+
+
+def splitmix64(x: int, count: int):
+    xs = ctypes.c_uint64(x)
+    return [int(_L().orc_splitmix64(ctypes.byref(xs))) for _ in range(count)]
+
+
+def quantize_xoshiro(x, seed: int = 0, stream: int = 0, am=None):
+    """Stochastic-rounding quantizer with the stateful generator as the source of bits: (q int8, scale)."""
+    x = _c(x, np.float32)
+    if am is None:
+        am = absmax(x)
+    q = np.empty(x.shape, np.int8)
+    _L().orc_quantize_xoshiro(_p(x), ctypes.c_size_t(x.size), _f32(float(am)), _u64(seed), _u64(stream), _p(q))
+    return q, scale_from_absmax(am)[0]
 
 
 def error_x(x, bits: int, rounding: int = SR, seed: int = 0, stream: int = 0) -> float:

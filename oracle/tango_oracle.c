@@ -185,6 +185,70 @@ void orc_unpack_int4(const uint8_t *p, size_t n, int8_t *q)
     }
 }
 
+/* ------------------------------------------------------------------ */
+/* Alternative source of the random bits (Sec. 3.2 "GPU-accelerated      */
+/* stochastic rounding": xoshiro256++ with its state kept in registers).  */
+/* A generator with state cannot be indexed by element, so the mapping is */
+/* fixed instead: 65,536 generators; generator g is seeded by four        */
+/* splitmix64 outputs from x0 = seed + stream*0xD1342543DE82EF95 +        */
+/* g*0x9E3779B97F4A7C15; one 64-bit output serves the four consecutive    */
+/* elements 4v .. 4v+3 (16 bits each, lowest bits first) of group v, and   */
+/* group v belongs to generator v % 65536 as its (v / 65536)-th output.    */
+/* ------------------------------------------------------------------ */
+#define ORC_XO_GENERATORS 65536u
+
+static uint64_t rotl64(uint64_t x, int k) { return (x << k) | (x >> (64 - k)); }
+
+uint64_t orc_splitmix64(uint64_t *x)
+{
+    uint64_t z = (*x += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+/* one step of xoshiro256++ (Blackman and Vigna): returns the output, advances s[4] */
+uint64_t orc_xoshiro256pp_next(uint64_t s[4])
+{
+    const uint64_t result = rotl64(s[0] + s[3], 23) + s[0];
+    const uint64_t t = s[1] << 17;
+    s[2] ^= s[0];
+    s[3] ^= s[1];
+    s[1] ^= s[2];
+    s[0] ^= s[3];
+    s[2] ^= t;
+    s[3] = rotl64(s[3], 45);
+    return result;
+}
+
+/* Stochastic-rounding quantizer (Eq. 3) drawing its bits as described above; otherwise orc_quantize. */
+void orc_quantize_xoshiro(const float *x, size_t n, float absmax, uint64_t seed, uint64_t stream, int8_t *q)
+{
+    float s, inv;
+    orc_scale_from_absmax(absmax, &s, &inv);
+    const uint64_t groups = ((uint64_t)n + 3) / 4;
+    for (uint64_t g = 0; g < ORC_XO_GENERATORS && g < groups; ++g) {
+        uint64_t x0 = seed + stream * 0xD1342543DE82EF95ull + g * 0x9E3779B97F4A7C15ull;
+        uint64_t st[4];
+        for (int k = 0; k < 4; ++k) st[k] = orc_splitmix64(&x0);
+        for (uint64_t v = g; v < groups; v += ORC_XO_GENERATORS) {
+            const uint64_t r = orc_xoshiro256pp_next(st);
+            for (int j = 0; j < 4; ++j) {
+                const uint64_t i = 4 * v + (uint64_t)j;
+                if (i >= n) break;
+                const float y = x[i] * inv;
+                const float f = floorf(y);
+                const float frac = y - f;
+                const float u = (float)((r >> (16 * j)) & 0xFFFFu) * (1.0f / 65536.0f);
+                int c = (int)f + (u < frac ? 1 : 0);
+                if (c > 127) c = 127;
+                if (c < -127) c = -127;
+                q[i] = (int8_t)c;
+            }
+        }
+    }
+}
+
 /* x_i = s * q_i (Eq. 2 with Z = 0). */
 void orc_dequantize(const int8_t *q, size_t n, float s, float *x)
 {

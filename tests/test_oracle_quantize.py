@@ -241,3 +241,44 @@ def test_int4_packing():
     assert np.array_equal(orc.unpack_int4(p), q)
     r = np.random.default_rng(0).integers(-7, 8, size=(37, 64), dtype=np.int8)
     assert np.array_equal(orc.unpack_int4(orc.pack_int4(r)), r)
+
+
+def test_xoshiro_known_answers_and_seeding(golden_dir):
+    want = [int(l) for l in open(os.path.join(golden_dir, "xoshiro256pp_kat.txt")) if l.strip() and not l.startswith("#")]
+    assert orc.xoshiro256pp([1, 2, 3, 4], 10) == want
+    # splitmix64: the first output from x = 0 is the finalizer applied to the golden-ratio increment
+    z = 0x9E3779B97F4A7C15
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & (2**64 - 1)
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & (2**64 - 1)
+    assert orc.splitmix64(0, 1)[0] == z ^ (z >> 31)
+
+
+def test_xoshiro_quantizer_mapping_and_statistics():
+    # element i -> group i//4 -> generator (i//4) % 65536, output number (i//4) // 65536, bit field i % 4
+    n = 4 * 65536 * 2 + 6
+    seed, stream = 77, 5
+    x = np.full(n, 3.25, np.float32)
+    x[0] = 127.0  # inv = 1: every other element has fraction 0.25
+    q, s = orc.quantize_xoshiro(x, seed, stream)
+    assert s == 1.0 and set(np.unique(q[1:])) == {3, 4}
+    M = 2**64 - 1
+    for i in (1, 2, 3, 4, 7, 4 * 65535 + 2, 4 * 65536 + 1, n - 1):
+        v = i // 4
+        g, j = v % 65536, v // 65536
+        st = orc.splitmix64((seed + stream * 0xD1342543DE82EF95 + g * 0x9E3779B97F4A7C15) & M, 4)
+        r = orc.xoshiro256pp(st, j + 1)[j]
+        u = ((r >> (16 * (i % 4))) & 0xFFFF) / 65536.0
+        assert q[i] == (4 if u < 0.25 else 3), i
+    up = (q[1:] == 4).mean()
+    assert abs(up - 0.25) < 4 * np.sqrt(0.25 * 0.75 / (n - 1))
+    # same rule as Eq. 3 otherwise: floor or floor + 1, unbiased, reproducible, seed- and stream-dependent
+    y = _x(300000, 41)
+    a, sa = orc.quantize_xoshiro(y, 1, 2)
+    b, _ = orc.quantize_xoshiro(y, 1, 2)
+    c, _ = orc.quantize_xoshiro(y, 1, 3)
+    assert np.array_equal(a, b) and (a != c).mean() > 0.1
+    _, inv = orc.scale_from_absmax(orc.absmax(y))
+    d = a.astype(np.float32) - np.clip(np.floor(y * inv), -127, 127)
+    assert set(np.unique(d)).issubset({0.0, 1.0})
+    err = float(sa) * a.astype(np.float64) - y.astype(np.float64)
+    assert abs(err.mean()) < 4 * float(sa) / (2 * np.sqrt(y.size))
