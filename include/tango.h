@@ -102,6 +102,22 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
                    const float *absmax_in, int8_t *q, float *scale_out, void *ws, size_t ws_bytes,
                    void *stream);
 
+/*
+ * tango_quantize with stochastic rounding whose bits come from xoshiro256++
+ * generators held in registers (Sec. 3.2 "GPU-accelerated stochastic
+ * rounding") instead of the counter-based generator.  The result is defined
+ * by a fixed mapping, not by the launch: 65,536 generators; generator g is
+ * seeded with four splitmix64 outputs from
+ * x0 = seed + stream_id*0xD1342543DE82EF95 + g*0x9E3779B97F4A7C15, and its
+ * j-th 64-bit output serves elements 4v..4v+3 (16 bits each, lowest first)
+ * of group v = j*65536 + g.  x 16-byte, q 4-byte aligned; other arguments
+ * as in tango_quantize.  For the comparison of the two sources; the layer
+ * entry points use the counter-based one.
+ */
+int tango_quantize_xoshiro(const float *x, size_t n, uint64_t seed, uint64_t stream_id,
+                           const float *absmax_in, int8_t *q, float *scale_out, void *ws,
+                           size_t ws_bytes, void *stream);
+
 /* x[i] = scale[0] * q[i]  (Eq. 2). */
 int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream);
 

@@ -63,6 +63,7 @@ SIGNATURES = {
                                            _vp, _sz, _vp]),
     "tango_gat_attention_bwd_src": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _int, _u64, _u64,
                                            _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "tango_quantize_xoshiro": (_int, [_vp, _sz, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_quantize_i4": (_int, [_vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_qspmm_i4": (_int, [_gp, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qsddmm_dot_i4": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -387,6 +388,16 @@ def tango_gat_attention_bwd_src(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_ls
             ws.numel() * ws.element_size(), _stream(),
         ),
         "tango_gat_attention_bwd_src",
+    )
+
+
+def tango_quantize_xoshiro(x, seed, stream_id, absmax_in, q, scale_out, ws):
+    _check(
+        load_library().tango_quantize_xoshiro(
+            _ptr(x, torch.float32), x.numel(), seed, stream_id, _ptr(absmax_in, torch.float32), _ptr(q, torch.int8),
+            _ptr(scale_out, torch.float32), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_quantize_xoshiro",
     )
 
 

@@ -24,12 +24,14 @@ __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, siz
         const size_t n4 = n / 4;
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         size_t i = tid;
-        // two independent loads per iteration keep more bytes in flight
-        for (; i + nthr < n4; i += 2 * nthr) {
-            const float4 a = x4[i];
-            const float4 b = x4[i + nthr];
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+        // eight independent loads per iteration keep enough bytes in flight to cover the memory latency
+        for (; i + 7 * nthr < n4; i += 8 * nthr) {
+            float4 a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = x4[i + u * nthr];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                m = fmaxf(m, fmaxf(fmaxf(fabsf(a[u].x), fabsf(a[u].y)), fmaxf(fabsf(a[u].z), fabsf(a[u].w))));
         }
         for (; i < n4; i += nthr) {
             const float4 a = x4[i];
@@ -84,7 +86,24 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
     const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
     const float4 *x4 = reinterpret_cast<const float4 *>(x);
     uint2 *q8 = reinterpret_cast<uint2 *>(q);
-    for (size_t i = tid; i < n8; i += nthr) {
+    // four independent 32-byte pieces per iteration keep enough loads in flight to cover the memory latency
+    constexpr int UNR = 4;
+    size_t i = tid;
+    for (; i + (UNR - 1) * nthr < n8; i += UNR * nthr) {
+        float4 a[UNR], b[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            a[u] = x4[2 * (i + u * nthr)];
+            b[u] = x4[2 * (i + u * nthr) + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const float y[8] = {a[u].x * inv, a[u].y * inv, a[u].z * inv, a[u].w * inv,
+                                b[u].x * inv, b[u].y * inv, b[u].z * inv, b[u].w * inv};
+            q8[i + u * nthr] = quantize8<ROUNDING>(y, rng, i + u * nthr);
+        }
+    }
+    for (; i < n8; i += nthr) {
         const float4 a = x4[2 * i];
         const float4 b = x4[2 * i + 1];
         const float y[8] = {a.x * inv, a.y * inv, a.z * inv, a.w * inv, b.x * inv, b.y * inv, b.z * inv, b.w * inv};

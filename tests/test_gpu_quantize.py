@@ -123,3 +123,18 @@ def test_error_x_and_bit_count_rule(T, rounding):
     T.tango_error_x(dev(np.arange(-127, 128, dtype=np.float32)), (8,), 0.3, rounding, 1, 1, None, err, bits, ws)
     torch.cuda.synchronize()
     assert host(err)[0] == 0.0 and int(host(bits)[0]) == 8
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1000, 4 * 65536 + 5, 3_000_001])
+def test_quantize_xoshiro(T, n):
+    import torch
+
+    x = ti.normal((n,), 900 + n)
+    q = empty((n,), torch.int8)
+    q.fill_(99)
+    s = scalar(-1)
+    T.tango_quantize_xoshiro(dev(x), 2308, 7, None, q, s, workspace(256))
+    torch.cuda.synchronize()
+    want_q, want_s = orc.quantize_xoshiro(x, 2308, 7)
+    assert host(s)[0] == want_s
+    assert_bit_exact(host(q), want_q, "codes from the register-resident generator")
