@@ -202,7 +202,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products", "qgemm_i8"])
+    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products", "qgemm_i8", "minibatch"])
     ap.add_argument("--gemm-shape", default="8192,8192,8192", help="M,N,K of the qgemm_i8 workload")
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -239,9 +239,17 @@ def main():
     if name == "qgemm_i8":
         bench_qgemm_i8(args, torch, T, dev)
         return
+    minibatch = name == "minibatch"
+    if minibatch:
+        # 256 sampled subgraphs of configuration-1 size (1,024 nodes, 17,408 edges each) handed over as one block-diagonal
+        # graph: the mini-batch regime, where per-graph launches would be dispatch-bound
+        name = "toy"
     cfg = ti.CONFIGS[name]
     t0 = time.perf_counter()
-    li = ti.layer_inputs(name, scale_down=args.scale_down)
+    if minibatch:
+        li = ti.layer_inputs("toy", graph=ti.minibatch_graph(256, 1024, 16384, ti.BASE_SEED + 40))
+    else:
+        li = ti.layer_inputs(name, scale_down=args.scale_down)
     g = li.graph
     log("inputs: %s, %d nodes, %d edges (with self-loops), built in %.1f s" % (name, g.n_nodes, g.n_edges, time.perf_counter() - t0))
     G = T.Graph.from_host(g, dev)
@@ -335,7 +343,10 @@ def main():
         "dtype": "int8 operands, int32 accumulation, fp32 softmax/outputs",
         "data": "synthetic",
         "config": {
-            "workload": "config %d (%s): %s graph, %d nodes, %d edges incl. self-loops, K_in %d, %d heads x %d, SR"
+            "workload": ("mini-batch of 256 uniform subgraphs of configuration-1 size as one block-diagonal graph: %d nodes, "
+                         "%d edges incl. self-loops, K_in %d, %d heads x %d, SR" % (g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim))
+            if minibatch else
+            "config %d (%s): %s graph, %d nodes, %d edges incl. self-loops, K_in %d, %d heads x %d, SR"
             % (cfg["config"], name, cfg["graph"], g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim),
             "scale_down": args.scale_down,
             "launch": "hip graph replay" if args.hipgraph else "eager",
@@ -355,6 +366,10 @@ def main():
     if not args.no_cpu_baseline:
         if name == "gat_products":
             log("no CPU baseline leg for the 3-layer workload")
+            print(json.dumps(out), flush=True)
+            return
+        if minibatch:
+            log("no CPU baseline leg for the mini-batch workload")
             print(json.dumps(out), flush=True)
             return
         sd = args.cpu_scale_down or {"gat_dense": 8, "gcn_arxiv": 1, "toy": 1}[name]

@@ -94,10 +94,26 @@ __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int
                 sd[j] += static_cast<double>(gd) * static_cast<double>(x);
             }
         }
+    }
+    // column sums: first across the rows of this block in LDS, then one atomic per column and block (per-thread
+    // atomics onto 2F addresses serialise: they took longer than the streaming part)
+    __shared__ double red[8][256];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        red[j][threadIdx.x] = active ? ss[j] : 0.0;
+        red[4 + j][threadIdx.x] = active ? sd[j] : 0.0;
+    }
+    __syncthreads();
+    if (threadIdx.x < tpr) {  // row offset 0: my quad of columns, all row offsets
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            atomicAdd(acc + c + j, ss[j]);
-            atomicAdd(acc + F + c + j, sd[j]);
+            double ts = 0.0, td = 0.0;
+            for (int r = 0; r < rpb; ++r) {
+                ts += red[j][r * tpr + threadIdx.x];
+                td += red[4 + j][r * tpr + threadIdx.x];
+            }
+            if (ts != 0.0) atomicAdd(acc + c + j, ts);
+            if (td != 0.0) atomicAdd(acc + F + c + j, td);
         }
     }
     if (absmax_dX) {

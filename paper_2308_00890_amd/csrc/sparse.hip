@@ -913,7 +913,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     // edges per wavefront: large chunks mean fewer rows cut by a boundary (fewer atomics); small graphs
     // need small chunks to fill 256 CUs
     a.chunk_shift = 6;
-    if ((a.nnz >> 10) >= 4096) a.chunk_shift = 10;
+    if ((a.nnz >> 10) >= 16384) a.chunk_shift = 10;  // at least 16 waves per SIMD worth of chunks
     else if ((a.nnz >> 8) >= 4096) a.chunk_shift = 8;
     // low mean degree, weights at the edge's own position, rows of at most two cache lines: rows of up to 64
     // edges go to the group-per-row kernel (measured: 3-20 % faster there, slower elsewhere)

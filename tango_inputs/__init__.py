@@ -121,6 +121,22 @@ def toy_graph(n_nodes: int = 1024, n_edges: int = 16384, seed: int = BASE_SEED +
     return graph_from_edges(n_nodes, u, v, self_loops=True)
 
 
+def batch_graphs(graphs) -> Graph:
+    """Block-diagonal union of several graphs (the usual way a mini-batch of sampled subgraphs is handed to the
+    primitives as one graph): node ids of graph k are shifted by the node count of graphs 0..k-1."""
+    srcs, dsts, off = [], [], 0
+    for g in graphs:
+        srcs.append(g.in_src.astype(np.uint64) + np.uint64(off))
+        dsts.append(g.in_dst().astype(np.uint64) + np.uint64(off))
+        off += g.n_nodes
+    return graph_from_edges(off, np.concatenate(srcs), np.concatenate(dsts), self_loops=False)
+
+
+def minibatch_graph(n_graphs: int, nodes_each: int, edges_each: int, seed: int) -> Graph:
+    """``n_graphs`` uniform random subgraphs (self-loops included in each), batched block-diagonally."""
+    return batch_graphs([toy_graph(nodes_each, edges_each, seed + k) for k in range(n_graphs)])
+
+
 def rmat_graph(
     n_nodes: int,
     n_edges: int,

@@ -31,6 +31,10 @@ def gat_case(name):
         g = ti.rmat_graph(3000, 60000, seed=21)
         li = ti.layer_inputs("gat_dense", graph=g, k_in=602)
         return li, 0.2
+    if name == "minibatch":  # six small sampled subgraphs handed over as one block-diagonal graph
+        g = ti.minibatch_graph(6, 96, 700, seed=23)
+        li = ti.layer_inputs("toy", graph=g, k_in=64)
+        return li, 0.2
     if name == "rmat_h3":  # configuration-4 widths
         g = ti.rmat_graph(2000, 30000, seed=22)
         li = ti.layer_inputs("gat_products", graph=g, k_in=100)
@@ -114,7 +118,7 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
         assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-2, name
 
 
-@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3"])
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "minibatch"])
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
 @pytest.mark.parametrize("mode", ["fused, nothing stored per edge", "fused, edge caches kept", "primitive by primitive"])
 def test_gat_layer_stagewise(T, case, rounding, mode):

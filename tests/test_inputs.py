@@ -54,3 +54,21 @@ def test_values_are_seeded():
     assert np.abs(w).max() <= np.sqrt(6 / 128)
     li = ti.layer_inputs("toy")
     assert li.feat.shape == (1024, 64) and li.weight.shape == (64, 64) and li.a_src.shape == (2, 32)
+
+
+def test_batched_minibatch_graph_is_block_diagonal():
+    parts = [ti.toy_graph(50 + 7 * k, 300 + 11 * k, seed=100 + k) for k in range(5)]
+    g = ti.batch_graphs(parts)
+    assert g.n_nodes == sum(p.n_nodes for p in parts) and g.n_edges == sum(p.n_edges for p in parts)
+    off = 0
+    dst = g.in_dst()
+    for p in parts:
+        lo, hi = g.in_ptr[off], g.in_ptr[off + p.n_nodes]
+        assert hi - lo == p.n_edges
+        assert np.array_equal(g.in_src[lo:hi] - off, p.in_src)  # same edges, same destination-major order, shifted ids
+        assert dst[lo:hi].min() >= off and dst[lo:hi].max() < off + p.n_nodes
+        assert np.array_equal(np.diff(g.out_ptr[off:off + p.n_nodes + 1]), np.diff(p.out_ptr))
+        off += p.n_nodes
+    assert np.array_equal(np.sort(g.out_eid), np.arange(g.n_edges))
+    m = ti.minibatch_graph(3, 40, 200, seed=5)
+    assert m.n_nodes == 120 and m.n_edges == 3 * 240
