@@ -131,6 +131,20 @@ __device__ static inline int tango_group_sum(int d, int n)
     return d;
 }
 
+// The same with the group size known at compile time (N = 0: not known, use n): no branches in the caller's loop.
+template <int N>
+__device__ static inline int tango_group_sum_c(int d, int n)
+{
+    if (N == 0) return tango_group_sum(d, n);
+    if (N >= 2) d += __builtin_amdgcn_update_dpp(0, d, 0xB1, 0xF, 0xF, true);
+    if (N >= 4) d += __builtin_amdgcn_update_dpp(0, d, 0x4E, 0xF, 0xF, true);
+    if (N >= 8) d += __builtin_amdgcn_update_dpp(0, d, 0x141, 0xF, 0xF, true);
+    if (N >= 16) d += __builtin_amdgcn_update_dpp(0, d, 0x140, 0xF, 0xF, true);
+#pragma unroll
+    for (int off = 16; off < N; off <<= 1) d += __shfl_xor(d, off, 64);
+    return d;
+}
+
 __device__ static inline float tango_wave_max(float v)
 {
 #pragma unroll

@@ -212,7 +212,9 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 // the row of dOut_q[v] gathered for 5' is also multiplied with the resident row X_q[u], which is dalpha of edge
 // (u -> v); with alpha (already recomputed for the edge weight), P[v] and the sign of the pre-activation this gives
 // dE, summed into dS_acc[u][h] - the second gather pass over the same rows that a separate SDDMM would need is gone.
-template <int VEC, bool HAS_EID, int WMODE, bool X4 = false, bool DS = false>
+// LPHC (DS only): lanes per head when known at compile time (0: computed from the arguments), so that the lane-group
+// sums in the gather loop carry no branches.
+template <int VEC, bool HAS_EID, int WMODE, bool X4 = false, bool DS = false, int LPHC = 0>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 0 ? 5 : 4))) void k_spmm(spmm_args a)
 {
     constexpr int CPL = X4 ? 2 * VEC : VEC;  // columns per lane
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     }
     const float sc = s_w * (*a.s_X);
     const int8_t *Xcol = a.X + li * VEC;
-    const int LPH = a.dim / VEC;  // DS: lanes per head (a power of two)
+    const int LPH = LPHC ? LPHC : a.dim / VEC;  // DS: lanes per head (a power of two)
     float sc_dot = 0.0f;
     if (DS) sc_dot = (*a.s_X) * (*a.att.s_Xrow);
 
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                             }
 #pragma unroll
                             for (int v = 0; v < 4; ++v) {
-                                const int d = tango_group_sum(d4[v], LPH);
+                                const int d = tango_group_sum_c<LPHC>(d4[v], LPH);
                                 const int k = (s0 + u + v) * G + gi;
                                 if (active && k < len && (li % LPH) == 0) dots_s[wv][(k0 + k) * a.heads + h] = d;
                             }
@@ -666,7 +668,8 @@ enum { DOT_STORE = 0, DOT_SRC = 1, DOT_DST = 2 };
 // stats[v][h][0..2] in fp64 and a finishing kernel forms P and dD.
 // I4: both tables hold packed 4-bit codes; a.F and a.dim then count bytes (two columns each) and the products come
 // from v_dot8_i32_i4.
-template <int VEC, int MODE, bool I4 = false>
+// LPHC: lanes per head when known at compile time (0: computed from the arguments).
+template <int VEC, int MODE, bool I4 = false, int LPHC = 0>
 __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_args a)
 {
     constexpr bool ATT_BWD = MODE == DOT_SRC;
@@ -691,7 +694,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     const bool active = gi < G;
     const int col = li * VEC;
     const int h = col / a.dim;
-    const int LPH = a.dim / VEC;  // lanes per head (power of two)
+    const int LPH = LPHC ? LPHC : a.dim / VEC;  // lanes per head (power of two)
     const float sc = (*a.s_dst) * (*a.s_src);
     constexpr int U = 8;
     // epilogue mapping: lane l < S handles the (edge, head) pairs l, l+S, l+2S, ... of a block, S a multiple of
@@ -752,7 +755,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                 }
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
-                    const int d = tango_group_sum(dot[u], LPH);
+                    const int d = tango_group_sum_c<LPHC>(dot[u], LPH);
                     const int k = (s0 + u) * G + gi;
                     if (active && k < cnt && (li % LPH) == 0) dots[wv][k * H + h] = d;
                 }
@@ -954,7 +957,11 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
             switch (pick_vec(a.F, dim, true)) {
                 case 4: k_spmm<4, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
                 case 8: k_spmm<8, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-                default: k_spmm<16, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+                default:
+                    if (dim == 64) k_spmm<16, true, W_ATT_REV, false, true, 4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+                    else if (dim == 128) k_spmm<16, true, W_ATT_REV, false, true, 8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+                    else k_spmm<16, true, W_ATT_REV, false, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+                    break;
             }
             TANGO_LAUNCH_CHECK();
             k_spmm_finalize<<<row_blocks, 256, 0, st>>>(a);
@@ -1054,7 +1061,11 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     switch (pick_vec(a.F, dim, true)) {
         case 4: k_sddmm_dot<4, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
         case 8: k_sddmm_dot<8, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-        default: k_sddmm_dot<16, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+        default:
+            if (a.dim == 64) k_sddmm_dot<16, DOT_STORE, false, 4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else if (a.dim == 128) k_sddmm_dot<16, DOT_STORE, false, 8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else k_sddmm_dot<16, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            break;
     }
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
@@ -1107,7 +1118,11 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
         switch (pick_vec(a.F, dim, true)) {
             case 4: k_sddmm_dot<4, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
             case 8: k_sddmm_dot<8, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            default: k_sddmm_dot<16, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default:
+            if (a.dim == 64) k_sddmm_dot<16, DOT_DST, false, 4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else if (a.dim == 128) k_sddmm_dot<16, DOT_DST, false, 8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else k_sddmm_dot<16, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            break;
         }
         TANGO_LAUNCH_CHECK();
     }
@@ -1147,7 +1162,11 @@ int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int
         switch (pick_vec(a.F, dim, true)) {
             case 4: k_sddmm_dot<4, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
             case 8: k_sddmm_dot<8, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
-            default: k_sddmm_dot<16, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
+            default:
+            if (a.dim == 64) k_sddmm_dot<16, DOT_SRC, false, 4><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else if (a.dim == 128) k_sddmm_dot<16, DOT_SRC, false, 8><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            else k_sddmm_dot<16, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a);
+            break;
         }
         TANGO_LAUNCH_CHECK();
     }
