@@ -62,7 +62,35 @@ struct attn_stats_op {
             m[h] = -INFINITY;
             s[h] = 0.0f;
         }
-        for (int e = b + tm.rank; e < t; e += tm.size()) {
+        // four edges per lane and iteration: the four index loads, then the four gathers, are issued back to back, and
+        // the running maximum is raised once per group (one rescaling exponential per four edges instead of one each)
+        constexpr int UE = 4;
+        int e = b + tm.rank;
+        for (; e + (UE - 1) * tm.size() < t; e += UE * tm.size()) {
+            int nb[UE];
+#pragma unroll
+            for (int u = 0; u < UE; ++u) nb[u] = src[e + u * tm.size()];
+            int sq[UE][H];
+#pragma unroll
+            for (int u = 0; u < UE; ++u) tango_load_heads<H>(Sq, nb[u], sq[u]);
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                float ev[UE];
+                float mx = m[h];
+#pragma unroll
+                for (int u = 0; u < UE; ++u) {
+                    bool pos;
+                    ev[u] = tango_attn_score(sS * static_cast<float>(sq[u][h]), td[h], slope, pos);
+                    mx = fmaxf(mx, ev[u]);
+                }
+                float acc = (mx > m[h]) ? s[h] * tango_attn_exp(m[h] - mx) : s[h];
+#pragma unroll
+                for (int u = 0; u < UE; ++u) acc += tango_attn_exp(ev[u] - mx);
+                s[h] = acc;
+                m[h] = mx;
+            }
+        }
+        for (; e < t; e += tm.size()) {
             int sq[H];
             tango_load_heads<H>(Sq, src[e], sq);
 #pragma unroll
