@@ -154,7 +154,9 @@ int tango_relu_bwd(const float *x, const float *dy, size_t n, float *dx, void *s
  * (the cache of Sec. 3.3 "Inter-primitive optimization").  Accumulation is
  * int32; C = (float)acc * (s_A*s_B); absmax_C[0] = max|C| (the scale
  * computation fused into the GEMM, Sec. 3.2).  absmax_C may be NULL.
- * A must be 16-byte aligned.
+ * A must be 16-byte aligned.  K <= 2048 runs the quantize-on-load kernel; a
+ * longer reduction needs K % 16 == 0 (else TANGO_ERR_UNSUPPORTED) and runs
+ * as a quantization pass followed by the tiled kernel of tango_qgemm_i8.
  */
 size_t tango_qgemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B, int rounding,
@@ -169,7 +171,7 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
  *   dA (M x K) = (float)(dC_q . B_q^T) * (s_dC*s_B)
  *   dB (K x N) = (float)(A_q^T . dC_q) * (s_A*s_dC)      (Sec. 3.2: fp32
  * gradients for the full-precision weight update).  dA or dB may be NULL to
- * skip that product.
+ * skip that product.  dA with N > 2048 needs N % 16 == 0.
  */
 size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,

@@ -16,6 +16,9 @@
 // + 4K (read) + K (A_q write) + 4N (C write).
 #include "internal.hip.h"
 
+int tango_gemm_i8_async(int64_t M, int64_t N, int64_t K, const int8_t *A_q, int64_t lda, const float *s_A, const int8_t *BT_q,
+                        int64_t ldb, const float *s_B, float *C, float *absmax_C, hipStream_t st);
+
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -362,7 +365,7 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(K <= KMAX, TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(K <= KMAX || K % 16 == 0, TANGO_ERR_UNSUPPORTED);  // long reductions go through the tiled int8 kernel
     TANGO_REQUIRE(A && B && A_q && s_A && B_q && s_B && C, TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(A, 16) && tango_aligned(A_q, 8) && tango_aligned(B, 4) && tango_aligned(C, 4),
                   TANGO_ERR_BAD_SHAPE);
@@ -385,6 +388,14 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
         k_quantize_b<TANGO_SR><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
     TANGO_LAUNCH_CHECK();
 
+    if (K > KMAX) {
+        // the 64-row panel of A no longer fits LDS: quantize A in a pass of its own, then the tiled kernel on the int8
+        // operands (BT: N rows of Kp bytes, zero-padded)
+        if ((rc = tango_quantize_with_absmax_async(A, static_cast<size_t>(M) * K, rounding, seed, stream_id_A, am, A_q, s_A, st)) !=
+            TANGO_OK)
+            return rc;
+        return tango_gemm_i8_async(M, N, K, A_q, K, s_A, BT, Kp, s_B, C, absmax_C, st);
+    }
     fused_args a;
     a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K); a.Kp = Kp; a.Np = Np;
     a.A = A; a.absmax_A = am; a.rng = tango_rng_make(seed, stream_id_A);
@@ -406,7 +417,7 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
     if (rc != TANGO_OK) return rc;
-    TANGO_REQUIRE(N <= KMAX, TANGO_ERR_UNSUPPORTED);  // N is the reduction length of the dA product
+    TANGO_REQUIRE(N <= KMAX || N % 16 == 0 || !dA, TANGO_ERR_UNSUPPORTED);  // N is the reduction length of the dA product
     TANGO_REQUIRE(dC && dC_q && s_dC, TANGO_ERR_NULL);
     TANGO_REQUIRE(!dA || (B_q && s_B), TANGO_ERR_NULL);
     TANGO_REQUIRE(!dB || (A_q && s_A), TANGO_ERR_NULL);
@@ -423,7 +434,14 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
         if ((rc = tango_absmax_accumulate_async(dC, static_cast<size_t>(M) * N, am, st)) != TANGO_OK) return rc;
         amp = am;
     }
-    if (dA) {
+    if (dA && N > KMAX) {
+        // long reduction: quantize dC first, then the tiled int8 kernel; B_q (K x N, rows contiguous along n) already is
+        // the transposed operand of this product
+        if ((rc = tango_quantize_with_absmax_async(dC, static_cast<size_t>(M) * N, rounding, seed, stream_id_dC, amp, dC_q,
+                                                   s_dC, st)) != TANGO_OK)
+            return rc;
+        if ((rc = tango_gemm_i8_async(M, K, N, dC_q, N, s_dC, B_q, N, s_B, dA, nullptr, st)) != TANGO_OK) return rc;
+    } else if (dA) {
         // dA = dC_q . B_q^T: the forward kernel with dC in the role of A and B_q (K x N, rows contiguous along
         // the reduction index n) in the role of the transposed operand.
         const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));

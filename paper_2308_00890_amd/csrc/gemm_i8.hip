@@ -23,6 +23,7 @@ constexpr int NJ = TM / 32;                  // staging passes: 8 lanes x 16 byt
 struct i8gemm_args {
     int64_t M;
     int N, K;
+    int lda, ldb;      // row strides in bytes (>= K, multiples of 16)
     const int8_t *A;   // M x K
     const int8_t *BT;  // N x K
     const float *s_A, *s_B;
@@ -63,14 +64,14 @@ __global__ __launch_bounds__(256) void k_gemm_i8(i8gemm_args a)
     // are never stored; columns past K are zeroed when the registers are written to LDS (not at the load, so that
     // no use of the loaded value sits next to it).  Addresses are a wave-uniform base plus a 32-bit lane offset.
     const int srow = tid / 8, sk = (tid % 8) * 16;
-    const int8_t *baseA = a.A + m0 * a.K;
-    const int8_t *baseB = a.BT + static_cast<int64_t>(n0) * a.K;
+    const int8_t *baseA = a.A + m0 * a.lda;
+    const int8_t *baseB = a.BT + static_cast<int64_t>(n0) * a.ldb;
     unsigned offA[NJ], offB[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int64_t ra = m0 + srow + 32 * j, rb = static_cast<int64_t>(n0) + srow + 32 * j;
-        offA[j] = static_cast<unsigned>(((ra < a.M ? ra : a.M - 1) - m0) * a.K);  // < 256 * K < 2^32
-        offB[j] = static_cast<unsigned>(((rb < a.N ? rb : a.N - 1) - n0) * a.K);
+        offA[j] = static_cast<unsigned>(((ra < a.M ? ra : a.M - 1) - m0) * a.lda);  // < 256 * lda < 2^32
+        offB[j] = static_cast<unsigned>(((rb < a.N ? rb : a.N - 1) - n0) * a.ldb);
     }
     auto gload = [&](stage_regs &r, int tile, auto masked) {
         unsigned k = static_cast<unsigned>(tile * TK + sk);
@@ -215,6 +216,29 @@ __global__ __launch_bounds__(256) void k_gemm_i8(i8gemm_args a)
 
 }  // namespace
 
+// The product for operands with row strides (bytes) lda, ldb >= K, both multiples of 16; used by the quantizing GEMM
+// entry points when the reduction is too long for their panel kernel.
+int tango_gemm_i8_async(int64_t M, int64_t N, int64_t K, const int8_t *A_q, int64_t lda, const float *s_A, const int8_t *BT_q,
+                        int64_t ldb, const float *s_B, float *C, float *absmax_C, hipStream_t st)
+{
+    TANGO_REQUIRE(K % 16 == 0 && lda % 16 == 0 && ldb % 16 == 0 && lda >= K && ldb >= K && lda < (int64_t(1) << 24) &&
+                      ldb < (int64_t(1) << 24),
+                  TANGO_ERR_UNSUPPORTED);
+    if (absmax_C) {
+        int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_C), 0u, 1, st);
+        if (rc != TANGO_OK) return rc;
+    }
+    i8gemm_args a;
+    a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K);
+    a.lda = static_cast<int>(lda); a.ldb = static_cast<int>(ldb);
+    a.A = A_q; a.BT = BT_q; a.s_A = s_A; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C;
+    const int64_t tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
+    TANGO_REQUIRE(tiles < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
+    k_gemm_i8<<<static_cast<unsigned>(tiles), 256, 0, st>>>(a);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
 extern "C" {
 
 int tango_qgemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *BT_q,
@@ -225,19 +249,7 @@ int tango_qgemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const flo
     TANGO_REQUIRE(K % 16 == 0, TANGO_ERR_UNSUPPORTED);
     TANGO_REQUIRE(A_q && s_A && BT_q && s_B && C, TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(A_q, 16) && tango_aligned(BT_q, 16) && tango_aligned(C, 4), TANGO_ERR_BAD_SHAPE);
-    hipStream_t st = tango_stream(stream);
-    if (absmax_C) {
-        int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_C), 0u, 1, st);
-        if (rc != TANGO_OK) return rc;
-    }
-    i8gemm_args a;
-    a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K);
-    a.A = A_q; a.BT = BT_q; a.s_A = s_A; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C;
-    const int64_t tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
-    TANGO_REQUIRE(tiles < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
-    k_gemm_i8<<<static_cast<unsigned>(tiles), 256, 0, st>>>(a);
-    TANGO_LAUNCH_CHECK();
-    return TANGO_OK;
+    return tango_gemm_i8_async(M, N, K, A_q, K, s_A, BT_q, K, s_B, C, absmax_C, tango_stream(stream));
 }
 
 }  // extern "C"

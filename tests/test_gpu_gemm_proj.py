@@ -31,6 +31,8 @@ GEMM_SHAPES = [
     (64, 384, 384),
     (1, 1, 1),
     (3000, 2048, 40),
+    (300, 4112, 136),  # reduction longer than the panel kernel takes: quantization pass + tiled int8 kernel
+    (260, 72, 2320),   # ... and the same for the dA product of the backward pass (its reduction length is N)
 ]
 
 
