@@ -1,7 +1,8 @@
 """CPU oracle for the quantized GNN-layer primitives -- TEST INFRASTRUCTURE ONLY.
 
 Thin numpy/ctypes front end of ``tango_oracle.c`` plus the layer-level
-compositions (one GAT layer and one GCN layer, forward and backward, with the
+compositions (one GAT layer, one GCN layer and one typed-edge GEMM+SPMM layer
+that covers GraphSAGE and the relational GCN, forward and backward, with the
 quantized tensors cached between primitives as in Sec. 3.3 "Inter-primitive
 optimization").  Only tests, the smoke check and the benchmark's CPU-baseline
 leg may import this package; it shares no code with the GPU library and the
@@ -451,3 +452,59 @@ def gcn_layer_bwd(g, fwd, w_q, s_w, grad_out, rounding=SR, seed=0, layer=0):
     dHp, am_dHp = spmm_rev(g, w_q, s_w, g_q, s_g)
     r = qgemm_bwd(fwd["H_q"], fwd["s_H"], fwd["W_q"], fwd["s_W"], dHp, rounding, seed, b + SID_DHP, am=am_dHp)
     return dict(g_q=g_q, s_g=s_g, dHp=dHp, absmax_dHp=am_dHp, dHp_q=r["dC_q"], s_dHp=r["s_dC"], dW=r["dB"], dH=r["dA"])
+
+
+# ------------------------------------------------ layers built from GEMM + SPMM over typed edges
+# Sec. 2.2 lists GraphSAGE and the relational GCN as models made of the same GEMM and SPMM primitives and gives no
+# formulas; the usual definitions are taken (the tests pin them to their dense fp64 forms, to brute force and, with
+# one type, to the GCN layer above):
+#   relational GCN   out[v] = H[v].W_0 + sum_r sum_{u ->_r v} (1/c_{v,r}) H[u].W_r
+#   GraphSAGE (mean) out[v] = H[v].W_self + mean_{u -> v} H[u] . W_neigh
+# Both are one layer over edges that carry a type t(e) and a fixed weight w(e):
+#   Z = H.[W_0 | W_1 | ... | W_{T-1}]   (one quantized GEMM),   out[v] = sum_{e: u -> v} w(e) * Z[u, block t(e)].
+# ``tg`` needs n_nodes, n_types, in_src, in_type, in_dst() in destination-major edge order.
+def typed_spmm_in(tg, w_q, s_w, Z_q, s_Z, want_acc: bool = False):
+    """out[v, :] = (s_w*s_Z) * sum over in-edges e=(u->v) of w_q[e] * Z_q[u, t(e)*F : (t(e)+1)*F]."""
+    T = tg.n_types
+    Zb = _c(Z_q, np.int8).reshape(tg.n_nodes, T, -1).astype(np.int64)
+    acc = np.zeros((tg.n_nodes, Zb.shape[2]), np.int64)
+    w = _c(w_q, np.int8).reshape(-1).astype(np.int64)
+    np.add.at(acc, tg.in_dst(), w[:, None] * Zb[tg.in_src, tg.in_type])
+    if np.abs(acc).max(initial=0) >= 2**31:
+        raise OverflowError("int32 overflow in typed SPMM")
+    out, am = dequant_i32(acc.astype(np.int32), s_w, s_Z)
+    return (out, am, acc.astype(np.int32)) if want_acc else (out, am)
+
+
+def typed_spmm_rev(tg, w_q, s_w, Y_q, s_Y, want_acc: bool = False):
+    """dZ[u, t*F:(t+1)*F] = (s_w*s_Y) * sum over out-edges e=(u->v) of type t of w_q[e] * Y_q[v, :]."""
+    T = tg.n_types
+    Y = _c(Y_q, np.int8).astype(np.int64)
+    acc = np.zeros((tg.n_nodes, T, Y.shape[1]), np.int64)
+    w = _c(w_q, np.int8).reshape(-1).astype(np.int64)
+    np.add.at(acc, (tg.in_src, tg.in_type), w[:, None] * Y[tg.in_dst()])
+    if np.abs(acc).max(initial=0) >= 2**31:
+        raise OverflowError("int32 overflow in typed SPMM")
+    acc = acc.reshape(tg.n_nodes, -1).astype(np.int32)
+    out, am = dequant_i32(acc, s_w, s_Y)
+    return (out, am, acc) if want_acc else (out, am)
+
+
+def typed_layer_fwd(tg, H, W_cat, w_q, s_w, rounding=SR, seed=0, layer=0):
+    """Transform with all type blocks in one GEMM, quantize, aggregate over the typed edges."""
+    b = 16 * layer
+    r = qgemm(H, W_cat, rounding, seed, b + SID_H, b + SID_W)
+    Z_q, s_Z = quantize(r["C"], rounding, seed, b + SID_HP, am=r["absmax_C"])
+    out, am_out = typed_spmm_in(tg, w_q, s_w, Z_q, s_Z)
+    return dict(
+        H_q=r["A_q"], s_H=r["s_A"], W_q=r["B_q"], s_W=r["s_B"], Hp=r["C"], absmax_Hp=r["absmax_C"], Hp_q=Z_q,
+        s_Hp=s_Z, out=out, absmax_out=am_out,
+    )
+
+
+def typed_layer_bwd(tg, fwd, w_q, s_w, grad_out, rounding=SR, seed=0, layer=0):
+    b = 16 * layer
+    g_q, s_g = quantize(grad_out, rounding, seed, b + SID_G)
+    dZ, am_dZ = typed_spmm_rev(tg, w_q, s_w, g_q, s_g)
+    r = qgemm_bwd(fwd["H_q"], fwd["s_H"], fwd["W_q"], fwd["s_W"], dZ, rounding, seed, b + SID_DHP, am=am_dZ)
+    return dict(g_q=g_q, s_g=s_g, dHp=dZ, absmax_dHp=am_dZ, dHp_q=r["dC_q"], s_dHp=r["s_dC"], dW=r["dB"], dH=r["dA"])

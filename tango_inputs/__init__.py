@@ -191,6 +191,96 @@ def rmat_graph(
     return graph_from_keys(n_nodes, have)
 
 
+@dataclass
+class TypedGraph:
+    """Multigraph whose edges carry a type in ``0 .. n_types-1`` (relation types of a relational GCN; self / neighbour
+    for GraphSAGE).  Destination-major edge order, ties by (source, type).  The source-major view has one row per
+    (source, type) pair, row index ``source * n_types + type``: a layer that keeps one block of ``F`` columns per type
+    in a row-major ``N x (n_types*F)`` table then sees the table as ``(N*n_types) x F`` and the typed graph as an
+    ordinary bipartite graph from these rows to the N destinations."""
+
+    n_nodes: int
+    n_types: int
+    n_edges: int
+    in_ptr: np.ndarray  # N + 1
+    in_src: np.ndarray  # nnz, source node
+    in_type: np.ndarray  # nnz
+    out_ptr: np.ndarray  # N * n_types + 1
+    out_dst: np.ndarray  # nnz
+    out_eid: np.ndarray  # nnz
+
+    def in_dst(self) -> np.ndarray:
+        return np.repeat(np.arange(self.n_nodes, dtype=np.int32), np.diff(self.in_ptr))
+
+    def in_key(self) -> np.ndarray:
+        """Row of the (source, type) pair of every edge."""
+        return (self.in_src.astype(np.int64) * self.n_types + self.in_type).astype(np.int32)
+
+    def dst_view(self) -> Graph:
+        """N destination rows gathering from N*n_types table rows (forward direction only)."""
+        return Graph(self.n_nodes, self.n_edges, self.in_ptr, self.in_key(), None, None, None)
+
+    def src_view(self) -> Graph:
+        """N*n_types (source, type) rows gathering from N destination rows (reverse direction only)."""
+        return Graph(self.n_nodes * self.n_types, self.n_edges, None, None, self.out_ptr, self.out_dst, self.out_eid)
+
+
+def typed_graph_from_edges(n_nodes: int, n_types: int, src, dst, etype) -> TypedGraph:
+    """Typed multigraph from an edge list; duplicate (src, dst, type) triples are removed."""
+    if n_nodes * n_types >= 2**31:
+        raise ValueError("n_nodes * n_types must be below 2^31")
+    key = np.asarray(src, dtype=np.uint64) * np.uint64(n_types) + np.asarray(etype, dtype=np.uint64)
+    keys = np.unique((np.asarray(dst, dtype=np.uint64) << np.uint64(32)) | key)
+    nnz = int(keys.shape[0])
+    in_dst = (keys >> np.uint64(32)).astype(np.int64)
+    in_key = (keys & np.uint64(0xFFFFFFFF)).astype(np.int64)
+    in_ptr = np.zeros(n_nodes + 1, np.int64)
+    np.cumsum(np.bincount(in_dst, minlength=n_nodes), out=in_ptr[1:])
+    order = np.argsort(in_key, kind="stable")  # source-major, ties keep the destination order
+    out_ptr = np.zeros(n_nodes * n_types + 1, np.int64)
+    np.cumsum(np.bincount(in_key, minlength=n_nodes * n_types), out=out_ptr[1:])
+    return TypedGraph(
+        n_nodes, n_types, nnz, in_ptr.astype(np.int32), (in_key // n_types).astype(np.int32),
+        (in_key % n_types).astype(np.int32), out_ptr.astype(np.int32), in_dst[order].astype(np.int32),
+        order.astype(np.int32),
+    )
+
+
+def sage_typed_graph(g: Graph):
+    """GraphSAGE with the mean aggregator as a two-type graph: type 0 = the node itself (weight 1), type 1 = its
+    in-neighbours other than itself (weight 1/their number).  Returns (TypedGraph, fp32 weights nnz x 1)."""
+    src, dst = g.in_src.astype(np.int64), g.in_dst().astype(np.int64)
+    keep = src != dst
+    ids = np.arange(g.n_nodes, dtype=np.int64)
+    tg = typed_graph_from_edges(
+        g.n_nodes, 2, np.concatenate([src[keep], ids]), np.concatenate([dst[keep], ids]),
+        np.concatenate([np.ones(int(keep.sum()), np.int64), np.zeros(g.n_nodes, np.int64)]),
+    )
+    n_neigh = np.bincount(tg.in_dst()[tg.in_type == 1], minlength=g.n_nodes).astype(np.float64)
+    w = np.where(tg.in_type == 0, 1.0, 1.0 / np.maximum(n_neigh[tg.in_dst()], 1.0))
+    return tg, w.astype(np.float32).reshape(-1, 1)
+
+
+def rgcn_typed_graph(g: Graph, n_relations: int, seed: int):
+    """Relational GCN input: every non-self edge of ``g`` gets one of ``n_relations`` relation types (uniform, seeded;
+    types 1..n_relations), weight 1/c with c = the number of in-edges of its destination under that relation; type 0
+    is the self-connection with weight 1.  Returns (TypedGraph, fp32 weights nnz x 1)."""
+    rng = np.random.default_rng(seed)
+    src, dst = g.in_src.astype(np.int64), g.in_dst().astype(np.int64)
+    keep = src != dst
+    rel = 1 + rng.integers(0, n_relations, size=int(keep.sum()))
+    ids = np.arange(g.n_nodes, dtype=np.int64)
+    T = n_relations + 1
+    tg = typed_graph_from_edges(
+        g.n_nodes, T, np.concatenate([src[keep], ids]), np.concatenate([dst[keep], ids]),
+        np.concatenate([rel, np.zeros(g.n_nodes, np.int64)]),
+    )
+    slot = tg.in_dst().astype(np.int64) * T + tg.in_type
+    c = np.bincount(slot, minlength=g.n_nodes * T).astype(np.float64)
+    w = np.where(tg.in_type == 0, 1.0, 1.0 / c[slot])
+    return tg, w.astype(np.float32).reshape(-1, 1)
+
+
 def normal(shape, seed: int) -> np.ndarray:
     """i.i.d. N(0,1) fp32."""
     rng = np.random.default_rng(seed)

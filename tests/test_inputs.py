@@ -72,3 +72,26 @@ def test_batched_minibatch_graph_is_block_diagonal():
     assert np.array_equal(np.sort(g.out_eid), np.arange(g.n_edges))
     m = ti.minibatch_graph(3, 40, 200, seed=5)
     assert m.n_nodes == 120 and m.n_edges == 3 * 240
+
+
+@pytest.mark.parametrize("kind", ["sage", "rgcn"])
+def test_typed_graph_views(kind):
+    g = ti.rmat_graph(400, 3000, seed=9)
+    tg, w = ti.sage_typed_graph(g) if kind == "sage" else ti.rgcn_typed_graph(g, 4, 10)
+    N, T, nnz = tg.n_nodes, tg.n_types, tg.n_edges
+    assert nnz == g.n_edges and w.shape == (nnz, 1) and T == (2 if kind == "sage" else 5)
+    assert tg.in_ptr[0] == 0 and tg.in_ptr[-1] == nnz and tg.out_ptr.shape == (N * T + 1,) and tg.out_ptr[-1] == nnz
+    dst, key = tg.in_dst().astype(np.int64), tg.in_key().astype(np.int64)
+    assert (np.diff(dst * N * T + key) > 0).all()  # destination-major, no duplicate (src, dst, type)
+    # the same (src, dst) pairs as the untyped graph; type 0 exactly on the self-connections
+    assert np.array_equal(np.sort(dst * N + tg.in_src), np.sort(g.in_dst().astype(np.int64) * N + g.in_src))
+    assert np.array_equal(tg.in_type == 0, tg.in_src == dst)
+    # source-major view: rows are (source, type) pairs, eid maps back
+    assert np.array_equal(np.sort(tg.out_eid), np.arange(nnz))
+    orow = np.repeat(np.arange(N * T), np.diff(tg.out_ptr))
+    assert np.array_equal(key[tg.out_eid], orow) and np.array_equal(dst[tg.out_eid], tg.out_dst)
+    # weights of one destination and type sum to one
+    sums = np.bincount(dst * T + tg.in_type, weights=w.reshape(-1).astype(np.float64), minlength=N * T)
+    assert np.allclose(sums[sums > 0], 1.0, atol=1e-5)
+    dv, sv = tg.dst_view(), tg.src_view()
+    assert dv.n_nodes == N and sv.n_nodes == N * T and np.array_equal(dv.in_src, key)

@@ -430,3 +430,83 @@ def test_quantized_gcn_layer_close_to_fp64_layer():
     assert rel_err(b["dHp"], dHp) < 0.05
     assert rel_err(b["dW"], H.astype(np.float64).T @ dHp) < 0.05
     assert rel_err(b["dH"], dHp @ W.astype(np.float64).T) < 0.05
+
+
+# ----------------------------------------------------------------- typed-edge layers (GraphSAGE, relational GCN)
+def typed_dense(tg, w):
+    """A[t][v, u] = weight of the type-t edge u -> v (fp64)."""
+    A = np.zeros((tg.n_types, tg.n_nodes, tg.n_nodes))
+    A[tg.in_type, tg.in_dst(), tg.in_src] = np.asarray(w, np.float64).reshape(-1)
+    return A
+
+
+def test_typed_spmm_brute_force_and_adjoint():
+    g = small_graph(23, 90, 51)
+    tg, w = ti.rgcn_typed_graph(g, 3, 52)
+    T, F = tg.n_types, 8
+    w_q = rand_i8((tg.n_edges, 1), 53)
+    Z_q = rand_i8((tg.n_nodes, T * F), 54)
+    Y_q = rand_i8((tg.n_nodes, F), 55)
+    _, _, acc = orc.typed_spmm_in(tg, w_q, 0.5, Z_q, 0.25, want_acc=True)
+    _, _, racc = orc.typed_spmm_rev(tg, w_q, 0.5, Y_q, 0.25, want_acc=True)
+    want = np.zeros((tg.n_nodes, F), np.int64)
+    rwant = np.zeros((tg.n_nodes, T * F), np.int64)
+    dst = tg.in_dst()
+    for e in range(tg.n_edges):
+        u, v, t = int(tg.in_src[e]), int(dst[e]), int(tg.in_type[e])
+        for d in range(F):
+            want[v, d] += int(w_q[e, 0]) * int(Z_q[u, t * F + d])
+            rwant[u, t * F + d] += int(w_q[e, 0]) * int(Y_q[v, d])
+    assert np.array_equal(acc, want) and np.array_equal(racc, rwant)
+    # <A z, y> == <z, A^T y> exactly in integers
+    assert int((acc.astype(np.int64) * Y_q).sum()) == int((racc.astype(np.int64) * Z_q).sum())
+    out, am = orc.typed_spmm_in(tg, w_q, 0.5, Z_q, 0.25)
+    assert np.array_equal(out, (want * 0.125).astype(np.float32)) and am == np.abs(out).max()
+
+
+def test_typed_layer_with_one_type_is_the_gcn_layer():
+    g = small_graph(64, 512, 56)
+    K, F = 24, 16
+    H, W, up = ti.normal((g.n_nodes, K), 57), ti.xavier_uniform(K, F, (K, F), 58), ti.normal((g.n_nodes, F), 59)
+    w_q, s_w = orc.quantize(ti.gcn_edge_weights(g), orc.SR, seed=4, stream=orc.SID_EW)
+    tg = ti.typed_graph_from_edges(g.n_nodes, 1, g.in_src, g.in_dst(), np.zeros(g.n_edges, np.int64))
+    assert np.array_equal(tg.in_src, g.in_src) and np.array_equal(tg.in_ptr, g.in_ptr)
+    f, ft = orc.gcn_layer_fwd(g, H, W, w_q, s_w, orc.SR, 4, 2), orc.typed_layer_fwd(tg, H, W, w_q, s_w, orc.SR, 4, 2)
+    b = orc.gcn_layer_bwd(g, f, w_q, s_w, up, orc.SR, 4, 2)
+    bt = orc.typed_layer_bwd(tg, ft, w_q, s_w, up, orc.SR, 4, 2)
+    for a, c in ((f, ft), (b, bt)):
+        assert a.keys() == c.keys()
+        for k in a:
+            assert np.array_equal(a[k], c[k]), k
+
+
+@pytest.mark.parametrize("model", ["sage", "rgcn"])
+def test_quantized_typed_layer_close_to_fp64_definition(model):
+    g = small_graph(64, 600, 61)
+    K, F = 32, 24
+    tg, w = ti.sage_typed_graph(g) if model == "sage" else ti.rgcn_typed_graph(g, 3, 62)
+    T = tg.n_types
+    H = ti.normal((g.n_nodes, K), 63)
+    Wc = ti.xavier_uniform(K, F, (K, T * F), 64)
+    up = ti.normal((g.n_nodes, F), 65)
+    w_q, s_w = orc.quantize(w, orc.SR, seed=5, stream=orc.SID_EW)
+    f = orc.typed_layer_fwd(tg, H, Wc, w_q, s_w, orc.SR, seed=5)
+    b = orc.typed_layer_bwd(tg, f, w_q, s_w, up, orc.SR, seed=5)
+    A = typed_dense(tg, w)
+    H64, W64, up64 = H.astype(np.float64), Wc.astype(np.float64), up.astype(np.float64)
+    if model == "sage":
+        # out = H.W_self + (row-normalised adjacency without the diagonal).H.W_neigh
+        adj = (to_dense(g, np.ones((g.n_edges, 1)))[0] > 0).astype(np.float64)
+        np.fill_diagonal(adj, 0.0)
+        mean = adj / np.maximum(adj.sum(axis=1, keepdims=True), 1.0)
+        assert np.array_equal(A[0], np.eye(g.n_nodes)) and np.allclose(A[1], mean)
+    else:
+        # every relation's weights of one destination sum to one (or the destination has no such edge)
+        sums = A[1:].sum(axis=2)
+        assert np.allclose(sums[sums > 0], 1.0) and np.array_equal(A[0], np.eye(g.n_nodes))
+    out = sum(A[t] @ (H64 @ W64[:, t * F:(t + 1) * F]) for t in range(T))
+    dZ = np.concatenate([A[t].T @ up64 for t in range(T)], axis=1)
+    assert rel_err(f["out"], out) < 0.05
+    assert rel_err(b["dHp"], dZ) < 0.05
+    assert rel_err(b["dW"], H64.T @ dZ) < 0.05
+    assert rel_err(b["dH"], dZ @ W64.T) < 0.05
