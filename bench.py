@@ -4,7 +4,7 @@
 One "step" = one quantized GAT layer, forward + backward (every abs-max, quantization and dequantization included,
 graph construction excluded), on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_dense|toy|gcn_arxiv|gat_products|qgemm_i8] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gat_dense|toy|gcn_arxiv|gat_products|qgemm_i8|minibatch|sage_arxiv|rgcn_arxiv] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -202,7 +202,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products", "qgemm_i8", "minibatch"])
+    ap.add_argument("--workload", default="gat_dense", choices=["gat_dense", "toy", "gcn_arxiv", "gat_products", "qgemm_i8", "minibatch", "sage_arxiv", "rgcn_arxiv"])
     ap.add_argument("--gemm-shape", default="8192,8192,8192", help="M,N,K of the qgemm_i8 workload")
     ap.add_argument("--scale-down", type=int, default=1, help="divide nodes and edges (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,6 +244,10 @@ def main():
         # 256 sampled subgraphs of configuration-1 size (1,024 nodes, 17,408 edges each) handed over as one block-diagonal
         # graph: the mini-batch regime, where per-graph launches would be dispatch-bound
         name = "toy"
+    typed = name if name in ("sage_arxiv", "rgcn_arxiv") else None
+    if typed:
+        # GraphSAGE (mean aggregator) and a relational GCN with three relations on the configuration-2 graph and widths
+        name = "gcn_arxiv"
     cfg = ti.CONFIGS[name]
     t0 = time.perf_counter()
     if minibatch:
@@ -255,7 +259,23 @@ def main():
     G = T.Graph.from_host(g, dev)
     to = lambda a: torch.from_numpy(a).to(dev)
     slope = 0.2
-    if cfg["kind"] == "gcn":
+    if typed:
+        tg, w_host = ti.sage_typed_graph(g) if typed == "sage_arxiv" else ti.rgcn_typed_graph(g, 3, ti.BASE_SEED + 41)
+        nt, F = tg.n_types, cfg["dim"]
+        G, G_src = T.Graph.from_host(tg.dst_view(), dev), T.Graph.from_host(tg.src_view(), dev)
+        w = to(w_host)
+        w_q = torch.empty(w.shape, dtype=torch.int8, device=dev)
+        s_w = torch.zeros(1, dtype=torch.float32, device=dev)
+        T.tango_quantize(w, T.SR, li.sr_seed, 9, None, w_q, s_w, torch.empty(256, dtype=torch.uint8, device=dev))
+        k = li.feat.shape[1]
+        W_cat = to(ti.xavier_uniform(k, F, (k, nt * F), li.sr_seed + 20))
+        L = T.TypedLayer(G, G_src, nt, to(li.feat), W_cat, w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0)
+        step = lambda: (T.tango_typed_layer_fwd(L), T.tango_typed_layer_bwd(L))
+        heads = 1
+        spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
+        spmm_name = "k_spmm<16, false, 0> (tango_qspmm, in-edge direction over (source, type) rows)"
+        alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
+    elif cfg["kind"] == "gcn":
         w = to(ti.gcn_edge_weights(g))  # fixed edge weights: inputs of the layer, quantized once outside the timed region
         w_q = torch.empty(w.shape, dtype=torch.int8, device=dev)
         s_w = torch.zeros(1, dtype=torch.float32, device=dev)
@@ -329,7 +349,9 @@ def main():
     log("%s: %.3f ms/launch, %.1f algorithmic GB/s" % (spmm_name, spmm_ms, achieved))
 
     out = {
-        "metric": ("ms per 3 stacked quantized GAT layers fwd+bwd" if name == "gat_products" else
+        "metric": ("ms per quantized GraphSAGE (mean) layer fwd+bwd" if typed == "sage_arxiv" else
+                   "ms per quantized relational GCN layer (3 relations) fwd+bwd" if typed == "rgcn_arxiv" else
+                   "ms per 3 stacked quantized GAT layers fwd+bwd" if name == "gat_products" else
                    "ms per quantized GAT layer fwd+bwd" if cfg["kind"] == "gat" else "ms per quantized GCN layer fwd+bwd"),
         "value": ms_per_step,
         "unit": "ms",
@@ -346,6 +368,9 @@ def main():
             "workload": ("mini-batch of 256 uniform subgraphs of configuration-1 size as one block-diagonal graph: %d nodes, "
                          "%d edges incl. self-loops, K_in %d, %d heads x %d, SR" % (g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim))
             if minibatch else
+            "%s on the config-2 graph: %d nodes, %d typed edges, %d edge types, K_in %d, F %d per type, SR"
+            % (typed, g.n_nodes, g.n_edges, nt, li.feat.shape[1], F)
+            if typed else
             "config %d (%s): %s graph, %d nodes, %d edges incl. self-loops, K_in %d, %d heads x %d, SR"
             % (cfg["config"], name, cfg["graph"], g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim),
             "scale_down": args.scale_down,
@@ -358,7 +383,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get(name) if args.scale_down == 1 else None,
+            "traffic": MEASURED_TRAFFIC.get(name) if args.scale_down == 1 and not typed and not minibatch else None,
             "algorithmic_bytes_per_launch": alg,
             "ms_per_launch": spmm_ms,
         },
@@ -368,8 +393,8 @@ def main():
             log("no CPU baseline leg for the 3-layer workload")
             print(json.dumps(out), flush=True)
             return
-        if minibatch:
-            log("no CPU baseline leg for the mini-batch workload")
+        if minibatch or typed:
+            log("no CPU baseline leg for this workload")
             print(json.dumps(out), flush=True)
             return
         sd = args.cpu_scale_down or {"gat_dense": 8, "gcn_arxiv": 1, "toy": 1}[name]

@@ -557,6 +557,55 @@ size_t tango_gcn_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_i
 int tango_gcn_layer_fwd(const tango_gcn_layer *L, void *stream);
 int tango_gcn_layer_bwd(const tango_gcn_layer *L, void *stream);
 
+/*
+ * One GEMM + SPMM layer over typed edges.  Sec. 2.2 names GraphSAGE and the
+ * relational GCN as models built from these two primitives; with a type t(e)
+ * in 0 .. n_types-1 and a fixed weight w(e) on every edge both are
+ *     Z = H . [W_0 | W_1 | ... | W_{n_types-1}]        (one qGEMM, Z: n x n_types*f_out)
+ *     out[v,:] = sum over e = (u -> v) of w(e) * Z[u, t(e)*f_out : (t(e)+1)*f_out]   (qSPMM)
+ * (relational GCN: t = 0 the self-connection, t = r the r-th relation, w = 1/c_{v,r};
+ * GraphSAGE with the mean aggregator: t = 0 self with w = 1, t = 1 neighbours with w = 1/degree).
+ * Row-major Z is also an (n*n_types) x f_out table whose row u*n_types + t is
+ * block t of node u, so the typed graph is passed as two one-directional views
+ * of a bipartite graph between these table rows and the n destinations:
+ *   g_dst: n_nodes = n, in_ptr[n+1], in_src[e] = u*n_types + t(e); out_* unused (may be NULL);
+ *   g_src: n_nodes = n*n_types, out_ptr[n*n_types+1], out_dst[j] = destination, out_eid[j] =
+ *          position of that edge in g_dst's order; in_* unused (may be NULL).
+ * Both views hold the same n_edges edges.  With n_types = 1 and g_dst = g_src
+ * this is tango_gcn_layer.  Buffers as in tango_gcn_layer with Hp, Hp_q, dHp,
+ * dHp_q of n x n_types*f_out, W, W_q, dW of k_in x n_types*f_out and out,
+ * grad_out, g_q of n x f_out.  Random streams as in tango_gat_layer.
+ * Limits: f_out % 4 == 0, f_out <= 1024, n*n_types < 2^31.
+ */
+typedef struct tango_typed_layer {
+    const tango_graph *g_dst;
+    const tango_graph *g_src;         /* backward only; may be NULL for forward-only use */
+    int n_types;
+    int k_in, f_out;
+    int rounding;
+    uint64_t seed, layer_id;
+    const float *H;          /* n x k_in */
+    const float *W;          /* k_in x n_types*f_out */
+    const int8_t *w_q; const float *s_w;  /* nnz edge weights, g_dst order */
+    int8_t *H_q;  float *s_H;
+    int8_t *W_q;  float *s_W;
+    float *Hp;    float *absmax_Hp;   /* Z */
+    int8_t *Hp_q; float *s_Hp;
+    float *out;   float *absmax_out;
+    const float *grad_out;
+    int8_t *g_q;  float *s_g;
+    float *dHp;   float *absmax_dHp;  /* dZ */
+    int8_t *dHp_q; float *s_dHp;
+    float *dW;
+    float *dH;                        /* n x k_in or NULL */
+    void *ws;
+    size_t ws_bytes;                  /* >= tango_typed_layer_workspace_bytes(...) */
+} tango_typed_layer;
+
+size_t tango_typed_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int n_types, int k_in, int f_out);
+int tango_typed_layer_fwd(const tango_typed_layer *L, void *stream);
+int tango_typed_layer_bwd(const tango_typed_layer *L, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

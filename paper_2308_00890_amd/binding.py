@@ -125,7 +125,7 @@ class Graph:
 
     def __init__(self, n_nodes, in_ptr, in_src, out_ptr=None, out_dst=None, out_eid=None):
         self.n_nodes = int(n_nodes)
-        self.n_edges = int(in_src.numel())
+        self.n_edges = int((in_src if in_src is not None else out_dst).numel())
         self.in_ptr, self.in_src = in_ptr, in_src
         self.out_ptr, self.out_dst, self.out_eid = out_ptr, out_dst, out_eid
         self.c = tango_graph(
@@ -136,7 +136,7 @@ class Graph:
     @classmethod
     def from_host(cls, g, device="cuda:0"):
         """``g``: object with numpy int32 arrays n_nodes, in_ptr, in_src, out_ptr, out_dst, out_eid."""
-        dev = lambda a: torch.from_numpy(a).to(device)
+        dev = lambda a: None if a is None else torch.from_numpy(a).to(device)
         return cls(g.n_nodes, dev(g.in_ptr), dev(g.in_src), dev(g.out_ptr), dev(g.out_dst), dev(g.out_eid))
 
     def ref(self):
@@ -535,7 +535,21 @@ class tango_gcn_layer(ctypes.Structure):
     )
 
 
+class tango_typed_layer(ctypes.Structure):
+    _fields_ = (
+        [("g_dst", _gp), ("g_src", _gp), ("n_types", _int), ("k_in", _int), ("f_out", _int), ("rounding", _int),
+         ("seed", _u64), ("layer_id", _u64)]
+        + [(n, _vp) for n in (
+            "H", "W", "w_q", "s_w", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "out",
+            "absmax_out", "grad_out", "g_q", "s_g", "dHp", "absmax_dHp", "dHp_q", "s_dHp", "dW", "dH", "ws")]
+        + [("ws_bytes", _sz)]
+    )
+
+
 SIGNATURES.update({
+    "tango_typed_layer_workspace_bytes": (_sz, [_i64, _i64, _int, _int, _int]),
+    "tango_typed_layer_fwd": (_int, [ctypes.POINTER(tango_typed_layer), _vp]),
+    "tango_typed_layer_bwd": (_int, [ctypes.POINTER(tango_typed_layer), _vp]),
     "tango_gat_layer_workspace_bytes": (_sz, [_i64, _i64, _int, _int, _int]),
     "tango_gat_layer_fwd": (_int, [ctypes.POINTER(tango_gat_layer), _vp]),
     "tango_gat_layer_bwd": (_int, [ctypes.POINTER(tango_gat_layer), _vp]),
@@ -676,6 +690,61 @@ class GcnLayer(_LayerBuffers):
         nbytes = tango_gcn_layer_workspace_bytes(n, graph.n_edges, k_in, f_out)
         self._alloc("ws", (nbytes,), torch.uint8)
         c.ws_bytes = nbytes
+
+
+class TypedLayer(_LayerBuffers):
+    """GEMM + SPMM layer over typed edges (GraphSAGE mean aggregator, relational GCN)."""
+
+    _struct = tango_typed_layer
+
+    def __init__(self, g_dst: "Graph", g_src: "Graph", n_types, H, W, w_q, s_w, grad_out=None, rounding=SR, seed=0,
+                 layer_id=0, want_dH=True):
+        super().__init__()
+        self.device = H.device
+        self.g_dst, self.g_src = g_dst, g_src
+        n, k_in = H.shape
+        f_cat = W.shape[1]
+        f_out = f_cat // n_types
+        c = self.c
+        c.g_dst = ctypes.pointer(g_dst.c)
+        if g_src is not None:
+            c.g_src = ctypes.pointer(g_src.c)
+        c.n_types, c.k_in, c.f_out, c.rounding, c.seed, c.layer_id = n_types, k_in, f_out, rounding, seed, layer_id
+        f32, i8 = torch.float32, torch.int8
+        self._bind("H", H, f32)
+        self._bind("W", W, f32)
+        self._bind("w_q", w_q, i8)
+        self._bind("s_w", s_w, f32)
+        for name in ("s_H", "s_W", "absmax_Hp", "s_Hp", "absmax_out", "s_g", "absmax_dHp", "s_dHp"):
+            self._alloc(name, (1,), f32)
+        self._alloc("H_q", (n, k_in), i8)
+        self._alloc("W_q", (k_in, f_cat), i8)
+        self._alloc("Hp", (n, f_cat), f32)
+        self._alloc("Hp_q", (n, f_cat), i8)
+        self._alloc("out", (n, f_out), f32)
+        if grad_out is not None:
+            self._bind("grad_out", grad_out, f32)
+            self._alloc("g_q", (n, f_out), i8)
+            self._alloc("dHp", (n, f_cat), f32)
+            self._alloc("dHp_q", (n, f_cat), i8)
+            self._alloc("dW", (k_in, f_cat), f32)
+            if want_dH:
+                self._alloc("dH", (n, k_in), f32)
+        nbytes = load_library().tango_typed_layer_workspace_bytes(n, g_dst.n_edges, n_types, k_in, f_out)
+        self._alloc("ws", (nbytes,), torch.uint8)
+        c.ws_bytes = nbytes
+
+
+def tango_typed_layer_workspace_bytes(n_nodes, n_edges, n_types, k_in, f_out) -> int:
+    return load_library().tango_typed_layer_workspace_bytes(n_nodes, n_edges, n_types, k_in, f_out)
+
+
+def tango_typed_layer_fwd(layer: TypedLayer):
+    _check(load_library().tango_typed_layer_fwd(layer.ref(), _stream()), "tango_typed_layer_fwd")
+
+
+def tango_typed_layer_bwd(layer: TypedLayer):
+    _check(load_library().tango_typed_layer_bwd(layer.ref(), _stream()), "tango_typed_layer_bwd")
 
 
 def tango_gat_layer_fwd(layer: GatLayer):

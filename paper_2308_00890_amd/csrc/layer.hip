@@ -183,4 +183,62 @@ int tango_gcn_layer_bwd(const tango_gcn_layer *L, void *stream)
     return TANGO_OK;
 }
 
+size_t tango_typed_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int n_types, int k_in, int f_out)
+{
+    return tango_gcn_layer_workspace_bytes(n_nodes, n_edges, k_in, n_types * f_out);
+}
+
+int tango_typed_layer_fwd(const tango_typed_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g_dst, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->k_in >= 1 && L->f_out >= 4 && L->n_types >= 1, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->H && L->W && L->w_q && L->s_w && L->H_q && L->s_H && L->W_q && L->s_W && L->Hp && L->absmax_Hp &&
+                      L->Hp_q && L->s_Hp && L->out,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g_dst->n_nodes, nnz = L->g_dst->n_edges;
+    const int64_t FT = static_cast<int64_t>(L->n_types) * L->f_out;
+    TANGO_REQUIRE(n * L->n_types < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_typed_layer_workspace_bytes(n, nnz, L->n_types, L->k_in, L->f_out),
+                  TANGO_ERR_WORKSPACE);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+    // all type blocks in one GEMM: Z = H.[W_0 | ... | W_{T-1}]
+    TANGO_TRY(tango_qgemm(n, FT, L->k_in, L->H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W, L->H_q, L->s_H,
+                          L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
+    TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n * FT), L->rounding, L->seed, sid + SID_HP, L->absmax_Hp, L->Hp_q,
+                             L->s_Hp, nullptr, 0, stream));
+    // Z_q seen as (n*T) x f_out: in_src of the destination view already names the (source, type) row
+    TANGO_TRY(tango_qspmm(L->g_dst, TANGO_IN, 1, L->f_out, L->w_q, L->s_w, L->Hp_q, L->s_Hp, L->out, L->absmax_out,
+                          stream));
+    return TANGO_OK;
+}
+
+int tango_typed_layer_bwd(const tango_typed_layer *L, void *stream)
+{
+    TANGO_REQUIRE(L && L->g_dst && L->g_src, TANGO_ERR_NULL);
+    TANGO_REQUIRE(L->k_in >= 1 && L->f_out >= 4 && L->n_types >= 1, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->grad_out && L->g_q && L->s_g && L->dHp && L->absmax_dHp && L->dHp_q && L->s_dHp && L->dW &&
+                      L->w_q && L->s_w && L->H_q && L->s_H && L->W_q && L->s_W,
+                  TANGO_ERR_NULL);
+    const int64_t n = L->g_dst->n_nodes, nnz = L->g_dst->n_edges;
+    const int64_t FT = static_cast<int64_t>(L->n_types) * L->f_out;
+    TANGO_REQUIRE(n * L->n_types < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->g_src->n_nodes == n * L->n_types && L->g_src->n_edges == nnz, TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
+                      L->ws_bytes >= tango_typed_layer_workspace_bytes(n, nnz, L->n_types, L->k_in, L->f_out),
+                  TANGO_ERR_WORKSPACE);
+    void *sub = static_cast<char *>(L->ws) + 256;
+    const size_t sub_bytes = L->ws_bytes - 256;
+    const uint64_t sid = 16 * L->layer_id;
+    TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n) * L->f_out, L->rounding, L->seed, sid + SID_G, nullptr,
+                             L->g_q, L->s_g, sub, sub_bytes, stream));
+    // dZ: one output row per (source, type) pair, i.e. n rows of n_types*f_out
+    TANGO_TRY(tango_qspmm(L->g_src, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
+    TANGO_TRY(tango_qgemm_bwd(n, FT, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
+                              L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
+    return TANGO_OK;
+}
+
 }  // extern "C"

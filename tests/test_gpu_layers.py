@@ -249,3 +249,65 @@ def test_gcn_layer_stagewise(T, rounding):
     for name, ref in (("s_H", f["s_H"]), ("s_W", f["s_W"]), ("s_Hp", f["s_Hp"]), ("absmax_out", f["absmax_out"]),
                       ("s_g", bw["s_g"]), ("absmax_dHp", bw["absmax_dHp"]), ("s_dHp", bw["s_dHp"])):
         assert o[name][0] == ref, name
+
+
+@pytest.mark.parametrize("model,rounding", [("sage", orc.SR), ("rgcn", orc.SR), ("rgcn", orc.RN), ("one_type", orc.SR)])
+def test_typed_layer_stagewise(T, model, rounding):
+    """GraphSAGE (mean) and relational GCN through the typed-edge GEMM + SPMM layer: every stage is integer-exact
+    given bit-identical inputs, so the whole chain is bit-exact."""
+    import torch
+
+    from gpu_util import scalar
+
+    g = ti.rmat_graph(4000, 36000, seed=31)
+    K, F = 100, 64
+    if model == "sage":
+        tg, w = ti.sage_typed_graph(g)
+    elif model == "rgcn":
+        tg, w = ti.rgcn_typed_graph(g, 3, 32)
+    else:
+        tg = ti.typed_graph_from_edges(g.n_nodes, 1, g.in_src, g.in_dst(), np.zeros(g.n_edges, np.int64))
+        w = ti.gcn_edge_weights(g)
+    nt = tg.n_types
+    H = ti.normal((g.n_nodes, K), 33)
+    W = ti.xavier_uniform(K, F, (K, nt * F), 34)
+    up = ti.normal((g.n_nodes, F), 35)
+    seed, layer_id = 77, 2
+    w_q, s_w = orc.quantize(w, rounding, seed, orc.SID_EW)
+    G_dst, G_src = T.Graph.from_host(tg.dst_view()), T.Graph.from_host(tg.src_view())
+    L = T.TypedLayer(G_dst, G_src, nt, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id)
+    T.tango_typed_layer_fwd(L)
+    T.tango_typed_layer_bwd(L)
+    torch.cuda.synchronize()
+    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    f = orc.typed_layer_fwd(tg, H, W, w_q, s_w, rounding, seed, layer_id)
+    bw = orc.typed_layer_bwd(tg, f, w_q, s_w, up, rounding, seed, layer_id)
+    for name in ("H_q", "W_q", "Hp", "Hp_q", "out"):
+        assert_bit_exact(o[name], f[name], name)
+    for name in ("g_q", "dHp", "dHp_q", "dW", "dH"):
+        assert_bit_exact(o[name], bw[name], name)
+    for name, ref in (("s_H", f["s_H"]), ("s_W", f["s_W"]), ("s_Hp", f["s_Hp"]), ("absmax_out", f["absmax_out"]),
+                      ("s_g", bw["s_g"]), ("absmax_dHp", bw["absmax_dHp"]), ("s_dHp", bw["s_dHp"])):
+        assert o[name][0] == ref, name
+
+
+def test_typed_layer_rejects_mismatched_views(T):
+    import torch
+
+    from gpu_util import scalar
+
+    g = ti.rmat_graph(300, 2000, seed=36)
+    tg, w = ti.sage_typed_graph(g)
+    K, F = 16, 8
+    H, W, up = ti.normal((g.n_nodes, K), 37), ti.normal((K, 2 * F), 38), ti.normal((g.n_nodes, F), 39)
+    w_q, s_w = orc.quantize(w, orc.RN, 0, orc.SID_EW)
+    G_dst = T.Graph.from_host(tg.dst_view())
+    G_bad = T.Graph.from_host(g)  # n rows instead of n * n_types
+    L = T.TypedLayer(G_dst, G_bad, 2, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), orc.RN, 0, 0)
+    T.tango_typed_layer_fwd(L)
+    with pytest.raises(T.TangoError):
+        T.tango_typed_layer_bwd(L)
+    L2 = T.TypedLayer(G_dst, None, 2, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), orc.RN, 0, 0)
+    with pytest.raises(T.TangoError):
+        T.tango_typed_layer_bwd(L2)
+    torch.cuda.synchronize()
