@@ -379,8 +379,8 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
  * The two halves of tango_gat_attention_bwd's no-edge-tensor path as calls of their own (the whole call is their
  * composition):
  *   _dst: one walk over the in-edges of every destination v (steps 5'', 4', 3''): dD (n x heads fp32) and, in `rec`
- *         (device, tango_gat_attention_bwd_rec_bytes() bytes, 16-byte aligned; an opaque table of 16 bytes per
- *         (node, head): P as fp64 and row_lse), what the other half needs;
+ *         (device, tango_gat_attention_bwd_rec_bytes() bytes, 16-byte aligned; an opaque table with one record
+ *         per node: row_lse and, as fp64, P of every head), what the other half needs;
  *   _src: one walk over the out-edges of every source u (steps 5' and 3'): dX_agg (n x F fp32, absmax_dX may be
  *         NULL) and dS (n x heads fp32), with the int8 attention codes recomputed as in tango_gat_attention_bwd.
  * ws: device scratch of the matching _workspace_bytes(), 256-byte aligned.  Other arguments as in

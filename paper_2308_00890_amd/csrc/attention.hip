@@ -23,11 +23,11 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
-                                      const float *s_X, const tango_attn_rec *rec, double *dS_acc, float *out,
+                                      const float *s_X, const void *rec, double *dS_acc, float *out,
                                       float *absmax_out, float *dS, hipStream_t st);
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                                   const float *sD, float slope, const float *row_lse, double *stats, tango_attn_rec *rec,
+                                   const float *sD, float slope, const float *row_lse, double *stats, void *rec,
                                    float *dD, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
@@ -37,7 +37,7 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
                           const int8_t *X_src, const float *s_src, float *out, hipStream_t st);
 int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                              const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const tango_attn_rec *rec, double *dS_acc, float *dS,
+                             const float *sD, float slope, const void *rec, double *dS_acc, float *dS,
                              hipStream_t st);
 
 namespace {
@@ -153,7 +153,7 @@ struct attn_bwd_dst_op {
     const int8_t *Sq, *Dq;
     float sS, sD, slope;
     const float *row_lse, *dalpha;
-    tango_attn_rec *rec;
+    void *rec;
     float *dD;
     template <class Team>
     __device__ void run(int row, int b, int t, Team tm)
@@ -202,11 +202,8 @@ struct attn_bwd_dst_op {
         for (int h = 0; h < H; ++h) {
             const double sacc = tm.sum(acc[h]);
             if (tm.rank == 0) {
-                tango_attn_rec rc;
-                rc.P = p[h];
-                rc.row_lse = lse[h];
-                rc.unused = 0.0f;
-                rec[static_cast<int64_t>(row) * H + h] = rc;
+                tango_rec_P(rec, row, H)[h] = p[h];
+                tango_rec_lse(rec, row, H)[h] = lse[h];
                 dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(sacc);
             }
         }
@@ -237,7 +234,7 @@ __global__ __launch_bounds__(TEAM_BLOCK_THREADS) void k_attn_bwd_dst_huge(const 
 
 int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
                              const float *sD, float slope, const float *row_lse,
-                             const float *dalpha, tango_attn_rec *rec, float *dD, int *huge, hipStream_t st)
+                             const float *dalpha, void *rec, float *dD, int *huge, hipStream_t st)
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
@@ -315,14 +312,15 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
 
 size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges, int heads)
 {
-    // per (node, head): a 16-byte record (P, row_lse), a double dS accumulator and three running sums; then the list
-    // of hub rows
-    return 256 + 6 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
+    // the per-destination records (P, row_lse); per (node, head) a double dS accumulator and three running sums; then
+    // the list of hub rows
+    return 256 + tango_gat_attention_bwd_rec_bytes(n_nodes, heads) +
+           4 * tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(double), 256) + huge_list_bytes(n_edges);
 }
 
 size_t tango_gat_attention_bwd_rec_bytes(int64_t n_nodes, int heads)
 {
-    return tango_round_up(static_cast<size_t>(n_nodes) * heads * sizeof(tango_attn_rec), 256);
+    return tango_round_up(static_cast<size_t>(n_nodes) * tango_rec_stride(heads), 256);
 }
 
 size_t tango_gat_attention_bwd_dst_workspace_bytes(int64_t n_nodes, int heads)
@@ -356,7 +354,7 @@ int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const 
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
                   TANGO_ERR_WORKSPACE);
     return tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse,
-                                          static_cast<double *>(ws), static_cast<tango_attn_rec *>(rec), dD,
+                                          static_cast<double *>(ws), rec, dD,
                                           tango_stream(stream));
 }
 
@@ -379,7 +377,7 @@ int tango_gat_attention_bwd_src(const tango_graph *g, int heads, int dim, const 
                   TANGO_ERR_WORKSPACE);
     return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                              stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X,
-                                             static_cast<const tango_attn_rec *>(rec), static_cast<double *>(ws), dX_agg,
+                                             rec, static_cast<double *>(ws), dX_agg,
                                              absmax_dX, dS, tango_stream(stream));
 }
 
@@ -412,10 +410,11 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                   TANGO_ERR_WORKSPACE);
     hipStream_t st = tango_stream(stream);
     const size_t nh_bytes = tango_round_up(static_cast<size_t>(g->n_nodes) * heads * sizeof(double), 256);
-    tango_attn_rec *rec = reinterpret_cast<tango_attn_rec *>(static_cast<char *>(ws) + 256);
-    double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 2 * nh_bytes);
-    double *stats = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + 3 * nh_bytes);
-    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + 6 * nh_bytes);
+    const size_t rec_bytes = tango_gat_attention_bwd_rec_bytes(g->n_nodes, heads);
+    void *rec = static_cast<char *>(ws) + 256;
+    double *dS_acc = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + rec_bytes);
+    double *stats = reinterpret_cast<double *>(static_cast<char *>(ws) + 256 + rec_bytes + nh_bytes);
+    int *huge = reinterpret_cast<int *>(static_cast<char *>(ws) + 256 + rec_bytes + 4 * nh_bytes);
     if (edge_part && !alpha_q && !dalpha) {
         // no edge tensor at all: 5'', 4', 3'' in one walk over the in-edges, then 5' and 3' in one walk over the out-edges
         rc = tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse, stats,

@@ -60,10 +60,41 @@ __device__ static inline void tango_load_heads_rt(const int8_t *__restrict__ tab
     }
 }
 
-// Per (destination, head) record gathered by the source-side backward pass: one 16-byte load instead of three
-// scattered ones, and the records of all heads of a node share a cache line.
-struct __attribute__((aligned(16))) tango_attn_rec {
-    double P;        // sum over the in-edges of dalpha*alpha
-    float row_lse;
-    float unused;
-};
+// Heads h0 .. h0+3 of a node (run-time head count; entries at or beyond `heads` are left zero).
+__device__ static inline void tango_load_heads4(const int8_t *__restrict__ table, int64_t node, int heads, int h0, int (&v)[4])
+{
+    const int8_t *p = table + node * heads + h0;
+    if ((heads & 3) == 0) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = static_cast<int>(static_cast<int8_t>(w >> (8 * j)));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (h0 + j < heads) ? static_cast<int>(p[j]) : 0;
+    }
+}
+
+// Per-destination record gathered by the source-side backward pass, one per node: row_lse of every head (fp32), then
+// P = sum over the in-edges of dalpha*alpha of every head (fp64), both padded to 4 or 8 heads.  A lane that needs all
+// heads of a destination fetches row_lse with one 16-byte load (two above 4 heads) and P with two (four): the load
+// unit handles a scattered access per lane and instruction, so fewer, wider loads per edge are what counts.
+__host__ __device__ static inline int tango_rec_heads(int heads) { return heads <= 4 ? 4 : 8; }
+__host__ __device__ static inline size_t tango_rec_stride(int heads) { return static_cast<size_t>(tango_rec_heads(heads)) * 12; }
+__device__ static inline float *tango_rec_lse(void *rec, int64_t node, int heads)
+{
+    return reinterpret_cast<float *>(static_cast<char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)));
+}
+__device__ static inline const float *tango_rec_lse(const void *rec, int64_t node, int heads)
+{
+    return reinterpret_cast<const float *>(static_cast<const char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)));
+}
+__device__ static inline double *tango_rec_P(void *rec, int64_t node, int heads)
+{
+    return reinterpret_cast<double *>(static_cast<char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)) +
+                                      4 * tango_rec_heads(heads));
+}
+__device__ static inline const double *tango_rec_P(const void *rec, int64_t node, int heads)
+{
+    return reinterpret_cast<const double *>(static_cast<const char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)) +
+                                            4 * tango_rec_heads(heads));
+}

@@ -106,7 +106,7 @@ struct attn_params {
     // reverse pass fused with step 3' (DS instantiations): the gathered rows also give dalpha of every out-edge
     const int8_t *Xrow;            // n x F: the table of the row side (H'_q of the source)
     const float *s_Xrow;
-    const tango_attn_rec *rec;     // n x heads: (P, row_lse) of the destination
+    const void *rec;     // per destination: row_lse and P of every head
     double *dS_acc;                // n x heads, zero-initialised
 };
 
@@ -222,6 +222,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     // DS: per wave, the dot products and the fp32 alpha of the current block of 64 edges, [edge][head], heads <= 8
     __shared__ int dots_s[DS ? WAVES_PER_BLOCK : 1][DS ? 64 * 8 : 1];
     __shared__ float alf_s[DS ? WAVES_PER_BLOCK : 1][DS ? 64 * 8 : 1];
+    // per wave, for the 64 edges of the current block: byte offset of the neighbour's row in the table (64 bit) and
+    // the packed weight codes of heads 0-3 and 4-7
+    __shared__ __align__(16) uint4 nbw_s[WAVES_PER_BLOCK][64];
     using V = typename vec_bytes<VEC>::type;
     __shared__ __align__(16) int stage[WAVES_PER_BLOCK][1024];  // one strip of F <= 1024 sums per wave
     const int lane = threadIdx.x % TANGO_WAVE;
@@ -254,6 +257,14 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     const float sc = s_w * (*a.s_X);
     const int8_t *Xcol = a.X + li * VEC;
     const int LPH = LPHC ? LPHC : a.dim / VEC;  // DS: lanes per head (a power of two)
+    const int log2G = 31 - __clz(G);
+    // which weight word of an entry of nbw_s holds my head, and the v_perm selectors that put byte (h & 3) of two
+    // weight words side by side (0x0c selects a zero byte)
+    const bool upper_heads = h >= 4;
+    const uint32_t hb = static_cast<uint32_t>(h & 3);
+    const uint32_t sel01 = hb | ((4u + hb) << 8) | 0x0c0c0000u;
+    const uint32_t sel23 = 0x00000c0cu | (hb << 16) | ((4u + hb) << 24);
+    const bool leader = DS && (li % LPH) == 0;
     float sc_dot = 0.0f;
     if (DS) sc_dot = (*a.s_X) * (*a.att.s_Xrow);
 
@@ -370,40 +381,48 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(a.eid[e])) * H;
                 uint4 blk = make_uint4(0, 0, 0, 0);
                 uint64_t have = ~uint64_t(0);
-                int sq[8], dq[8];
-                tango_load_heads_rt(a.att.Sq, src_node, H, sq);
-                tango_load_heads_rt(a.att.Dq, dst_node, H, dq);
+                // four heads at a time (one pass up to 4 heads, two up to 8)
+                for (int h0 = 0; h0 < H; h0 += 4) {
+                    int sq[4], dq[4];
+                    tango_load_heads4(a.att.Sq, src_node, H, h0, sq);
+                    tango_load_heads4(a.att.Dq, dst_node, H, h0, dq);
+                    float4 lse4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    // DS: row_lse of four heads of the destination in one 16-byte load
+                    if (DS) lse4 = *reinterpret_cast<const float4 *>(tango_rec_lse(a.att.rec, dst_node, H) + h0);
+                    uint32_t wpk = 0;
 #pragma unroll
-                for (int hh = 0; hh < 8; ++hh) {  // constant trip count: sq/dq stay in registers
-                    if (hh >= H) break;
-                    bool pos;
-                    const float ev = tango_attn_score(att_sS * static_cast<float>(sq[hh]), att_sD * static_cast<float>(dq[hh]),
-                                                      a.att.slope, pos);
-                    // DS: row_lse comes from the record that the epilogue reads again for P (one table, one cache line)
-                    const float lse = DS ? a.att.rec[dst_node * H + hh].row_lse : a.att.row_lse[dst_node * H + hh];
-                    const float al = tango_attn_alpha(ev, lse);
-                    if (DS) {
-                        alf_s[wv][lane * H + hh] = al;
-                        pos_mask |= (pos ? 1u : 0u) << hh;
-                    }
-                    if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
-                    int q;
-                    if (a.att.rounding == TANGO_SR) {
-                        const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
-                        if (bi != have) {
-                            blk = tango_philox_block(a.att.rng, bi);
-                            have = bi;
+                    for (int j = 0; j < 4; ++j) {
+                        const int hh = h0 + j;
+                        if (hh >= H) break;
+                        bool pos;
+                        const float ev = tango_attn_score(att_sS * static_cast<float>(sq[j]), att_sD * static_cast<float>(dq[j]),
+                                                          a.att.slope, pos);
+                        const float lse = DS ? (j == 0 ? lse4.x : j == 1 ? lse4.y : j == 2 ? lse4.z : lse4.w)
+                                             : a.att.row_lse[dst_node * H + hh];
+                        const float al = tango_attn_alpha(ev, lse);
+                        if (DS) {
+                            alf_s[wv][lane * H + hh] = al;
+                            pos_mask |= (pos ? 1u : 0u) << hh;
                         }
-                        q = tango_round_clamp<TANGO_SR>(al * inv_w, tango_bits16(blk, static_cast<int>((i0 + hh) & 7)));
-                    } else {
-                        q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
+                        if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
+                        int q;
+                        if (a.att.rounding == TANGO_SR) {
+                            const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
+                            if (bi != have) {
+                                blk = tango_philox_block(a.att.rng, bi);
+                                have = bi;
+                            }
+                            q = tango_round_clamp<TANGO_SR>(al * inv_w, tango_bits16(blk, static_cast<int>((i0 + hh) & 7)));
+                        } else {
+                            q = tango_round_clamp<TANGO_RN>(al * inv_w, 0u);
+                        }
+                        if (WMODE == W_ATT_FWD && a.att.alpha_q) a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
+                        wpk |= (static_cast<uint32_t>(q) & 0xffu) << (8 * j);
                     }
-                    if (WMODE == W_ATT_FWD && a.att.alpha_q) a.att.alpha_q[i0 + hh] = static_cast<int8_t>(q);
-                    const uint32_t b = static_cast<uint32_t>(q) & 0xffu;
-                    if (hh < 4)
-                        my_w0 |= b << (8 * hh);
+                    if (h0 == 0)
+                        my_w0 = wpk;
                     else
-                        my_w1 |= b << (8 * (hh - 4));
+                        my_w1 = wpk;
                 }
             } else {
                 const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
@@ -415,6 +434,12 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         my_w1 |= b << (8 * (hh - 4));
                 }
             }
+        }
+        {
+            const uint64_t off = static_cast<uint64_t>(static_cast<uint32_t>(my_nb)) * static_cast<uint32_t>(row_bytes);
+            nbw_s[wv][lane] = make_uint4(static_cast<uint32_t>(off), static_cast<uint32_t>(off >> 32), my_w0, my_w1);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
         // pass 2: the row segments [k0, k1) of the block
         for (int k0 = 0; k0 < cnt;) {
@@ -429,29 +454,31 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             }
             if (rt - open_rb > a.short_max) {
                 const int steps = (len + G - 1) / G;
-                auto batch = [&](int s0, auto uu) {
+                const int full = len >> log2G;  // steps in which every group has an edge
+                // MASKED = false: every group's edge exists, so nothing in the batch depends on the edge count (no
+                // selects, no branches: the eight gathers, dot products and lane sums interleave freely).
+                auto batch = [&](int s0, auto uu, auto masked) {
                     constexpr int UU = decltype(uu)::value;
-                    uint32_t wq[UU];
+                    constexpr bool MASKED = decltype(masked)::value;
+                    uint32_t ww[UU];
                     V xv[UU];
+                    bool ok[UU];
 #pragma unroll
                     for (int u = 0; u < UU; ++u) {
                         const int k = (s0 + u) * G + gi;
-                        const bool ok = active && k < len;
-                        const int kk = ok ? k0 + k : 0;
-                        const int nb = __shfl(my_nb, kk, 64);
-                        uint32_t ww = __shfl(static_cast<int>(my_w0), kk, 64);
-                        if (a.heads > 4) {
-                            const uint32_t w1 = __shfl(static_cast<int>(my_w1), kk, 64);
-                            if (h >= 4) ww = w1;
-                        }
-                        wq[u] = ok ? ((ww >> (8 * (h & 3))) & 0xffu) : 0u;
-                        xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * row_bytes);
+                        ok[u] = !MASKED || k < len;
+                        const int kk = ok[u] ? k0 + k : 0;
+                        const uint4 ent = nbw_s[wv][kk];
+                        ww[u] = upper_heads ? ent.w : ent.z;
+                        if (MASKED && !ok[u]) ww[u] = 0u;
+                        xv[u] = *reinterpret_cast<const V *>(Xcol + ((static_cast<uint64_t>(ent.y) << 32) | ent.x));
                     }
                     // 4 edges at a time: transpose each 4x4 byte block so that one dot4 multiplies one column of
                     // four neighbour rows by the four edge weights
 #pragma unroll
                     for (int u = 0; u < UU; u += 4) {
-                        const uint32_t wpack = wq[u] | (wq[u + 1] << 8) | (wq[u + 2] << 16) | (wq[u + 3] << 24);
+                        // byte (h & 3) of the four weight words, side by side
+                        const uint32_t wpack = __builtin_amdgcn_perm(ww[u + 1], ww[u], sel01) | __builtin_amdgcn_perm(ww[u + 3], ww[u + 2], sel23);
                         uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
                         unpack_words<VEC>(xv[u], w0);
                         unpack_words<VEC>(xv[u + 1], w1);
@@ -472,7 +499,12 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                             for (int v = 0; v < 4; ++v) {
                                 const int d = tango_group_sum_c<LPHC>(d4[v], LPH);
                                 const int k = (s0 + u + v) * G + gi;
-                                if (active && k < len && (li % LPH) == 0) dots_s[wv][(k0 + k) * a.heads + h] = d;
+                                if (MASKED) {
+                                    if (ok[u + v] && leader) dots_s[wv][(k0 + k) * a.heads + h] = d;
+                                } else {
+                                    // every lane of the head holds the sum and stores it (same value, same word)
+                                    dots_s[wv][(k0 + k) * a.heads + h] = d;
+                                }
                             }
                         }
 #pragma unroll
@@ -501,9 +533,14 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         }
                     }
                 };
-                int s0 = 0;
-                for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
-                for (; s0 < steps; s0 += 4) batch(s0, std::integral_constant<int, 4>{});
+                if (active) {  // lanes beyond the last whole group sit the gathers out
+                    constexpr std::false_type all_there{};
+                    constexpr std::true_type masked{};
+                    int s0 = 0;
+                    for (; s0 + U <= full; s0 += U) batch(s0, std::integral_constant<int, U>{}, all_there);
+                    for (; s0 + 4 <= full; s0 += 4) batch(s0, std::integral_constant<int, 4>{}, all_there);
+                    for (; s0 < steps; s0 += 4) batch(s0, std::integral_constant<int, 4>{}, masked);
+                }
                 pending = true;
             }
             if (base + k1 == rt) {  // the row ends here
@@ -518,13 +555,24 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int H = a.heads;
-            for (int hh = 0; hh < H; ++hh) {
+            for (int h0 = 0; h0 < H; h0 += 4) {
+            // P of four heads of my edge's destination: two 16-byte loads
+            double2 p01 = make_double2(0.0, 0.0), p23 = make_double2(0.0, 0.0);
+            if (lane < cnt) {
+                const double2 *pp = reinterpret_cast<const double2 *>(tango_rec_P(a.att.rec, my_nb, H) + h0);
+                p01 = pp[0];
+                p23 = pp[1];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int hh = h0 + j;
+                if (hh >= H) break;
                 double contrib = 0.0;
                 if (lane < cnt) {
                     const float da = static_cast<float>(dots_s[wv][lane * H + hh]) * sc_dot;
-                    const tango_attn_rec rc = a.att.rec[static_cast<int64_t>(my_nb) * H + hh];
                     const float al = alf_s[wv][lane * H + hh];
-                    const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
+                    const double Pj = j == 0 ? p01.x : j == 1 ? p01.y : j == 2 ? p23.x : p23.y;
+                    const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - Pj));
                     contrib = static_cast<double>(dE * (((pos_mask >> hh) & 1u) ? 1.0f : a.att.slope));
                 }
                 for (int k0 = 0; k0 < cnt;) {
@@ -536,6 +584,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                     if (lane == 0 && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(r) * H + hh, v);
                     k0 = k1;
                 }
+            }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -649,7 +698,7 @@ struct sddmm_dot_args {
     const int8_t *Sq, *Dq;
     const float *sS, *sD;
     float slope;
-    const tango_attn_rec *rec;       // n x heads: (P, row_lse) of the destination
+    const void *rec;       // per destination: row_lse and P of every head
     double *dS_acc;                  // n x heads, zero-initialised
     // DOT_DST instantiations only (rows = destination nodes): three running sums per (destination, head)
     const float *row_lse;            // n x heads
@@ -773,9 +822,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                         const int64_t vh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
                         bool pos;
                         const float ev = tango_attn_score(ts_row, sD * static_cast<float>(a.Dq[vh]), a.slope, pos);
-                        const tango_attn_rec rc = a.rec[vh];
-                        const float al = tango_attn_alpha(ev, rc.row_lse);
-                        const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
+                        const float al = tango_attn_alpha(ev, tango_rec_lse(a.rec, nbl[wv][k], H)[eh]);
+                        const float dE = static_cast<float>(static_cast<double>(al) *
+                                                            (static_cast<double>(da) - tango_rec_P(a.rec, nbl[wv][k], H)[eh]));
                         acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
                     } else if (ATT_DST) {
                         const int64_t uh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
@@ -1018,7 +1067,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
-                                      const float *s_X, const tango_attn_rec *rec, double *dS_acc, float *out,
+                                      const float *s_X, const void *rec, double *dS_acc, float *out,
                                       float *absmax_out, float *dS, hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
@@ -1071,17 +1120,16 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     return TANGO_OK;
 }
 
-__global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, const double *__restrict__ stats, const float *__restrict__ row_lse,
-                                                         tango_attn_rec *__restrict__ rec, float *__restrict__ dD)
+__global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, const double *__restrict__ stats, const float *__restrict__ row_lse,
+                                                         void *__restrict__ rec, float *__restrict__ dD)
 {
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nh;
          i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
         const double A = stats[3 * i], B = stats[3 * i + 1], C = stats[3 * i + 2];
-        tango_attn_rec rc;
-        rc.P = A;
-        rc.row_lse = row_lse[i];
-        rc.unused = 0.0f;
-        rec[i] = rc;
+        const int64_t node = i / heads;
+        const int h = static_cast<int>(i - node * heads);
+        tango_rec_P(rec, node, heads)[h] = A;
+        tango_rec_lse(rec, node, heads)[h] = row_lse[i];
         dD[i] = static_cast<float>(B - A * C);
     }
 }
@@ -1090,7 +1138,7 @@ __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, const doubl
 // doubles of scratch.
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                                   const float *sD, float slope, const float *row_lse, double *stats, tango_attn_rec *rec,
+                                   const float *sD, float slope, const float *row_lse, double *stats, void *rec,
                                    float *dD, hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
@@ -1126,7 +1174,7 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
         }
         TANGO_LAUNCH_CHECK();
     }
-    k_attn_dst_finish<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(nh, stats, row_lse, rec, dD);
+    k_attn_dst_finish<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(nh, heads, stats, row_lse, rec, dD);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
@@ -1135,7 +1183,7 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
 // quantized dot product of dOut_q[v] and X_q[u]; dS_acc: n x heads doubles of scratch.
 int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                              const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
-                             const float *sD, float slope, const tango_attn_rec *rec, double *dS_acc, float *dS,
+                             const float *sD, float slope, const void *rec, double *dS_acc, float *dS,
                              hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
