@@ -350,8 +350,21 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         pending = false;
     };
 
+    // neighbour index (and edge id) of my edge of the next block, fetched one block ahead: a block then starts with its
+    // dependent loads instead of waiting for the index first
+    constexpr bool USE_EID = HAS_EID && WMODE != W_ATT_FWD;
+    int nb_ahead = 0, eid_ahead = 0;
+    if (c0i + lane < c1i) {
+        nb_ahead = a.idx[c0i + lane];
+        if (USE_EID) eid_ahead = a.eid[c0i + lane];
+    }
     for (int base = c0i; base < c1i; base += 64) {
         const int cnt = min(64, c1i - base);
+        const int nb_now = nb_ahead, eid_now = eid_ahead;
+        if (base + 64 + lane < c1i) {
+            nb_ahead = a.idx[base + 64 + lane];
+            if (USE_EID) eid_ahead = a.eid[base + 64 + lane];
+        }
         // pass 1 over the rows of this block: every lane learns the row of its edge and where that row ends
         // (seg_r, seg_rt: the walker's state at the start of the block, replayed by pass 2)
         const int seg_r = cur_r, seg_rt = cur_rt;
@@ -368,9 +381,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         int my_nb = 0;
         uint32_t my_w0 = 0, my_w1 = 0;
         uint32_t pos_mask = 0;  // DS: bit h = the pre-activation score of my edge, head h, is positive
+        double2 pre01 = make_double2(0.0, 0.0), pre23 = make_double2(0.0, 0.0);  // DS: P of heads 0-3 of my edge's destination
         if (lane < cnt) {
             const int e = base + lane;
-            my_nb = a.idx[e];
+            my_nb = nb_now;
             if (ATT) {
                 // steps 3-4 and the quantization of alpha for this edge, all heads.  Forward: the row is the
                 // destination, the neighbour the source; reverse: the other way round, and the edge's
@@ -378,7 +392,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 const int H = a.heads;
                 const int64_t src_node = (WMODE == W_ATT_FWD) ? my_nb : my_row;
                 const int64_t dst_node = (WMODE == W_ATT_FWD) ? my_row : my_nb;
-                const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(a.eid[e])) * H;
+                const int64_t i0 = (WMODE == W_ATT_FWD ? static_cast<int64_t>(e) : static_cast<int64_t>(eid_now)) * H;
                 uint4 blk = make_uint4(0, 0, 0, 0);
                 uint64_t have = ~uint64_t(0);
                 // four heads at a time (one pass up to 4 heads, two up to 8)
@@ -389,6 +403,12 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                     float4 lse4 = make_float4(0.f, 0.f, 0.f, 0.f);
                     // DS: row_lse of four heads of the destination in one 16-byte load
                     if (DS) lse4 = *reinterpret_cast<const float4 *>(tango_rec_lse(a.att.rec, dst_node, H) + h0);
+                    if (DS && h0 == 0) {
+                        // P of heads 0-3 (same record, needed after the gathers): fetched now, its latency hidden behind them
+                        const double2 *pp = reinterpret_cast<const double2 *>(tango_rec_P(a.att.rec, dst_node, H));
+                        pre01 = pp[0];
+                        pre23 = pp[1];
+                    }
                     uint32_t wpk = 0;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -425,7 +445,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         my_w1 = wpk;
                 }
             } else {
-                const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[e]) : static_cast<int64_t>(e)) * a.heads;
+                const int64_t wp = (HAS_EID ? static_cast<int64_t>(eid_now) : static_cast<int64_t>(e)) * a.heads;
                 for (int hh = 0; hh < a.heads; ++hh) {
                     const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
                     if (hh < 4)
@@ -556,9 +576,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             __builtin_amdgcn_wave_barrier();
             const int H = a.heads;
             for (int h0 = 0; h0 < H; h0 += 4) {
-            // P of four heads of my edge's destination: two 16-byte loads
-            double2 p01 = make_double2(0.0, 0.0), p23 = make_double2(0.0, 0.0);
-            if (lane < cnt) {
+            // P of four heads of my edge's destination (heads 0-3: fetched with row_lse; beyond: two 16-byte loads)
+            double2 p01 = pre01, p23 = pre23;
+            if (h0 > 0 && lane < cnt) {
                 const double2 *pp = reinterpret_cast<const double2 *>(tango_rec_P(a.att.rec, my_nb, H) + h0);
                 p01 = pp[0];
                 p23 = pp[1];
