@@ -202,8 +202,11 @@ struct attn_bwd_dst_op {
         for (int h = 0; h < H; ++h) {
             const double sacc = tm.sum(acc[h]);
             if (tm.rank == 0) {
-                tango_rec_P(rec, row, H)[h] = p[h];
-                tango_rec_lse(rec, row, H)[h] = lse[h];
+                tango_attn_rec rc;
+                rc.P = p[h];
+                rc.row_lse = lse[h];
+                rc.dq = dq[h];
+                static_cast<tango_attn_rec *>(rec)[static_cast<int64_t>(row) * tango_rec_heads(H) + h] = rc;
                 dD[static_cast<int64_t>(row) * H + h] = static_cast<float>(sacc);
             }
         }
@@ -320,7 +323,7 @@ size_t tango_gat_attention_bwd_workspace_bytes(int64_t n_nodes, int64_t n_edges,
 
 size_t tango_gat_attention_bwd_rec_bytes(int64_t n_nodes, int heads)
 {
-    return tango_round_up(static_cast<size_t>(n_nodes) * tango_rec_stride(heads), 256);
+    return tango_round_up(static_cast<size_t>(n_nodes) * tango_rec_heads(heads) * sizeof(tango_attn_rec), 256);
 }
 
 size_t tango_gat_attention_bwd_dst_workspace_bytes(int64_t n_nodes, int heads)

@@ -74,27 +74,13 @@ __device__ static inline void tango_load_heads4(const int8_t *__restrict__ table
     }
 }
 
-// Per-destination record gathered by the source-side backward pass, one per node: row_lse of every head (fp32), then
-// P = sum over the in-edges of dalpha*alpha of every head (fp64), both padded to 4 or 8 heads.  A lane that needs all
-// heads of a destination fetches row_lse with one 16-byte load (two above 4 heads) and P with two (four): the load
-// unit handles a scattered access per lane and instruction, so fewer, wider loads per edge are what counts.
-__host__ __device__ static inline int tango_rec_heads(int heads) { return heads <= 4 ? 4 : 8; }
-__host__ __device__ static inline size_t tango_rec_stride(int heads) { return static_cast<size_t>(tango_rec_heads(heads)) * 12; }
-__device__ static inline float *tango_rec_lse(void *rec, int64_t node, int heads)
-{
-    return reinterpret_cast<float *>(static_cast<char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)));
-}
-__device__ static inline const float *tango_rec_lse(const void *rec, int64_t node, int heads)
-{
-    return reinterpret_cast<const float *>(static_cast<const char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)));
-}
-__device__ static inline double *tango_rec_P(void *rec, int64_t node, int heads)
-{
-    return reinterpret_cast<double *>(static_cast<char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)) +
-                                      4 * tango_rec_heads(heads));
-}
-__device__ static inline const double *tango_rec_P(const void *rec, int64_t node, int heads)
-{
-    return reinterpret_cast<const double *>(static_cast<const char *>(rec) + node * static_cast<int64_t>(tango_rec_stride(heads)) +
-                                            4 * tango_rec_heads(heads));
-}
+// Per (destination, head) record gathered by the source-side backward pass: everything that pass needs of the
+// destination in 16 bytes.  The table has tango_rec_heads(heads) records per node (heads rounded up to a power of two),
+// so the records of one node are one aligned run of 16, 32, 64 or 128 bytes: lanes that fetch one record each, with the
+// heads of an edge in adjacent lanes, touch one such run per edge.
+struct __attribute__((aligned(16))) tango_attn_rec {
+    double P;        // sum over the in-edges of dalpha*alpha
+    float row_lse;   // log-sum-exp of the destination's scores
+    int32_t dq;      // the destination's quantized projection D_q[v][h]
+};
+__host__ __device__ static inline int tango_rec_heads(int heads) { return heads <= 1 ? 1 : heads <= 2 ? 2 : heads <= 4 ? 4 : 8; }

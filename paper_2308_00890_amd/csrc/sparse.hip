@@ -258,6 +258,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     const int8_t *Xcol = a.X + li * VEC;
     const int LPH = LPHC ? LPHC : a.dim / VEC;  // DS: lanes per head (a power of two)
     const int log2G = 31 - __clz(G);
+    const int HP = DS ? tango_rec_heads(a.heads) : 1;  // DS: records per node in the table (heads rounded up to a power of two)
+    const int log2HP = 31 - __clz(HP);
     // which weight word of an entry of nbw_s holds my head, and the v_perm selectors that put byte (h & 3) of two
     // weight words side by side (0x0c selects a zero byte)
     const bool upper_heads = h >= 4;
@@ -380,8 +382,35 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         }
         int my_nb = 0;
         uint32_t my_w0 = 0, my_w1 = 0;
-        uint32_t pos_mask = 0;  // DS: bit h = the pre-activation score of my edge, head h, is positive
-        double2 pre01 = make_double2(0.0, 0.0), pre23 = make_double2(0.0, 0.0);  // DS: P of heads 0-3 of my edge's destination
+        double P_r[4] = {0.0, 0.0, 0.0, 0.0};  // DS: P of my (edge, head) pairs of rounds 0-3, kept for the block's epilogue
+        if (DS) {
+            // The records (P, row_lse, D_q) of the destinations of the block's edges, one 16-byte load per (edge, head)
+            // pair with the heads of an edge in adjacent lanes: pair p = lane + 64*round, edge = p / HP, head = p % HP.
+            // A lane keeps P for the epilogue (which works on the same pairs) and passes row_lse and D_q through LDS to
+            // the lane that owns the edge in the alpha phase below (dots_s and nbw_s are free until then).
+            const tango_attn_rec *recs = static_cast<const tango_attn_rec *>(a.att.rec);
+            // (the pair indices are a few shifts from the lane number: recomputed per block through an opaque copy of it,
+            // because as loop invariants they would each occupy a register for the whole kernel)
+            int lane_o = lane;
+            asm volatile("" : "+v"(lane_o));
+            for (int g0 = 0; g0 < HP; g0 += 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (g0 + j >= HP) break;
+                    const int pr = lane_o + 64 * (g0 + j);
+                    const int edge = pr >> log2HP, head = pr & (HP - 1);
+                    const int nbe = __shfl(nb_now, edge, 64);
+                    if (edge < cnt && head < a.heads) {
+                        const tango_attn_rec rc = recs[static_cast<int64_t>(nbe) * HP + head];
+                        if (g0 == 0) P_r[j] = rc.P;
+                        dots_s[wv][edge * a.heads + head] = __float_as_int(rc.row_lse);
+                        reinterpret_cast<int8_t *>(&nbw_s[wv][0])[edge * a.heads + head] = static_cast<int8_t>(rc.dq);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
         if (lane < cnt) {
             const int e = base + lane;
             my_nb = nb_now;
@@ -398,16 +427,17 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 // four heads at a time (one pass up to 4 heads, two up to 8)
                 for (int h0 = 0; h0 < H; h0 += 4) {
                     int sq[4], dq[4];
+                    float lse4[4] = {0.f, 0.f, 0.f, 0.f};
                     tango_load_heads4(a.att.Sq, src_node, H, h0, sq);
-                    tango_load_heads4(a.att.Dq, dst_node, H, h0, dq);
-                    float4 lse4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                    // DS: row_lse of four heads of the destination in one 16-byte load
-                    if (DS) lse4 = *reinterpret_cast<const float4 *>(tango_rec_lse(a.att.rec, dst_node, H) + h0);
-                    if (DS && h0 == 0) {
-                        // P of heads 0-3 (same record, needed after the gathers): fetched now, its latency hidden behind them
-                        const double2 *pp = reinterpret_cast<const double2 *>(tango_rec_P(a.att.rec, dst_node, H));
-                        pre01 = pp[0];
-                        pre23 = pp[1];
+                    if (DS) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (h0 + j >= H) break;
+                            lse4[j] = __int_as_float(dots_s[wv][lane * H + h0 + j]);
+                            dq[j] = static_cast<int>(reinterpret_cast<const int8_t *>(&nbw_s[wv][0])[lane * H + h0 + j]);
+                        }
+                    } else {
+                        tango_load_heads4(a.att.Dq, dst_node, H, h0, dq);
                     }
                     uint32_t wpk = 0;
 #pragma unroll
@@ -417,13 +447,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         bool pos;
                         const float ev = tango_attn_score(att_sS * static_cast<float>(sq[j]), att_sD * static_cast<float>(dq[j]),
                                                           a.att.slope, pos);
-                        const float lse = DS ? (j == 0 ? lse4.x : j == 1 ? lse4.y : j == 2 ? lse4.z : lse4.w)
-                                             : a.att.row_lse[dst_node * H + hh];
+                        const float lse = DS ? lse4[j] : a.att.row_lse[dst_node * H + hh];
                         const float al = tango_attn_alpha(ev, lse);
-                        if (DS) {
-                            alf_s[wv][lane * H + hh] = al;
-                            pos_mask |= (pos ? 1u : 0u) << hh;
-                        }
+                        if (DS) alf_s[wv][lane * H + hh] = pos ? al : -al;  // the sign bit says "pre-activation not positive"
                         if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
                         int q;
                         if (a.att.rounding == TANGO_SR) {
@@ -570,41 +596,48 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             k0 = k1;
         }
         if (DS) {
-            // step 4', LeakyReLU' and step 3' for the 64 edges of the block, one edge per lane: dE = alpha*(dalpha - P),
-            // times the slope where the score was not positive, summed per (row segment, head) in fp64
+            // step 4', LeakyReLU' and step 3' for the edges of the block, on the (edge, head) pairs of the record loads
+            // above: dE = alpha*(dalpha - P), times the slope where the score was not positive, summed per (row segment,
+            // head) in fp64.  A lane's pairs all have the same head (64 is a multiple of HP), so one lane sum over the
+            // rounds and one reduction over the lanes of equal head serve all heads at once.
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int H = a.heads;
-            for (int h0 = 0; h0 < H; h0 += 4) {
-            // P of four heads of my edge's destination (heads 0-3: fetched with row_lse; beyond: two 16-byte loads)
-            double2 p01 = pre01, p23 = pre23;
-            if (h0 > 0 && lane < cnt) {
-                const double2 *pp = reinterpret_cast<const double2 *>(tango_rec_P(a.att.rec, my_nb, H) + h0);
-                p01 = pp[0];
-                p23 = pp[1];
-            }
+            int lane_o = lane;
+            asm volatile("" : "+v"(lane_o));
+            const int head = lane_o & (HP - 1);
+            for (int g0 = 0; g0 < HP; g0 += 4) {  // four rounds at a time (one pass up to 4 heads, two up to 8)
+                double contrib[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int hh = h0 + j;
-                if (hh >= H) break;
-                double contrib = 0.0;
-                if (lane < cnt) {
-                    const float da = static_cast<float>(dots_s[wv][lane * H + hh]) * sc_dot;
-                    const float al = alf_s[wv][lane * H + hh];
-                    const double Pj = j == 0 ? p01.x : j == 1 ? p01.y : j == 2 ? p23.x : p23.y;
-                    const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - Pj));
-                    contrib = static_cast<double>(dE * (((pos_mask >> hh) & 1u) ? 1.0f : a.att.slope));
+                for (int j = 0; j < 4; ++j) {
+                    contrib[j] = 0.0;
+                    if (g0 + j >= HP) break;
+                    const int edge = (lane_o + 64 * (g0 + j)) >> log2HP;
+                    if (edge < cnt && head < H) {
+                        const float da = static_cast<float>(dots_s[wv][edge * H + head]) * sc_dot;
+                        const float als = alf_s[wv][edge * H + head];
+                        double Pv = P_r[j];
+                        if (g0 > 0) {  // more than four heads: rounds 4-7 fetch P again
+                            const int nbe = static_cast<int>(nbw_s[wv][edge].x / static_cast<uint32_t>(row_bytes));
+                            Pv = static_cast<const tango_attn_rec *>(a.att.rec)[static_cast<int64_t>(nbe) * HP + head].P;
+                        }
+                        const float dE = static_cast<float>(static_cast<double>(fabsf(als)) * (static_cast<double>(da) - Pv));
+                        contrib[j] = static_cast<double>(dE * (__float_as_int(als) < 0 ? a.att.slope : 1.0f));
+                    }
                 }
                 for (int k0 = 0; k0 < cnt;) {
                     const int r = __builtin_amdgcn_readlane(my_row, k0);
                     const int k1 = min(__builtin_amdgcn_readlane(my_rt, k0) - base, cnt);
-                    double v = (lane >= k0 && lane < k1) ? contrib : 0.0;
+                    double v = 0.0;
 #pragma unroll
-                    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-                    if (lane == 0 && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(r) * H + hh, v);
+                    for (int j = 0; j < 4; ++j) {
+                        const int edge = (lane_o + 64 * (g0 + j)) >> log2HP;
+                        if (g0 + j < HP && edge >= k0 && edge < k1) v += contrib[j];
+                    }
+                    for (int o = 32; o >= HP; o >>= 1) v += __shfl_xor(v, o, 64);
+                    if (lane < H && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(r) * H + lane, v);
                     k0 = k1;
                 }
-            }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -842,9 +875,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                         const int64_t vh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
                         bool pos;
                         const float ev = tango_attn_score(ts_row, sD * static_cast<float>(a.Dq[vh]), a.slope, pos);
-                        const float al = tango_attn_alpha(ev, tango_rec_lse(a.rec, nbl[wv][k], H)[eh]);
-                        const float dE = static_cast<float>(static_cast<double>(al) *
-                                                            (static_cast<double>(da) - tango_rec_P(a.rec, nbl[wv][k], H)[eh]));
+                        const tango_attn_rec rc =
+                            static_cast<const tango_attn_rec *>(a.rec)[static_cast<int64_t>(nbl[wv][k]) * tango_rec_heads(H) + eh];
+                        const float al = tango_attn_alpha(ev, rc.row_lse);
+                        const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
                         acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
                     } else if (ATT_DST) {
                         const int64_t uh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
@@ -1141,6 +1175,7 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
 }
 
 __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, const double *__restrict__ stats, const float *__restrict__ row_lse,
+                                                         const int8_t *__restrict__ Dq,
                                                          void *__restrict__ rec, float *__restrict__ dD)
 {
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < nh;
@@ -1148,8 +1183,11 @@ __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, 
         const double A = stats[3 * i], B = stats[3 * i + 1], C = stats[3 * i + 2];
         const int64_t node = i / heads;
         const int h = static_cast<int>(i - node * heads);
-        tango_rec_P(rec, node, heads)[h] = A;
-        tango_rec_lse(rec, node, heads)[h] = row_lse[i];
+        tango_attn_rec rc;
+        rc.P = A;
+        rc.row_lse = row_lse[i];
+        rc.dq = static_cast<int>(Dq[i]);
+        static_cast<tango_attn_rec *>(rec)[node * tango_rec_heads(heads) + h] = rc;
         dD[i] = static_cast<float>(B - A * C);
     }
 }
@@ -1194,7 +1232,7 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
         }
         TANGO_LAUNCH_CHECK();
     }
-    k_attn_dst_finish<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(nh, heads, stats, row_lse, rec, dD);
+    k_attn_dst_finish<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(nh, heads, stats, row_lse, Dq, rec, dD);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
