@@ -19,32 +19,118 @@ __global__ __launch_bounds__(256) void k_head_proj(int64_t npairs, int heads, in
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * blockDim.x / TANGO_WAVE;
     const int q = dim / 4;  // float4 per pair
     float ms = 0.0f, md = 0.0f;
-    for (int64_t p0 = wave * ppw; p0 < npairs; p0 += nwaves * ppw) {
-        const int64_t p = p0 + lane / lpp;
-        double accs = 0.0, accd = 0.0;
-        if (p < npairs) {
-            const int h = static_cast<int>(p % heads);
-            const float4 *x4 = reinterpret_cast<const float4 *>(X + p * dim);
-            const float4 *as4 = reinterpret_cast<const float4 *>(a_src + static_cast<int64_t>(h) * dim);
-            const float4 *ad4 = reinterpret_cast<const float4 *>(a_dst + static_cast<int64_t>(h) * dim);
-            for (int k = lg; k < q; k += lpp) {
-                const float4 x = x4[k], s = as4[k], d = ad4[k];
-                accs += static_cast<double>(x.x) * s.x + static_cast<double>(x.y) * s.y + static_cast<double>(x.z) * s.z +
-                        static_cast<double>(x.w) * s.w;
-                accd += static_cast<double>(x.x) * d.x + static_cast<double>(x.y) * d.y + static_cast<double>(x.z) * d.z +
-                        static_cast<double>(x.w) * d.w;
+    // UNR groups of pairs per wave-iteration: their first loads are issued together (with one float4 per lane and
+    // pair - dim <= 256 - the loop is otherwise one dependent load per iteration)
+    constexpr int UNR = 4;
+    const bool small = npairs < (int64_t(1) << 32);
+    for (int64_t p0 = wave * ppw * UNR; p0 < npairs; p0 += nwaves * ppw * UNR) {
+        int64_t p[UNR];
+        float4 x0[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            p[u] = p0 + u * ppw + lane / lpp;
+            x0[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p[u] < npairs && lg < q) x0[u] = reinterpret_cast<const float4 *>(X + p[u] * dim)[lg];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            double accs = 0.0, accd = 0.0;
+            if (p[u] < npairs) {
+                // (a 64-bit remainder costs more instructions than the dot product itself)
+                const int h = small ? static_cast<int>(static_cast<uint32_t>(p[u]) % static_cast<uint32_t>(heads))
+                                    : static_cast<int>(p[u] % heads);
+                const float4 *x4 = reinterpret_cast<const float4 *>(X + p[u] * dim);
+                const float4 *as4 = reinterpret_cast<const float4 *>(a_src + static_cast<int64_t>(h) * dim);
+                const float4 *ad4 = reinterpret_cast<const float4 *>(a_dst + static_cast<int64_t>(h) * dim);
+                for (int k = lg; k < q; k += lpp) {
+                    const float4 x = (k == lg) ? x0[u] : x4[k], s = as4[k], d = ad4[k];
+                    accs += static_cast<double>(x.x) * s.x + static_cast<double>(x.y) * s.y + static_cast<double>(x.z) * s.z +
+                            static_cast<double>(x.w) * s.w;
+                    accd += static_cast<double>(x.x) * d.x + static_cast<double>(x.y) * d.y + static_cast<double>(x.z) * d.z +
+                            static_cast<double>(x.w) * d.w;
+                }
+            }
+            for (int o = lpp / 2; o > 0; o >>= 1) {
+                accs += __shfl_xor(accs, o, 64);
+                accd += __shfl_xor(accd, o, 64);
+            }
+            if (p[u] < npairs && lg == 0) {
+                const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
+                S[p[u]] = fs;
+                D[p[u]] = fd;
+                ms = fmaxf(ms, fabsf(fs));
+                md = fmaxf(md, fabsf(fd));
             }
         }
-        for (int o = lpp / 2; o > 0; o >>= 1) {
-            accs += __shfl_xor(accs, o, 64);
-            accd += __shfl_xor(accd, o, 64);
+    }
+    ms = tango_wave_max(ms);
+    md = tango_wave_max(md);
+    if (lane == 0) {
+        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
+        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
+    }
+}
+
+// The same for the usual widths (dim/4 a power of two <= 64, F <= 1024): a wave takes whole node rows, lane l the
+// float4 number 64*j + l of the row in pass j, so the slices of a_src / a_dst a lane needs never change (loaded once)
+// and no index arithmetic is left in the loop; the loads of several rows are issued before the first is used.  The
+// sums are formed in the same order as in k_head_proj (a lane's four products, then the xor tree over the head's lanes).
+template <int PASSES>
+__global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, int dim, const float *__restrict__ X,
+                                                        const float *__restrict__ a_src, const float *__restrict__ a_dst,
+                                                        float *__restrict__ S, float *__restrict__ D, float *absmax_S,
+                                                        float *absmax_D)
+{
+    constexpr int UNR = 4 / PASSES;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    const int64_t nwaves = static_cast<int64_t>(gridDim.x) * blockDim.x / TANGO_WAVE;
+    const int F = heads * dim, q = F / 4, lph = dim / 4;
+    float4 as[PASSES], ad[PASSES];
+    int hd[PASSES];
+    bool on[PASSES], first[PASSES];
+#pragma unroll
+    for (int j = 0; j < PASSES; ++j) {
+        const int idx = 64 * j + lane;
+        on[j] = idx < q;
+        hd[j] = idx / lph;
+        first[j] = on[j] && (idx % lph) == 0;
+        as[j] = on[j] ? reinterpret_cast<const float4 *>(a_src)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        ad[j] = on[j] ? reinterpret_cast<const float4 *>(a_dst)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float ms = 0.0f, md = 0.0f;
+    for (int64_t v0 = wave * UNR; v0 < n; v0 += nwaves * UNR) {
+        float4 x[UNR][PASSES];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+            for (int j = 0; j < PASSES; ++j) {
+                x[u][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v0 + u < n && on[j]) x[u][j] = reinterpret_cast<const float4 *>(X + (v0 + u) * F)[64 * j + lane];
+            }
         }
-        if (p < npairs && lg == 0) {
-            const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
-            S[p] = fs;
-            D[p] = fd;
-            ms = fmaxf(ms, fabsf(fs));
-            md = fmaxf(md, fabsf(fd));
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+            for (int j = 0; j < PASSES; ++j) {
+                const float4 xv = x[u][j], s = as[j], d = ad[j];
+                double accs = 0.0, accd = 0.0;
+                accs += static_cast<double>(xv.x) * s.x + static_cast<double>(xv.y) * s.y + static_cast<double>(xv.z) * s.z +
+                        static_cast<double>(xv.w) * s.w;
+                accd += static_cast<double>(xv.x) * d.x + static_cast<double>(xv.y) * d.y + static_cast<double>(xv.z) * d.z +
+                        static_cast<double>(xv.w) * d.w;
+                for (int o = lph / 2; o > 0; o >>= 1) {
+                    accs += __shfl_xor(accs, o, 64);
+                    accd += __shfl_xor(accd, o, 64);
+                }
+                if (v0 + u < n && first[j]) {
+                    const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
+                    S[(v0 + u) * heads + hd[j]] = fs;
+                    D[(v0 + u) * heads + hd[j]] = fd;
+                    ms = fmaxf(ms, fabsf(fs));
+                    md = fmaxf(md, fabsf(fd));
+                }
+            }
         }
     }
     ms = tango_wave_max(ms);
@@ -139,10 +225,19 @@ int tango_head_proj_async(int64_t n, int heads, int dim, const float *X, const f
     int rc;
     if (absmax_S && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 0u, 1, st)) != TANGO_OK) return rc;
     if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
+    const int lph = dim / 4, q = heads * dim / 4;
+    if (lph >= 1 && lph <= 64 && (lph & (lph - 1)) == 0 && q <= 256) {
+        const unsigned grid = tango_grid_for(static_cast<size_t>(n), 16, 256 * 8);
+        if (q <= 64) k_head_proj_rows<1><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
+        else if (q <= 128) k_head_proj_rows<2><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
+        else k_head_proj_rows<4><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
+        TANGO_LAUNCH_CHECK();
+        return TANGO_OK;
+    }
     int lpp = 1;
     while (lpp * 2 <= 64 && lpp * 2 <= dim / 4) lpp *= 2;
     const int64_t npairs = n * heads;
-    const size_t waves_needed = static_cast<size_t>((npairs + (64 / lpp) - 1) / (64 / lpp));
+    const size_t waves_needed = static_cast<size_t>((npairs + 4 * (64 / lpp) - 1) / (4 * (64 / lpp)));
     k_head_proj<<<tango_grid_for(waves_needed, 4, 256 * 8), 256, 0, st>>>(npairs, heads, dim, lpp, X, a_src, a_dst, S, D,
                                                                          absmax_S, absmax_D);
     TANGO_LAUNCH_CHECK();

@@ -440,6 +440,14 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         tango_load_heads4(a.att.Dq, dst_node, H, h0, dq);
                     }
                     uint32_t wpk = 0;
+                    // head counts that are multiples of four: the group's four random fields are one 64-bit half of one
+                    // Philox block (i0 and h0 are multiples of four), fetched once for the group
+                    const bool one_block = (H & 3) == 0 && a.att.rounding == TANGO_SR;
+                    uint64_t half = 0;
+                    if (one_block) {
+                        const uint4 b4 = tango_philox_block(a.att.rng, static_cast<uint64_t>(i0 + h0) >> 3);
+                        half = ((i0 + h0) & 4) ? ((static_cast<uint64_t>(b4.w) << 32) | b4.z) : ((static_cast<uint64_t>(b4.y) << 32) | b4.x);
+                    }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int hh = h0 + j;
@@ -452,7 +460,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         if (DS) alf_s[wv][lane * H + hh] = pos ? al : -al;  // the sign bit says "pre-activation not positive"
                         if (WMODE == W_ATT_FWD && a.att.alpha_dump) a.att.alpha_dump[i0 + hh] = al;
                         int q;
-                        if (a.att.rounding == TANGO_SR) {
+                        if (one_block) {
+                            q = tango_round_clamp<TANGO_SR>(al * inv_w, static_cast<uint32_t>(half >> (16 * j)) & 0xffffu);
+                        } else if (a.att.rounding == TANGO_SR) {
                             const uint64_t bi = static_cast<uint64_t>(i0 + hh) >> 3;
                             if (bi != have) {
                                 blk = tango_philox_block(a.att.rng, bi);
