@@ -291,25 +291,26 @@ def main():
         # forward through all three, then backward through all three
         F = li.heads * li.dim
         heads = li.heads
-        grads = [torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev) for _ in range(3)]
-        grads[2].copy_(to(li.grad_out))
-        acts = [to(li.feat)] + [torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev) for _ in range(2)]
+        # the ReLU sits inside the layers: a layer writes max(0, aggregate) from its SPMM epilogue and passes that
+        # tensor's abs-max to the next layer's GEMM; a layer's input gradient is the layer below's grad_out, and ReLU'
+        # is applied while that gradient is quantized
         layers = []
         for i in range(3):
             k = li.feat.shape[1] if i == 0 else F
             W = to(ti.xavier_uniform(k, F, (k, F), li.sr_seed + 10 + i))
-            layers.append(T.GatLayer(G, acts[i], W, to(li.a_src), to(li.a_dst), grads[i], slope, T.SR, li.sr_seed, i,
-                                     want_dH=(i > 0)))
+            feat = to(li.feat) if i == 0 else layers[i - 1]["out"]
+            grad = to(li.grad_out) if i == 2 else torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev)
+            layers.append(T.GatLayer(G, feat, W, to(li.a_src), to(li.a_dst), grad, slope, T.SR, li.sr_seed, i,
+                                     want_dH=False, relu_out=(i < 2),
+                                     absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None)))
+        for i in (1, 2):
+            layers[i]._bind("dH", layers[i - 1]["grad_out"], torch.float32)
 
         def step():
             for i in range(3):
                 T.tango_gat_layer_fwd(layers[i])
-                if i < 2:
-                    T.tango_relu(layers[i]["out"], acts[i + 1])
             for i in (2, 1, 0):
                 T.tango_gat_layer_bwd(layers[i])
-                if i > 0:
-                    T.tango_relu_bwd(layers[i - 1]["out"], layers[i]["dH"], grads[i - 1])
 
         L = layers[2]
         spmm, spmm_name = attention_bwd_src_launch(torch, T, G, L, heads, li.dim, slope, li.sr_seed, 16 * 2 + 6)

@@ -122,6 +122,15 @@ int tango_quantize_xoshiro(const float *x, size_t n, uint64_t seed, uint64_t str
 int tango_dequantize(const int8_t *q, size_t n, const float *scale, float *x, void *stream);
 
 /*
+ * Quantization of a gradient that arrives behind a ReLU (Sec. 3.3 caching rule applied to the activation: the
+ * gradient is quantized once, and ReLU' is folded into that pass): q = quantize(x[i] if y[i] > 0 else 0), per-tensor
+ * scale from the abs-max of the masked tensor, rounding and random stream as in tango_quantize.  x, y: n floats,
+ * 16-byte aligned; q: n bytes, 8-byte aligned; ws: 256 bytes, 256-byte aligned (device).
+ */
+int tango_quantize_relu_bwd(const float *x, const float *y, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                            int8_t *q, float *scale_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Quantization-error metric and bit-count rule (Sec. 3.2 Eq. 4): for each candidate bit count B (2..8, at most 4
  * candidates, host array) error_out[c] = mean_i |(x_i - xq_i) / (x_i + xq_i + 0.0005)| (device doubles), xq the grid
  * point of the B-bit symmetric per-tensor quantizer (codes in +-(2^(B-1)-1), scale absmax/(2^(B-1)-1), rounding and
@@ -515,6 +524,14 @@ typedef struct tango_gat_layer {
     /* scratch */
     void *ws;
     size_t ws_bytes;              /* >= tango_gat_layer_workspace_bytes(...) */
+    /* Stacked layers (the paper does not say what sits between layers; a ReLU is taken).  relu_out != 0: the forward
+     * pass writes out = max(0, aggregate) from the SPMM's own epilogue (absmax_out is of that), and the backward pass
+     * takes grad_out as the gradient behind that ReLU: ReLU' (out > 0) is applied while grad_out is quantized, so no
+     * activation kernel and no extra fp32 tensor exist between two layers; grad_out and out must then be 16-byte
+     * aligned.  absmax_H: max|H| on the device if the caller already has it (the absmax_out of the layer below),
+     * else NULL - it saves the pass over H that finds it. */
+    int relu_out;
+    const float *absmax_H;
 } tango_gat_layer;
 
 size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim);

@@ -396,7 +396,7 @@ def head_proj_bwd(dS, dD, a_src, a_dst, X_q, s_X, dX_agg):
 
 
 # ------------------------------------------------------------- layers
-def gat_layer_fwd(g, H, W, a_src, a_dst, slope=0.2, rounding=SR, seed=0, layer=0):
+def gat_layer_fwd(g, H, W, a_src, a_dst, slope=0.2, rounding=SR, seed=0, layer=0, relu_out=False):
     """One quantized GAT layer forward (Fig. 1a steps 1-5); returns every intermediate."""
     b = 16 * layer
     r = qgemm(H, W, rounding, seed, b + SID_H, b + SID_W)
@@ -410,6 +410,9 @@ def gat_layer_fwd(g, H, W, a_src, a_dst, slope=0.2, rounding=SR, seed=0, layer=0
     alpha = edge_softmax(g, E)
     alpha_q, s_alpha = quantize(alpha, rounding, seed, b + SID_ALPHA)
     out, am_out = spmm_in(g, alpha_q, s_alpha, Hp_q, s_Hp)
+    if relu_out:  # ReLU between stacked layers (the paper leaves the activation open): out = max(0, aggregate)
+        out = np.maximum(out, np.float32(0))
+        am_out = absmax(out)
     return dict(
         H_q=r["A_q"], s_H=r["s_A"], W_q=r["B_q"], s_W=r["s_B"], Hp=Hp, absmax_Hp=r["absmax_C"], S=S, D=D,
         Hp_q=Hp_q, s_Hp=s_Hp, S_q=S_q, s_S=s_S, D_q=D_q, s_D=s_D, E=E, alpha=alpha, alpha_q=alpha_q,
@@ -417,10 +420,12 @@ def gat_layer_fwd(g, H, W, a_src, a_dst, slope=0.2, rounding=SR, seed=0, layer=0
     )
 
 
-def gat_layer_bwd(g, fwd, a_src, a_dst, grad_out, slope=0.2, rounding=SR, seed=0, layer=0):
+def gat_layer_bwd(g, fwd, a_src, a_dst, grad_out, slope=0.2, rounding=SR, seed=0, layer=0, relu_out=False):
     """Backward of gat_layer_fwd (Fig. 1b steps 5', 5'', 4', 3', 3'', 2', 1')."""
     b = 16 * layer
     heads = a_src.shape[0]
+    if relu_out:  # grad_out is the gradient behind the ReLU: its derivative is 1 where the output is positive, else 0
+        grad_out = np.where(fwd["out"] > 0, grad_out, np.float32(0)).astype(np.float32)
     g_q, s_g = quantize(grad_out, rounding, seed, b + SID_G)
     dHp_agg, _ = spmm_rev(g, fwd["alpha_q"], fwd["s_alpha"], g_q, s_g)
     dalpha = sddmm_dot(g, g_q, s_g, fwd["Hp_q"], fwd["s_Hp"], heads)

@@ -51,6 +51,7 @@ SIGNATURES = {
     "tango_quantize_workspace_bytes": (_sz, [_sz]),
     "tango_quantize": (_int, [_vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_dequantize": (_int, [_vp, _sz, _vp, _vp, _vp]),
+    "tango_quantize_relu_bwd": (_int, [_vp, _vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _sz, _vp]),
     "tango_qgemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -187,6 +188,16 @@ SIGNATURES.update({
     "tango_error_x_workspace_bytes": (_sz, []),
     "tango_error_x": (_int, [_vp, _sz, ctypes.POINTER(ctypes.c_int), _int, _f32, _int, _u64, _u64, _vp, _vp, _vp, _vp, _sz, _vp]),
 })
+
+
+def tango_quantize_relu_bwd(x, y, rounding, seed, stream_id, q, scale_out, ws):
+    _check(
+        load_library().tango_quantize_relu_bwd(
+            _ptr(x, torch.float32), _ptr(y, torch.float32), x.numel(), rounding, seed, stream_id, _ptr(q, torch.int8),
+            _ptr(scale_out, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream(),
+        ),
+        "tango_quantize_relu_bwd",
+    )
 
 
 def tango_error_x_workspace_bytes() -> int:
@@ -521,7 +532,8 @@ class tango_gat_layer(ctypes.Structure):
             "H", "W", "a_src", "a_dst", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "S", "D",
             "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
             "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst")]
-        + [("fused", _int), ("row_lse", _vp), ("absmax_alpha", _vp), ("ws", _vp), ("ws_bytes", _sz)]
+        + [("fused", _int), ("row_lse", _vp), ("absmax_alpha", _vp), ("ws", _vp), ("ws_bytes", _sz),
+           ("relu_out", _int), ("absmax_H", _vp)]
     )
 
 
@@ -598,7 +610,8 @@ class GatLayer(_LayerBuffers):
     _struct = tango_gat_layer
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
-                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False, keep_dalpha=False):
+                 want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False, keep_dalpha=False,
+                 relu_out=False, absmax_H=None):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -622,6 +635,9 @@ class GatLayer(_LayerBuffers):
             self._alloc(name, (n, heads), f32)
         self._alloc("S_q", (n, heads), i8)
         self._alloc("D_q", (n, heads), i8)
+        c.relu_out = 1 if relu_out else 0
+        if absmax_H is not None:
+            self._bind("absmax_H", absmax_H, f32)
         c.fused = 1 if fused else 0
         if fused:
             self._alloc("row_lse", (n, heads), f32)

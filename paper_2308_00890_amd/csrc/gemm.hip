@@ -362,6 +362,17 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                 uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A, int8_t *B_q, float *s_B, float *C,
                 float *absmax_C, void *ws, size_t ws_bytes, void *stream)
 {
+    return tango_qgemm_known_absmax(M, N, K, A, nullptr, B, rounding, seed, stream_id_A, stream_id_B, A_q, s_A, B_q, s_B, C,
+                                    absmax_C, ws, ws_bytes, stream);
+}
+
+}  // extern "C"
+
+// tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL): the pass over A that finds it is skipped.
+int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
+                             int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
+                             int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream)
+{
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
     if (rc != TANGO_OK) return rc;
@@ -377,7 +388,8 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
 
     if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(am), 0u, 2, st)) != TANGO_OK) return rc;
     if (absmax_C && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_C), 0u, 1, st)) != TANGO_OK) return rc;
-    if ((rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
+    const float *am_A = absmax_A_in ? absmax_A_in : am;
+    if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
     if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
     if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, Np * Kp / 4, st)) != TANGO_OK) return rc;
     const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
@@ -391,17 +403,19 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
     if (K > KMAX) {
         // the 64-row panel of A no longer fits LDS: quantize A in a pass of its own, then the tiled kernel on the int8
         // operands (BT: N rows of Kp bytes, zero-padded)
-        if ((rc = tango_quantize_with_absmax_async(A, static_cast<size_t>(M) * K, rounding, seed, stream_id_A, am, A_q, s_A, st)) !=
+        if ((rc = tango_quantize_with_absmax_async(A, static_cast<size_t>(M) * K, rounding, seed, stream_id_A, am_A, A_q, s_A, st)) !=
             TANGO_OK)
             return rc;
         return tango_gemm_i8_async(M, N, K, A_q, K, s_A, BT, Kp, s_B, C, absmax_C, st);
     }
     fused_args a;
     a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K); a.Kp = Kp; a.Np = Np;
-    a.A = A; a.absmax_A = am; a.rng = tango_rng_make(seed, stream_id_A);
+    a.A = A; a.absmax_A = am_A; a.rng = tango_rng_make(seed, stream_id_A);
     a.A_q = A_q; a.s_A = s_A; a.BT = BT; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C;
     return launch_fused(a, rounding, st);
 }
+
+extern "C" {
 
 size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {

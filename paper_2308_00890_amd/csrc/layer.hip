@@ -54,8 +54,8 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     const uint64_t sid = 16 * L->layer_id;
 
     // step 1: H' = H.W, quantize-on-load, cached H_q / W_q, fused abs-max of H'
-    TANGO_TRY(tango_qgemm(n, F, L->k_in, L->H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W, L->H_q, L->s_H,
-                          L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
+    TANGO_TRY(tango_qgemm_known_absmax(n, F, L->k_in, L->H, L->absmax_H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W,
+                                       L->H_q, L->s_H, L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
     // step 2: S, D in fp32, with their abs-max
     TANGO_TRY(tango_head_proj(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
                               sc + SC_ABSMAX_D, stream));
@@ -68,9 +68,10 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                              L->D_q, L->s_D, nullptr, 0, stream));
     if (L->fused) {
         // steps 3-5 fused: E and alpha never reach memory in fp32
-        return tango_gat_attention_fwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
-                                       L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
-                                       L->absmax_alpha, L->alpha, L->out, L->absmax_out, sub, sub_bytes, stream);
+        return tango_gat_attention_fwd_act(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
+                                           L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
+                                           L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out, sub, sub_bytes,
+                                           stream);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -82,6 +83,7 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     // step 5: quantized SPMM
     TANGO_TRY(tango_qspmm(L->g, TANGO_IN, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->out,
                           L->absmax_out, stream));
+    if (L->relu_out) TANGO_TRY(tango_relu(L->out, static_cast<size_t>(n * F), L->out, L->absmax_out, stream));
     return TANGO_OK;
 }
 
@@ -106,8 +108,17 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     const uint64_t sid = 16 * L->layer_id;
 
     // the upstream gradient is quantized once and shared by steps 5' and 5''
-    TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
-                             L->s_g, sub, sub_bytes, stream));
+    if (L->relu_out) {
+        // the gradient arrives behind the layer's ReLU: ReLU' (out > 0) is applied while it is quantized
+        TANGO_REQUIRE(L->out && tango_aligned(L->grad_out, 16) && tango_aligned(L->out, 16) && tango_aligned(L->g_q, 8),
+                      TANGO_ERR_BAD_SHAPE);
+        TANGO_TRY(tango_quantize_masked_async(L->grad_out, L->out, static_cast<size_t>(n * F), L->rounding, L->seed,
+                                              sid + SID_G, L->g_q, L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G,
+                                              tango_stream(stream)));
+    } else {
+        TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
+                                 L->s_g, sub, sub_bytes, stream));
+    }
     if (L->fused) {
         // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
         TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,

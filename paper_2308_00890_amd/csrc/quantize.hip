@@ -12,10 +12,17 @@ __global__ void k_fill_u32(uint32_t *p, uint32_t v, int n)
     if (i < n) p[i] = v;
 }
 
+__device__ inline float4 tango_mask4(const float4 a, const float4 k)
+{
+    return make_float4(k.x > 0.0f ? a.x : 0.0f, k.y > 0.0f ? a.y : 0.0f, k.z > 0.0f ? a.z : 0.0f, k.w > 0.0f ? a.w : 0.0f);
+}
+
 // max|x| over n floats into *out (as the bit pattern of a non-negative float; *out must start at 0).
 // VEC = 4: x is 16-byte aligned and float4 loads are used for the body.
-template <int VEC>
-__global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, size_t n, float *out)
+// MASKED: element i counts as 0 where mask[i] <= 0 (the gradient behind a ReLU whose output is `mask`).
+template <int VEC, bool MASKED = false>
+__global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, size_t n, float *out,
+                                                const float *__restrict__ mask = nullptr)
 {
     float m = 0.0f;
     const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -25,21 +32,29 @@ __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, siz
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         size_t i = tid;
         // eight independent loads per iteration keep enough bytes in flight to cover the memory latency
-        for (; i + 7 * nthr < n4; i += 8 * nthr) {
-            float4 a[8];
+        const float4 *k4 = reinterpret_cast<const float4 *>(mask);
+        constexpr int UA = MASKED ? 4 : 8;
+        for (; i + (UA - 1) * nthr < n4; i += UA * nthr) {
+            float4 a[UA], k[UA];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] = x4[i + u * nthr];
+            for (int u = 0; u < UA; ++u) {
+                a[u] = x4[i + u * nthr];
+                if (MASKED) k[u] = k4[i + u * nthr];
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < UA; ++u) {
+                if (MASKED) a[u] = tango_mask4(a[u], k[u]);
                 m = fmaxf(m, fmaxf(fmaxf(fabsf(a[u].x), fabsf(a[u].y)), fmaxf(fabsf(a[u].z), fabsf(a[u].w))));
+            }
         }
         for (; i < n4; i += nthr) {
-            const float4 a = x4[i];
+            float4 a = x4[i];
+            if (MASKED) a = tango_mask4(a, k4[i]);
             m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
         }
-        for (size_t j = n4 * 4 + tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
+        for (size_t j = n4 * 4 + tid; j < n; j += nthr) m = fmaxf(m, (!MASKED || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
     } else {
-        for (size_t j = tid; j < n; j += nthr) m = fmaxf(m, fabsf(x[j]));
+        for (size_t j = tid; j < n; j += nthr) m = fmaxf(m, (!MASKED || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
     }
     m = tango_wave_max(m);
     __shared__ float part[4];
@@ -73,10 +88,11 @@ __device__ inline uint2 quantize8(const float (&y)[8], const tango_rng &rng, uin
 }
 
 // Vector path: x 16-byte aligned, q 8-byte aligned.  One thread-iteration = 8 elements.
-template <int ROUNDING>
+template <int ROUNDING, bool MASKED = false>
 __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
                                                       const float *__restrict__ absmax, tango_rng rng,
-                                                      int8_t *__restrict__ q, float *scale_out)
+                                                      int8_t *__restrict__ q, float *scale_out,
+                                                      const float *__restrict__ mask = nullptr)
 {
     float s, inv;
     tango_scale_from_absmax(*absmax, s, inv);
@@ -89,12 +105,17 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
     // four independent 32-byte pieces per iteration keep enough loads in flight to cover the memory latency
     constexpr int UNR = 4;
     size_t i = tid;
+    const float4 *k4 = reinterpret_cast<const float4 *>(mask);
     for (; i + (UNR - 1) * nthr < n8; i += UNR * nthr) {
         float4 a[UNR], b[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             a[u] = x4[2 * (i + u * nthr)];
             b[u] = x4[2 * (i + u * nthr) + 1];
+            if (MASKED) {
+                a[u] = tango_mask4(a[u], k4[2 * (i + u * nthr)]);
+                b[u] = tango_mask4(b[u], k4[2 * (i + u * nthr) + 1]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
@@ -104,8 +125,12 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
         }
     }
     for (; i < n8; i += nthr) {
-        const float4 a = x4[2 * i];
-        const float4 b = x4[2 * i + 1];
+        float4 a = x4[2 * i];
+        float4 b = x4[2 * i + 1];
+        if (MASKED) {
+            a = tango_mask4(a, k4[2 * i]);
+            b = tango_mask4(b, k4[2 * i + 1]);
+        }
         const float y[8] = {a.x * inv, a.y * inv, a.z * inv, a.w * inv, b.x * inv, b.y * inv, b.z * inv, b.w * inv};
         q8[i] = quantize8<ROUNDING>(y, rng, i);
     }
@@ -113,8 +138,10 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
     if (tid == 0 && n8 * 8 < n) {
         uint4 b = make_uint4(0, 0, 0, 0);
         if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, n8);
-        for (size_t j = n8 * 8; j < n; ++j)
-            q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(x[j] * inv, tango_bits16(b, static_cast<int>(j & 7))));
+        for (size_t j = n8 * 8; j < n; ++j) {
+            const float xv = (!MASKED || mask[j] > 0.0f) ? x[j] : 0.0f;
+            q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(xv * inv, tango_bits16(b, static_cast<int>(j & 7))));
+        }
     }
 }
 
@@ -288,6 +315,25 @@ int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uin
     return TANGO_OK;
 }
 
+// q = quantize(x where mask > 0, else 0) with its own abs-max (found here into ws[0]); x, mask 16-byte and q 8-byte aligned.
+int tango_quantize_masked_async(const float *x, const float *mask, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                                int8_t *q, float *scale_out, float *absmax_ws, hipStream_t st)
+{
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_ws), 0u, 1, st);
+    if (rc != TANGO_OK) return rc;
+    if (n == 0) return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, absmax_ws, q, scale_out, st);
+    k_absmax<4, true><<<tango_grid_for(n / 4 + 1, 256 * 2), 256, 0, st>>>(x, n, absmax_ws, mask);
+    TANGO_LAUNCH_CHECK();
+    const tango_rng rng = tango_rng_make(seed, stream_id);
+    const unsigned grid = tango_grid_for(n / 8 + 1, 256 * 2);
+    if (rounding == TANGO_RN)
+        k_quantize_vec<TANGO_RN, true><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
+    else
+        k_quantize_vec<TANGO_SR, true><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
 extern "C" {
 
 int tango_version(void) { return 100; }
@@ -337,6 +383,17 @@ int tango_quantize(const float *x, size_t n, int rounding, uint64_t seed, uint64
         am = wam;
     }
     return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, am, q, scale_out, st);
+}
+
+int tango_quantize_relu_bwd(const float *x, const float *y, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
+                            int8_t *q, float *scale_out, void *ws, size_t ws_bytes, void *stream)
+{
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    TANGO_REQUIRE(n == 0 || (x != nullptr && y != nullptr && q != nullptr), TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(x, 16) && tango_aligned(y, 16) && tango_aligned(q, 8), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(ws != nullptr && ws_bytes >= 256 && tango_aligned(ws, 256), TANGO_ERR_WORKSPACE);
+    return tango_quantize_masked_async(x, y, n, rounding, seed, stream_id, q, scale_out, static_cast<float *>(ws),
+                                       tango_stream(stream));
 }
 
 size_t tango_error_x_workspace_bytes(void) { return 512; }

@@ -108,6 +108,7 @@ struct attn_params {
     const float *s_Xrow;
     const void *rec;     // per destination: row_lse and P of every head
     double *dS_acc;                // n x heads, zero-initialised
+    int relu_out;                  // forward: out = max(0, aggregate) (ReLU between stacked layers), absmax of that
 };
 
 enum { W_LOAD = 0, W_ATT_FWD = 1, W_ATT_REV = 2 };
@@ -127,6 +128,7 @@ struct spmm_args {
     int chunk_shift;       // log2 of the edges per wavefront
     int short_max;         // rows with at most this many edges are left to k_spmm_short (0: none)
     attn_params att;       // used by the ATT instantiations only
+    int relu;              // out = max(0, .)
 };
 
 // True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
             mask &= mask - 1;
             float *row = a.out + (base + k) * a.F;
             for (int c = lane; c < a.F; c += 64) {
-                const int acc = __float_as_int(row[c]);
+                int acc = __float_as_int(row[c]);
+                if (a.relu) acc = max(acc, 0);
                 const float o = static_cast<float>(acc) * sc;
                 row[c] = o;
                 m = fmaxf(m, fabsf(o));
@@ -320,6 +323,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
 #pragma unroll
                 for (int j = 0; j < CPL; j += 4) {
                     float4 o;
+                    if (WMODE == W_ATT_FWD && a.relu) {  // sc > 0: the sign of the sum is the sign of the output
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) acc[j + jj] = max(acc[j + jj], 0);
+                    }
                     o.x = static_cast<float>(acc[j + 0]) * sc;
                     o.y = static_cast<float>(acc[j + 1]) * sc;
                     o.z = static_cast<float>(acc[j + 2]) * sc;
@@ -1012,6 +1019,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
 {
     spmm_args a;
     if (att) a.att = *att;
+    a.relu = (att && direction == TANGO_IN) ? att->relu_out : 0;
     a.n = g->n_nodes;
     a.nnz = g->n_edges;
     a.ptr = direction == TANGO_IN ? g->in_ptr : g->out_ptr;
@@ -1113,9 +1121,10 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
-                               float *out, float *absmax_out, hipStream_t st)
+                               float *out, float *absmax_out, int relu_out, hipStream_t st)
 {
     attn_params att;
+    att.relu_out = relu_out;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
@@ -1142,7 +1151,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
-    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc;
+    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0;
     rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st);
     if (rc != TANGO_OK) return rc;
     k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);

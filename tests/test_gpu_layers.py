@@ -42,7 +42,8 @@ def gat_case(name):
     raise KeyError(name)
 
 
-def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding, seed, layer_id, fused, chain=True):
+def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding, seed, layer_id, fused, chain=True,
+                     relu_out=False):
     """Stage-by-stage check of one GAT layer's device tensors `o` (host copies) against the oracle primitives applied
     to the GPU's own inputs of each stage."""
     heads = a_src.shape[0]
@@ -74,10 +75,15 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
         o = dict(o, alpha_q=q)
     assert sc("s_alpha") == s
     out, am = orc.spmm_in(g, o["alpha_q"], sc("s_alpha"), o["Hp_q"], sc("s_Hp"))
+    if relu_out:
+        out = np.maximum(out, np.float32(0))
+        am = orc.absmax(out)
     assert_bit_exact(o["out"], out, "out")
     assert sc("absmax_out") == am
 
     # ---- backward, stage by stage
+    if relu_out:
+        grad_out = np.where(o["out"] > 0, grad_out, np.float32(0)).astype(np.float32)
     q, s = orc.quantize(grad_out, rounding, seed, b + orc.SID_G)
     assert_bit_exact(o["g_q"], q, "g_q")
     assert sc("s_g") == s
@@ -108,6 +114,7 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
         return
     # ---- the all-oracle chain, as a whole: int8 codes may flip where an fp32 intermediate sits on a rounding
     # threshold, so this is a closeness check in norm plus a count of differing codes
+    assert not relu_out  # (grad_out was masked with the GPU's own output above)
     f = orc.gat_layer_fwd(g, feat, weight, a_src, a_dst, slope, rounding, seed, layer_id)
     bw = orc.gat_layer_bwd(g, f, a_src, a_dst, grad_out, slope, rounding, seed, layer_id)
     rel = lambda a, c: np.linalg.norm(a.astype(np.float64) - c) / max(np.linalg.norm(c), 1e-30)
@@ -189,6 +196,48 @@ def test_three_layer_gat_chain(T):
             assert_bit_exact(gout, np.where(host(layers[i]["out"]) > 0, host(layers[i + 1]["dH"]), 0).astype(np.float32),
                              "relu backward")
         verify_gat_layer(o, g, feat, W, a_s, a_d, gout, slope, orc.SR, seed, i, True, chain=False)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_three_layer_gat_chain_activation_inside_the_layers(T, fused):
+    """The same stack with the ReLU inside the layers: a layer writes max(0, aggregate) from its SPMM epilogue and
+    hands its abs-max to the next layer's GEMM; the next layer's input gradient is the previous layer's grad_out, and
+    ReLU' is applied while that gradient is quantized.  No activation kernel runs and no tensor sits between layers."""
+    import torch
+
+    g = ti.rmat_graph(2500, 40000, seed=31)
+    heads, dim, widths = 3, 128, [100, 384, 384]
+    F = heads * dim
+    seed, slope = 778, 0.2
+    G = T.Graph.from_host(g)
+    x0 = ti.normal((g.n_nodes, widths[0]), 32)
+    up = ti.normal((g.n_nodes, F), 33)
+    params = [(ti.xavier_uniform(k, F, (k, F), 40 + i), ti.xavier_uniform(heads, dim, (heads, dim), 50 + i),
+               ti.xavier_uniform(heads, dim, (heads, dim), 60 + i)) for i, k in enumerate(widths)]
+    grads = [torch.empty((g.n_nodes, F), dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    grads[2].copy_(dev(up))
+    layers = []
+    for i in range(3):
+        W, a_s, a_d = params[i]
+        feat = dev(x0) if i == 0 else layers[i - 1]["out"]
+        L = T.GatLayer(G, feat, dev(W), dev(a_s), dev(a_d), grads[i], slope, orc.SR, seed, i, fused=fused, keep_alpha=True,
+                       keep_alpha_q=True, alias_E_alpha=False, relu_out=(i < 2),
+                       absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None))
+        if i > 0:  # this layer's input gradient is the gradient behind the previous layer's ReLU
+            L._bind("dH", grads[i - 1], torch.float32)
+        layers.append(L)
+    for L in layers:
+        T.tango_gat_layer_fwd(L)
+    for L in reversed(layers):
+        T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    for i in range(3):
+        o = {k: host(v) for k, v in layers[i].t.items() if k not in ("ws", "absmax_H")}
+        W, a_s, a_d = params[i]
+        feat = x0 if i == 0 else host(layers[i - 1]["out"])
+        assert i == 0 or feat.min() >= 0
+        verify_gat_layer(o, g, feat, W, a_s, a_d, host(grads[i]), slope, orc.SR, seed, i, fused, chain=False,
+                         relu_out=(i < 2))
 
 
 def test_fused_gat_layer_without_edge_caches(T):

@@ -138,3 +138,24 @@ def test_quantize_xoshiro(T, n):
     want_q, want_s = orc.quantize_xoshiro(x, 2308, 7)
     assert host(s)[0] == want_s
     assert_bit_exact(host(q), want_q, "codes from the register-resident generator")
+
+
+@pytest.mark.parametrize("rounding", [orc.RN, orc.SR])
+@pytest.mark.parametrize("n", [0, 5, 8, 1000003])
+def test_quantize_behind_relu(T, rounding, n):
+    """q = quantize(x where y > 0 else 0), scale from the abs-max of the masked tensor: bit-exact against the oracle's
+    quantizer applied to the masked tensor."""
+    import torch
+
+    x = ti.normal((n,), 91)
+    y = np.maximum(ti.normal((n,), 92), 0)  # a ReLU output: zeros and positives
+    if n > 8:
+        x[np.argmax(np.abs(x))] *= 3.0  # the overall abs-max ...
+        y[np.argmax(np.abs(x))] = 0.0   # ... is masked out, so the scale must come from the masked tensor
+    q = torch.empty(n, dtype=torch.int8, device="cuda:0")
+    s = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    T.tango_quantize_relu_bwd(dev(x), dev(y), rounding, 7, 21, q, s, workspace(256))
+    torch.cuda.synchronize()
+    want_q, want_s = orc.quantize(np.where(y > 0, x, 0).astype(np.float32), rounding, 7, 21)
+    assert_bit_exact(host(q), want_q, "q")
+    assert host(s)[0] == want_s

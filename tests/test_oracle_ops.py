@@ -510,3 +510,33 @@ def test_quantized_typed_layer_close_to_fp64_definition(model):
     assert rel_err(b["dHp"], dZ) < 0.05
     assert rel_err(b["dW"], H64.T @ dZ) < 0.05
     assert rel_err(b["dH"], dZ @ W64.T) < 0.05
+
+
+def test_gat_layer_with_relu_output_is_relu_of_plain_layer():
+    """relu_out: forward = max(0, plain output) (and its abs-max); backward = plain backward of the gradient with the
+    entries zeroed where the output is not positive - the ReLU of the fp64 layer, by the chain rule."""
+    g = small_graph(48, 400, 71)
+    heads, dim, K = 2, 8, 12
+    H = ti.normal((g.n_nodes, K), 72)
+    W = ti.xavier_uniform(K, heads * dim, (K, heads * dim), 73)
+    a_s = ti.xavier_uniform(heads, dim, (heads, dim), 74)
+    a_d = ti.xavier_uniform(heads, dim, (heads, dim), 75)
+    up = ti.normal((g.n_nodes, heads * dim), 76)
+    plain = orc.gat_layer_fwd(g, H, W, a_s, a_d, 0.2, orc.SR, seed=11)
+    act = orc.gat_layer_fwd(g, H, W, a_s, a_d, 0.2, orc.SR, seed=11, relu_out=True)
+    assert np.array_equal(act["out"], np.where(plain["out"] > 0, plain["out"], 0).astype(np.float32))
+    assert act["absmax_out"] == np.float32(max(plain["out"].max(), 0.0))
+    assert (plain["out"] < 0).mean() > 0.2  # the case exercises the mask
+    for k in plain:
+        if k not in ("out", "absmax_out"):
+            assert np.array_equal(plain[k], act[k]), k
+    masked = np.where(plain["out"] > 0, up, 0).astype(np.float32)
+    want = orc.gat_layer_bwd(g, plain, a_s, a_d, masked, 0.2, orc.SR, seed=11)
+    got = orc.gat_layer_bwd(g, act, a_s, a_d, up, 0.2, orc.SR, seed=11, relu_out=True)
+    for k in want:
+        assert np.array_equal(want[k], got[k]), k
+    # against the fp64 layer followed by a ReLU
+    rf = gat_forward(g, H, W, a_s, a_d, 0.2)
+    rb = gat_backward(g, H, W, a_s, a_d, 0.2, rf, np.where(rf["out"] > 0, up, 0.0))
+    assert rel_err(act["out"], np.maximum(rf["out"], 0.0)) < 0.12
+    assert rel_err(got["dW"], rb["dW"]) < 0.2 and rel_err(got["dH"], rb["dH"]) < 0.2
