@@ -261,29 +261,47 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const 
     v16i acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
 
     for (int64_t m0 = m_begin; m0 < m_end; m0 += MS) {
-        // stage: 16 row-quads x 32 column-quads per operand, two blocks per thread per operand
+        // stage: waves 0-1 transpose the P slab, waves 2-3 the Q slab.  A thread takes one quad of columns (32 per tile,
+        // consecutive lanes = 128 contiguous bytes of a row) and 16 consecutive rows: four 4x4 byte transposes give, for
+        // each of its 4 columns, the 16 row bytes that one MFMA operand read wants - one 16-byte LDS store each.  The
+        // 16-byte chunk index is XORed with (row / 8) % 4 so that neither these stores (lanes 4 rows apart) nor the
+        // operand reads (lanes 1 row apart) collide in the LDS banks.
+        {
+            const int half = tid / 128, t128 = tid % 128;
+            const int qb = t128 % 32, qa = t128 / 32;
+            const int8_t *src = half ? Q : P;
+            const int ld = half ? N : K;
+            const int c0 = (half ? n0 : k0) + 4 * qb;
+            int8_t *dstT = half ? Qt : Pt;
+            uint32_t w[16];
+            if (m0 + MS <= m_end && c0 + 3 < ld) {
+                // interior: sixteen independent loads, no per-load bounds check between them
+                const int8_t *p0 = src + (m0 + 16 * qa) * ld + c0;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int bid = tid + 256 * j;
-            const int qa = bid / 32, qb = bid % 32;
-            uint32_t t[4];
-            const int64_t r = m0 + 4 * qa;
-            transpose4x4(load_quad(P, r, m_end, K, k0 + 4 * qb, K), load_quad(P, r + 1, m_end, K, k0 + 4 * qb, K),
-                         load_quad(P, r + 2, m_end, K, k0 + 4 * qb, K), load_quad(P, r + 3, m_end, K, k0 + 4 * qb, K), t);
+                for (int i = 0; i < 16; ++i) w[i] = reinterpret_cast<const unaligned_u32 *>(p0 + static_cast<int64_t>(i) * ld)->v;
+            } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) *reinterpret_cast<uint32_t *>(Pt + (4 * qb + c) * LDM + 4 * qa) = t[c];
-            transpose4x4(load_quad(Q, r, m_end, N, n0 + 4 * qb, N), load_quad(Q, r + 1, m_end, N, n0 + 4 * qb, N),
-                         load_quad(Q, r + 2, m_end, N, n0 + 4 * qb, N), load_quad(Q, r + 3, m_end, N, n0 + 4 * qb, N), t);
+                for (int i = 0; i < 16; ++i) w[i] = load_quad(src, m0 + 16 * qa + i, m_end, ld, c0, ld);
+            }
+            uint32_t t[4][4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) *reinterpret_cast<uint32_t *>(Qt + (4 * qb + c) * LDM + 4 * qa) = t[c];
+            for (int b = 0; b < 4; ++b) transpose4x4(w[4 * b], w[4 * b + 1], w[4 * b + 2], w[4 * b + 3], t[b]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int row = 4 * qb + c;
+                *reinterpret_cast<uint4 *>(dstT + row * LDM + 16 * (qa ^ ((row / 8) % 4))) =
+                    make_uint4(t[0][c], t[1][c], t[2][c], t[3][c]);
+            }
         }
         __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < MS; ks += 32) {
-            const v4i a0 = *reinterpret_cast<const v4i *>(Pt + (rbase + lane % 32) * LDM + ks + 16 * (lane / 32));
-            const v4i a1 = *reinterpret_cast<const v4i *>(Pt + (rbase + 32 + lane % 32) * LDM + ks + 16 * (lane / 32));
-            const v4i b0 = *reinterpret_cast<const v4i *>(Qt + (cbase + lane % 32) * LDM + ks + 16 * (lane / 32));
-            const v4i b1 = *reinterpret_cast<const v4i *>(Qt + (cbase + 32 + lane % 32) * LDM + ks + 16 * (lane / 32));
+            const int mc = ks / 16 + lane / 32;  // 16-byte chunk of the reduction rows
+            const int ra = rbase + lane % 32, rb = cbase + lane % 32;
+            const v4i a0 = *reinterpret_cast<const v4i *>(Pt + ra * LDM + 16 * (mc ^ ((ra / 8) % 4)));
+            const v4i a1 = *reinterpret_cast<const v4i *>(Pt + (ra + 32) * LDM + 16 * (mc ^ (((ra + 32) / 8) % 4)));
+            const v4i b0 = *reinterpret_cast<const v4i *>(Qt + rb * LDM + 16 * (mc ^ ((rb / 8) % 4)));
+            const v4i b1 = *reinterpret_cast<const v4i *>(Qt + (rb + 32) * LDM + 16 * (mc ^ (((rb + 32) / 8) % 4)));
             acc00 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc00, 0, 0, 0);
             acc01 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b1, acc01, 0, 0, 0);
             acc10 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b0, acc10, 0, 0, 0);
