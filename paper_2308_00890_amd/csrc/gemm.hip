@@ -42,6 +42,7 @@ struct fused_args {
     const float *s_B;
     float *C;        // M x N
     float *absmax_C; // or NULL
+    uint32_t K_magic;  // ceil(2^32 / K): f / K == umulhi(f, K_magic) for the flat panel offsets f < 64 * K (K >= 2)
 };
 
 template <int ROUNDING>
@@ -82,26 +83,15 @@ __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
     const int ngroups = (cnt + 7) / 8;
     const float *Ap = a.A + flat0;
     int8_t *Aq = a.A_q + flat0;
-    for (int g = tid; g < ngroups; g += 256) {
-        const int f = g * 8;
-        const int valid = min(8, cnt - f);
-        float y[8];
-        if (valid == 8) {
-            const float4 x0 = *reinterpret_cast<const float4 *>(Ap + f);
-            const float4 x1 = *reinterpret_cast<const float4 *>(Ap + f + 4);
-            y[0] = x0.x * inv; y[1] = x0.y * inv; y[2] = x0.z * inv; y[3] = x0.w * inv;
-            y[4] = x1.x * inv; y[5] = x1.y * inv; y[6] = x1.z * inv; y[7] = x1.w * inv;
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) y[j] = (j < valid) ? Ap[f + j] * inv : 0.0f;
-        }
+    // one group of 8 elements (one Philox block): quantize y, write the int8 copy back and into the LDS panel
+    auto finish_group = [&](int f, int valid, const float (&y)[8]) {
         const uint2 q = quantize8_packed<ROUNDING>(y, a.rng, static_cast<uint64_t>((flat0 + f) >> 3));
         if (valid == 8) {
             *reinterpret_cast<uint2 *>(Aq + f) = q;
         } else {
             for (int j = 0; j < valid; ++j) Aq[f + j] = static_cast<int8_t>((j < 4 ? q.x >> (8 * j) : q.y >> (8 * (j - 4))) & 0xffu);
         }
-        int row = f / a.K;
+        int row = a.K == 1 ? f : static_cast<int>(__umulhi(static_cast<uint32_t>(f), a.K_magic));  // f / K
         int col = f - row * a.K;
         const uint64_t bits = (static_cast<uint64_t>(q.y) << 32) | q.x;
 #pragma unroll
@@ -121,6 +111,39 @@ __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
                 }
             }
         }
+    };
+    // four full groups per thread and iteration: their eight 16-byte loads are in flight together
+    constexpr int UG = 4;
+    const int nfull = cnt / 8;  // groups with all 8 elements
+    int g = tid;
+    for (; g + (UG - 1) * 256 < nfull; g += UG * 256) {
+        float4 x0[UG], x1[UG];
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            x0[u] = *reinterpret_cast<const float4 *>(Ap + (g + u * 256) * 8);
+            x1[u] = *reinterpret_cast<const float4 *>(Ap + (g + u * 256) * 8 + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < UG; ++u) {
+            const float y[8] = {x0[u].x * inv, x0[u].y * inv, x0[u].z * inv, x0[u].w * inv,
+                                x1[u].x * inv, x1[u].y * inv, x1[u].z * inv, x1[u].w * inv};
+            finish_group((g + u * 256) * 8, 8, y);
+        }
+    }
+    for (; g < ngroups; g += 256) {
+        const int f = g * 8;
+        const int valid = min(8, cnt - f);
+        float y[8];
+        if (valid == 8) {
+            const float4 x0 = *reinterpret_cast<const float4 *>(Ap + f);
+            const float4 x1 = *reinterpret_cast<const float4 *>(Ap + f + 4);
+            y[0] = x0.x * inv; y[1] = x0.y * inv; y[2] = x0.z * inv; y[3] = x0.w * inv;
+            y[4] = x1.x * inv; y[5] = x1.y * inv; y[6] = x1.z * inv; y[7] = x1.w * inv;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) y[j] = (j < valid) ? Ap[f + j] * inv : 0.0f;
+        }
+        finish_group(f, valid, y);
     }
     __syncthreads();
 
@@ -331,8 +354,10 @@ __global__ __launch_bounds__(256) void k_dequant_i32(const int32_t *__restrict__
         out[i] = static_cast<float>(acc[i]) * sc;
 }
 
-int launch_fused(const fused_args &a, int rounding, hipStream_t st)
+int launch_fused(const fused_args &a_in, int rounding, hipStream_t st)
 {
+    fused_args a = a_in;
+    a.K_magic = static_cast<uint32_t>(((uint64_t(1) << 32) + a.K - 1) / static_cast<uint64_t>(a.K > 1 ? a.K : 2));
     const size_t lds_bytes = static_cast<size_t>(BM) * (a.Kp + LDS_PAD);
     const unsigned grid = static_cast<unsigned>((a.M + BM - 1) / BM);
     const int wl = (a.K % 4 == 0) ? 4 : ((a.K % 2 == 0) ? 2 : 1);
