@@ -47,19 +47,6 @@ __device__ static inline void tango_load_heads(const int8_t *__restrict__ table,
     }
 }
 
-// Same with a run-time head count (heads <= 8).
-__device__ static inline void tango_load_heads_rt(const int8_t *__restrict__ table, int64_t node, int heads, int (&v)[8])
-{
-    const int8_t *p = table + node * heads;
-    if (heads == 4) {
-        const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) v[h] = static_cast<int>(static_cast<int8_t>(w >> (8 * h)));
-    } else {
-        for (int h = 0; h < heads; ++h) v[h] = static_cast<int>(p[h]);
-    }
-}
-
 // Heads h0 .. h0+3 of a node (run-time head count; entries at or beyond `heads` are left zero).
 __device__ static inline void tango_load_heads4(const int8_t *__restrict__ table, int64_t node, int heads, int h0, int (&v)[4])
 {

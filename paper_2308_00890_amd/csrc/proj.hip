@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int
         red[4 + j][threadIdx.x] = active ? sd[j] : 0.0;
     }
     __syncthreads();
-    if (threadIdx.x < tpr) {  // row offset 0: my quad of columns, all row offsets
+    if (static_cast<int>(threadIdx.x) < tpr) {  // row offset 0: my quad of columns, all row offsets
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             double ts = 0.0, td = 0.0;

@@ -86,8 +86,6 @@ __device__ inline void unpack_words<16>(const uint4 &v, uint32_t (&w)[4])
     w[3] = v.w;
 }
 
-__device__ inline int sbyte(uint32_t w, int j) { return static_cast<int>(static_cast<int8_t>(w >> (8 * j))); }
-
 // Edge weights computed on the fly (fused attention, Sec. 2.1 steps 3-5): alpha of edge (u -> v), head h is
 // exp(lrelu(s_S*S_q[u][h] + s_D*D_q[v][h]) - row_lse[v][h]), quantized with the abs-max found by the statistics
 // pass; the random bits of stochastic rounding belong to the edge's destination-major position, so the forward
