@@ -10,7 +10,8 @@ namespace {
 enum { SID_H = 1, SID_W = 2, SID_HP = 3, SID_S = 4, SID_D = 5, SID_ALPHA = 6, SID_G = 7, SID_DHP = 8 };
 
 // layout of the layer workspace: 256 bytes of scalars, then the largest sub-call workspace
-enum { SC_ABSMAX_S = 0, SC_ABSMAX_D = 1, SC_ABSMAX_ALPHA = 2, SC_ABSMAX_G = 3 };
+// (S and D are updated by one kernel at the same time: kept in different 128-byte lines)
+enum { SC_ABSMAX_S = 0, SC_ABSMAX_D = 32, SC_ABSMAX_ALPHA = 16, SC_ABSMAX_G = 48 };
 
 size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 

@@ -86,31 +86,37 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
     const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / TANGO_WAVE;
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * blockDim.x / TANGO_WAVE;
     const int F = heads * dim, q = F / 4, lph = dim / 4;
+    // narrow rows (q < 64, one pass): a wave takes 64 / q rows side by side
+    const int rpw = (PASSES == 1 && q < 64) ? 64 / q : 1;
+    const int lane_row = (PASSES == 1 && q < 64) ? lane / q : 0;
+    const int lane_idx = lane - lane_row * q;
     float4 as[PASSES], ad[PASSES];
     int hd[PASSES];
     bool on[PASSES], first[PASSES];
 #pragma unroll
     for (int j = 0; j < PASSES; ++j) {
-        const int idx = 64 * j + lane;
-        on[j] = idx < q;
+        const int idx = 64 * j + lane_idx;
+        on[j] = idx < q && lane_row < rpw;
         hd[j] = idx / lph;
         first[j] = on[j] && (idx % lph) == 0;
         as[j] = on[j] ? reinterpret_cast<const float4 *>(a_src)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
         ad[j] = on[j] ? reinterpret_cast<const float4 *>(a_dst)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float ms = 0.0f, md = 0.0f;
-    for (int64_t v0 = wave * UNR; v0 < n; v0 += nwaves * UNR) {
+    for (int64_t v0 = wave * UNR * rpw; v0 < n; v0 += nwaves * UNR * rpw) {
         float4 x[UNR][PASSES];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
+            const int64_t v = v0 + u * rpw + lane_row;
 #pragma unroll
             for (int j = 0; j < PASSES; ++j) {
                 x[u][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v0 + u < n && on[j]) x[u][j] = reinterpret_cast<const float4 *>(X + (v0 + u) * F)[64 * j + lane];
+                if (v < n && on[j]) x[u][j] = reinterpret_cast<const float4 *>(X + v * F)[64 * j + lane_idx];
             }
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
+            const int64_t v = v0 + u * rpw + lane_row;
 #pragma unroll
             for (int j = 0; j < PASSES; ++j) {
                 const float4 xv = x[u][j], s = as[j], d = ad[j];
@@ -123,10 +129,10 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
                     accs += __shfl_xor(accs, o, 64);
                     accd += __shfl_xor(accd, o, 64);
                 }
-                if (v0 + u < n && first[j]) {
+                if (v < n && first[j]) {
                     const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
-                    S[(v0 + u) * heads + hd[j]] = fs;
-                    D[(v0 + u) * heads + hd[j]] = fd;
+                    S[v * heads + hd[j]] = fs;
+                    D[v * heads + hd[j]] = fd;
                     ms = fmaxf(ms, fabsf(fs));
                     md = fmaxf(md, fabsf(fd));
                 }
@@ -227,7 +233,8 @@ int tango_head_proj_async(int64_t n, int heads, int dim, const float *X, const f
     if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
     const int lph = dim / 4, q = heads * dim / 4;
     if (lph >= 1 && lph <= 64 && (lph & (lph - 1)) == 0 && q <= 256) {
-        const unsigned grid = tango_grid_for(static_cast<size_t>(n), 16, 256 * 8);
+        const int rpw = q < 64 ? 64 / q : 1;  // rows a wave takes side by side
+        const unsigned grid = tango_grid_for(static_cast<size_t>((n + rpw - 1) / rpw), 16, 256 * 8);
         if (q <= 64) k_head_proj_rows<1><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
         else if (q <= 128) k_head_proj_rows<2><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
         else k_head_proj_rows<4><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D);
