@@ -365,6 +365,18 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         nb_ahead = a.idx[c0i + lane];
         if (USE_EID) eid_ahead = a.eid[c0i + lane];
     }
+    // DS: dS of the row being walked, per lane (lanes of equal lane % HP hold parts of one head's sum); reduced over the
+    // lanes and added to dS_acc when the row changes or the chunk ends
+    double ds_run = 0.0;
+    int ds_row = -1;
+    auto flush_dS = [&]() {
+        if (DS && ds_row >= 0) {
+            double v = ds_run;
+            for (int o = 32; o >= HP; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (lane < a.heads && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(ds_row) * a.heads + lane, v);
+        }
+        ds_run = 0.0;
+    };
     for (int base = c0i; base < c1i; base += 64) {
         const int cnt = min(64, c1i - base);
         const int nb_now = nb_ahead, eid_now = eid_ahead;
@@ -613,8 +625,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         if (DS) {
             // step 4', LeakyReLU' and step 3' for the edges of the block, on the (edge, head) pairs of the record loads
             // above: dE = alpha*(dalpha - P), times the slope where the score was not positive, summed per (row segment,
-            // head) in fp64.  A lane's pairs all have the same head (64 is a multiple of HP), so one lane sum over the
-            // rounds and one reduction over the lanes of equal head serve all heads at once.
+            // head) in fp64.  A lane's pairs all have the same head (64 is a multiple of HP), so the sums of all heads
+            // build up in the lanes and one reduction over the lanes of equal head per row serves them all.
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             const int H = a.heads;
@@ -649,8 +661,12 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         const int edge = (lane_o + 64 * (g0 + j)) >> log2HP;
                         if (g0 + j < HP && edge >= k0 && edge < k1) v += contrib[j];
                     }
-                    for (int o = 32; o >= HP; o >>= 1) v += __shfl_xor(v, o, 64);
-                    if (lane < H && v != 0.0) atomicAdd(a.att.dS_acc + static_cast<int64_t>(r) * H + lane, v);
+                    // a row that runs on over many blocks (a hub) is summed in the lanes and leaves the wave once
+                    if (r != ds_row) {
+                        flush_dS();
+                        ds_row = r;
+                    }
+                    ds_run += v;
                     k0 = k1;
                 }
             }
@@ -658,6 +674,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
             __builtin_amdgcn_wave_barrier();
         }
     }
+    if (DS) flush_dS();
     if (pending) finish_row(cur_r, false);  // the last row continues in the next chunk
     if (a.absmax) {
         // max|out| over whole rows = (float)max|acc| * sc (conversion and the product are monotone)
