@@ -127,6 +127,7 @@ struct spmm_args {
     int short_max;         // rows with at most this many edges are left to k_spmm_short (0: none)
     attn_params att;       // used by the ATT instantiations only
     int relu;              // out = max(0, .)
+    int w_words;           // the head codes of an edge can be read as 32-bit words (heads 4 or 8, w 4-byte aligned)
 };
 
 // True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
@@ -499,12 +500,17 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 }
             } else {
                 const int64_t wp = (HAS_EID ? static_cast<int64_t>(eid_now) : static_cast<int64_t>(e)) * a.heads;
-                for (int hh = 0; hh < a.heads; ++hh) {
-                    const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
-                    if (hh < 4)
-                        my_w0 |= b << (8 * hh);
-                    else
-                        my_w1 |= b << (8 * (hh - 4));
+                if (a.w_words) {  // 4 or 8 heads, 4-byte aligned table: the edge's codes in one or two word loads
+                    my_w0 = *reinterpret_cast<const uint32_t *>(a.w + wp);
+                    if (a.heads == 8) my_w1 = *reinterpret_cast<const uint32_t *>(a.w + wp + 4);
+                } else {
+                    for (int hh = 0; hh < a.heads; ++hh) {
+                        const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
+                        if (hh < 4)
+                            my_w0 |= b << (8 * hh);
+                        else
+                            my_w1 |= b << (8 * (hh - 4));
+                    }
                 }
             }
         }
@@ -1035,6 +1041,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     spmm_args a;
     if (att) a.att = *att;
     a.relu = (att && direction == TANGO_IN) ? att->relu_out : 0;
+    a.w_words = (heads == 4 || heads == 8) && w_q != nullptr && tango_aligned(w_q, 4);
     a.n = g->n_nodes;
     a.nnz = g->n_edges;
     a.ptr = direction == TANGO_IN ? g->in_ptr : g->out_ptr;
