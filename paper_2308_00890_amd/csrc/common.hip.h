@@ -145,6 +145,26 @@ __device__ static inline int tango_group_sum_c(int d, int n)
     return d;
 }
 
+// Sum of a double over aligned groups of n adjacent lanes (n a power of two), result in every lane of the group: the
+// same additions as an xor-shuffle tree (the mirrored partners hold the value the xor partner holds), but up to 16
+// lanes through DPP moves of the two halves instead of LDS-pipe shuffles.  Must be called by all 64 lanes.
+__device__ static inline double tango_group_sum_f64(double v, int n)
+{
+#define TANGO_DPP_ADD_F64(CTRL)                                                                           \
+    {                                                                                                     \
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);           \
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);           \
+        v += __hiloint2double(hi, lo);                                                                    \
+    }
+    if (n >= 2) TANGO_DPP_ADD_F64(0xB1)    // quad_perm [1,0,3,2]
+    if (n >= 4) TANGO_DPP_ADD_F64(0x4E)    // quad_perm [2,3,0,1]
+    if (n >= 8) TANGO_DPP_ADD_F64(0x141)   // row_half_mirror
+    if (n >= 16) TANGO_DPP_ADD_F64(0x140)  // row_mirror
+#undef TANGO_DPP_ADD_F64
+    for (int off = 16; off < n; off <<= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
 __device__ static inline float tango_wave_max(float v)
 {
 #pragma unroll

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
                                                         float *__restrict__ S, float *__restrict__ D, float *absmax_S,
                                                         float *absmax_D)
 {
-    constexpr int UNR = 4 / PASSES;
+    constexpr int UNR = PASSES == 4 ? 2 : 4;  // rows whose loads are in flight together
     const int lane = threadIdx.x % TANGO_WAVE;
     const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) / TANGO_WAVE;
     const int64_t nwaves = static_cast<int64_t>(gridDim.x) * blockDim.x / TANGO_WAVE;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
     const int rpw = (PASSES == 1 && q < 64) ? 64 / q : 1;
     const int lane_row = (PASSES == 1 && q < 64) ? lane / q : 0;
     const int lane_idx = lane - lane_row * q;
-    float4 as[PASSES], ad[PASSES];
+    double as[PASSES][4], ad[PASSES][4];  // my slices of a_src / a_dst, widened once
     int hd[PASSES];
     bool on[PASSES], first[PASSES];
 #pragma unroll
@@ -99,8 +99,10 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
         on[j] = idx < q && lane_row < rpw;
         hd[j] = idx / lph;
         first[j] = on[j] && (idx % lph) == 0;
-        as[j] = on[j] ? reinterpret_cast<const float4 *>(a_src)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
-        ad[j] = on[j] ? reinterpret_cast<const float4 *>(a_dst)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 s4 = on[j] ? reinterpret_cast<const float4 *>(a_src)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 d4 = on[j] ? reinterpret_cast<const float4 *>(a_dst)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        as[j][0] = s4.x; as[j][1] = s4.y; as[j][2] = s4.z; as[j][3] = s4.w;
+        ad[j][0] = d4.x; ad[j][1] = d4.y; ad[j][2] = d4.z; ad[j][3] = d4.w;
     }
     float ms = 0.0f, md = 0.0f;
     for (int64_t v0 = wave * UNR * rpw; v0 < n; v0 += nwaves * UNR * rpw) {
@@ -119,16 +121,13 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
             const int64_t v = v0 + u * rpw + lane_row;
 #pragma unroll
             for (int j = 0; j < PASSES; ++j) {
-                const float4 xv = x[u][j], s = as[j], d = ad[j];
+                const float4 xv = x[u][j];
+                const double x0 = xv.x, x1 = xv.y, x2 = xv.z, x3 = xv.w;
                 double accs = 0.0, accd = 0.0;
-                accs += static_cast<double>(xv.x) * s.x + static_cast<double>(xv.y) * s.y + static_cast<double>(xv.z) * s.z +
-                        static_cast<double>(xv.w) * s.w;
-                accd += static_cast<double>(xv.x) * d.x + static_cast<double>(xv.y) * d.y + static_cast<double>(xv.z) * d.z +
-                        static_cast<double>(xv.w) * d.w;
-                for (int o = lph / 2; o > 0; o >>= 1) {
-                    accs += __shfl_xor(accs, o, 64);
-                    accd += __shfl_xor(accd, o, 64);
-                }
+                accs += x0 * as[j][0] + x1 * as[j][1] + x2 * as[j][2] + x3 * as[j][3];
+                accd += x0 * ad[j][0] + x1 * ad[j][1] + x2 * ad[j][2] + x3 * ad[j][3];
+                accs = tango_group_sum_f64(accs, lph);
+                accd = tango_group_sum_f64(accd, lph);
                 if (v < n && first[j]) {
                     const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
                     S[v * heads + hd[j]] = fs;
