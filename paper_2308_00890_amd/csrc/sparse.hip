@@ -651,7 +651,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                         const float als = alf_s[wv][edge * H + head];
                         double Pv = P_r[j];
                         if (g0 > 0) {  // more than four heads: rounds 4-7 fetch P again
-                            const int nbe = static_cast<int>(nbw_s[wv][edge].x / static_cast<uint32_t>(row_bytes));
+                            const uint4 ent = nbw_s[wv][edge];  // the neighbour's row offset, back to its index
+                            const int nbe = static_cast<int>(((static_cast<uint64_t>(ent.y) << 32) | ent.x) /
+                                                             static_cast<uint32_t>(row_bytes));
                             Pv = static_cast<const tango_attn_rec *>(a.att.rec)[static_cast<int64_t>(nbe) * HP + head].P;
                         }
                         const float dE = static_cast<float>(static_cast<double>(fabsf(als)) * (static_cast<double>(da) - Pv));
