@@ -69,7 +69,11 @@ def attention_bwd_src_launch(torch, T, G, L, heads, dim, slope, seed, sid_alpha)
     fn = lambda: T.tango_gat_attention_bwd_src(G, heads, dim, L["S_q"], L["s_S"], L["D_q"], L["s_D"], slope, L["row_lse"],
                                                L["s_alpha"], L["absmax_alpha"], T.SR, seed, sid_alpha, L["Hp_q"], L["s_Hp"],
                                                L["g_q"], L["s_g"], rec, L["dHp"], None, dS, ws_s)
-    return fn, "k_spmm<16, true, 2, false, true> (attention backward, source side: steps 5' and 3' in one walk over the out-edges)"
+    F = heads * dim
+    vec = 4 if F <= 64 else (8 if F <= 128 else 16)  # bytes of a feature row per lane, as the library picks them
+    lanes_per_head = {64: 4, 128: 8}.get(dim, 0) if vec == 16 else 0  # compile-time only for the common head widths
+    name = "k_spmm<%d, true, 2, false, true, %d>" % (vec, lanes_per_head)
+    return fn, name + " (attention backward, source side: steps 5' and 3' in one walk over the out-edges)"
 
 
 def time_events(torch, fn, iters):
