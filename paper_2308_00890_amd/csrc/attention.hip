@@ -370,6 +370,7 @@ int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const 
     int rc = attention_bwd_common_checks(g, heads, dim);
     if (rc != TANGO_OK) return rc;
     TANGO_REQUIRE(S_q && s_S && D_q && s_D && row_lse && X_q && s_X && dOut_q && s_dOut && rec && dD, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(S_q, heads == 3 ? 1 : heads) && tango_aligned(D_q, heads == 3 ? 1 : heads), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) && tango_aligned(rec, 16), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
                   TANGO_ERR_WORKSPACE);

@@ -821,6 +821,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     __shared__ int dots[WAVES_PER_BLOCK][64 * 8];
     __shared__ int nbl[WAVES_PER_BLOCK][64];
     __shared__ double red[WAVES_PER_BLOCK][ATT_DST ? 3 * 64 : 64];
+    // DOT_DST: the packed S_q codes (heads 0-3, 4-7) of the sources of a block's edges, fetched before the gathers
+    __shared__ uint2 sqw_s[ATT_DST ? WAVES_PER_BLOCK : 1][ATT_DST ? 64 : 1];
     const int lane = threadIdx.x % TANGO_WAVE;
     const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));  // wave-uniform, see k_spmm
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
@@ -851,6 +853,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
         sD = *a.sD;
     }
 
+    // the blocks of a chunk follow each other in the edge array whatever rows they belong to, so the neighbour indices
+    // of the next block can be requested while this one is gathered
+    int nb_ahead = (c0 + lane < c1) ? a.idx[c0 + lane] : 0;
     int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
     for (; r < a.n; ++r) {
         const int rb = a.ptr[r], rt = a.ptr[r + 1];
@@ -873,9 +878,30 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
         }
         for (int base = sb; base < se; base += 64) {
             const int cnt = min(64, se - base);
-            int my_nb = 0;
-            if (lane < cnt) my_nb = a.idx[base + lane];
+            const int my_nb = lane < cnt ? nb_ahead : 0;
+            if (base + cnt + lane < c1) nb_ahead = a.idx[base + cnt + lane];
             if (ATT_BWD || ATT_DST) nbl[wv][lane] = my_nb;
+            if (ATT_DST) {
+                // S_q of my edge's source, all heads, needed only after the gathers: requested now
+                uint2 w = make_uint2(0u, 0u);
+                if (lane < cnt) {
+                    const int8_t *sp = a.Sq + static_cast<int64_t>(my_nb) * H;
+                    if (H == 4) {
+                        w.x = *reinterpret_cast<const uint32_t *>(sp);
+                    } else if (H == 8) {
+                        w = *reinterpret_cast<const uint2 *>(sp);
+                    } else {
+                        for (int hh = 0; hh < H; ++hh) {
+                            const uint32_t b = static_cast<uint8_t>(sp[hh]);
+                            if (hh < 4)
+                                w.x |= b << (8 * hh);
+                            else
+                                w.y |= b << (8 * (hh - 4));
+                        }
+                    }
+                }
+                sqw_s[wv][lane] = w;
+            }
             const int steps = (cnt + G - 1) / G;
             auto batch = [&](int s0, auto uu) {
                 constexpr int UU = decltype(uu)::value;
@@ -921,9 +947,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                         const float dE = static_cast<float>(static_cast<double>(al) * (static_cast<double>(da) - rc.P));
                         acc_s += static_cast<double>(dE * (pos ? 1.0f : a.slope));
                     } else if (ATT_DST) {
-                        const int64_t uh = static_cast<int64_t>(nbl[wv][k]) * H + eh;
+                        const uint2 sw = sqw_s[wv][k];
+                        const int sq = static_cast<int>(static_cast<int8_t>((eh < 4 ? sw.x : sw.y) >> (8 * (eh & 3))));
                         bool pos;
-                        const float ev = tango_attn_score(sS * static_cast<float>(a.Sq[uh]), td_row, a.slope, pos);
+                        const float ev = tango_attn_score(sS * static_cast<float>(sq), td_row, a.slope, pos);
                         const float al = tango_attn_alpha(ev, lse_row);
                         const double ad = static_cast<double>(al) * static_cast<double>(da);
                         const double sl = pos ? 1.0 : static_cast<double>(a.slope);
