@@ -241,7 +241,7 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
 #define CALL(HH)                                                                                            \
@@ -262,7 +262,7 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
     if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st)) != TANGO_OK) return rc;

@@ -243,7 +243,7 @@ int tango_sddmm_add_async(const tango_graph *g, int heads, const int8_t *Sq, con
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
 #define CALL(HH)                                                                        \
     {                                                                                   \
         sddmm_add_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, E};                     \
@@ -261,7 +261,7 @@ int tango_sddmm_add_bwd_async(const tango_graph *g, int heads, const int8_t *Sq,
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
     if (dD || dEpre) {
 #define CALL(HH)                                                                                \
     {                                                                                           \
@@ -290,7 +290,7 @@ int tango_edge_softmax_async(const tango_graph *g, int heads, const float *E, fl
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
     if (absmax) {
         int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax), 0u, 1, st);
         if (rc != TANGO_OK) return rc;
@@ -311,7 +311,7 @@ int tango_edge_softmax_bwd_async(const tango_graph *g, int heads, const float *a
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n);
+    const unsigned grid = row_grid(n, grp);
 #define CALL(HH)                                                                \
     {                                                                           \
         softmax_bwd_op<HH> op{alpha, dalpha, dE};                               \

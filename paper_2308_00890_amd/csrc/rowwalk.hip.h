@@ -149,8 +149,11 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op,
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>((blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE));
     const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
     constexpr int RPI = 64 / GROUP;  // rows per wave-iteration
-    for (int64_t base = static_cast<int64_t>(wave) * 64; base < n; base += static_cast<int64_t>(nwaves) * 64) {
-        const int r = static_cast<int>(base) + lane;
+    // rows a wave takes per outer iteration: with a whole wave per row they are walked one after the other, each with
+    // its own chain of dependent loads, so fewer rows per wave (more waves) hide more of that latency
+    constexpr int ROWS = GROUP == 64 ? 4 : 64;
+    for (int64_t base = static_cast<int64_t>(wave) * ROWS; base < n; base += static_cast<int64_t>(nwaves) * ROWS) {
+        const int r = (lane < ROWS) ? static_cast<int>(base) + lane : n;
         int b = 0, t = 0;
         if (r < n) {
             b = ptr[r];
@@ -201,7 +204,13 @@ inline int pick_group(int n, int64_t nnz)
     return 64;
 }
 
-inline unsigned row_grid(int n) { return tango_grid_for((static_cast<size_t>(n) + 63) / 64, 4, 256 * 8); }
+// group = lanes per row as picked by pick_group (walk_rows hands a wave 16 rows per iteration when a row takes the
+// whole wave, else 64)
+inline unsigned row_grid(int n, int group = 0)
+{
+    const size_t rows = group == 64 ? 4 : 64;
+    return tango_grid_for((static_cast<size_t>(n) + rows - 1) / rows, 4, 256 * 16);
+}
 
 // Dispatch a kernel template K<H, GROUP> over the supported head counts and group sizes.
 #define TANGO_DISPATCH_HG(H_, G_, CALL)                         \
