@@ -305,7 +305,7 @@ def main():
             feat = to(li.feat) if i == 0 else layers[i - 1]["out"]
             grad = to(li.grad_out) if i == 2 else torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev)
             layers.append(T.GatLayer(G, feat, W, to(li.a_src), to(li.a_dst), grad, slope, T.SR, li.sr_seed, i,
-                                     want_dH=False, relu_out=(i < 2),
+                                     want_dH=False, relu_out=(i < 2), relu_bits=True,
                                      absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None)))
         for i in (1, 2):
             layers[i]._bind("dH", layers[i - 1]["grad_out"], torch.float32)

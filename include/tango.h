@@ -529,9 +529,14 @@ typedef struct tango_gat_layer {
      * takes grad_out as the gradient behind that ReLU: ReLU' (out > 0) is applied while grad_out is quantized, so no
      * activation kernel and no extra fp32 tensor exist between two layers; grad_out and out must then be 16-byte
      * aligned.  absmax_H: max|H| on the device if the caller already has it (the absmax_out of the layer below),
-     * else NULL - it saves the pass over H that finds it. */
+     * else NULL - it saves the pass over H that finds it.  relu_bits (optional, device, 8-byte aligned,
+     * n*heads*dim/8 bytes, written by the forward pass and read by the backward pass): one bit per output element,
+     * bit i%8 of byte i/8 set where out[i] > 0.  Where it is given, the layer is fused and a row is wider than 128
+     * columns (heads*dim in {256, 512, 1024}, dim a multiple of 16), the backward pass reads these bits instead of the
+     * fp32 `out` (1/32 of the bytes); otherwise it is ignored, in both passes alike. */
     int relu_out;
     const float *absmax_H;
+    void *relu_bits;
 } tango_gat_layer;
 
 size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim);

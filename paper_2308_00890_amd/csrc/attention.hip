@@ -18,7 +18,7 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
-                               float *out, float *absmax_out, int relu_out, hipStream_t st);
+                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, hipStream_t st);
 int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
                                       const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
@@ -289,18 +289,20 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
                             void *ws, size_t ws_bytes, void *stream)
 {
     return tango_gat_attention_fwd_act(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, rounding, seed, stream_id_alpha,
-                                       row_lse, alpha_q, s_alpha, absmax_alpha, alpha_dump, out, absmax_out, 0, ws, ws_bytes,
-                                       stream);
+                                       row_lse, alpha_q, s_alpha, absmax_alpha, alpha_dump, out, absmax_out, 0, nullptr, ws,
+                                       ws_bytes, stream);
 }
 
 }  // extern "C"
 
 // tango_gat_attention_fwd with an optional ReLU on the aggregate (relu_out != 0: out = max(0, .), absmax_out of that).
+// relu_bits (optional, 8-byte aligned, n*heads*dim/8 bytes, only where tango_spmm_relu_bits_supported): bit i of the flat
+// output is set where out[i] > 0.
 int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *ws, size_t ws_bytes, void *stream)
+                                int relu_out, void *relu_bits, void *ws, size_t ws_bytes, void *stream)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -310,6 +312,9 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
     int rc = tango_validate_spmm_shape(heads, dim);
     if (rc != TANGO_OK) return rc;
     TANGO_REQUIRE(S_q && s_S && D_q && s_D && X_q && s_X && row_lse && s_alpha && absmax_alpha && out, TANGO_ERR_NULL);
+    TANGO_REQUIRE(!relu_bits || (relu_out && tango_aligned(relu_bits, 8) &&
+                                 tango_spmm_relu_bits_supported(g->n_nodes, heads, dim)),
+                  TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
                       ws_bytes >= tango_gat_attention_workspace_bytes(g->n_nodes, g->n_edges, heads),
@@ -325,7 +330,7 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
     if (rc != TANGO_OK) return rc;
     return tango_spmm_attention_async(g, TANGO_IN, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, relu_out,
-                                      st);
+                                      static_cast<uint16_t *>(relu_bits), st);
 }
 
 extern "C" {
@@ -463,7 +468,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     else
         rc = tango_spmm_attention_async(g, TANGO_OUT, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                         seed, stream_id_alpha, nullptr, const_cast<float *>(s_alpha), nullptr, dOut_q,
-                                        s_dOut, dX_agg, absmax_dX, 0, st);
+                                        s_dOut, dX_agg, absmax_dX, 0, nullptr, st);
     if (rc != TANGO_OK || !edge_part) return rc;
     // 5'': dalpha, the only fp32 edge tensor of the backward pass
     rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);

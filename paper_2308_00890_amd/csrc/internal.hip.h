@@ -14,17 +14,26 @@ int tango_absmax_accumulate_async(const float *x, size_t n, float *out, hipStrea
 int tango_quantize_masked_async(const float *x, const float *mask, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
                                 int8_t *q, float *scale_out, float *absmax_ws, hipStream_t st);
 
+// The same with the ReLU's sign bits (bit i of mask_bits set where output i is positive); n a multiple of 8.
+int tango_quantize_bitmasked_async(const float *x, const uint8_t *mask_bits, size_t n, int rounding, uint64_t seed,
+                                   uint64_t stream_id, int8_t *q, float *scale_out, float *absmax_ws, hipStream_t st);
+
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL).
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
                              int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
                              int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream);
 
-// tango_gat_attention_fwd with an optional ReLU on the aggregate (relu_out != 0: out = max(0, .), absmax_out of that).
+// Whether the forward attention SPMM can write its ReLU's sign bits for this shape (rows wider than 128 columns).
+bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim);
+
+// tango_gat_attention_fwd with an optional ReLU on the aggregate (relu_out != 0: out = max(0, .), absmax_out of that);
+// relu_bits (optional, 8-byte aligned, n*heads*dim/8 bytes, only where tango_spmm_relu_bits_supported): bit i of the flat
+// output set where out[i] > 0.
 int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *ws, size_t ws_bytes, void *stream);
+                                int relu_out, void *relu_bits, void *ws, size_t ws_bytes, void *stream);
 
 // Quantize with a known abs-max (device float).
 int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,

@@ -21,6 +21,13 @@ size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b 
         if (rc_ != TANGO_OK) return rc_; \
     } while (0)
 
+// whether the ReLU between layers is carried as sign bits (forward SPMM epilogue writes them, backward quantize reads them)
+bool gat_uses_relu_bits(const tango_gat_layer *L)
+{
+    return L->fused && L->relu_out && L->relu_bits && tango_aligned(L->relu_bits, 8) &&
+           tango_spmm_relu_bits_supported(L->g->n_nodes, L->heads, L->dim);
+}
+
 }  // namespace
 
 extern "C" {
@@ -71,8 +78,8 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
         // steps 3-5 fused: E and alpha never reach memory in fp32
         return tango_gat_attention_fwd_act(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
                                            L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
-                                           L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out, sub, sub_bytes,
-                                           stream);
+                                           L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out,
+                                           gat_uses_relu_bits(L) ? L->relu_bits : nullptr, sub, sub_bytes, stream);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -113,9 +120,14 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
         // the gradient arrives behind the layer's ReLU: ReLU' (out > 0) is applied while it is quantized
         TANGO_REQUIRE(L->out && tango_aligned(L->grad_out, 16) && tango_aligned(L->out, 16) && tango_aligned(L->g_q, 8),
                       TANGO_ERR_BAD_SHAPE);
-        TANGO_TRY(tango_quantize_masked_async(L->grad_out, L->out, static_cast<size_t>(n * F), L->rounding, L->seed,
-                                              sid + SID_G, L->g_q, L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G,
-                                              tango_stream(stream)));
+        if (gat_uses_relu_bits(L))
+            TANGO_TRY(tango_quantize_bitmasked_async(L->grad_out, static_cast<const uint8_t *>(L->relu_bits),
+                                                     static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, L->g_q,
+                                                     L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G, tango_stream(stream)));
+        else
+            TANGO_TRY(tango_quantize_masked_async(L->grad_out, L->out, static_cast<size_t>(n * F), L->rounding, L->seed,
+                                                  sid + SID_G, L->g_q, L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G,
+                                                  tango_stream(stream)));
     } else {
         TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
                                  L->s_g, sub, sub_bytes, stream));

@@ -17,12 +17,20 @@ __device__ inline float4 tango_mask4(const float4 a, const float4 k)
     return make_float4(k.x > 0.0f ? a.x : 0.0f, k.y > 0.0f ? a.y : 0.0f, k.z > 0.0f ? a.z : 0.0f, k.w > 0.0f ? a.w : 0.0f);
 }
 
+// the same with one bit per element (bit j of `bits` for component j) instead of a float
+__device__ inline float4 tango_mask4b(const float4 a, const uint32_t bits)
+{
+    return make_float4((bits & 1u) ? a.x : 0.0f, (bits & 2u) ? a.y : 0.0f, (bits & 4u) ? a.z : 0.0f, (bits & 8u) ? a.w : 0.0f);
+}
+
 // max|x| over n floats into *out (as the bit pattern of a non-negative float; *out must start at 0).
 // VEC = 4: x is 16-byte aligned and float4 loads are used for the body.
-// MASKED: element i counts as 0 where mask[i] <= 0 (the gradient behind a ReLU whose output is `mask`).
-template <int VEC, bool MASKED = false>
+// MASKED = 1: element i counts as 0 where mask[i] <= 0 (the gradient behind a ReLU whose output is `mask`).
+// MASKED = 2: the same with mask_bits, bit i set where the ReLU's output is positive (n a multiple of 8).
+template <int VEC, int MASKED = 0>
 __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, size_t n, float *out,
-                                                const float *__restrict__ mask = nullptr)
+                                                const float *__restrict__ mask = nullptr,
+                                                const uint8_t *__restrict__ mask_bits = nullptr)
 {
     float m = 0.0f;
     const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -39,22 +47,25 @@ __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, siz
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
                 a[u] = x4[i + u * nthr];
-                if (MASKED) k[u] = k4[i + u * nthr];
+                if (MASKED == 1) k[u] = k4[i + u * nthr];
+                if (MASKED == 2) k[u].x = __uint_as_float(mask_bits[(i + u * nthr) >> 1]);
             }
 #pragma unroll
             for (int u = 0; u < UA; ++u) {
-                if (MASKED) a[u] = tango_mask4(a[u], k[u]);
+                if (MASKED == 1) a[u] = tango_mask4(a[u], k[u]);
+                if (MASKED == 2) a[u] = tango_mask4b(a[u], __float_as_uint(k[u].x) >> (4 * ((i + u * nthr) & 1)));
                 m = fmaxf(m, fmaxf(fmaxf(fabsf(a[u].x), fabsf(a[u].y)), fmaxf(fabsf(a[u].z), fabsf(a[u].w))));
             }
         }
         for (; i < n4; i += nthr) {
             float4 a = x4[i];
-            if (MASKED) a = tango_mask4(a, k4[i]);
+            if (MASKED == 1) a = tango_mask4(a, k4[i]);
+            if (MASKED == 2) a = tango_mask4b(a, static_cast<uint32_t>(mask_bits[i >> 1]) >> (4 * (i & 1)));
             m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
         }
-        for (size_t j = n4 * 4 + tid; j < n; j += nthr) m = fmaxf(m, (!MASKED || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
+        for (size_t j = n4 * 4 + tid; j < n; j += nthr) m = fmaxf(m, (MASKED != 1 || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
     } else {
-        for (size_t j = tid; j < n; j += nthr) m = fmaxf(m, (!MASKED || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
+        for (size_t j = tid; j < n; j += nthr) m = fmaxf(m, (MASKED != 1 || mask[j] > 0.0f) ? fabsf(x[j]) : 0.0f);
     }
     m = tango_wave_max(m);
     __shared__ float part[4];
@@ -88,11 +99,12 @@ __device__ inline uint2 quantize8(const float (&y)[8], const tango_rng &rng, uin
 }
 
 // Vector path: x 16-byte aligned, q 8-byte aligned.  One thread-iteration = 8 elements.
-template <int ROUNDING, bool MASKED = false>
+template <int ROUNDING, int MASKED = 0>
 __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
                                                       const float *__restrict__ absmax, tango_rng rng,
                                                       int8_t *__restrict__ q, float *scale_out,
-                                                      const float *__restrict__ mask = nullptr)
+                                                      const float *__restrict__ mask = nullptr,
+                                                      const uint8_t *__restrict__ mask_bits = nullptr)
 {
     float s, inv;
     tango_scale_from_absmax(*absmax, s, inv);
@@ -112,9 +124,14 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
         for (int u = 0; u < UNR; ++u) {
             a[u] = x4[2 * (i + u * nthr)];
             b[u] = x4[2 * (i + u * nthr) + 1];
-            if (MASKED) {
+            if (MASKED == 1) {
                 a[u] = tango_mask4(a[u], k4[2 * (i + u * nthr)]);
                 b[u] = tango_mask4(b[u], k4[2 * (i + u * nthr) + 1]);
+            }
+            if (MASKED == 2) {
+                const uint32_t kb = mask_bits[i + u * nthr];
+                a[u] = tango_mask4b(a[u], kb);
+                b[u] = tango_mask4b(b[u], kb >> 4);
             }
         }
 #pragma unroll
@@ -127,9 +144,14 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
     for (; i < n8; i += nthr) {
         float4 a = x4[2 * i];
         float4 b = x4[2 * i + 1];
-        if (MASKED) {
+        if (MASKED == 1) {
             a = tango_mask4(a, k4[2 * i]);
             b = tango_mask4(b, k4[2 * i + 1]);
+        }
+        if (MASKED == 2) {
+            const uint32_t kb = mask_bits[i];
+            a = tango_mask4b(a, kb);
+            b = tango_mask4b(b, kb >> 4);
         }
         const float y[8] = {a.x * inv, a.y * inv, a.z * inv, a.w * inv, b.x * inv, b.y * inv, b.z * inv, b.w * inv};
         q8[i] = quantize8<ROUNDING>(y, rng, i);
@@ -139,7 +161,7 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
         uint4 b = make_uint4(0, 0, 0, 0);
         if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, n8);
         for (size_t j = n8 * 8; j < n; ++j) {
-            const float xv = (!MASKED || mask[j] > 0.0f) ? x[j] : 0.0f;
+            const float xv = (MASKED != 1 || mask[j] > 0.0f) ? x[j] : 0.0f;
             q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(xv * inv, tango_bits16(b, static_cast<int>(j & 7))));
         }
     }
@@ -322,14 +344,34 @@ int tango_quantize_masked_async(const float *x, const float *mask, size_t n, int
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_ws), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
     if (n == 0) return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, absmax_ws, q, scale_out, st);
-    k_absmax<4, true><<<tango_grid_for(n / 4 + 1, 256 * 2), 256, 0, st>>>(x, n, absmax_ws, mask);
+    k_absmax<4, 1><<<tango_grid_for(n / 4 + 1, 256 * 2), 256, 0, st>>>(x, n, absmax_ws, mask);
     TANGO_LAUNCH_CHECK();
     const tango_rng rng = tango_rng_make(seed, stream_id);
     const unsigned grid = tango_grid_for(n / 8 + 1, 256 * 2);
     if (rounding == TANGO_RN)
-        k_quantize_vec<TANGO_RN, true><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
+        k_quantize_vec<TANGO_RN, 1><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
     else
-        k_quantize_vec<TANGO_SR, true><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
+        k_quantize_vec<TANGO_SR, 1><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, mask);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+// The same with the ReLU's sign bits (bit i set where output i is positive) in place of the output; n a multiple of 8.
+int tango_quantize_bitmasked_async(const float *x, const uint8_t *mask_bits, size_t n, int rounding, uint64_t seed,
+                                   uint64_t stream_id, int8_t *q, float *scale_out, float *absmax_ws, hipStream_t st)
+{
+    TANGO_REQUIRE(n % 8 == 0, TANGO_ERR_BAD_SHAPE);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_ws), 0u, 1, st);
+    if (rc != TANGO_OK) return rc;
+    if (n == 0) return tango_quantize_with_absmax_async(x, n, rounding, seed, stream_id, absmax_ws, q, scale_out, st);
+    k_absmax<4, 2><<<tango_grid_for(n / 4 + 1, 256 * 2), 256, 0, st>>>(x, n, absmax_ws, nullptr, mask_bits);
+    TANGO_LAUNCH_CHECK();
+    const tango_rng rng = tango_rng_make(seed, stream_id);
+    const unsigned grid = tango_grid_for(n / 8 + 1, 256 * 2);
+    if (rounding == TANGO_RN)
+        k_quantize_vec<TANGO_RN, 2><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, nullptr, mask_bits);
+    else
+        k_quantize_vec<TANGO_SR, 2><<<grid, 256, 0, st>>>(x, n, absmax_ws, rng, q, scale_out, nullptr, mask_bits);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }

@@ -107,6 +107,7 @@ struct attn_params {
     const void *rec;     // per destination: row_lse and P of every head
     double *dS_acc;                // n x heads, zero-initialised
     int relu_out;                  // forward: out = max(0, aggregate) (ReLU between stacked layers), absmax of that
+    uint16_t *relu_bits;           // forward, optional: one bit per output element, set where the output is positive
 };
 
 enum { W_LOAD = 0, W_ATT_FWD = 1, W_ATT_REV = 2 };
@@ -127,6 +128,7 @@ struct spmm_args {
     int short_max;         // rows with at most this many edges are left to k_spmm_short (0: none)
     attn_params att;       // used by the ATT instantiations only
     int relu;              // out = max(0, .)
+    uint16_t *relu_bits;   // with relu, optional: bit i = (out[i] > 0) over the flat n x F output (F % 64 == 0, 16 columns per lane)
     int w_words;           // the head codes of an edge can be read as 32-bit words (heads 4 or 8, w 4-byte aligned)
 };
 
@@ -156,6 +158,10 @@ __global__ __launch_bounds__(256) void k_spmm_prepare(spmm_args a)
             mask &= mask - 1;
             float *row = a.out + (base + k) * a.F;
             for (int c = lane; c < a.F; c += 64) row[c] = 0.0f;
+            if (a.relu_bits) {
+                uint16_t *bits = a.relu_bits + (base + k) * (a.F / 16);
+                for (int c = lane; c < a.F / 16; c += 64) bits[c] = 0;
+            }
         }
     }
 }
@@ -183,6 +189,11 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
                 const float o = static_cast<float>(acc) * sc;
                 row[c] = o;
                 m = fmaxf(m, fabsf(o));
+                if (a.relu_bits) {  // F is a multiple of 64 here: the 64 lanes' signs are one aligned 64-bit word
+                    const unsigned long long w = __ballot(acc > 0);
+                    if (lane == 0)
+                        *reinterpret_cast<unsigned long long *>(a.relu_bits + ((base + k) * a.F + (c - lane)) / 16) = w;
+                }
             }
         }
     }
@@ -217,7 +228,7 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 // LPHC (DS only): lanes per head when known at compile time (0: computed from the arguments), so that the lane-group
 // sums in the gather loop carry no branches.
 template <int VEC, bool HAS_EID, int WMODE, bool X4 = false, bool DS = false, int LPHC = 0>
-__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 0 ? 5 : 4))) void k_spmm(spmm_args a)
+__global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WMODE == 2 ? 4 : 5))) void k_spmm(spmm_args a)
 {
     constexpr int CPL = X4 ? 2 * VEC : VEC;  // columns per lane
     static_assert(!DS || (WMODE == W_ATT_REV && !X4), "the fused dS path belongs to the reverse attention mode");
@@ -319,12 +330,16 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
         if (whole) {
             if (gi == 0) {
                 float *orow = a.out + static_cast<int64_t>(r) * a.F + col;
+                uint32_t bits = 0;
 #pragma unroll
                 for (int j = 0; j < CPL; j += 4) {
                     float4 o;
                     if (WMODE == W_ATT_FWD && a.relu) {  // sc > 0: the sign of the sum is the sign of the output
 #pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) acc[j + jj] = max(acc[j + jj], 0);
+                        for (int jj = 0; jj < 4; ++jj) {
+                            acc[j + jj] = max(acc[j + jj], 0);
+                            if (CPL == 16) bits |= static_cast<uint32_t>(min(acc[j + jj], 1)) << (j + jj);
+                        }
                     }
                     o.x = static_cast<float>(acc[j + 0]) * sc;
                     o.y = static_cast<float>(acc[j + 1]) * sc;
@@ -333,6 +348,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                     *reinterpret_cast<float4 *>(orow + j) = o;
                     maxabs = max(maxabs, max(max(abs(acc[j]), abs(acc[j + 1])), max(abs(acc[j + 2]), abs(acc[j + 3]))));
                 }
+                if (WMODE == W_ATT_FWD && CPL == 16 && a.relu_bits)  // 16 columns per lane: one halfword of sign bits
+                    a.relu_bits[(static_cast<uint32_t>(r) * static_cast<uint32_t>(a.F / 16)) + (col >> 4)] = static_cast<uint16_t>(bits);
             }
         } else {
             // Row cut by a chunk boundary: int32 atomics.  The sums are first laid out by column in this
@@ -1063,6 +1080,15 @@ int validate_feature_shape(int heads, int dim)
 
 }  // namespace
 
+// The forward attention SPMM can also write its ReLU's sign bits when every lane holds 16 columns (one 16-bit store per
+// lane) and a row is a whole number of 64-bit words.
+bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim)
+{
+    const int F = heads * dim;
+    return validate_feature_shape(heads, dim) == TANGO_OK && F % 64 == 0 && pick_vec(F, dim, false) == 16 &&
+           n_nodes * (F / 16) < (int64_t(1) << 32);  // halfword index kept in 32 bits
+}
+
 static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
                        const int8_t *X_q, const float *s_X, float *out, float *absmax_out, const attn_params *att,
                        hipStream_t st, bool x4 = false)
@@ -1070,6 +1096,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     spmm_args a;
     if (att) a.att = *att;
     a.relu = (att && direction == TANGO_IN) ? att->relu_out : 0;
+    a.relu_bits = (a.relu && att->relu_bits && tango_spmm_relu_bits_supported(g->n_nodes, heads, dim)) ? att->relu_bits : nullptr;
     a.w_words = (heads == 4 || heads == 8) && w_q != nullptr && tango_aligned(w_q, 4);
     a.n = g->n_nodes;
     a.nnz = g->n_edges;
@@ -1172,10 +1199,11 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
-                               float *out, float *absmax_out, int relu_out, hipStream_t st)
+                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, hipStream_t st)
 {
     attn_params att;
     att.relu_out = relu_out;
+    att.relu_bits = relu_bits;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
@@ -1202,7 +1230,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
-    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0;
+    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0; att.relu_bits = nullptr;
     rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st);
     if (rc != TANGO_OK) return rc;
     k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);

@@ -198,13 +198,16 @@ def test_three_layer_gat_chain(T):
         verify_gat_layer(o, g, feat, W, a_s, a_d, gout, slope, orc.SR, seed, i, True, chain=False)
 
 
-@pytest.mark.parametrize("fused", [True, False])
-def test_three_layer_gat_chain_activation_inside_the_layers(T, fused):
+@pytest.mark.parametrize("mode", ["fused", "fused, sign bits", "primitive by primitive"])
+def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
     """The same stack with the ReLU inside the layers: a layer writes max(0, aggregate) from its SPMM epilogue and
     hands its abs-max to the next layer's GEMM; the next layer's input gradient is the previous layer's grad_out, and
-    ReLU' is applied while that gradient is quantized.  No activation kernel runs and no tensor sits between layers."""
+    ReLU' is applied while that gradient is quantized.  No activation kernel runs and no tensor sits between layers.
+    With sign bits the forward epilogue also writes one bit per output element and the backward pass reads those
+    instead of the fp32 output: same results, bit for bit."""
     import torch
 
+    fused, bits = mode != "primitive by primitive", mode == "fused, sign bits"
     g = ti.rmat_graph(2500, 40000, seed=31)
     heads, dim, widths = 3, 128, [100, 384, 384]
     F = heads * dim
@@ -221,8 +224,10 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, fused):
         W, a_s, a_d = params[i]
         feat = dev(x0) if i == 0 else layers[i - 1]["out"]
         L = T.GatLayer(G, feat, dev(W), dev(a_s), dev(a_d), grads[i], slope, orc.SR, seed, i, fused=fused, keep_alpha=True,
-                       keep_alpha_q=True, alias_E_alpha=False, relu_out=(i < 2),
+                       keep_alpha_q=True, alias_E_alpha=False, relu_out=(i < 2), relu_bits=bits,
                        absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None))
+        if bits and i < 2:
+            L["relu_bits"].fill_(0xA5)  # stale contents must not survive the forward pass
         if i > 0:  # this layer's input gradient is the gradient behind the previous layer's ReLU
             L._bind("dH", grads[i - 1], torch.float32)
         layers.append(L)
@@ -236,8 +241,30 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, fused):
         W, a_s, a_d = params[i]
         feat = x0 if i == 0 else host(layers[i - 1]["out"])
         assert i == 0 or feat.min() >= 0
+        if bits and i < 2:
+            got = np.unpackbits(o["relu_bits"], bitorder="little")[: g.n_nodes * F].reshape(g.n_nodes, F)
+            assert_bit_exact(got, (o["out"] > 0).astype(np.uint8), "ReLU sign bits")
         verify_gat_layer(o, g, feat, W, a_s, a_d, host(grads[i]), slope, orc.SR, seed, i, fused, chain=False,
                          relu_out=(i < 2))
+
+
+def test_relu_sign_bits_are_ignored_for_narrow_rows(T):
+    """Rows of at most 128 columns have no sign-bit path: the buffer is left alone and the results do not change."""
+    import torch
+
+    li, slope = gat_case("toy")
+    G = T.Graph.from_host(li.graph)
+    args = (G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, orc.SR, li.sr_seed, 0)
+    A = T.GatLayer(*args, relu_out=True)
+    B = T.GatLayer(*args, relu_out=True, relu_bits=True)
+    B["relu_bits"].fill_(0x5A)
+    for L in (A, B):
+        T.tango_gat_layer_fwd(L)
+        T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    assert (host(B["relu_bits"]) == 0x5A).all()
+    for name in ("out", "g_q", "dW", "dH"):
+        assert_bit_exact(host(B[name]), host(A[name]), name)
 
 
 def test_fused_gat_layer_without_edge_caches(T):
