@@ -165,6 +165,27 @@ __device__ static inline double tango_group_sum_f64(double v, int n)
     return v;
 }
 
+// Sum of a double over the lanes of a wave that share lane % stride (stride a power of two, wave-uniform), result in
+// every lane: rotations inside the rows of 16 lanes through DPP moves of the two halves, then two xor shuffles.
+// Must be called by all 64 lanes.
+__device__ static inline double tango_stride_sum_f64(double v, int stride)
+{
+#define TANGO_DPP_ROR_ADD_F64(CTRL)                                                                       \
+    {                                                                                                     \
+        const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);           \
+        const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);           \
+        v += __hiloint2double(hi, lo);                                                                    \
+    }
+    if (stride <= 1) TANGO_DPP_ROR_ADD_F64(0x121)  // row_ror:1
+    if (stride <= 2) TANGO_DPP_ROR_ADD_F64(0x122)  // row_ror:2
+    if (stride <= 4) TANGO_DPP_ROR_ADD_F64(0x124)  // row_ror:4
+    if (stride <= 8) TANGO_DPP_ROR_ADD_F64(0x128)  // row_ror:8
+#undef TANGO_DPP_ROR_ADD_F64
+    if (stride <= 16) v += __shfl_xor(v, 16, 64);
+    if (stride <= 32) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 __device__ static inline float tango_wave_max(float v)
 {
 #pragma unroll

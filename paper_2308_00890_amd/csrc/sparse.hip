@@ -837,7 +837,7 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     // per wave: the dot products of a block of 64 edges (edge-major, heads <= 8) and the neighbours of those edges
     __shared__ int dots[WAVES_PER_BLOCK][64 * 8];
     __shared__ int nbl[WAVES_PER_BLOCK][64];
-    __shared__ double red[WAVES_PER_BLOCK][ATT_DST ? 3 * 64 : 64];
+    __shared__ double red[ATT_BWD ? WAVES_PER_BLOCK : 1][64];
     // DOT_DST: the packed S_q codes (heads 0-3, 4-7) of the sources of a block's edges, fetched before the gathers
     __shared__ uint2 sqw_s[ATT_DST ? WAVES_PER_BLOCK : 1][ATT_DST ? 64 : 1];
     const int lane = threadIdx.x % TANGO_WAVE;
@@ -859,11 +859,15 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     const float sc = (*a.s_dst) * (*a.s_src);
     constexpr int U = 8;
     // epilogue mapping: lane l < S handles the (edge, head) pairs l, l+S, l+2S, ... of a block, S a multiple of
-    // the head count so that a lane always sees the same head
-    const int S = (64 / H) * H;
-    const int eh = lane % H;       // my head in the epilogue
-    const int ek0 = lane / H;      // my first edge of a block
-    const int ekstep = S / H;
+    // the head count so that a lane always sees the same head.  DOT_DST: the head count is padded to a power of two
+    // (lanes of a padding head idle), so that the lanes of one head are a fixed stride apart and the row sums can be
+    // formed by lane rotations
+    const int HP = ATT_DST ? tango_rec_heads(H) : H;
+    const int S = (64 / HP) * HP;
+    const int eh = lane % HP;      // my head in the epilogue
+    const int ek0 = lane / HP;     // my first edge of a block
+    const int ekstep = S / HP;
+    const bool ep_on = lane < S && eh < H;
     float sS = 0.0f, sD = 0.0f;
     if (ATT_BWD || ATT_DST) {
         sS = *a.sS;
@@ -874,8 +878,17 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     // of the next block can be requested while this one is gathered
     int nb_ahead = (c0 + lane < c1) ? a.idx[c0 + lane] : 0;
     int r = wave_find_row(a.ptr, a.n, static_cast<int>(c0));
+    // row ends of 64 rows at a time in the lanes (one coalesced load instead of a dependent scalar load per row)
+    int win_r0 = r;
+    int win_end = (win_r0 + lane < a.n) ? a.ptr[win_r0 + lane + 1] : 0x7fffffff;
+    int rb_next = a.ptr[r];
     for (; r < a.n; ++r) {
-        const int rb = a.ptr[r], rt = a.ptr[r + 1];
+        if (r - win_r0 >= 64) {
+            win_r0 = r;
+            win_end = (win_r0 + lane < a.n) ? a.ptr[win_r0 + lane + 1] : 0x7fffffff;
+        }
+        const int rb = rb_next, rt = __builtin_amdgcn_readlane(win_end, r - win_r0);
+        rb_next = rt;
         if (rb >= c1) break;
         const int sb = max(rb, static_cast<int>(c0)), se = min(rt, static_cast<int>(c1));
         if (sb >= se) continue;
@@ -884,15 +897,15 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
             const V dv = *reinterpret_cast<const V *>(a.Xdst + static_cast<int64_t>(r) * a.F + (active ? col : 0));
             unpack_words<VEC>(dv, dw);
         }
-        float ts_row = 0.0f;
-        double acc_s = 0.0;
-        if (ATT_BWD && lane < S) ts_row = sS * static_cast<float>(a.Sq[static_cast<int64_t>(r) * H + eh]);
         float td_row = 0.0f, lse_row = 0.0f;
-        double acc_a = 0.0, acc_b = 0.0, acc_c = 0.0;
-        if (ATT_DST && lane < S) {
+        if (ATT_DST && ep_on) {
             td_row = sD * static_cast<float>(a.Dq[static_cast<int64_t>(r) * H + eh]);
             lse_row = a.row_lse[static_cast<int64_t>(r) * H + eh];
         }
+        float ts_row = 0.0f;
+        double acc_s = 0.0;
+        if (ATT_BWD && lane < S) ts_row = sS * static_cast<float>(a.Sq[static_cast<int64_t>(r) * H + eh]);
+        double acc_a = 0.0, acc_b = 0.0, acc_c = 0.0;
         for (int base = sb; base < se; base += 64) {
             const int cnt = min(64, se - base);
             const int my_nb = lane < cnt ? nb_ahead : 0;
@@ -920,15 +933,18 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                 sqw_s[wv][lane] = w;
             }
             const int steps = (cnt + G - 1) / G;
-            auto batch = [&](int s0, auto uu) {
+            auto batch = [&](int s0, auto uu, auto masked) {
                 constexpr int UU = decltype(uu)::value;
+                constexpr bool MASKED = decltype(masked)::value;  // the last steps of a block may lie beyond its edges
                 int dot[UU];
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
                     const int k = (s0 + u) * G + gi;
                     const bool ok = active && k < cnt;
                     const int nb = __shfl(my_nb, ok ? k : 0, 64);
-                    const V xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
+                    V xv = V();
+                    if (!MASKED || ok)
+                        xv = *reinterpret_cast<const V *>(a.Xsrc + static_cast<int64_t>(nb) * a.F + (active ? col : 0));
                     uint32_t w[VEC / 4];
                     unpack_words<VEC>(xv, w);
                     int d = 0;
@@ -945,13 +961,19 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                     if (active && k < cnt && (li % LPH) == 0) dots[wv][k * H + h] = d;
                 }
             };
+            // whole batches of U steps, then what is left in one more batch (2, 4 or U steps, the excess masked): a
+            // short row costs two rounds of gathers, not one per pair of steps
+            const int full_steps = cnt / G;  // steps in which every group has an edge
             int s0 = 0;
-            for (; s0 + U <= steps; s0 += U) batch(s0, std::integral_constant<int, U>{});
-            for (; s0 < steps; s0 += 2) batch(s0, std::integral_constant<int, 2>{});
+            for (; s0 + U <= full_steps; s0 += U) batch(s0, std::integral_constant<int, U>{}, std::false_type{});
+            const int left = steps - s0;
+            if (left > 4) batch(s0, std::integral_constant<int, U>{}, std::true_type{});
+            else if (left > 2) batch(s0, std::integral_constant<int, 4>{}, std::true_type{});
+            else if (left > 0) batch(s0, std::integral_constant<int, 2>{}, std::true_type{});
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             // epilogue at full lane occupancy: one (edge, head) pair per lane and step
-            if (lane < S) {
+            if (ep_on) {
                 for (int k = ek0; k < cnt; k += ekstep) {
                     const float da = static_cast<float>(dots[wv][k * H + eh]) * sc;
                     if (ATT_BWD) {
@@ -983,19 +1005,15 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
             __builtin_amdgcn_wave_barrier();
         }
         if (ATT_DST) {
-            red[wv][lane] = (lane < S) ? acc_a : 0.0;
-            red[wv][64 + lane] = (lane < S) ? acc_b : 0.0;
-            red[wv][128 + lane] = (lane < S) ? acc_c : 0.0;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            if (lane < 3 * H) {  // lane = 3*head + which sum
-                const int hd = lane / 3, w = lane - 3 * hd;
-                double t = 0.0;
-                for (int l = hd; l < S; l += H) t += red[wv][64 * w + l];
-                if (t != 0.0) atomicAdd(a.stats + (static_cast<int64_t>(r) * H + hd) * 3 + w, t);
+            // the lanes of one head are HP apart: after the rotations every lane holds its head's three sums
+            const double ta = tango_stride_sum_f64(acc_a, HP);
+            const double tb = tango_stride_sum_f64(acc_b, HP);
+            const double tc = tango_stride_sum_f64(acc_c, HP);
+            const int w = lane / HP;  // lane = HP*(which sum) + head
+            if (w < 3 && eh < H) {
+                const double t = w == 0 ? ta : (w == 1 ? tb : tc);
+                if (t != 0.0) atomicAdd(a.stats + (static_cast<int64_t>(r) * H + eh) * 3 + w, t);
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            __builtin_amdgcn_wave_barrier();
         }
         if (ATT_BWD) {
             // sum the lanes that share a head (lanes eh, eh+H, ...), in lane order
