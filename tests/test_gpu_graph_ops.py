@@ -35,6 +35,8 @@ def graph(name):
             g = ti.rmat_graph(30011, 90000, seed=12)
         elif name == "holes":  # no self-loops: nodes without in-edges and nodes without out-edges
             g = ti.rmat_graph(5000, 20000, seed=13, self_loops=False)
+        elif name == "dense":  # mean degree ~100: the kernels that switch on the mean degree take their long-row paths
+            g = ti.rmat_graph(600, 60000, seed=14)
         elif name == "one":
             g = ti.graph_from_edges(1, [], [], self_loops=True)
         else:
