@@ -305,7 +305,7 @@ def main():
             feat = to(li.feat) if i == 0 else layers[i - 1]["out"]
             grad = to(li.grad_out) if i == 2 else torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev)
             layers.append(T.GatLayer(G, feat, W, to(li.a_src), to(li.a_dst), grad, slope, T.SR, li.sr_seed, i,
-                                     want_dH=False, relu_out=(i < 2), relu_bits=True,
+                                     want_dH=False, relu_out=(i < 2), relu_bits=True, src_codes=True,
                                      absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None)))
         for i in (1, 2):
             layers[i]._bind("dH", layers[i - 1]["grad_out"], torch.float32)
@@ -320,7 +320,8 @@ def main():
         spmm, spmm_name = attention_bwd_src_launch(torch, T, G, L, heads, li.dim, slope, li.sr_seed, 16 * 2 + 6)
         alg = attention_bwd_src_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     else:
-        L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0)
+        L = T.GatLayer(G, to(li.feat), to(li.weight), to(li.a_src), to(li.a_dst), to(li.grad_out), slope, T.SR, li.sr_seed, 0,
+                       src_codes=True)
         step = lambda: (T.tango_gat_layer_fwd(L), T.tango_gat_layer_bwd(L))
         heads, F = li.heads, li.heads * li.dim
         # the kernel with the largest share of the step: the source-side walk of the attention backward (steps 5' and 3'

@@ -537,6 +537,11 @@ typedef struct tango_gat_layer {
     int relu_out;
     const float *absmax_H;
     void *relu_bits;
+    /* Optional cache of the fused layer (device, 8-byte aligned, n_edges*heads bytes, else NULL): the forward pass's first
+     * walk over the in-edges leaves S_q[src(e)] of every edge here, in edge order, and its second walk and the backward
+     * pass's walk over the in-edges read that stream instead of gathering from S_q once more per edge (Sec. 3.3's
+     * caching of quantized tensors between operators, applied to a gathered tensor).  Results do not change. */
+    int8_t *src_codes;
 } tango_gat_layer;
 
 size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim);

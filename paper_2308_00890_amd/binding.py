@@ -533,7 +533,7 @@ class tango_gat_layer(ctypes.Structure):
             "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
             "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst")]
         + [("fused", _int), ("row_lse", _vp), ("absmax_alpha", _vp), ("ws", _vp), ("ws_bytes", _sz),
-           ("relu_out", _int), ("absmax_H", _vp), ("relu_bits", _vp)]
+           ("relu_out", _int), ("absmax_H", _vp), ("relu_bits", _vp), ("src_codes", _vp)]
     )
 
 
@@ -611,7 +611,7 @@ class GatLayer(_LayerBuffers):
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
                  want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False, keep_dalpha=False,
-                 relu_out=False, absmax_H=None, relu_bits=False):
+                 relu_out=False, absmax_H=None, relu_bits=False, src_codes=False):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -642,6 +642,8 @@ class GatLayer(_LayerBuffers):
             self._bind("absmax_H", absmax_H, f32)
         c.fused = 1 if fused else 0
         if fused:
+            if src_codes:
+                self._alloc("src_codes", (nnz, heads), i8)
             self._alloc("row_lse", (n, heads), f32)
             self._alloc("absmax_alpha", (1,), f32)
             if keep_alpha:

@@ -18,7 +18,8 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
-                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, hipStream_t st);
+                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, const int8_t *src_codes,
+                               hipStream_t st);
 int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
                                       const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
@@ -28,7 +29,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, hipStream_t st);
+                                   float *dD, const int8_t *src_codes, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -50,6 +51,7 @@ struct attn_stats_op {
     float sS, sD, slope;
     float *row_lse;
     float amax;
+    int8_t *src_codes;  // optional: S_q of every edge's source, in edge order (written here, read by the later walks)
     template <class Team>
     __device__ void run(int row, int b, int t, Team tm)
     {
@@ -73,6 +75,10 @@ struct attn_stats_op {
             int sq[UE][H];
 #pragma unroll
             for (int u = 0; u < UE; ++u) tango_load_heads<H>(Sq, nb[u], sq[u]);
+            if (src_codes) {
+#pragma unroll
+                for (int u = 0; u < UE; ++u) tango_store_heads<H>(src_codes, e + u * tm.size(), sq[u]);
+            }
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 float ev[UE];
@@ -93,6 +99,7 @@ struct attn_stats_op {
         for (; e < t; e += tm.size()) {
             int sq[H];
             tango_load_heads<H>(Sq, src[e], sq);
+            if (src_codes) tango_store_heads<H>(src_codes, e, sq);
 #pragma unroll
             for (int h = 0; h < H; ++h) {
                 bool pos;
@@ -258,7 +265,7 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
 
 int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
                            const float *sD, float slope, float *row_lse, float *absmax_alpha,
-                           int *huge, hipStream_t st)
+                           int *huge, int8_t *src_codes, hipStream_t st)
 {
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
@@ -268,7 +275,7 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
     if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st)) != TANGO_OK) return rc;
 #define CALL(HH)                                                                                             \
     {                                                                                                        \
-        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f};                    \
+        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f, src_codes};         \
         k_attn_stats<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge);         \
         k_attn_stats_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, absmax_alpha, huge); \
     }
@@ -289,8 +296,8 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
                             void *ws, size_t ws_bytes, void *stream)
 {
     return tango_gat_attention_fwd_act(g, heads, dim, S_q, s_S, D_q, s_D, slope, X_q, s_X, rounding, seed, stream_id_alpha,
-                                       row_lse, alpha_q, s_alpha, absmax_alpha, alpha_dump, out, absmax_out, 0, nullptr, ws,
-                                       ws_bytes, stream);
+                                       row_lse, alpha_q, s_alpha, absmax_alpha, alpha_dump, out, absmax_out, 0, nullptr, nullptr,
+                                       ws, ws_bytes, stream);
 }
 
 }  // extern "C"
@@ -298,11 +305,14 @@ int tango_gat_attention_fwd(const tango_graph *g, int heads, int dim, const int8
 // tango_gat_attention_fwd with an optional ReLU on the aggregate (relu_out != 0: out = max(0, .), absmax_out of that).
 // relu_bits (optional, 8-byte aligned, n*heads*dim/8 bytes, only where tango_spmm_relu_bits_supported): bit i of the flat
 // output is set where out[i] > 0.
+// src_codes (optional, 8-byte aligned, n_edges*heads bytes): receives S_q[src(e)] of every in-edge e, in edge order, from the
+// statistics pass; the aggregation pass (and the backward pass, if handed the same buffer) then reads these in a
+// stream instead of gathering from S_q once more per edge.
 int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *relu_bits, void *ws, size_t ws_bytes, void *stream)
+                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -315,7 +325,7 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
     TANGO_REQUIRE(!relu_bits || (relu_out && tango_aligned(relu_bits, 8) &&
                                  tango_spmm_relu_bits_supported(g->n_nodes, heads, dim)),
                   TANGO_ERR_BAD_SHAPE);
-    TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16) && tango_aligned(src_codes, 8), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
                       ws_bytes >= tango_gat_attention_workspace_bytes(g->n_nodes, g->n_edges, heads),
                   TANGO_ERR_WORKSPACE);
@@ -326,11 +336,11 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
         rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(s_alpha), 0x3f800000u, 1, st);
         if (rc != TANGO_OK) return rc;
     }
-    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, huge, st);
+    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, huge, src_codes, st);
     if (rc != TANGO_OK) return rc;
     return tango_spmm_attention_async(g, TANGO_IN, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, relu_out,
-                                      static_cast<uint16_t *>(relu_bits), st);
+                                      static_cast<uint16_t *>(relu_bits), src_codes, st);
 }
 
 extern "C" {
@@ -380,7 +390,7 @@ int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const 
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
                   TANGO_ERR_WORKSPACE);
     return tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse,
-                                          static_cast<double *>(ws), rec, dD,
+                                          static_cast<double *>(ws), rec, dD, nullptr,
                                           tango_stream(stream));
 }
 
@@ -414,6 +424,22 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
                             const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha, float *dS, float *dD,
                             void *ws, size_t ws_bytes, void *stream)
 {
+    return tango_gat_attention_bwd_cached(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, alpha_q, s_alpha, absmax_alpha,
+                                          rounding, seed, stream_id_alpha, X_q, s_X, dOut_q, s_dOut, dX_agg, absmax_dX, dalpha,
+                                          dS, dD, nullptr, ws, ws_bytes, stream);
+}
+
+}  // extern "C"
+
+// tango_gat_attention_bwd with the edge-ordered source codes the forward pass left (src_codes, may be NULL): the walk over
+// the in-edges then reads them in a stream instead of gathering from S_q.
+int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                   const int8_t *D_q, const float *s_D, float slope, const float *row_lse,
+                                   const int8_t *alpha_q, const float *s_alpha, const float *absmax_alpha, int rounding,
+                                   uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
+                                   const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
+                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream)
+{
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
     TANGO_REQUIRE(g->n_nodes > 0 && g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
@@ -428,7 +454,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     TANGO_REQUIRE(!edge_part || (dS && dD), TANGO_ERR_NULL);
     TANGO_REQUIRE(!(alpha_q && edge_part && g->n_edges > 0 && !dalpha), TANGO_ERR_NULL);  // the cached-codes path keeps dalpha
     TANGO_REQUIRE(tango_aligned(dX_agg, 16) && tango_aligned(X_q, 16) && tango_aligned(dOut_q, 16) &&
-                      tango_aligned(dalpha, 16),
+                      tango_aligned(dalpha, 16) && tango_aligned(src_codes, 8),
                   TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(tango_aligned(S_q, heads == 3 ? 1 : heads) && tango_aligned(D_q, heads == 3 ? 1 : heads), TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) &&
@@ -444,7 +470,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     if (edge_part && !alpha_q && !dalpha) {
         // no edge tensor at all: 5'', 4', 3'' in one walk over the in-edges, then 5' and 3' in one walk over the out-edges
         rc = tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse, stats,
-                                            rec, dD, st);
+                                            rec, dD, src_codes, st);
         if (rc != TANGO_OK) return rc;
         return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                                  stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
@@ -468,7 +494,7 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     else
         rc = tango_spmm_attention_async(g, TANGO_OUT, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                         seed, stream_id_alpha, nullptr, const_cast<float *>(s_alpha), nullptr, dOut_q,
-                                        s_dOut, dX_agg, absmax_dX, 0, nullptr, st);
+                                        s_dOut, dX_agg, absmax_dX, 0, nullptr, nullptr, st);
     if (rc != TANGO_OK || !edge_part) return rc;
     // 5'': dalpha, the only fp32 edge tensor of the backward pass
     rc = tango_sddmm_dot_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, dalpha, st);
@@ -479,4 +505,4 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
     return tango_attn_bwd_src_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, rec, dS_acc, dS, st);
 }
 
-}  // extern "C"
+

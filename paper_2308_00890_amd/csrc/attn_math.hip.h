@@ -47,6 +47,31 @@ __device__ static inline void tango_load_heads(const int8_t *__restrict__ table,
     }
 }
 
+// The reverse: the H codes in v become entry `node` of a table (aligned like the table of tango_load_heads).
+template <int H>
+__device__ static inline void tango_store_heads(int8_t *__restrict__ table, int64_t node, const int (&v)[H])
+{
+    int8_t *p = table + node * H;
+    if constexpr (H == 4 || H == 8) {
+        uint32_t w[H / 4];
+#pragma unroll
+        for (int q = 0; q < H / 4; ++q) {
+            w[q] = 0;
+#pragma unroll
+            for (int h = 0; h < 4; ++h) w[q] |= (static_cast<uint32_t>(v[4 * q + h]) & 0xffu) << (8 * h);
+        }
+        if constexpr (H == 4)
+            *reinterpret_cast<uint32_t *>(p) = w[0];
+        else
+            *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
+    } else if constexpr (H == 2) {
+        *reinterpret_cast<uint16_t *>(p) = static_cast<uint16_t>((static_cast<uint32_t>(v[0]) & 0xffu) | ((static_cast<uint32_t>(v[1]) & 0xffu) << 8));
+    } else {
+#pragma unroll
+        for (int h = 0; h < H; ++h) p[h] = static_cast<int8_t>(v[h]);
+    }
+}
+
 // Heads h0 .. h0+3 of a node (run-time head count; entries at or beyond `heads` are left zero).
 __device__ static inline void tango_load_heads4(const int8_t *__restrict__ table, int64_t node, int heads, int h0, int (&v)[4])
 {

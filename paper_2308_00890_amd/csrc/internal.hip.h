@@ -28,12 +28,21 @@ bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim);
 
 // tango_gat_attention_fwd with an optional ReLU on the aggregate (relu_out != 0: out = max(0, .), absmax_out of that);
 // relu_bits (optional, 8-byte aligned, n*heads*dim/8 bytes, only where tango_spmm_relu_bits_supported): bit i of the flat
-// output set where out[i] > 0.
+// output set where out[i] > 0.  src_codes (optional, 8-byte aligned, n_edges*heads bytes): receives S_q[src(e)] of every
+// in-edge in edge order; the aggregation pass and tango_gat_attention_bwd_cached read it instead of gathering from S_q.
 int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *relu_bits, void *ws, size_t ws_bytes, void *stream);
+                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream);
+
+// tango_gat_attention_bwd with the edge-ordered source codes the forward pass left (src_codes, may be NULL).
+int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
+                                   const int8_t *D_q, const float *s_D, float slope, const float *row_lse,
+                                   const int8_t *alpha_q, const float *s_alpha, const float *absmax_alpha, int rounding,
+                                   uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
+                                   const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
+                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream);
 
 // Quantize with a known abs-max (device float).
 int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,

@@ -79,7 +79,8 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
         return tango_gat_attention_fwd_act(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
                                            L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
                                            L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out,
-                                           gat_uses_relu_bits(L) ? L->relu_bits : nullptr, sub, sub_bytes, stream);
+                                           gat_uses_relu_bits(L) ? L->relu_bits : nullptr, L->src_codes, sub, sub_bytes,
+                                           stream);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -134,10 +135,10 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     }
     if (L->fused) {
         // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
-        TANGO_TRY(tango_gat_attention_bwd(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,
-                                          L->alpha_q, L->s_alpha, L->absmax_alpha, L->rounding, L->seed, sid + SID_ALPHA,
-                                          L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp, nullptr, L->dalpha, L->dS, L->dD, sub,
-                                          sub_bytes, stream));
+        TANGO_TRY(tango_gat_attention_bwd_cached(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,
+                                                 L->alpha_q, L->s_alpha, L->absmax_alpha, L->rounding, L->seed,
+                                                 sid + SID_ALPHA, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp, nullptr, L->dalpha,
+                                                 L->dS, L->dD, L->src_codes, sub, sub_bytes, stream));
     } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
     TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,

@@ -108,6 +108,7 @@ struct attn_params {
     double *dS_acc;                // n x heads, zero-initialised
     int relu_out;                  // forward: out = max(0, aggregate) (ReLU between stacked layers), absmax of that
     uint16_t *relu_bits;           // forward, optional: one bit per output element, set where the output is positive
+    const int8_t *src_codes;       // forward, optional: S_q[src(e)] per in-edge, in edge order (read instead of gathered)
 };
 
 enum { W_LOAD = 0, W_ATT_FWD = 1, W_ATT_REV = 2 };
@@ -463,7 +464,10 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
                 for (int h0 = 0; h0 < H; h0 += 4) {
                     int sq[4], dq[4];
                     float lse4[4] = {0.f, 0.f, 0.f, 0.f};
-                    tango_load_heads4(a.att.Sq, src_node, H, h0, sq);
+                    if (WMODE == W_ATT_FWD && a.att.src_codes)
+                        tango_load_heads4(a.att.src_codes, e, H, h0, sq);
+                    else
+                        tango_load_heads4(a.att.Sq, src_node, H, h0, sq);
                     if (DS) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
@@ -812,6 +816,7 @@ struct sddmm_dot_args {
     double *dS_acc;                  // n x heads, zero-initialised
     // DOT_DST instantiations only (rows = destination nodes): three running sums per (destination, head)
     const float *row_lse;            // n x heads
+    const int8_t *src_codes = nullptr;  // optional: S_q[src(e)] per in-edge, in edge order (read instead of gathered)
     double *stats;                   // n x heads x 3, zero-initialised: sum alpha*dalpha, sum alpha*dalpha*s, sum alpha*s
 };
 
@@ -915,7 +920,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
                 // S_q of my edge's source, all heads, needed only after the gathers: requested now
                 uint2 w = make_uint2(0u, 0u);
                 if (lane < cnt) {
-                    const int8_t *sp = a.Sq + static_cast<int64_t>(my_nb) * H;
+                    const int8_t *sp = a.src_codes ? a.src_codes + (static_cast<int64_t>(base) + lane) * H
+                                                   : a.Sq + static_cast<int64_t>(my_nb) * H;
                     if (H == 4) {
                         w.x = *reinterpret_cast<const uint32_t *>(sp);
                     } else if (H == 8) {
@@ -1217,11 +1223,13 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *sS, const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
-                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, hipStream_t st)
+                               float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, const int8_t *src_codes,
+                               hipStream_t st)
 {
     attn_params att;
     att.relu_out = relu_out;
     att.relu_bits = relu_bits;
+    att.src_codes = direction == TANGO_IN ? src_codes : nullptr;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
@@ -1248,7 +1256,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
     att.row_lse = row_lse; att.absmax_alpha = absmax_alpha;
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
-    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0; att.relu_bits = nullptr;
+    att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0; att.relu_bits = nullptr; att.src_codes = nullptr;
     rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st);
     if (rc != TANGO_OK) return rc;
     k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
@@ -1313,7 +1321,7 @@ __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, 
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, hipStream_t st)
+                                   float *dD, const int8_t *src_codes, hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(stats), 0u, static_cast<int>(6 * nh), st);
@@ -1334,7 +1342,7 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
         a.F = heads * dim;
         a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
         a.rec = nullptr; a.dS_acc = nullptr;
-        a.row_lse = row_lse; a.stats = stats;
+        a.row_lse = row_lse; a.stats = stats; a.src_codes = src_codes;
         const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         switch (pick_vec(a.F, dim, true)) {

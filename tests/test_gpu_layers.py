@@ -248,6 +248,37 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
                          relu_out=(i < 2))
 
 
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8"])
+def test_cached_source_codes_change_nothing(T, case):
+    """With `src_codes` the first walk over the in-edges leaves S_q[src(e)] per edge and the later walks read that stream
+    instead of gathering: the buffer holds exactly those codes and every output is the same bit for bit (fp32 edge sums
+    included: the same values are added in the same order)."""
+    import torch
+
+    if case == "dense_h8":  # long rows (the row-by-row destination-side walk), eight heads
+        g = ti.rmat_graph(600, 60000, seed=14)
+        li = ti.layer_inputs("toy", graph=g, k_in=48)
+        li.a_src = ti.xavier_uniform(8, 16, (8, 16), 71)
+        li.a_dst = ti.xavier_uniform(8, 16, (8, 16), 72)
+        li.weight = ti.xavier_uniform(48, 128, (48, 128), 73)
+        li.grad_out = ti.normal((g.n_nodes, 128), 74)
+        slope = 0.2
+    else:
+        li, slope = gat_case(case)
+    G = T.Graph.from_host(li.graph)
+    args = (G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, orc.SR, li.sr_seed, 2)
+    A = T.GatLayer(*args)
+    B = T.GatLayer(*args, src_codes=True)
+    B["src_codes"].fill_(99)
+    for L in (A, B):
+        T.tango_gat_layer_fwd(L)
+        T.tango_gat_layer_bwd(L)
+    torch.cuda.synchronize()
+    assert_bit_exact(host(B["src_codes"]), host(B["S_q"])[li.graph.in_src], "S_q of every edge's source")
+    for name in ("out", "row_lse", "absmax_alpha", "s_alpha", "g_q", "dHp", "dS", "dD", "dW", "dH", "da_src", "da_dst"):
+        assert_bit_exact(host(B[name]), host(A[name]), name)
+
+
 def test_relu_sign_bits_are_ignored_for_narrow_rows(T):
     """Rows of at most 128 columns have no sign-bit path: the buffer is left alone and the results do not change."""
     import torch
