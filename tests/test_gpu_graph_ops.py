@@ -37,6 +37,14 @@ def graph(name):
             g = ti.rmat_graph(5000, 20000, seed=13, self_loops=False)
         elif name == "dense":  # mean degree ~100: the kernels that switch on the mean degree take their long-row paths
             g = ti.rmat_graph(600, 60000, seed=14)
+        elif name == "hub":  # two nodes with ~6,000 in- and out-edges each (beyond the 4,096-edge limit of the one-wave-per-row
+            # walks) among short rows
+            n = 6000
+            rng = np.random.default_rng(15)
+            everyone = np.arange(n)
+            src = np.concatenate([everyone, everyone, np.full(n, 5), np.full(n, 4321), rng.integers(0, n, 30000)])
+            dst = np.concatenate([np.full(n, 5), np.full(n, 4321), everyone, everyone, rng.integers(0, n, 30000)])
+            g = ti.graph_from_edges(n, src, dst)
         elif name == "one":
             g = ti.graph_from_edges(1, [], [], self_loops=True)
         else:
@@ -62,6 +70,8 @@ CASES = [
     ("holes", 2, 32),
     ("holes", 1, 1024),
     ("one", 4, 64),
+    ("hub", 4, 64),
+    ("hub", 3, 128),
 ]
 
 
@@ -126,7 +136,8 @@ def test_qspmm_bwd_is_reverse_spmm_plus_sddmm_dot(T, gname, heads, dim):
     assert host(am)[0] == want_am
 
 
-EDGE_CASES = [("toy", 2), ("rmat", 4), ("rmat", 3), ("rmat", 1), ("sparse", 1), ("sparse", 8), ("holes", 2), ("one", 4)]
+EDGE_CASES = [("toy", 2), ("rmat", 4), ("rmat", 3), ("rmat", 1), ("sparse", 1), ("sparse", 8), ("holes", 2), ("one", 4),
+              ("hub", 4), ("hub", 3), ("dense", 2)]
 
 
 @pytest.mark.parametrize("gname,heads", EDGE_CASES)
