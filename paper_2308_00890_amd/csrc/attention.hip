@@ -126,28 +126,21 @@ struct attn_stats_op {
     }
 };
 
+// The workgroups below huge_blocks take the rows longer than HUGE_ROW, a whole workgroup per row; the others walk the
+// remaining rows with a group of lanes per row.  One launch: the hub rows no longer wait for the short ones.
 template <int H, int GROUP>
 __global__ __launch_bounds__(256) void k_attn_stats(int n, const int32_t *ptr, attn_stats_op<H> op, const float *sS,
-                                                    const float *sD, float *absmax_alpha, int *huge)
+                                                    const float *sD, float *absmax_alpha, int huge_blocks)
 {
+    __shared__ double scratch[2 * 256 / 64];
+    __shared__ int list[256 + 1];
     op.sS = *sS;
     op.sD = *sD;
     op.amax = 0.0f;
-    walk_rows<GROUP>(ptr, n, op, huge);
-    const float m = tango_wave_max(op.amax);
-    if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
-}
-
-template <int H>
-__global__ __launch_bounds__(TEAM_BLOCK_THREADS) void k_attn_stats_huge(const int32_t *ptr, attn_stats_op<H> op,
-                                                                        const float *sS, const float *sD,
-                                                                        float *absmax_alpha, const int *huge)
-{
-    __shared__ double scratch[2 * TEAM_BLOCK_THREADS / 64];
-    op.sS = *sS;
-    op.sD = *sD;
-    op.amax = 0.0f;
-    walk_huge_rows(ptr, huge, op, scratch);
+    if (static_cast<int>(blockIdx.x) < huge_blocks)
+        walk_huge_rows_strided(ptr, n, static_cast<int>(blockIdx.x), huge_blocks, op, scratch, list);
+    else
+        walk_rows<GROUP>(ptr, n, op, nullptr, huge_blocks, huge_blocks > 0);
     const float m = tango_wave_max(op.amax);
     if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
 }
@@ -267,17 +260,18 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
                            const float *sD, float slope, float *row_lse, float *absmax_alpha,
                            int *huge, int8_t *src_codes, hipStream_t st)
 {
+    (void)huge;  // (the list of long rows is only used by the backward walk; here they are found inside the launch)
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
     const unsigned grid = row_grid(n, grp);
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
-    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(huge), 0u, 1, st)) != TANGO_OK) return rc;
+    // no row can be longer than HUGE_ROW unless the graph has that many edges
+    const int huge_blocks = g->n_edges > HUGE_ROW ? static_cast<int>(std::min<int64_t>(HUGE_GRID, n)) : 0;
 #define CALL(HH)                                                                                             \
     {                                                                                                        \
-        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f, src_codes};         \
-        k_attn_stats<HH, GROUP><<<grid, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge);         \
-        k_attn_stats_huge<HH><<<HUGE_GRID, TEAM_BLOCK_THREADS, 0, st>>>(g->in_ptr, op, sS, sD, absmax_alpha, huge); \
+        attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f, src_codes};                   \
+        k_attn_stats<HH, GROUP><<<grid + huge_blocks, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge_blocks); \
     }
     TANGO_DISPATCH_H(heads, grp, CALL)
 #undef CALL

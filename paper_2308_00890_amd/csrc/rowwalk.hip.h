@@ -140,14 +140,18 @@ inline size_t huge_list_bytes(int64_t nnz) { return tango_round_up(static_cast<s
 // Hand rows to lane teams: op.run(row, begin, end, team) is called by all lanes of the team.
 // huge: NULL, or a list (huge[0] = count, zero-initialised; huge[1..] = rows) that receives rows longer than
 // HUGE_ROW instead of processing them here.
+// first_block, skip_huge: the launch's workgroups below first_block do something else (walk_huge_rows_strided) and the
+// rows longer than HUGE_ROW are theirs: skipped here, no list.
 template <int GROUP, class Op>
-__device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op, int *huge = nullptr)
+__device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op, int *huge = nullptr, int first_block = 0,
+                                 bool skip_huge = false)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
     // readfirstlane / readlane: the wave index and the bounds of a row taken by the whole wave are wave-uniform, and
     // saying so keeps them (and the loops over a row's edges) in scalar registers
-    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>((blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE));
-    const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
+    const int wave = __builtin_amdgcn_readfirstlane(
+        static_cast<int>(((blockIdx.x - first_block) * blockDim.x + threadIdx.x) / TANGO_WAVE));
+    const int nwaves = (gridDim.x - first_block) * blockDim.x / TANGO_WAVE;
     constexpr int RPI = 64 / GROUP;  // rows per wave-iteration
     // rows a wave takes per outer iteration: with a whole wave per row they are walked one after the other, each with
     // its own chain of dependent loads, so fewer rows per wave (more waves) hide more of that latency
@@ -160,8 +164,8 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op,
             t = ptr[r + 1];
         }
         int is_long = (GROUP == 64) ? 1 : ((t - b) > 16 * GROUP ? 1 : 0);
-        if (huge && r < n && (t - b) > HUGE_ROW) {
-            huge[1 + atomicAdd(huge, 1)] = r;
+        if ((huge || skip_huge) && r < n && (t - b) > HUGE_ROW) {
+            if (huge) huge[1 + atomicAdd(huge, 1)] = r;
             is_long = 2;  // neither a group nor this wave processes it
         }
         if (GROUP < 64) {
@@ -190,6 +194,28 @@ __device__ inline void walk_huge_rows(const int32_t *__restrict__ ptr, const int
     for (int i = blockIdx.x; i < count; i += gridDim.x) {
         const int row = huge[1 + i];
         op.run(row, ptr[row], ptr[row + 1], block_team{static_cast<int>(threadIdx.x), scratch});
+    }
+}
+
+// The same without a list, inside the launch that walks the other rows: workgroup j of nblocks looks at the rows
+// j, j + nblocks, ... (strided, so that hubs clustered at neighbouring ids spread over the workgroups), collects those
+// longer than HUGE_ROW, up to one per thread and round, in LDS (list: blockDim.x + 1 ints) and takes them one by one.
+template <class Op>
+__device__ inline void walk_huge_rows_strided(const int32_t *__restrict__ ptr, int n, int j, int nblocks, Op &op,
+                                              double *scratch, int *list)
+{
+    for (int64_t r0 = j; r0 < n; r0 += static_cast<int64_t>(nblocks) * blockDim.x) {
+        if (threadIdx.x == 0) list[0] = 0;
+        __syncthreads();
+        const int64_t r = r0 + static_cast<int64_t>(threadIdx.x) * nblocks;
+        if (r < n && ptr[r + 1] - ptr[r] > HUGE_ROW) list[1 + atomicAdd(&list[0], 1)] = static_cast<int>(r);
+        __syncthreads();
+        const int count = list[0];
+        for (int i = 0; i < count; ++i) {
+            const int row = list[1 + i];
+            op.run(row, ptr[row], ptr[row + 1], block_team{static_cast<int>(threadIdx.x), scratch});
+        }
+        __syncthreads();
     }
 }
 
