@@ -114,6 +114,26 @@ __device__ static inline int tango_round_clamp(float y, uint32_t bits16)
     return min(127, max(-127, v));
 }
 
+// Quantize 8 consecutive elements (one Philox block) held in y[8] = x*inv.
+template <int ROUNDING>
+__device__ static inline uint2 tango_quantize8(const float (&y)[8], const tango_rng &rng, uint64_t blk)
+{
+    uint4 b = make_uint4(0, 0, 0, 0);
+    if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, blk);
+    const uint32_t w[4] = {b.x, b.y, b.z, b.w};
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+        const uint32_t byte = static_cast<uint32_t>(tango_round_clamp<ROUNDING>(y[j], bits)) & 0xffu;
+        if (j < 4)
+            lo |= byte << (8 * j);
+        else
+            hi |= byte << (8 * (j - 4));
+    }
+    return make_uint2(lo, hi);
+}
+
 // ---------------------------------------------------------------------------
 // Wave-level reductions (wave64) via cross-lane shuffles.
 // ---------------------------------------------------------------------------

@@ -18,6 +18,13 @@ int tango_quantize_masked_async(const float *x, const float *mask, size_t n, int
 int tango_quantize_bitmasked_async(const float *x, const uint8_t *mask_bits, size_t n, int rounding, uint64_t seed,
                                    uint64_t stream_id, int8_t *q, float *scale_out, float *absmax_ws, hipStream_t st);
 
+// tango_head_proj and the quantization of X (abs-max known: absmax_X, device) in one pass over X; X 16-byte and X_q
+// 8-byte aligned; only where tango_head_proj_quantize_supported.  The results are those of the two separate calls.
+bool tango_head_proj_quantize_supported(int heads, int dim);
+int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst,
+                                   float *S, float *D, float *absmax_S, float *absmax_D, const float *absmax_X, int rounding,
+                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st);
+
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL).
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
                              int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,

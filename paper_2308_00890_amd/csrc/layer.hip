@@ -65,11 +65,19 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
     TANGO_TRY(tango_qgemm_known_absmax(n, F, L->k_in, L->H, L->absmax_H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W,
                                        L->H_q, L->s_H, L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
     // step 2: S, D in fp32, with their abs-max
-    TANGO_TRY(tango_head_proj(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
-                              sc + SC_ABSMAX_D, stream));
-    // sequential quantization of the tensors the sparse primitives will access randomly (Sec. 3.3)
-    TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_HP, L->absmax_Hp, L->Hp_q,
-                             L->s_Hp, nullptr, 0, stream));
+    // and the sequential quantization of the tensors the sparse primitives will access randomly (Sec. 3.3): H' in the
+    // same pass over H' where the shape allows
+    if (tango_head_proj_quantize_supported(L->heads, L->dim) && tango_aligned(L->Hp, 16) && tango_aligned(L->Hp_q, 8) &&
+        tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16)) {
+        TANGO_TRY(tango_head_proj_quantize_async(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
+                                                 sc + SC_ABSMAX_D, L->absmax_Hp, L->rounding, L->seed, sid + SID_HP, L->Hp_q,
+                                                 L->s_Hp, tango_stream(stream)));
+    } else {
+        TANGO_TRY(tango_head_proj(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
+                                  sc + SC_ABSMAX_D, stream));
+        TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_HP, L->absmax_Hp,
+                                 L->Hp_q, L->s_Hp, nullptr, 0, stream));
+    }
     TANGO_TRY(tango_quantize(L->S, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_S, sc + SC_ABSMAX_S,
                              L->S_q, L->s_S, nullptr, 0, stream));
     TANGO_TRY(tango_quantize(L->D, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_D, sc + SC_ABSMAX_D,

@@ -146,6 +146,93 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
     }
 }
 
+// Head projections and the quantization of X in one pass over X (Sec. 3.3: the tensor the sparse primitives gather
+// from is quantized once, sequentially; its abs-max is already known from the GEMM that wrote it).  The tensor is taken
+// as a flat run of groups of 8 elements - one block of random bits each, like the stand-alone quantizer - lane l of a
+// wave taking group base + l: with dim/8 a power of two the dim/8 lanes of one (node, head) pair are adjacent and
+// aligned, every lane is busy whatever the row width, and a_src / a_dst are read from LDS by column.
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_head_proj_quant(int64_t n, int heads, int dim, const float *__restrict__ X,
+                                                         const float *__restrict__ a_src, const float *__restrict__ a_dst,
+                                                         float *__restrict__ S, float *__restrict__ D, float *absmax_S,
+                                                         float *absmax_D, const float *__restrict__ absmax_X, tango_rng rng,
+                                                         int8_t *__restrict__ Xq, float *scale_out)
+{
+    __shared__ __attribute__((aligned(16))) float a_s[2][1024];
+    const int F = heads * dim;
+    for (int i = threadIdx.x; i < F; i += blockDim.x) {
+        a_s[0][i] = a_src[i];
+        a_s[1][i] = a_dst[i];
+    }
+    __syncthreads();
+    float s, inv;
+    tango_scale_from_absmax(*absmax_X, s, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+    const uint32_t g8 = static_cast<uint32_t>(F / 8);    // groups per row
+    const int lph = dim / 8;                             // lanes per head (power of two)
+    const int log2lph = __ffs(lph) - 1;
+    const int64_t ngroups = n * g8;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t nthr = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    const float4 *x4 = reinterpret_cast<const float4 *>(X);
+    uint2 *q8 = reinterpret_cast<uint2 *>(Xq);
+    constexpr int UNR = 4;
+    float ms = 0.0f, md = 0.0f;
+    // the loop bound is the wave's: all 64 lanes take part in the lane sums
+    for (int64_t w0 = tid - lane; w0 < ngroups; w0 += UNR * nthr) {
+        float4 xa[UNR], xb[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t i = w0 + lane + u * nthr;
+            xa[u] = xb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < ngroups) {
+                xa[u] = x4[2 * i];
+                xb[u] = x4[2 * i + 1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t i = w0 + lane + u * nthr;
+            const int64_t row = (ngroups >> 32) == 0 ? static_cast<int64_t>(static_cast<uint32_t>(i) / g8) : i / g8;
+            const int c8 = static_cast<int>(i - row * g8);
+            const int head = c8 >> log2lph;
+            const float x[8] = {xa[u].x, xa[u].y, xa[u].z, xa[u].w, xb[u].x, xb[u].y, xb[u].z, xb[u].w};
+            float as[8], ad[8];
+            *reinterpret_cast<float4 *>(as) = *reinterpret_cast<const float4 *>(&a_s[0][8 * c8]);
+            *reinterpret_cast<float4 *>(as + 4) = *reinterpret_cast<const float4 *>(&a_s[0][8 * c8 + 4]);
+            *reinterpret_cast<float4 *>(ad) = *reinterpret_cast<const float4 *>(&a_s[1][8 * c8]);
+            *reinterpret_cast<float4 *>(ad + 4) = *reinterpret_cast<const float4 *>(&a_s[1][8 * c8 + 4]);
+            double accs = 0.0, accd = 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const double xd = static_cast<double>(x[k]);
+                accs += xd * static_cast<double>(as[k]);
+                accd += xd * static_cast<double>(ad[k]);
+            }
+            accs = tango_group_sum_f64(accs, lph);
+            accd = tango_group_sum_f64(accd, lph);
+            if (i < ngroups) {
+                if ((c8 & (lph - 1)) == 0) {
+                    const float fs = static_cast<float>(accs), fd = static_cast<float>(accd);
+                    S[row * heads + head] = fs;
+                    D[row * heads + head] = fd;
+                    ms = fmaxf(ms, fabsf(fs));
+                    md = fmaxf(md, fabsf(fd));
+                }
+                const float y[8] = {x[0] * inv, x[1] * inv, x[2] * inv, x[3] * inv, x[4] * inv, x[5] * inv, x[6] * inv, x[7] * inv};
+                q8[i] = tango_quantize8<ROUNDING>(y, rng, static_cast<uint64_t>(i));
+            }
+        }
+    }
+    ms = tango_wave_max(ms);
+    md = tango_wave_max(md);
+    if (lane == 0) {
+        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
+        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
+    }
+}
+
 // dX = dX_agg + (dS*a_src + dD*a_dst); column sums of dS*(sX*Xq), dD*(sX*Xq) into acc[2F] (double, atomics).
 // Thread <-> one quad of columns; 256/TPR rows per block-iteration.
 __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int dim, const float *__restrict__ dS,
@@ -246,6 +333,38 @@ int tango_head_proj_async(int64_t n, int heads, int dim, const float *X, const f
     const size_t waves_needed = static_cast<size_t>((npairs + 4 * (64 / lpp) - 1) / (4 * (64 / lpp)));
     k_head_proj<<<tango_grid_for(waves_needed, 4, 256 * 8), 256, 0, st>>>(npairs, heads, dim, lpp, X, a_src, a_dst, S, D,
                                                                          absmax_S, absmax_D);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+bool tango_head_proj_quantize_supported(int heads, int dim)
+{
+    const int lph = dim / 8;
+    return heads >= 1 && dim % 8 == 0 && lph <= 64 && (lph & (lph - 1)) == 0 && static_cast<int64_t>(heads) * dim <= 1024;
+}
+
+// tango_head_proj and the quantization of X (abs-max known: absmax_X, device) in one pass over X; X 16-byte and X_q
+// 8-byte aligned; only where tango_head_proj_quantize_supported.  The results are those of the two separate calls.
+int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst,
+                                   float *S, float *D, float *absmax_S, float *absmax_D, const float *absmax_X, int rounding,
+                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st)
+{
+    TANGO_REQUIRE(tango_head_proj_quantize_supported(heads, dim), TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
+    TANGO_REQUIRE(n > 0 && X && a_src && a_dst && S && D && absmax_X && X_q, TANGO_ERR_NULL);
+    TANGO_REQUIRE(tango_aligned(X, 16) && tango_aligned(X_q, 8), TANGO_ERR_BAD_SHAPE);
+    int rc;
+    if (absmax_S && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 0u, 1, st)) != TANGO_OK) return rc;
+    if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
+    const tango_rng rng = tango_rng_make(seed, stream_id);
+    const size_t ngroups = static_cast<size_t>(n) * (heads * dim / 8);
+    const unsigned grid = tango_grid_for(ngroups / 4 + 1, 256, 256 * 8);
+    if (rounding == TANGO_RN)
+        k_head_proj_quant<TANGO_RN><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D, absmax_X,
+                                                         rng, X_q, s_X);
+    else
+        k_head_proj_quant<TANGO_SR><<<grid, 256, 0, st>>>(n, heads, dim, X, a_src, a_dst, S, D, absmax_S, absmax_D, absmax_X,
+                                                         rng, X_q, s_X);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }

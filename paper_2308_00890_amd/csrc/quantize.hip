@@ -78,26 +78,6 @@ __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, siz
     }
 }
 
-// Quantize 8 consecutive elements (one Philox block) held in y[8] = x*inv.
-template <int ROUNDING>
-__device__ inline uint2 quantize8(const float (&y)[8], const tango_rng &rng, uint64_t blk)
-{
-    uint4 b = make_uint4(0, 0, 0, 0);
-    if (ROUNDING == TANGO_SR) b = tango_philox_block(rng, blk);
-    const uint32_t w[4] = {b.x, b.y, b.z, b.w};
-    uint32_t lo = 0, hi = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t bits = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
-        const uint32_t byte = static_cast<uint32_t>(tango_round_clamp<ROUNDING>(y[j], bits)) & 0xffu;
-        if (j < 4)
-            lo |= byte << (8 * j);
-        else
-            hi |= byte << (8 * (j - 4));
-    }
-    return make_uint2(lo, hi);
-}
-
 // Vector path: x 16-byte aligned, q 8-byte aligned.  One thread-iteration = 8 elements.
 template <int ROUNDING, int MASKED = 0>
 __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
@@ -138,7 +118,7 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
         for (int u = 0; u < UNR; ++u) {
             const float y[8] = {a[u].x * inv, a[u].y * inv, a[u].z * inv, a[u].w * inv,
                                 b[u].x * inv, b[u].y * inv, b[u].z * inv, b[u].w * inv};
-            q8[i + u * nthr] = quantize8<ROUNDING>(y, rng, i + u * nthr);
+            q8[i + u * nthr] = tango_quantize8<ROUNDING>(y, rng, i + u * nthr);
         }
     }
     for (; i < n8; i += nthr) {
@@ -154,7 +134,7 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
             b = tango_mask4b(b, kb >> 4);
         }
         const float y[8] = {a.x * inv, a.y * inv, a.z * inv, a.w * inv, b.x * inv, b.y * inv, b.z * inv, b.w * inv};
-        q8[i] = quantize8<ROUNDING>(y, rng, i);
+        q8[i] = tango_quantize8<ROUNDING>(y, rng, i);
     }
     // ragged tail: fewer than 8 elements, one thread
     if (tid == 0 && n8 * 8 < n) {
