@@ -248,7 +248,7 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
                          relu_out=(i < 2))
 
 
-@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8"])
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8", "hub_h1"])
 def test_cached_source_codes_change_nothing(T, case):
     """With `src_codes` the first walk over the in-edges leaves S_q[src(e)] per edge and the later walks read that stream
     instead of gathering: the buffer holds exactly those codes and every output is the same bit for bit (fp32 edge sums
@@ -262,6 +262,16 @@ def test_cached_source_codes_change_nothing(T, case):
         li.a_dst = ti.xavier_uniform(8, 16, (8, 16), 72)
         li.weight = ti.xavier_uniform(48, 128, (48, 128), 73)
         li.grad_out = ti.normal((g.n_nodes, 128), 74)
+        slope = 0.2
+    elif case == "hub_h1":  # one head; two rows beyond the one-wave-per-row limit of the statistics pass
+        from test_gpu_graph_ops import graph
+
+        g = graph("hub")
+        li = ti.layer_inputs("toy", graph=g, k_in=40)
+        li.a_src = ti.xavier_uniform(1, 64, (1, 64), 75)
+        li.a_dst = ti.xavier_uniform(1, 64, (1, 64), 76)
+        li.weight = ti.xavier_uniform(40, 64, (40, 64), 77)
+        li.grad_out = ti.normal((g.n_nodes, 64), 78)
         slope = 0.2
     else:
         li, slope = gat_case(case)
