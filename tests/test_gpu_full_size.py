@@ -147,11 +147,12 @@ def test_full_size_gat_layer_sampled(T, name):
     # sums come from the two fused walks.  Checked against the run verified above.
     del X, dS, dD
     P = T.GatLayer(G, dev(li.feat), dev(li.weight), dev(li.a_src), dev(li.a_dst), dev(li.grad_out), slope, rounding, seed, 0,
-                   fused=True)
+                   fused=True, src_codes=True)
     assert "alpha_q" not in P.t and "dalpha" not in P.t and "alpha" not in P.t
     T.tango_gat_layer_fwd(P)
     T.tango_gat_layer_bwd(P)
     torch.cuda.synchronize()
+    assert_bit_exact(host(P["src_codes"]), o["S_q"][g.in_src], "S_q of every edge's source (production launch)")
     assert_bit_exact(host(P["out"]), o["out"], "out (production launch)")
     assert_close(host(P["dS"]), o["dS"], "dS (production launch)")
     assert_close(host(P["dD"]), o["dD"], "dD (production launch)")
