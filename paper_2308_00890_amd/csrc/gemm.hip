@@ -272,13 +272,21 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 
 __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const int8_t *__restrict__ P,
                                                  const int8_t *__restrict__ Q, int32_t *acc_out, int64_t slab_rows,
-                                                 int tiles_n)
+                                                 int tiles_k, int tiles_n)
 {
     __shared__ __align__(16) int8_t Pt[TT * LDM];
     __shared__ __align__(16) int8_t Qt[TT * LDM];
     const int tid = threadIdx.x, lane = tid % TANGO_WAVE, wave = tid / TANGO_WAVE;
-    const int k0 = (blockIdx.x / tiles_n) * TT, n0 = (blockIdx.x % tiles_n) * TT;
-    const int64_t m_begin = static_cast<int64_t>(blockIdx.y) * slab_rows;
+    // Workgroups go to the 8 XCDs in turn, each with an L2 of its own: the output tiles of one slab of rows read the same
+    // rows of P and Q, so they are given to workgroups 8 apart (same XCD, consecutive there) and share those rows in
+    // that L2 instead of each fetching them across the fabric.
+    const int tiles = tiles_k * tiles_n;
+    const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+    const int tile = j % tiles;
+    const int64_t slab = static_cast<int64_t>(j / tiles) * 8 + xcd;
+    const int k0 = (tile / tiles_n) * TT, n0 = (tile % tiles_n) * TT;
+    const int64_t m_begin = slab * slab_rows;
+    if (m_begin >= M) return;  // (the slab count is padded to a multiple of 8)
     const int64_t m_end = min(M, m_begin + slab_rows);
     const int rbase = (wave / 2) * 64, cbase = (wave % 2) * 64;
     v16i acc00 = {0}, acc01 = {0}, acc10 = {0}, acc11 = {0};
@@ -523,8 +531,9 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
         if (slabs < 1) slabs = 1;
         int64_t slab_rows = tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS);
         slabs = (M + slab_rows - 1) / slab_rows;
-        dim3 grid(static_cast<unsigned>(tiles_k * tiles_n), static_cast<unsigned>(slabs));
-        k_gemm_tn<<<grid, 256, 0, st>>>(M, static_cast<int>(K), static_cast<int>(N), A_q, dC_q, acc, slab_rows, tiles_n);
+        const unsigned grid = static_cast<unsigned>(tiles_k * tiles_n * tango_round_up(static_cast<size_t>(slabs), 8));
+        k_gemm_tn<<<grid, 256, 0, st>>>(M, static_cast<int>(K), static_cast<int>(N), A_q, dC_q, acc, slab_rows, tiles_k,
+                                        tiles_n);
         TANGO_LAUNCH_CHECK();
         k_dequant_i32<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(acc, K * N, s_A, s_dC, dB);
         TANGO_LAUNCH_CHECK();
