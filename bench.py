@@ -50,7 +50,10 @@ def attention_bwd_src_algorithmic_bytes(n, nnz, heads, F):
 # HBM-side traffic of the dominant kernel per launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this file, scaled by a 1 GiB copy kernel (FETCH_SIZE reads half the copied bytes, WRITE_SIZE all of them); see
 # profiles/.  Keyed by workload; None where no counter run has been recorded.
-MEASURED_TRAFFIC = {"gat_dense": 27.5e9}  # profiles/gat_dense_hbm_traffic.md, k_spmm<16, true, 2, false, true, 4>
+MEASURED_TRAFFIC = {
+    "gat_dense": 27.5e9,      # profiles/gat_dense_hbm_traffic.md, k_spmm<16, true, 2, false, true, 4>
+    "gat_products": 33.85e9,  # profiles/gat_products_kernel_stats_and_traffic.md, k_spmm<16, true, 2, false, true, 8>
+}
 
 
 def attention_bwd_src_launch(torch, T, G, L, heads, dim, slope, seed, sid_alpha):
