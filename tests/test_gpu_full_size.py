@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE sizes, in the launch configuration bench.py times (fused GAT layer, SR).
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times (fused GAT layer, SR).
 
 The oracle cannot run a whole layer at these sizes in test time, so every stage is checked on sampled outputs that
 the oracle computes one by one from the GPU's own inputs of that stage: sampled rows of the GEMMs, sampled elements
