@@ -309,9 +309,13 @@ def main():
             grad = to(li.grad_out) if i == 2 else torch.empty((g.n_nodes, F), dtype=torch.float32, device=dev)
             layers.append(T.GatLayer(G, feat, W, to(li.a_src), to(li.a_dst), grad, slope, T.SR, li.sr_seed, i,
                                      want_dH=False, relu_out=(i < 2), relu_bits=True, src_codes=True,
-                                     absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None)))
+                                     absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None),
+                                     dH_keep_bits=(layers[i - 1]["relu_bits"] if i > 0 else None)))
         for i in (1, 2):
+            # the input-gradient GEMM of layer i writes the lower layer's grad_out with that layer's ReLU' applied and
+            # leaves its abs-max
             layers[i]._bind("dH", layers[i - 1]["grad_out"], torch.float32)
+            layers[i - 1]._bind("absmax_grad_out", layers[i]["absmax_dH"], torch.float32)
 
         def step():
             for i in range(3):

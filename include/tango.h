@@ -542,6 +542,15 @@ typedef struct tango_gat_layer {
      * pass's walk over the in-edges read that stream instead of gathering from S_q once more per edge (Sec. 3.3's
      * caching of quantized tensors between operators, applied to a gathered tensor).  Results do not change. */
     int8_t *src_codes;
+    /* Stacked layers, the ReLU' of the layer below applied where the gradient is produced (all optional, else NULL):
+     * dH_keep_bits - the relu_bits of the layer below (whose ReLU output is this layer's H; k_in a multiple of 32 and at
+     * most 2048): the backward pass writes dH with zeros where the bit is clear; absmax_dH (device, out) receives max|dH|
+     * as written.  absmax_grad_out (device, in) - max|grad_out| if the caller has it (the absmax_dH of the layer above):
+     * the pass over grad_out that finds it is skipped, and with relu_out set grad_out is then taken to carry the ReLU'
+     * mask already (the layer above applied it through its dH_keep_bits). */
+    const void *dH_keep_bits;
+    float *absmax_dH;
+    const float *absmax_grad_out;
 } tango_gat_layer;
 
 size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int heads, int dim);

@@ -533,7 +533,8 @@ class tango_gat_layer(ctypes.Structure):
             "S_q", "s_S", "D_q", "s_D", "E", "alpha", "alpha_q", "s_alpha", "out", "absmax_out", "grad_out", "g_q",
             "s_g", "dHp", "absmax_dHp", "dalpha", "dS", "dD", "dHp_q", "s_dHp", "dW", "dH", "da_src", "da_dst")]
         + [("fused", _int), ("row_lse", _vp), ("absmax_alpha", _vp), ("ws", _vp), ("ws_bytes", _sz),
-           ("relu_out", _int), ("absmax_H", _vp), ("relu_bits", _vp), ("src_codes", _vp)]
+           ("relu_out", _int), ("absmax_H", _vp), ("relu_bits", _vp), ("src_codes", _vp),
+           ("dH_keep_bits", _vp), ("absmax_dH", _vp), ("absmax_grad_out", _vp)]
     )
 
 
@@ -611,7 +612,8 @@ class GatLayer(_LayerBuffers):
 
     def __init__(self, graph: "Graph", H, W, a_src, a_dst, grad_out=None, slope=0.2, rounding=SR, seed=0, layer_id=0,
                  want_dH=True, alias_E_alpha=True, fused=True, keep_alpha=False, keep_alpha_q=False, keep_dalpha=False,
-                 relu_out=False, absmax_H=None, relu_bits=False, src_codes=False):
+                 relu_out=False, absmax_H=None, relu_bits=False, src_codes=False, dH_keep_bits=None,
+                 absmax_grad_out=None):
         super().__init__()
         self.device = H.device
         self.graph = graph
@@ -640,6 +642,11 @@ class GatLayer(_LayerBuffers):
             self._alloc("relu_bits", ((n * F + 63) // 64 * 8,), torch.uint8)
         if absmax_H is not None:
             self._bind("absmax_H", absmax_H, f32)
+        if absmax_grad_out is not None:
+            self._bind("absmax_grad_out", absmax_grad_out, f32)
+        if dH_keep_bits is not None:  # the relu_bits of the layer below: dH leaves with its ReLU' applied, and its abs-max
+            self._bind("dH_keep_bits", dH_keep_bits, torch.uint8)
+            self._alloc("absmax_dH", (1,), f32)
         c.fused = 1 if fused else 0
         if fused:
             if src_codes:

@@ -42,6 +42,8 @@ struct fused_args {
     const float *s_B;
     float *C;        // M x N
     float *absmax_C; // or NULL
+    const uint32_t *C_keep_bits;  // or NULL: bit i of the flat M x N output clear -> C[i] is written as 0 and does not count
+                                  // in absmax_C (a ReLU' applied on the way out); N a multiple of 32
     uint32_t K_magic;  // ceil(2^32 / K): f / K == umulhi(f, K_magic) for the flat panel offsets f < 64 * K (K >= 2)
 };
 
@@ -65,7 +67,7 @@ __device__ inline uint2 quantize8_packed(const float (&y)[8], const tango_rng &r
 }
 
 // WL = bytes per LDS write: 4 if K % 4 == 0, 2 if K % 2 == 0, else 1 (pieces never straddle a row then).
-template <int ROUNDING, int WL>
+template <int ROUNDING, int WL, bool KEEP = false>
 __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
 {
     extern __shared__ __align__(16) int8_t lds[];
@@ -181,12 +183,31 @@ __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
             const v16i &acc = t == 0 ? acc00 : (t == 1 ? acc01 : (t == 2 ? acc10 : acc11));
             const int rb = t / 2, cb = t % 2;
             const int col = col0 + cb * 32 + lane % 32;
+            if constexpr (!KEEP) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                if (r < rows && col < a.N) {
-                    a.C[(row0 + r) * a.N + col] = static_cast<float>(acc[i]) * sc;
-                    maxabs = max(maxabs, abs(acc[i]));
+                for (int i = 0; i < 16; ++i) {
+                    const int r = rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                    if (r < rows && col < a.N) {
+                        a.C[(row0 + r) * a.N + col] = static_cast<float>(acc[i]) * sc;
+                        maxabs = max(maxabs, abs(acc[i]));
+                    }
+                }
+            } else {
+                // the 32 columns of a tile row are one aligned word of the bit array (N a multiple of 32): lane l fetches
+                // the word of row l % 32 of this tile, and every lane then picks the words of its sixteen rows
+                const int64_t wr = row0 + rb * 32 + lane % 32;
+                uint32_t mine = 0u;
+                if (rb * 32 + lane % 32 < rows && col < a.N) mine = a.C_keep_bits[(wr * a.N + (col - lane % 32)) >> 5];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int rl = (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
+                    const uint32_t kw = static_cast<uint32_t>(__shfl(static_cast<int>(mine), rl, 64));
+                    const int r = rb * 32 + rl;
+                    if (r < rows && col < a.N) {
+                        const int v = ((kw >> (lane % 32)) & 1u) ? acc[i] : 0;
+                        a.C[(row0 + r) * a.N + col] = static_cast<float>(v) * sc;
+                        maxabs = max(maxabs, abs(v));
+                    }
                 }
             }
         }
@@ -369,13 +390,17 @@ int launch_fused(const fused_args &a_in, int rounding, hipStream_t st)
     const size_t lds_bytes = static_cast<size_t>(BM) * (a.Kp + LDS_PAD);
     const unsigned grid = static_cast<unsigned>((a.M + BM - 1) / BM);
     const int wl = (a.K % 4 == 0) ? 4 : ((a.K % 2 == 0) ? 2 : 1);
-#define TANGO_FUSED(R, W)                                                                                   \
+#define TANGO_FUSED_K(R, W, KEEP_)                                                                          \
     {                                                                                                       \
         if (lds_bytes > 48 * 1024 &&                                                                        \
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_qgemm_fused<R, W>),                       \
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_qgemm_fused<R, W, KEEP_>),                \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes)) != hipSuccess) \
             return TANGO_ERR_LAUNCH;                                                                        \
-        k_qgemm_fused<R, W><<<grid, 256, lds_bytes, st>>>(a);                                               \
+        k_qgemm_fused<R, W, KEEP_><<<grid, 256, lds_bytes, st>>>(a);                                        \
+    }
+#define TANGO_FUSED(R, W)                                                  \
+    {                                                                      \
+        if (a.C_keep_bits) TANGO_FUSED_K(R, W, true) else TANGO_FUSED_K(R, W, false) \
     }
     if (rounding == TANGO_RN) {
         if (wl == 4) TANGO_FUSED(TANGO_RN, 4) else if (wl == 2) TANGO_FUSED(TANGO_RN, 2) else TANGO_FUSED(TANGO_RN, 1)
@@ -383,6 +408,7 @@ int launch_fused(const fused_args &a_in, int rounding, hipStream_t st)
         if (wl == 4) TANGO_FUSED(TANGO_SR, 4) else if (wl == 2) TANGO_FUSED(TANGO_SR, 2) else TANGO_FUSED(TANGO_SR, 1)
     }
 #undef TANGO_FUSED
+#undef TANGO_FUSED_K
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
@@ -462,7 +488,7 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     fused_args a;
     a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K); a.Kp = Kp; a.Np = Np;
     a.A = A; a.absmax_A = am_A; a.rng = tango_rng_make(seed, stream_id_A);
-    a.A_q = A_q; a.s_A = s_A; a.BT = BT; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C;
+    a.A_q = A_q; a.s_A = s_A; a.BT = BT; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C; a.C_keep_bits = nullptr;
     return launch_fused(a, rounding, st);
 }
 
@@ -479,6 +505,20 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
                     const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, float *dB, void *ws, size_t ws_bytes,
                     void *stream)
 {
+    return tango_qgemm_bwd_masked(M, N, K, A_q, s_A, B_q, s_B, dC, rounding, seed, stream_id_dC, absmax_dC_in, dC_q, s_dC, dA,
+                                  nullptr, nullptr, dB, ws, ws_bytes, stream);
+}
+
+}  // extern "C"
+
+// tango_qgemm_bwd with a ReLU' on dA's way out: dA_keep_bits (optional; bit i of the flat M x K tensor, 4-byte aligned,
+// K a multiple of 32, K <= the on-chip panel limit) clear -> dA[i] = 0; absmax_dA (optional, device) receives max|dA| of
+// what was written.
+int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
+                           const float *s_B, const float *dC, int rounding, uint64_t seed, uint64_t stream_id_dC,
+                           const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, const uint32_t *dA_keep_bits,
+                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream)
+{
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
     if (rc != TANGO_OK) return rc;
@@ -489,7 +529,10 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
     TANGO_REQUIRE(tango_aligned(dC, 16) && tango_aligned(dC_q, 8) && tango_aligned(dA, 4) && tango_aligned(dB, 4),
                   TANGO_ERR_BAD_SHAPE);
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_qgemm_bwd_workspace_bytes(M, N, K), TANGO_ERR_WORKSPACE);
+    TANGO_REQUIRE((!dA_keep_bits && !absmax_dA) || (dA && N <= KMAX), TANGO_ERR_UNSUPPORTED);
+    TANGO_REQUIRE(!dA_keep_bits || (K % 32 == 0 && tango_aligned(dA_keep_bits, 4)), TANGO_ERR_BAD_SHAPE);
     hipStream_t st = tango_stream(stream);
+    if (absmax_dA && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_dA), 0u, 1, st)) != TANGO_OK) return rc;
     float *am = static_cast<float *>(ws);
     int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
     int32_t *acc = reinterpret_cast<int32_t *>(BT + bt_bytes(K, N));
@@ -516,7 +559,7 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
         fused_args a;
         a.M = M; a.N = static_cast<int>(K); a.K = static_cast<int>(N); a.Kp = Rp; a.Np = Cp;
         a.A = dC; a.absmax_A = amp; a.rng = tango_rng_make(seed, stream_id_dC);
-        a.A_q = dC_q; a.s_A = s_dC; a.BT = BT; a.s_B = s_B; a.C = dA; a.absmax_C = nullptr;
+        a.A_q = dC_q; a.s_A = s_dC; a.BT = BT; a.s_B = s_B; a.C = dA; a.absmax_C = absmax_dA; a.C_keep_bits = dA_keep_bits;
         if ((rc = launch_fused(a, rounding, st)) != TANGO_OK) return rc;
     } else {
         if ((rc = tango_quantize_with_absmax_async(dC, static_cast<size_t>(M) * N, rounding, seed, stream_id_dC, amp, dC_q,
@@ -541,4 +584,4 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
     return TANGO_OK;
 }
 
-}  // extern "C"
+

@@ -25,6 +25,13 @@ int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X
                                    float *S, float *D, float *absmax_S, float *absmax_D, const float *absmax_X, int rounding,
                                    uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st);
 
+// tango_qgemm_bwd with a ReLU' on dA's way out: dA_keep_bits (optional; bit i of the flat M x K tensor, 4-byte aligned,
+// K a multiple of 32 and at most 2048) clear -> dA[i] = 0; absmax_dA (optional, device) receives max|dA| as written.
+int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
+                           const float *s_B, const float *dC, int rounding, uint64_t seed, uint64_t stream_id_dC,
+                           const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, const uint32_t *dA_keep_bits,
+                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream);
+
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL).
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
                              int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,

@@ -125,7 +125,11 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     const uint64_t sid = 16 * L->layer_id;
 
     // the upstream gradient is quantized once and shared by steps 5' and 5''
-    if (L->relu_out) {
+    if (L->absmax_grad_out) {
+        // the layer above left max|grad_out| (and, with relu_out, wrote grad_out with this layer's ReLU' applied)
+        TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, L->absmax_grad_out,
+                                 L->g_q, L->s_g, sub, sub_bytes, stream));
+    } else if (L->relu_out) {
         // the gradient arrives behind the layer's ReLU: ReLU' (out > 0) is applied while it is quantized
         TANGO_REQUIRE(L->out && tango_aligned(L->grad_out, 16) && tango_aligned(L->out, 16) && tango_aligned(L->g_q, 8),
                       TANGO_ERR_BAD_SHAPE);
@@ -161,8 +165,10 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     TANGO_TRY(tango_head_proj_bwd(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
                                   L->absmax_dHp, L->da_src, L->da_dst, sub, sub_bytes, stream));
     // 1': both GEMMs from the cached H_q, W_q
-    TANGO_TRY(tango_qgemm_bwd(n, F, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
-                              L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
+    TANGO_REQUIRE((!L->dH_keep_bits && !L->absmax_dH) || L->dH, TANGO_ERR_NULL);
+    TANGO_TRY(tango_qgemm_bwd_masked(n, F, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
+                                     L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, static_cast<const uint32_t *>(L->dH_keep_bits),
+                                     L->absmax_dH, L->dW, sub, sub_bytes, stream));
     return TANGO_OK;
 }
 

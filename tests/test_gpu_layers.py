@@ -43,7 +43,7 @@ def gat_case(name):
 
 
 def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding, seed, layer_id, fused, chain=True,
-                     relu_out=False):
+                     relu_out=False, dH_keep=None):
     """Stage-by-stage check of one GAT layer's device tensors `o` (host copies) against the oracle primitives applied
     to the GPU's own inputs of each stage."""
     heads = a_src.shape[0]
@@ -108,7 +108,12 @@ def verify_gat_layer(o, g, feat, weight, a_src, a_dst, grad_out, slope, rounding
     assert_bit_exact(o["dHp_q"], rb["dC_q"], "dHp_q")
     assert sc("s_dHp") == rb["s_dC"]
     assert_bit_exact(o["dW"], rb["dB"], "dW")
-    assert_bit_exact(o["dH"], rb["dA"], "dH")
+    if dH_keep is None:
+        assert_bit_exact(o["dH"], rb["dA"], "dH")
+    else:  # the ReLU' of the layer below was applied on dH's way out of the GEMM
+        want = np.where(dH_keep, rb["dA"], np.float32(0)).astype(np.float32)
+        assert_bit_exact(o["dH"], want, "dH behind the lower layer's ReLU'")
+        assert o["absmax_dH"][0] == orc.absmax(want)
 
     if not chain:
         return
@@ -198,7 +203,8 @@ def test_three_layer_gat_chain(T):
         verify_gat_layer(o, g, feat, W, a_s, a_d, gout, slope, orc.SR, seed, i, True, chain=False)
 
 
-@pytest.mark.parametrize("mode", ["fused", "fused, sign bits", "primitive by primitive"])
+@pytest.mark.parametrize("mode", ["fused", "fused, sign bits", "fused, sign bits, ReLU' where the gradient is produced",
+                                  "primitive by primitive"])
 def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
     """The same stack with the ReLU inside the layers: a layer writes max(0, aggregate) from its SPMM epilogue and
     hands its abs-max to the next layer's GEMM; the next layer's input gradient is the previous layer's grad_out, and
@@ -207,7 +213,8 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
     instead of the fp32 output: same results, bit for bit."""
     import torch
 
-    fused, bits = mode != "primitive by primitive", mode == "fused, sign bits"
+    fused, bits = mode != "primitive by primitive", mode.startswith("fused, sign bits")
+    at_producer = mode.endswith("produced")  # the upper layer's input-gradient GEMM masks dH and leaves its abs-max
     g = ti.rmat_graph(2500, 40000, seed=31)
     heads, dim, widths = 3, 128, [100, 384, 384]
     F = heads * dim
@@ -225,11 +232,14 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
         feat = dev(x0) if i == 0 else layers[i - 1]["out"]
         L = T.GatLayer(G, feat, dev(W), dev(a_s), dev(a_d), grads[i], slope, orc.SR, seed, i, fused=fused, keep_alpha=True,
                        keep_alpha_q=True, alias_E_alpha=False, relu_out=(i < 2), relu_bits=bits,
-                       absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None))
+                       absmax_H=(layers[i - 1]["absmax_out"] if i > 0 else None),
+                       dH_keep_bits=(layers[i - 1]["relu_bits"] if at_producer and i > 0 else None))
         if bits and i < 2:
             L["relu_bits"].fill_(0xA5)  # stale contents must not survive the forward pass
         if i > 0:  # this layer's input gradient is the gradient behind the previous layer's ReLU
             L._bind("dH", grads[i - 1], torch.float32)
+            if at_producer:
+                layers[i - 1]._bind("absmax_grad_out", L["absmax_dH"], torch.float32)
         layers.append(L)
     for L in layers:
         T.tango_gat_layer_fwd(L)
@@ -244,8 +254,9 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
         if bits and i < 2:
             got = np.unpackbits(o["relu_bits"], bitorder="little")[: g.n_nodes * F].reshape(g.n_nodes, F)
             assert_bit_exact(got, (o["out"] > 0).astype(np.uint8), "ReLU sign bits")
+        keep = (host(layers[i - 1]["out"]) > 0) if at_producer and i > 0 else None
         verify_gat_layer(o, g, feat, W, a_s, a_d, host(grads[i]), slope, orc.SR, seed, i, fused, chain=False,
-                         relu_out=(i < 2))
+                         relu_out=(i < 2), dH_keep=keep)
 
 
 @pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8", "hub_h1"])
