@@ -1053,9 +1053,9 @@ bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 int pick_vec(int F, int dim, bool pow2_lanes_per_head, bool wide_lanes = false)
 {
     int pref[3] = {16, 8, 4};
-    // wide_lanes (the plain in-direction SPMM and the plain SDDMM-dot, measured on 64- and 128-byte rows of a large
+    // wide_lanes (the plain in-direction SPMM and the plain SDDMM-dot, measured on 32- to 128-byte rows of a large
     // table): 16 bytes per lane also for narrow rows - more rows per load instruction, 8-20 % faster there
-    if (wide_lanes && F >= 64) { /* 16, 8, 4 */ }
+    if (wide_lanes && F >= 32) { /* 16, 8, 4 */ }
     else if (F <= 64) { pref[0] = 4; pref[1] = 8; pref[2] = 16; }
     else if (F <= 128) { pref[0] = 8; pref[1] = 4; pref[2] = 16; }
     for (int i = 0; i < 3; ++i) {
