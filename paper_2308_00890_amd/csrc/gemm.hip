@@ -571,6 +571,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, static_cast<int>(K * N), st)) != TANGO_OK) return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
         int64_t slabs = 4096 / (tiles_k * tiles_n);
+        slabs = std::min<int64_t>(slabs, M / (8 * MS));  // at least eight steps per workgroup before its 64 KB of atomics
         if (slabs < 1) slabs = 1;
         int64_t slab_rows = tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS);
         slabs = (M + slab_rows - 1) / slab_rows;
