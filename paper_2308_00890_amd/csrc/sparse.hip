@@ -126,6 +126,7 @@ struct spmm_args {
     float *absmax;         // or NULL
     int heads, dim, F;
     int chunk_shift;       // log2 of the edges per wavefront
+    int short_rows;        // k_spmm_short: rows a wave takes per pass (16 or 64)
     int short_max;         // rows with at most this many edges are left to k_spmm_short (0: none)
     attn_params att;       // used by the ATT instantiations only
     int relu;              // out = max(0, .)
@@ -717,7 +718,8 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
 // edges alone, so a wave works on G rows at once and a row needs no cross-group reduction, no atomics and no
 // chunk search.  Low-degree graphs spend most of their edges here; the chunked kernel above then only sees the
 // longer rows.
-template <int VEC, bool HAS_EID>
+constexpr int SHORT_ROWS = 16;
+template <int VEC, bool HAS_EID, int UE>
 __global__ __launch_bounds__(256) void k_spmm_short(spmm_args a)
 {
     using V = typename vec_bytes<VEC>::type;
@@ -734,47 +736,58 @@ __global__ __launch_bounds__(256) void k_spmm_short(spmm_args a)
     const float sc = (*a.s_w) * (*a.s_X);
     const int8_t *Xcol = a.X + col;
     int maxabs = 0;
-    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+    // a wave takes a.short_rows rows per pass and walks a row's edges UE at a time.  Small graphs: 16 rows and eight
+    // edges (many waves, one round of gathers for the typical short row); large ones: 64 rows (one row-pointer load per
+    // 64 rows) and four edges (measured: faster there)
+    const int RP = max(a.short_rows, G);  // rows per pass: at least one per group
+    for (int64_t base = static_cast<int64_t>(wave) * RP; base < a.n; base += static_cast<int64_t>(nwaves) * RP) {
         const int rl = static_cast<int>(base) + lane;
         int pb = 0, pt = 0;
-        if (rl < a.n) {
+        if (lane < RP && rl < a.n) {
             pb = a.ptr[rl];
             pt = a.ptr[rl + 1];
         }
-        for (int k0 = 0; k0 < 64; k0 += G) {
-            const int src_lane = min(k0 + gi, 63);
+        for (int k0 = 0; k0 < RP; k0 += G) {
+            const int src_lane = min(k0 + gi, RP - 1);
             const int rb = __shfl(pb, src_lane, 64), rt = __shfl(pt, src_lane, 64);
             const int row = static_cast<int>(base) + k0 + gi;
             const int deg = rt - rb;
-            if (!active || row >= a.n || deg <= 0 || deg > a.short_max) continue;
+            if (!active || row >= a.n || row >= base + RP || deg <= 0 || deg > a.short_max) continue;
             int acc[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) acc[j] = 0;
-            for (int e = rb; e < rt; e += 4) {
-                uint32_t wq[4];
-                V xv[4];
+            for (int e = rb; e < rt; e += UE) {
+                uint32_t wq[UE];
+                V xv[UE];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const bool ok = e + u < rt;
-                    const int ee = ok ? e + u : rt - 1;
-                    const int nb = a.idx[ee];
-                    const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[ee]) : static_cast<int64_t>(ee)) * a.heads + h;
-                    wq[u] = ok ? static_cast<uint32_t>(static_cast<uint8_t>(a.w[wp])) : 0u;
-                    xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                for (int u = 0; u < UE; ++u) {
+                    // (edges beyond the row's end: no load at all, a zero weight)
+                    wq[u] = 0u;
+                    xv[u] = V();
+                    if (e + u < rt) {
+                        const int ee = e + u;
+                        const int nb = a.idx[ee];
+                        const int64_t wp = (HAS_EID ? static_cast<int64_t>(a.eid[ee]) : static_cast<int64_t>(ee)) * a.heads + h;
+                        wq[u] = static_cast<uint32_t>(static_cast<uint8_t>(a.w[wp]));
+                        xv[u] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nb) * a.F);
+                    }
                 }
-                const uint32_t wpack = wq[0] | (wq[1] << 8) | (wq[2] << 16) | (wq[3] << 24);
-                uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
-                unpack_words<VEC>(xv[0], w0);
-                unpack_words<VEC>(xv[1], w1);
-                unpack_words<VEC>(xv[2], w2);
-                unpack_words<VEC>(xv[3], w3);
 #pragma unroll
-                for (int q = 0; q < VEC / 4; ++q) {
-                    uint32_t t[4];
-                    transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+                for (int u = 0; u < UE; u += 4) {
+                    const uint32_t wpack = wq[u] | (wq[u + 1] << 8) | (wq[u + 2] << 16) | (wq[u + 3] << 24);
+                    uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
+                    unpack_words<VEC>(xv[u], w0);
+                    unpack_words<VEC>(xv[u + 1], w1);
+                    unpack_words<VEC>(xv[u + 2], w2);
+                    unpack_words<VEC>(xv[u + 3], w3);
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                    for (int q = 0; q < VEC / 4; ++q) {
+                        uint32_t t[4];
+                        transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                    }
                 }
             }
             float *orow = a.out + static_cast<int64_t>(row) * a.F + col;
@@ -1152,12 +1165,15 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     TANGO_LAUNCH_CHECK();
     if (a.short_max > 0 && a.nnz > 0) {
         const int vec = pick_vec(a.F, dim, false, true);
-        const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 32);
+        // rows per wave pass: 64 (one row-pointer load per 64 rows) when that still gives every SIMD many waves, else 16
+        a.short_rows = a.n >= 64 * 1024 * 8 ? 64 : SHORT_ROWS;
+        const int rp = std::max(a.short_rows, 64 / (a.F / vec));  // as in the kernel
+        const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + rp - 1) / rp, 4, 256 * 32);
 #define TANGO_SPMM_SHORT(V_)                                     \
-    if (a.eid)                                                   \
-        k_spmm_short<V_, true><<<sb, 256, 0, st>>>(a);           \
+    if (a.short_rows == 64)                                      \
+        k_spmm_short<V_, false, 4><<<sb, 256, 0, st>>>(a);       \
     else                                                         \
-        k_spmm_short<V_, false><<<sb, 256, 0, st>>>(a);
+        k_spmm_short<V_, false, 8><<<sb, 256, 0, st>>>(a);
         if (vec == 4) { TANGO_SPMM_SHORT(4) } else if (vec == 8) { TANGO_SPMM_SHORT(8) } else { TANGO_SPMM_SHORT(16) }
 #undef TANGO_SPMM_SHORT
         TANGO_LAUNCH_CHECK();
