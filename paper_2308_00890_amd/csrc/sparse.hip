@@ -1159,19 +1159,22 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     else if ((a.nnz >> 8) >= 4096) a.chunk_shift = 8;
     // low mean degree, weights at the edge's own position, rows of at most two cache lines: rows of up to 64
     // edges go to the group-per-row kernel (measured: 3-20 % faster there, slower elsewhere)
-    a.short_max = (!x4 && !att && !a.eid && a.F <= 256 && a.n > 0 && a.nnz / a.n <= 20) ? 64 : 0;
+    const bool small_graph = a.n < 64 * 1024 * 8;
+    a.short_max = (!x4 && !att && (!a.eid || small_graph) && a.F <= 256 && a.n > 0 && a.nnz / a.n <= 20) ? 64 : 0;
     const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
     k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
     TANGO_LAUNCH_CHECK();
     if (a.short_max > 0 && a.nnz > 0) {
-        const int vec = pick_vec(a.F, dim, false, true);
+        const int vec = pick_vec(a.F, dim, false, !a.eid);
         // rows per wave pass: 64 (one row-pointer load per 64 rows) when that still gives every SIMD many waves, else 16
-        a.short_rows = a.n >= 64 * 1024 * 8 ? 64 : SHORT_ROWS;
+        a.short_rows = small_graph ? SHORT_ROWS : 64;
         const int rp = std::max(a.short_rows, 64 / (a.F / vec));  // as in the kernel
         const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + rp - 1) / rp, 4, 256 * 32);
 #define TANGO_SPMM_SHORT(V_)                                     \
     if (a.short_rows == 64)                                      \
         k_spmm_short<V_, false, 4><<<sb, 256, 0, st>>>(a);       \
+    else if (a.eid)                                              \
+        k_spmm_short<V_, true, 8><<<sb, 256, 0, st>>>(a);        \
     else                                                         \
         k_spmm_short<V_, false, 8><<<sb, 256, 0, st>>>(a);
         if (vec == 4) { TANGO_SPMM_SHORT(4) } else if (vec == 8) { TANGO_SPMM_SHORT(8) } else { TANGO_SPMM_SHORT(16) }
