@@ -829,6 +829,7 @@ struct sddmm_dot_args {
     double *dS_acc;                  // n x heads, zero-initialised
     // DOT_DST instantiations only (rows = destination nodes): three running sums per (destination, head)
     const float *row_lse;            // n x heads
+    int chunk_shift = CHUNK_SHIFT_DEFAULT;  // log2 of the edges per wavefront
     const int8_t *src_codes = nullptr;  // optional: S_q[src(e)] per in-edge, in edge order (read instead of gathered)
     double *stats;                   // n x heads x 3, zero-initialised: sum alpha*dalpha, sum alpha*dalpha*s, sum alpha*s
 };
@@ -861,9 +862,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) void k_sddmm_dot(sddmm_dot_ar
     const int lane = threadIdx.x % TANGO_WAVE;
     const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x / TANGO_WAVE));  // wave-uniform, see k_spmm
     const int64_t chunk = static_cast<int64_t>(blockIdx.x) * WAVES_PER_BLOCK + wv;
-    const int64_t c0 = chunk << CHUNK_SHIFT_DEFAULT;
+    const int64_t c0 = chunk << a.chunk_shift;
     if (c0 >= a.nnz) return;
-    const int64_t c1 = min(c0 + (int64_t(1) << CHUNK_SHIFT_DEFAULT), a.nnz);
+    const int64_t c1 = min(c0 + (int64_t(1) << a.chunk_shift), a.nnz);
 
     const int H = a.heads;
     const int LPR = a.F / VEC;
@@ -1058,6 +1059,10 @@ __global__ __launch_bounds__(256) void k_f64_to_f32(const double *__restrict__ x
 }
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// SDDMM-dot: 256 edges per wavefront, 64 on graphs too small to give every SIMD a few such chunks (a wave walks its
+// rows one after the other, so on a small graph the longest chain of rows sets the time)
+int dot_chunk_shift(int64_t nnz) { return (nnz >> CHUNK_SHIFT_DEFAULT) >= 4096 ? CHUNK_SHIFT_DEFAULT : 6; }
 
 // Bytes of a feature row per lane: aim at ~16 lanes per row.  Every lane's bytes must stay inside one
 // head, the lanes of one row must fit a wave, and the number of row groups per wave must be a power
@@ -1305,7 +1310,8 @@ int tango_sddmm_dot_async(const tango_graph *g, int heads, int dim, const int8_t
     a.heads = heads;
     a.dim = dim;
     a.F = heads * dim;
-    const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+    a.chunk_shift = dot_chunk_shift(a.nnz);
+        const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (pick_vec(a.F, dim, true, true)) {
         case 4: k_sddmm_dot<4, DOT_STORE><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
@@ -1365,7 +1371,8 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
         a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
         a.rec = nullptr; a.dS_acc = nullptr;
         a.row_lse = row_lse; a.stats = stats; a.src_codes = src_codes;
-        const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+        a.chunk_shift = dot_chunk_shift(a.nnz);
+        const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         switch (pick_vec(a.F, dim, true)) {
             case 4: k_sddmm_dot<4, DOT_DST><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
@@ -1409,7 +1416,8 @@ int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int
         a.F = heads * dim;
         a.Sq = Sq; a.Dq = Dq; a.sS = sS; a.sD = sD; a.slope = slope;
         a.rec = rec; a.dS_acc = dS_acc;
-        const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+        a.chunk_shift = dot_chunk_shift(a.nnz);
+        const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
         const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
         switch (pick_vec(a.F, dim, true)) {
             case 4: k_sddmm_dot<4, DOT_SRC><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
@@ -1491,7 +1499,8 @@ int tango_qsddmm_dot_i4(const tango_graph *g, int heads, int dim, const uint8_t 
     a.heads = heads;
     a.dim = dim / 2;
     a.F = heads * dim / 2;
-    const int64_t chunks = (a.nnz + (int64_t(1) << CHUNK_SHIFT_DEFAULT) - 1) >> CHUNK_SHIFT_DEFAULT;
+    a.chunk_shift = dot_chunk_shift(a.nnz);
+        const int64_t chunks = (a.nnz + (int64_t(1) << a.chunk_shift) - 1) >> a.chunk_shift;
     const unsigned blocks = static_cast<unsigned>((chunks + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
     switch (vec) {
         case 4: k_sddmm_dot<4, DOT_STORE, true><<<blocks, 64 * WAVES_PER_BLOCK, 0, st>>>(a); break;
