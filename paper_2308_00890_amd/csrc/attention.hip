@@ -130,7 +130,7 @@ struct attn_stats_op {
 // remaining rows with a group of lanes per row.  One launch: the hub rows no longer wait for the short ones.
 template <int H, int GROUP>
 __global__ __launch_bounds__(256) void k_attn_stats(int n, const int32_t *ptr, attn_stats_op<H> op, const float *sS,
-                                                    const float *sD, float *absmax_alpha, int huge_blocks)
+                                                    const float *sD, float *absmax_alpha, int huge_blocks, int rows_per_wave)
 {
     __shared__ double scratch[2 * 256 / 64];
     __shared__ int list[256 + 1];
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void k_attn_stats(int n, const int32_t *ptr, a
     if (static_cast<int>(blockIdx.x) < huge_blocks)
         walk_huge_rows_strided(ptr, n, static_cast<int>(blockIdx.x), huge_blocks, op, scratch, list);
     else
-        walk_rows<GROUP>(ptr, n, op, nullptr, huge_blocks, huge_blocks > 0);
+        walk_rows<GROUP>(ptr, n, op, nullptr, huge_blocks, huge_blocks > 0, rows_per_wave);
     const float m = tango_wave_max(op.amax);
     if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
 }
@@ -263,7 +263,8 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
     (void)huge;  // (the list of long rows is only used by the backward walk; here they are found inside the launch)
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
-    const unsigned grid = row_grid(n, grp);
+    const int rpw = pick_rows_per_wave(n, grp);
+    const unsigned grid = row_grid(n, grp, rpw);
     int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
     if (rc != TANGO_OK) return rc;
     // no row can be longer than HUGE_ROW unless the graph has that many edges
@@ -271,7 +272,7 @@ int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, co
 #define CALL(HH)                                                                                             \
     {                                                                                                        \
         attn_stats_op<HH> op{g->in_src, Sq, Dq, 0.f, 0.f, slope, row_lse, 0.f, src_codes};                   \
-        k_attn_stats<HH, GROUP><<<grid + huge_blocks, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge_blocks); \
+        k_attn_stats<HH, GROUP><<<grid + huge_blocks, 256, 0, st>>>(n, g->in_ptr, op, sS, sD, absmax_alpha, huge_blocks, rpw); \
     }
     TANGO_DISPATCH_H(heads, grp, CALL)
 #undef CALL

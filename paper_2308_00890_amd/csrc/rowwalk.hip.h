@@ -142,9 +142,11 @@ inline size_t huge_list_bytes(int64_t nnz) { return tango_round_up(static_cast<s
 // HUGE_ROW instead of processing them here.
 // first_block, skip_huge: the launch's workgroups below first_block do something else (walk_huge_rows_strided) and the
 // rows longer than HUGE_ROW are theirs: skipped here, no list.
+// rows_per_wave (groups of fewer than 64 lanes only; a power of two, 64 / GROUP <= rows_per_wave <= 64): the rows a wave
+// takes per outer iteration - fewer on small graphs, so that more waves share them.
 template <int GROUP, class Op>
 __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op, int *huge = nullptr, int first_block = 0,
-                                 bool skip_huge = false)
+                                 bool skip_huge = false, int rows_per_wave = 64)
 {
     const int lane = threadIdx.x % TANGO_WAVE;
     // readfirstlane / readlane: the wave index and the bounds of a row taken by the whole wave are wave-uniform, and
@@ -155,7 +157,7 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op,
     constexpr int RPI = 64 / GROUP;  // rows per wave-iteration
     // rows a wave takes per outer iteration: with a whole wave per row they are walked one after the other, each with
     // its own chain of dependent loads, so fewer rows per wave (more waves) hide more of that latency
-    constexpr int ROWS = GROUP == 64 ? 4 : 64;
+    const int ROWS = GROUP == 64 ? 4 : rows_per_wave;
     for (int64_t base = static_cast<int64_t>(wave) * ROWS; base < n; base += static_cast<int64_t>(nwaves) * ROWS) {
         const int r = (lane < ROWS) ? static_cast<int>(base) + lane : n;
         int b = 0, t = 0;
@@ -169,7 +171,7 @@ __device__ inline void walk_rows(const int32_t *__restrict__ ptr, int n, Op &op,
             is_long = 2;  // neither a group nor this wave processes it
         }
         if (GROUP < 64) {
-            for (int k = 0; k < GROUP; ++k) {
+            for (int k = 0; k * RPI < ROWS; ++k) {
                 const int src = k * RPI + lane / GROUP;
                 const int rb = __shfl(b, src, 64), rt = __shfl(t, src, 64), lg = __shfl(is_long, src, 64);
                 const int row = static_cast<int>(base) + src;
@@ -221,6 +223,16 @@ __device__ inline void walk_huge_rows_strided(const int32_t *__restrict__ ptr, i
 
 constexpr unsigned HUGE_GRID = 2048;
 
+// Rows per wave for walk_rows with groups of `group` lanes: 64, or fewer (down to one per group) while the graph has
+// fewer than 2,048 waves' worth of rows.
+inline int pick_rows_per_wave(int n, int group)
+{
+    if (group >= 64) return 64;
+    int rows = 64;
+    while (rows > 64 / group && static_cast<int64_t>(n) / rows < 2048) rows /= 2;
+    return rows;
+}
+
 inline int pick_group(int n, int64_t nnz)
 {
     const double avg = n > 0 ? static_cast<double>(nnz) / n : 0.0;
@@ -232,9 +244,9 @@ inline int pick_group(int n, int64_t nnz)
 
 // group = lanes per row as picked by pick_group (walk_rows hands a wave 16 rows per iteration when a row takes the
 // whole wave, else 64)
-inline unsigned row_grid(int n, int group = 0)
+inline unsigned row_grid(int n, int group = 0, int rows_per_wave = 64)
 {
-    const size_t rows = group == 64 ? 4 : 64;
+    const size_t rows = group == 64 ? 4 : rows_per_wave;
     return tango_grid_for((static_cast<size_t>(n) + rows - 1) / rows, 4, 256 * 16);
 }
 
