@@ -463,8 +463,8 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     int8_t *BT = static_cast<int8_t *>(ws) + 256;
     const int Kp = static_cast<int>(tango_round_up(K, 32)), Np = static_cast<int>(tango_round_up(N, 64));
 
-    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(am), 0u, 2, st)) != TANGO_OK) return rc;
-    if (absmax_C && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_C), 0u, 1, st)) != TANGO_OK) return rc;
+    if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(am), 2, reinterpret_cast<uint32_t *>(absmax_C), 1, st)) != TANGO_OK)
+        return rc;
     const float *am_A = absmax_A_in ? absmax_A_in : am;
     if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
     if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
@@ -536,6 +536,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     float *am = static_cast<float *>(ws);
     int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
     int32_t *acc = reinterpret_cast<int32_t *>(BT + bt_bytes(K, N));
+    bool acc_zeroed = false;
     const float *amp = absmax_dC_in;
     if (!amp) {
         if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(am), 0u, 1, st)) != TANGO_OK) return rc;
@@ -553,7 +554,11 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         // dA = dC_q . B_q^T: the forward kernel with dC in the role of A and B_q (K x N, rows contiguous along
         // the reduction index n) in the role of the transposed operand.
         const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));
-        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, Cp * Rp / 4, st)) != TANGO_OK) return rc;
+        // (the zero padding of BT and, if the weight gradient follows, its accumulator: one launch)
+        if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(BT), Cp * Rp / 4, reinterpret_cast<uint32_t *>(acc),
+                                        dB ? static_cast<int>(K * N) : 0, st)) != TANGO_OK)
+            return rc;
+        acc_zeroed = true;
         k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Rp, B_q, BT);
         TANGO_LAUNCH_CHECK();
         fused_args a;
@@ -568,7 +573,8 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     }
     if (dB) {
         // dB = A_q^T . dC_q, reduction over the M rows, split into slabs
-        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, static_cast<int>(K * N), st)) != TANGO_OK) return rc;
+        if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, static_cast<int>(K * N), st)) != TANGO_OK)
+            return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
         int64_t slabs = 4096 / (tiles_k * tiles_n);
         slabs = std::min<int64_t>(slabs, M / (8 * MS));  // at least eight steps per workgroup before its 64 KB of atomics

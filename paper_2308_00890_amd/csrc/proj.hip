@@ -315,8 +315,8 @@ int tango_head_proj_async(int64_t n, int heads, int dim, const float *X, const f
                           float *S, float *D, float *absmax_S, float *absmax_D, hipStream_t st)
 {
     int rc;
-    if (absmax_S && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 0u, 1, st)) != TANGO_OK) return rc;
-    if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
+    if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 1, reinterpret_cast<uint32_t *>(absmax_D), 1, st)) != TANGO_OK)
+        return rc;
     const int lph = dim / 4, q = heads * dim / 4;
     if (lph >= 1 && lph <= 64 && (lph & (lph - 1)) == 0 && q <= 256) {
         const int rpw = q < 64 ? 64 / q : 1;  // rows a wave takes side by side
@@ -354,8 +354,8 @@ int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X
     TANGO_REQUIRE(n > 0 && X && a_src && a_dst && S && D && absmax_X && X_q, TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(X, 16) && tango_aligned(X_q, 8), TANGO_ERR_BAD_SHAPE);
     int rc;
-    if (absmax_S && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 0u, 1, st)) != TANGO_OK) return rc;
-    if (absmax_D && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_D), 0u, 1, st)) != TANGO_OK) return rc;
+    if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 1, reinterpret_cast<uint32_t *>(absmax_D), 1, st)) != TANGO_OK)
+        return rc;
     const tango_rng rng = tango_rng_make(seed, stream_id);
     const size_t ngroups = static_cast<size_t>(n) * (heads * dim / 8);
     const unsigned grid = tango_grid_for(ngroups / 4 + 1, 256, 256 * 8);
@@ -375,9 +375,8 @@ int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, co
 {
     const int F = heads * dim;
     double *acc = static_cast<double *>(ws);
-    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, 4 * F, st);
+    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(acc), 4 * F, reinterpret_cast<uint32_t *>(absmax_dX), 1, st);
     if (rc != TANGO_OK) return rc;
-    if (absmax_dX && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_dX), 0u, 1, st)) != TANGO_OK) return rc;
     const int rpb = 256 / (F / 4);
     k_head_proj_bwd<<<tango_grid_for(static_cast<size_t>((n + rpb - 1) / rpb), 8, 256 * 4), 256, 0, st>>>(
         n, heads, dim, dS, dD, a_src, a_dst, X_q, s_X, dX_agg, dX, absmax_dX, acc);
