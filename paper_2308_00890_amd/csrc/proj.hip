@@ -233,6 +233,8 @@ __global__ __launch_bounds__(256) void k_head_proj_quant(int64_t n, int heads, i
     }
 }
 
+constexpr int ACC_COPIES = 16;  // copies of the column-sum accumulator of k_head_proj_bwd
+
 // dX = dX_agg + (dS*a_src + dD*a_dst); column sums of dS*(sX*Xq), dD*(sX*Xq) into acc[2F] (double, atomics).
 // Thread <-> one quad of columns; 256/TPR rows per block-iteration.
 __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int dim, const float *__restrict__ dS,
@@ -290,8 +292,11 @@ __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int
                 ts += red[j][r * tpr + threadIdx.x];
                 td += red[4 + j][r * tpr + threadIdx.x];
             }
-            if (ts != 0.0) atomicAdd(acc + c + j, ts);
-            if (td != 0.0) atomicAdd(acc + F + c + j, td);
+            // (the accumulator exists ACC_COPIES times; workgroup b adds to copy b % ACC_COPIES: sixteen times fewer
+            // atomics per address, and neighbouring workgroups do not queue on the same cache lines)
+            double *mine = acc + static_cast<size_t>(blockIdx.x % ACC_COPIES) * 2 * F;
+            if (ts != 0.0) atomicAdd(mine + c + j, ts);
+            if (td != 0.0) atomicAdd(mine + F + c + j, td);
         }
     }
     if (absmax_dX) {
@@ -304,8 +309,13 @@ __global__ void k_head_proj_bwd_finish(int F, const double *acc, float *da_src, 
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c < F) {
-        da_src[c] = static_cast<float>(acc[c]);
-        da_dst[c] = static_cast<float>(acc[F + c]);
+        double ts = 0.0, td = 0.0;
+        for (int k = 0; k < ACC_COPIES; ++k) {
+            ts += acc[static_cast<size_t>(k) * 2 * F + c];
+            td += acc[static_cast<size_t>(k) * 2 * F + F + c];
+        }
+        da_src[c] = static_cast<float>(ts);
+        da_dst[c] = static_cast<float>(td);
     }
 }
 
@@ -375,7 +385,7 @@ int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, co
 {
     const int F = heads * dim;
     double *acc = static_cast<double *>(ws);
-    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(acc), 4 * F, reinterpret_cast<uint32_t *>(absmax_dX), 1, st);
+    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(acc), 4 * F * ACC_COPIES, reinterpret_cast<uint32_t *>(absmax_dX), 1, st);
     if (rc != TANGO_OK) return rc;
     const int rpb = 256 / (F / 4);
     k_head_proj_bwd<<<tango_grid_for(static_cast<size_t>((n + rpb - 1) / rpb), 8, 256 * 4), 256, 0, st>>>(
@@ -399,7 +409,7 @@ int tango_head_proj(int64_t n, int heads, int dim, const float *X, const float *
 
 size_t tango_head_proj_bwd_workspace_bytes(int64_t, int heads, int dim)
 {
-    return tango_round_up(static_cast<size_t>(2) * heads * dim * sizeof(double), 256);
+    return tango_round_up(static_cast<size_t>(2) * heads * dim * sizeof(double) * ACC_COPIES, 256);
 }
 
 int tango_head_proj_bwd(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
