@@ -225,9 +225,18 @@ __global__ __launch_bounds__(256) void k_head_proj_quant(int64_t n, int heads, i
             }
         }
     }
+    // one update per workgroup, not per wave: the device-scope reads of the two scalars queue up at one L2 channel
     ms = tango_wave_max(ms);
     md = tango_wave_max(md);
+    __shared__ float part[2][4];
     if (lane == 0) {
+        part[0][threadIdx.x / TANGO_WAVE] = ms;
+        part[1][threadIdx.x / TANGO_WAVE] = md;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        ms = fmaxf(fmaxf(part[0][0], part[0][1]), fmaxf(part[0][2], part[0][3]));
+        md = fmaxf(fmaxf(part[1][0], part[1][1]), fmaxf(part[1][2], part[1][3]));
         if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
         if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
     }
