@@ -141,8 +141,7 @@ __global__ __launch_bounds__(256) void k_attn_stats(int n, const int32_t *ptr, a
         walk_huge_rows_strided(ptr, n, static_cast<int>(blockIdx.x), huge_blocks, op, scratch, list);
     else
         walk_rows<GROUP>(ptr, n, op, nullptr, huge_blocks, huge_blocks > 0, rows_per_wave);
-    const float m = tango_wave_max(op.amax);
-    if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_alpha, m);
+    tango_block_max_update(op.amax, absmax_alpha);
 }
 
 // Backward over the in-edges of each destination (steps 4' and 3''): alpha is recomputed from the row statistics,

@@ -237,3 +237,20 @@ __device__ static inline void tango_atomic_max_nonneg(float *addr, float v)
     if (bits > __hip_atomic_load(reinterpret_cast<const unsigned int *>(addr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
         atomicMax(reinterpret_cast<unsigned int *>(addr), bits);
 }
+
+// *addr = max(*addr, max of m over the workgroup): one update per workgroup.  (Per-wave updates all read the scalar with
+// device scope first; when the waves of a launch finish together those reads queue at one L2 channel.)  Must be
+// reached by every thread of the workgroup; blockDim.x a multiple of 64, at most 1024.
+__device__ static inline void tango_block_max_update(float m, float *addr)
+{
+    __shared__ float tango_block_max_part[16];
+    m = tango_wave_max(m);
+    if (threadIdx.x % TANGO_WAVE == 0) tango_block_max_part[threadIdx.x / TANGO_WAVE] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (unsigned w = 1; w < blockDim.x / TANGO_WAVE; ++w) m = fmaxf(m, tango_block_max_part[w]);
+        if (m > 0.0f) tango_atomic_max_nonneg(addr, m);
+    }
+    __syncthreads();
+}
+

@@ -63,12 +63,8 @@ __global__ __launch_bounds__(256) void k_head_proj(int64_t npairs, int heads, in
             }
         }
     }
-    ms = tango_wave_max(ms);
-    md = tango_wave_max(md);
-    if (lane == 0) {
-        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
-        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
-    }
+    if (absmax_S) tango_block_max_update(ms, absmax_S);
+    if (absmax_D) tango_block_max_update(md, absmax_D);
 }
 
 // The same for the usual widths (dim/4 a power of two <= 64, F <= 1024): a wave takes whole node rows, lane l the
@@ -138,12 +134,8 @@ __global__ __launch_bounds__(256) void k_head_proj_rows(int64_t n, int heads, in
             }
         }
     }
-    ms = tango_wave_max(ms);
-    md = tango_wave_max(md);
-    if (lane == 0) {
-        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
-        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
-    }
+    if (absmax_S) tango_block_max_update(ms, absmax_S);
+    if (absmax_D) tango_block_max_update(md, absmax_D);
 }
 
 // Head projections and the quantization of X in one pass over X (Sec. 3.3: the tensor the sparse primitives gather
@@ -226,20 +218,8 @@ __global__ __launch_bounds__(256) void k_head_proj_quant(int64_t n, int heads, i
         }
     }
     // one update per workgroup, not per wave: the device-scope reads of the two scalars queue up at one L2 channel
-    ms = tango_wave_max(ms);
-    md = tango_wave_max(md);
-    __shared__ float part[2][4];
-    if (lane == 0) {
-        part[0][threadIdx.x / TANGO_WAVE] = ms;
-        part[1][threadIdx.x / TANGO_WAVE] = md;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        ms = fmaxf(fmaxf(part[0][0], part[0][1]), fmaxf(part[0][2], part[0][3]));
-        md = fmaxf(fmaxf(part[1][0], part[1][1]), fmaxf(part[1][2], part[1][3]));
-        if (absmax_S && ms > 0.0f) tango_atomic_max_nonneg(absmax_S, ms);
-        if (absmax_D && md > 0.0f) tango_atomic_max_nonneg(absmax_D, md);
-    }
+    if (absmax_S) tango_block_max_update(ms, absmax_S);
+    if (absmax_D) tango_block_max_update(md, absmax_D);
 }
 
 constexpr int ACC_COPIES = 16;  // copies of the column-sum accumulator of k_head_proj_bwd
@@ -308,10 +288,7 @@ __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int
             if (td != 0.0) atomicAdd(mine + F + c + j, td);
         }
     }
-    if (absmax_dX) {
-        m = tango_wave_max(m);
-        if (threadIdx.x % TANGO_WAVE == 0 && m > 0.0f) tango_atomic_max_nonneg(absmax_dX, m);
-    }
+    if (absmax_dX) tango_block_max_update(m, absmax_dX);
 }
 
 __global__ void k_head_proj_bwd_finish(int F, const double *acc, float *da_src, float *da_dst)

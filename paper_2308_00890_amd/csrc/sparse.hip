@@ -199,10 +199,7 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
             }
         }
     }
-    if (a.absmax) {
-        m = tango_wave_max(m);
-        if (lane == 0 && m > 0.0f) tango_atomic_max_nonneg(a.absmax, m);
-    }
+    if (a.absmax) tango_block_max_update(m, a.absmax);
 }
 
 // t[c] = (r0.byte c, r1.byte c, r2.byte c, r3.byte c): 4x4 byte transpose with v_perm_b32.
