@@ -25,11 +25,11 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
                                       const float *s_X, const void *rec, double *dS_acc, float *out,
-                                      float *absmax_out, float *dS, hipStream_t st);
+                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st);
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, const int8_t *src_codes, hipStream_t st);
+                                   float *dD, const int8_t *src_codes, double *also_zero, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -384,7 +384,7 @@ int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const 
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
                   TANGO_ERR_WORKSPACE);
     return tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse,
-                                          static_cast<double *>(ws), rec, dD, nullptr,
+                                          static_cast<double *>(ws), rec, dD, nullptr, nullptr,
                                           tango_stream(stream));
 }
 
@@ -408,7 +408,7 @@ int tango_gat_attention_bwd_src(const tango_graph *g, int heads, int dim, const 
     return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                              stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X,
                                              rec, static_cast<double *>(ws), dX_agg,
-                                             absmax_dX, dS, tango_stream(stream));
+                                             absmax_dX, dS, false, tango_stream(stream));
 }
 
 int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
@@ -464,11 +464,11 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
     if (edge_part && !alpha_q && !dalpha) {
         // no edge tensor at all: 5'', 4', 3'' in one walk over the in-edges, then 5' and 3' in one walk over the out-edges
         rc = tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse, stats,
-                                            rec, dD, src_codes, st);
+                                            rec, dD, src_codes, dS_acc, st);
         if (rc != TANGO_OK) return rc;
         return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                                  stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
-                                                 absmax_dX, dS, st);
+                                                 absmax_dX, dS, true, st);
     }
     if (edge_part && !alpha_q) {
         // 5'' over in-edges (dalpha, the only fp32 edge tensor of the backward pass), 4' and 3'' over in-edges, then
@@ -479,7 +479,7 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
         if (rc != TANGO_OK) return rc;
         return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                                  stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
-                                                 absmax_dX, dS, st);
+                                                 absmax_dX, dS, false, st);
     }
     // 5': SPMM on the reversed graph.  With a cached alpha_q its codes are read through the edge-id map (a random
     // 4-byte access per edge); without, the identical codes are recomputed from the cache-resident S_q, D_q, row_lse.

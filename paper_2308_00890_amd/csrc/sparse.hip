@@ -1270,10 +1270,11 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
                                       const float *s_X, const void *rec, double *dS_acc, float *out,
-                                      float *absmax_out, float *dS, hipStream_t st)
+                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
-    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
+    int rc = TANGO_OK;
+    if (!dS_acc_zeroed) rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
     if (rc != TANGO_OK) return rc;
     attn_params att;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
@@ -1346,10 +1347,12 @@ __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, 
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, const int8_t *src_codes, hipStream_t st)
+                                   float *dD, const int8_t *src_codes, double *also_zero, hipStream_t st)
 {
+    // also_zero (may be NULL): n x heads more doubles zeroed by the same launch (the source-side pass's accumulator)
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
-    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(stats), 0u, static_cast<int>(6 * nh), st);
+    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(stats), static_cast<int>(6 * nh),
+                                   reinterpret_cast<uint32_t *>(also_zero), static_cast<int>(2 * nh), st);
     if (rc != TANGO_OK) return rc;
     if (g->n_edges > 0) {
         sddmm_dot_args a;
