@@ -280,7 +280,7 @@ def main():
         step = lambda: (T.tango_typed_layer_fwd(L), T.tango_typed_layer_bwd(L))
         heads = 1
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
-        spmm_name = "k_spmm<16, false, 0> (tango_qspmm, in-edge direction over (source, type) rows)"
+        spmm_name = "tango_qspmm, in-edge direction over (source, type) rows (k_spmm_short for rows of up to 64 edges, k_spmm for the rest, prepare/finalize)"
         alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     elif cfg["kind"] == "gcn":
         w = to(ti.gcn_edge_weights(g))  # fixed edge weights: inputs of the layer, quantized once outside the timed region
@@ -291,7 +291,7 @@ def main():
         step = lambda: (T.tango_gcn_layer_fwd(L), T.tango_gcn_layer_bwd(L))
         heads, F = 1, cfg["dim"]
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
-        spmm_name = "k_spmm<16, false, 0> (tango_qspmm, in-edge direction)"
+        spmm_name = "tango_qspmm, in-edge direction (k_spmm_short for rows of up to 64 edges, k_spmm for the rest, prepare/finalize)"
         alg = spmm_algorithmic_bytes(g.n_nodes, g.n_edges, heads, F)
     elif name == "gat_products":
         # configuration 4: three stacked GAT layers (K_in 100 -> 384 -> 384 -> 384), ReLU between them; one step =
@@ -388,6 +388,8 @@ def main():
             % (cfg["config"], name, cfg["graph"], g.n_nodes, g.n_edges, li.feat.shape[1], li.heads, li.dim),
             "scale_down": args.scale_down,
             "launch": "hip graph replay" if args.hipgraph else "eager",
+            "layer_caches": ("edge-ordered source codes" + (", ReLU sign bits" if name == "gat_products" else ""))
+            if cfg["kind"] == "gat" and not typed else "none",
         },
         "roofline": {
             "kernel": spmm_name,
