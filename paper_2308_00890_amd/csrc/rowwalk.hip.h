@@ -236,9 +236,11 @@ inline int pick_rows_per_wave(int n, int group)
 inline int pick_group(int n, int64_t nnz)
 {
     const double avg = n > 0 ? static_cast<double>(nnz) / n : 0.0;
-    if (avg <= 12.0) return 8;
-    if (avg <= 24.0) return 16;
-    if (avg <= 48.0) return 32;
+    // (measured on the softmax statistics pass: with rows of 17-26 edges groups of 8 lanes beat 16 and 32 - more rows in
+    // flight per wave matter more than one pass per row)
+    if (avg <= 32.0) return 8;
+    if (avg <= 64.0) return 16;
+    if (avg <= 128.0) return 32;
     return 64;
 }
 
