@@ -556,7 +556,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));
         // (the zero padding of BT and, if the weight gradient follows, its accumulator: one launch)
         if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(BT), Cp * Rp / 4, reinterpret_cast<uint32_t *>(acc),
-                                        dB ? static_cast<int>(K * N) : 0, st)) != TANGO_OK)
+                                        dB ? K * N : 0, st)) != TANGO_OK)
             return rc;
         acc_zeroed = true;
         k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Rp, B_q, BT);
@@ -573,7 +573,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     }
     if (dB) {
         // dB = A_q^T . dC_q, reduction over the M rows, split into slabs
-        if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, static_cast<int>(K * N), st)) != TANGO_OK)
+        if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, K * N, st)) != TANGO_OK)
             return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
         int64_t slabs = 4096 / (tiles_k * tiles_n);

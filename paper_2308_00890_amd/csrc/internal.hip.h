@@ -4,10 +4,10 @@
 #include "common.hip.h"
 
 // p[0..n) = v on the stream (a kernel, so it is safe inside captured graphs).
-int tango_fill_u32_async(uint32_t *p, uint32_t v, int n, hipStream_t st);
+int tango_fill_u32_async(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
 
 // p1[0..n1) = 0 and p2[0..n2) = 0 in one launch (either pointer may be NULL, its count is then ignored).
-int tango_zero2_u32_async(uint32_t *p1, int n1, uint32_t *p2, int n2, hipStream_t st);
+int tango_zero2_u32_async(uint32_t *p1, int64_t n1, uint32_t *p2, int64_t n2, hipStream_t st);
 
 // *out = max(*out, max|x|) with *out holding the bits of a non-negative float.
 int tango_absmax_accumulate_async(const float *x, size_t n, float *out, hipStream_t st);

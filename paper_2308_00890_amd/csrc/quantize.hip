@@ -6,10 +6,11 @@
 
 namespace {
 
-__global__ void k_fill_u32(uint32_t *p, uint32_t v, int n)
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, int64_t n)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+        p[i] = v;
 }
 
 __device__ inline float4 tango_mask4(const float4 a, const float4 k)
@@ -278,29 +279,32 @@ __global__ void k_error_x_finish(error_x_cands cands, size_t n, float threshold,
 }  // namespace
 
 // Internal (not part of the ABI): used by the other translation units.
-static __global__ void k_zero2_u32(uint32_t *p1, int n1, uint32_t *p2, int n2)
+static __global__ void k_zero2_u32(uint32_t *p1, int64_t n1, uint32_t *p2, int64_t n2)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n1)
-        p1[i] = 0u;
-    else if (i - n1 < n2)
-        p2[i - n1] = 0u;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n1 + n2;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        if (i < n1)
+            p1[i] = 0u;
+        else
+            p2[i - n1] = 0u;
+    }
 }
 
 // p1[0..n1) = 0 and p2[0..n2) = 0 in one launch (either pointer may be NULL with its count ignored).
-int tango_zero2_u32_async(uint32_t *p1, int n1, uint32_t *p2, int n2, hipStream_t st)
+int tango_zero2_u32_async(uint32_t *p1, int64_t n1, uint32_t *p2, int64_t n2, hipStream_t st)
 {
-    if (!p1) n1 = 0;
-    if (!p2) n2 = 0;
+    if (!p1 || n1 < 0) n1 = 0;
+    if (!p2 || n2 < 0) n2 = 0;
     if (n1 + n2 == 0) return TANGO_OK;
-    k_zero2_u32<<<(n1 + n2 + 255) / 256, 256, 0, st>>>(p1, n1, p2, n2);
+    k_zero2_u32<<<tango_grid_for(static_cast<size_t>(n1 + n2), 256, 256 * 64), 256, 0, st>>>(p1, n1, p2, n2);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
 
-int tango_fill_u32_async(uint32_t *p, uint32_t v, int n, hipStream_t st)
+int tango_fill_u32_async(uint32_t *p, uint32_t v, int64_t n, hipStream_t st)
 {
-    k_fill_u32<<<(n + 63) / 64, 64, 0, st>>>(p, v, n);
+    if (n <= 0) return TANGO_OK;
+    k_fill_u32<<<tango_grid_for(static_cast<size_t>(n), 256, 256 * 64), 256, 0, st>>>(p, v, n);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }

@@ -1274,7 +1274,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
     int rc = TANGO_OK;
-    if (!dS_acc_zeroed) rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
+    if (!dS_acc_zeroed) rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, 2 * nh, st);
     if (rc != TANGO_OK) return rc;
     attn_params att;
     att.Sq = Sq; att.Dq = Dq; att.sS = sS; att.sD = sD; att.slope = slope;
@@ -1351,8 +1351,8 @@ int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, con
 {
     // also_zero (may be NULL): n x heads more doubles zeroed by the same launch (the source-side pass's accumulator)
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
-    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(stats), static_cast<int>(6 * nh),
-                                   reinterpret_cast<uint32_t *>(also_zero), static_cast<int>(2 * nh), st);
+    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(stats), 6 * nh,
+                                   reinterpret_cast<uint32_t *>(also_zero), 2 * nh, st);
     if (rc != TANGO_OK) return rc;
     if (g->n_edges > 0) {
         sddmm_dot_args a;
@@ -1398,7 +1398,7 @@ int tango_attn_bwd_src_async(const tango_graph *g, int heads, int dim, const int
                              hipStream_t st)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
-    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, static_cast<int>(2 * nh), st);
+    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(dS_acc), 0u, 2 * nh, st);
     if (rc != TANGO_OK) return rc;
     if (g->n_edges > 0) {
         sddmm_dot_args a;
