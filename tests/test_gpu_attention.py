@@ -24,7 +24,8 @@ def T():
 @pytest.mark.parametrize("gname,heads,dim", [("toy", 2, 32), ("rmat", 4, 64), ("rmat", 3, 128), ("sparse", 1, 64),
                                              ("sparse", 8, 16), ("holes", 2, 32), ("one", 4, 64),
                                              ("dense", 4, 64), ("dense", 3, 128), ("dense", 8, 16), ("dense", 1, 32),
-                                             ("sparse", 2, 128), ("hub", 4, 64), ("hub", 3, 128), ("hub", 1, 32)])
+                                             ("sparse", 2, 128), ("hub", 4, 64), ("hub", 3, 128), ("hub", 1, 32),
+                                             ("edgeless", 4, 64)])
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
 def test_fused_attention_forward_backward(T, gname, heads, dim, rounding):
     import torch

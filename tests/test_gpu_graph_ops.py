@@ -45,6 +45,8 @@ def graph(name):
             src = np.concatenate([everyone, everyone, np.full(n, 5), np.full(n, 4321), rng.integers(0, n, 30000)])
             dst = np.concatenate([np.full(n, 5), np.full(n, 4321), everyone, everyone, rng.integers(0, n, 30000)])
             g = ti.graph_from_edges(n, src, dst)
+        elif name == "edgeless":  # nodes only
+            g = ti.graph_from_edges(37, [], [], self_loops=False)
         elif name == "one":
             g = ti.graph_from_edges(1, [], [], self_loops=True)
         else:
@@ -72,6 +74,7 @@ CASES = [
     ("one", 4, 64),
     ("hub", 4, 64),
     ("hub", 3, 128),
+    ("edgeless", 2, 32),
 ]
 
 
@@ -137,7 +140,7 @@ def test_qspmm_bwd_is_reverse_spmm_plus_sddmm_dot(T, gname, heads, dim):
 
 
 EDGE_CASES = [("toy", 2), ("rmat", 4), ("rmat", 3), ("rmat", 1), ("sparse", 1), ("sparse", 8), ("holes", 2), ("one", 4),
-              ("hub", 4), ("hub", 3), ("dense", 2)]
+              ("hub", 4), ("hub", 3), ("dense", 2), ("edgeless", 2)]
 
 
 @pytest.mark.parametrize("gname,heads", EDGE_CASES)

@@ -259,7 +259,7 @@ def test_three_layer_gat_chain_activation_inside_the_layers(T, mode):
                          relu_out=(i < 2), dH_keep=keep)
 
 
-@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8", "hub_h1"])
+@pytest.mark.parametrize("case", ["toy", "rmat_h4", "rmat_h3", "dense_h8", "hub_h1", "edgeless"])
 def test_cached_source_codes_change_nothing(T, case):
     """With `src_codes` the first walk over the in-edges leaves S_q[src(e)] per edge and the later walks read that stream
     instead of gathering: the buffer holds exactly those codes and every output is the same bit for bit (fp32 edge sums
@@ -273,6 +273,11 @@ def test_cached_source_codes_change_nothing(T, case):
         li.a_dst = ti.xavier_uniform(8, 16, (8, 16), 72)
         li.weight = ti.xavier_uniform(48, 128, (48, 128), 73)
         li.grad_out = ti.normal((g.n_nodes, 128), 74)
+        slope = 0.2
+    elif case == "edgeless":  # no edge at all: every aggregate is zero, the layer must still run
+        from test_gpu_graph_ops import graph
+
+        li = ti.layer_inputs("toy", graph=graph("edgeless"), k_in=24)
         slope = 0.2
     elif case == "hub_h1":  # one head; two rows beyond the one-wave-per-row limit of the statistics pass
         from test_gpu_graph_ops import graph
@@ -296,6 +301,8 @@ def test_cached_source_codes_change_nothing(T, case):
         T.tango_gat_layer_bwd(L)
     torch.cuda.synchronize()
     assert_bit_exact(host(B["src_codes"]), host(B["S_q"])[li.graph.in_src], "S_q of every edge's source")
+    if li.graph.n_edges == 0:
+        assert not host(A["out"]).any() and host(A["s_alpha"])[0] == 1.0
     for name in ("out", "row_lse", "absmax_alpha", "s_alpha", "g_q", "dHp", "dS", "dD", "dW", "dH", "da_src", "da_dst"):
         assert_bit_exact(host(B[name]), host(A[name]), name)
 
