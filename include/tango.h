@@ -21,6 +21,11 @@
  *    tensors hold `heads` values per edge and are indexed by the edge's
  *    position in destination-major order (see tango_graph).
  *  - Indices are int32, n_edges < 2^31; element offsets are formed in 64 bit.
+ *  - Floating-point inputs must be finite (the paper's quantizer is defined on
+ *    finite tensors only).  A NaN never wins an abs-max and is cast to code 0,
+ *    an infinity makes the scale infinite and every code 0: neither is
+ *    reported, so a caller that wants divergence to surface checks its loss or
+ *    its tensors before handing them over.
  *  - `ws`/`ws_bytes`: caller-provided scratch, at least the value returned by
  *    the matching *_workspace_bytes() query, 256-byte aligned.  Its contents
  *    on entry do not matter and are undefined on return.
@@ -181,6 +186,11 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
  *   dB (K x N) = (float)(A_q^T . dC_q) * (s_A*s_dC)      (Sec. 3.2: fp32
  * gradients for the full-precision weight update).  dA or dB may be NULL to
  * skip that product.  dA with N > 2048 needs N % 16 == 0.
+ * dB is a reduction over all M rows: slabs of at most 2^17 rows are summed in
+ * int32 (exact: 2^17 * 127^2 < 2^31) and the slabs are combined in 64-bit
+ * integers, so dB is the exact integer product for any M (for sums that fit
+ * int32 -- every case the paper's 32-bit accumulator covers, Sec. 3.2 -- the
+ * result is the same bit for bit).
  */
 size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,
@@ -200,20 +210,6 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
  */
 int tango_qgemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A,
                    const int8_t *BT_q, const float *s_B, float *C, float *absmax_C, void *stream);
-
-/*
- * Measurement aid (not a step of the method; for callers that report the
- * matrix-core roofline of tango_qgemm_i8): launches 256 workgroups x 4 waves
- * that each issue 8*iters independent v_mfma_i32_32x32x32_i8 from registers.
- * random_operands != 0 fills the operand registers with pseudo-random bytes
- * (realistic switching activity; the chip then runs power-limited), 0 with
- * constant bytes.  *ops (host) receives the int8 operation count (2 per MAC)
- * of the launch; the caller times it.  ws: device scratch of
- * tango_mfma_i8_rate_workspace_bytes().
- */
-size_t tango_mfma_i8_rate_workspace_bytes(void);
-int tango_mfma_i8_rate_launch(int iters, int random_operands, void *ws, size_t ws_bytes, double *ops,
-                              void *stream);
 
 /* ------------------------------------------------------------------------ */
 /* Attention projections (Sec. 2.1 step 2 and 2'), fp32.                      */

@@ -55,8 +55,6 @@ SIGNATURES = {
     "tango_qgemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
-    "tango_mfma_i8_rate_workspace_bytes": (_sz, []),
-    "tango_mfma_i8_rate_launch": (_int, [_int, _int, _vp, _sz, ctypes.POINTER(ctypes.c_double), _vp]),
     "tango_gat_attention_bwd_rec_bytes": (_sz, [_i64, _int]),
     "tango_gat_attention_bwd_dst_workspace_bytes": (_sz, [_i64, _int]),
     "tango_gat_attention_bwd_src_workspace_bytes": (_sz, [_i64, _int]),
@@ -258,18 +256,6 @@ def tango_qgemm_i8(A_q, s_A, BT_q, s_B, C, absmax_C):
         ),
         "tango_qgemm_i8",
     )
-
-
-def tango_mfma_i8_rate_workspace_bytes() -> int:
-    return load_library().tango_mfma_i8_rate_workspace_bytes()
-
-
-def tango_mfma_i8_rate_launch(iters, random_operands, ws) -> float:
-    """Enqueues the register-only int8 MFMA loop; returns its operation count (the caller times the launch)."""
-    ops = ctypes.c_double(0.0)
-    _check(load_library().tango_mfma_i8_rate_launch(iters, int(bool(random_operands)), _ptr(ws), ws.numel() * ws.element_size(),
-                                                    ctypes.byref(ops), _stream()), "tango_mfma_i8_rate_launch")
-    return ops.value
 
 
 def tango_qgemm_bwd_workspace_bytes(M, N, K) -> int:
@@ -680,6 +666,46 @@ class GatLayer(_LayerBuffers):
         nbytes = tango_gat_layer_workspace_bytes(n, nnz, k_in, heads, dim)
         self._alloc("ws", (nbytes,), torch.uint8)
         c.ws_bytes = nbytes
+
+
+class GatStack:
+    """Stacked GAT layers in the configuration the stacked-layer workloads run (allocation and pointer wiring only): the
+    ReLU between layers sits inside the layers (`relu_out`, sign bits kept in `relu_bits`), a layer's output is the next
+    layer's input with its abs-max handed over (`absmax_H`), a layer's input gradient is written straight into the
+    lower layer's `grad_out` with that layer's ReLU' applied (`dH_keep_bits`) and its abs-max handed down
+    (`absmax_grad_out`), the sources' S_q codes are kept as an edge-ordered stream (`src_codes`), and nothing else is
+    stored per edge unless `keep_alpha` asks for the fp32 attention that was quantized (verification only)."""
+
+    def __init__(self, graph: "Graph", feat, weights, a_src, a_dst, grad_out, slope=0.2, rounding=SR, seed=0,
+                 keep_alpha=False):
+        n = feat.shape[0]
+        last = len(weights) - 1
+        self.layers = []
+        for i, W in enumerate(weights):
+            F = W.shape[1]
+            below = self.layers[i - 1] if i > 0 else None
+            grad = grad_out if i == last else torch.empty((n, F), dtype=torch.float32, device=feat.device)
+            self.layers.append(GatLayer(
+                graph, feat if i == 0 else below["out"], W, a_src[i], a_dst[i], grad, slope, rounding, seed, i,
+                want_dH=False, relu_out=(i < last), relu_bits=True, src_codes=True, keep_alpha=keep_alpha,
+                absmax_H=(below["absmax_out"] if below else None),
+                dH_keep_bits=(below["relu_bits"] if below else None)))
+        for i in range(1, len(weights)):
+            self.layers[i]._bind("dH", self.layers[i - 1]["grad_out"], torch.float32)
+            self.layers[i - 1]._bind("absmax_grad_out", self.layers[i]["absmax_dH"], torch.float32)
+
+    def __getitem__(self, i):
+        return self.layers[i]
+
+    def __len__(self):
+        return len(self.layers)
+
+    def step(self):
+        """Forward through every layer, then backward through every layer."""
+        for L in self.layers:
+            tango_gat_layer_fwd(L)
+        for L in reversed(self.layers):
+            tango_gat_layer_bwd(L)
 
 
 class GcnLayer(_LayerBuffers):

@@ -12,6 +12,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtango.so")
+AID_SRC = os.path.join(CSRC, "benchaid", "benchaid.hip")  # measurement aids of the harness: a library of their own
+AID_LIB = os.path.join(HERE, "libtango_benchaid.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -31,6 +33,13 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def _link(objs, lib):
+    tmp = lib + ".tmp.%d" % os.getpid()
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], check=True,
+                   stdout=subprocess.PIPE, stderr=subprocess.PIPE)
+    os.replace(tmp, lib)
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
     subprocess.run([HIPCC, *FLAGS, "-c", src, "-o", obj], check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE)
@@ -38,18 +47,15 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every csrc/*.hip and link libtango.so next to this file."""
+    """Compile every csrc/*.hip and link libtango.so next to this file; the harness's measurement aids
+    (csrc/benchaid/) become libtango_benchaid.so."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sources()
     try:
-        with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-            objs = list(ex.map(_compile, srcs))
-        tmp = LIB + ".tmp.%d" % os.getpid()
-        subprocess.run(
-            [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
-            check=True, stdout=subprocess.PIPE, stderr=subprocess.PIPE,
-        )
-        os.replace(tmp, LIB)
+        with ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
+            objs = list(ex.map(_compile, srcs + [AID_SRC]))
+        _link(objs[:-1], LIB)
+        _link(objs[-1:], AID_LIB)
     except subprocess.CalledProcessError as e:
         sys.stderr.write(e.stderr.decode(errors="replace"))
         raise
@@ -59,10 +65,10 @@ def build(verbose: bool = False) -> str:
 
 
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(AID_LIB):
         return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    t = min(os.path.getmtime(LIB), os.path.getmtime(AID_LIB))
+    deps = sources() + [AID_SRC] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -1,0 +1,150 @@
+// Measurement aids of the benchmark harness (libtango_benchaid.so), not steps of the method: the rate the matrix cores
+// sustain when every SIMD issues matrix instructions back to back from registers (no LDS, no memory), and a plain
+// streaming copy of known size.  With operand bits that toggle (random bytes) the chip runs power-limited well below
+// its nominal clock, so the register-only rate is the practical ceiling a GEMM main loop is measured against, next to
+// the published peak.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tango.h"
+#include "tango_benchaid.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ inline void operand_words(int i, int c, int random_operands, int &a, int &b)
+{
+    unsigned h = (threadIdx.x * 16u + i * 4u + c + blockIdx.x * 4096u) * 2654435761u;
+    h ^= h >> 15;
+    h *= 2246822519u;
+    h ^= h >> 13;
+    unsigned g = h * 3266489917u;
+    g ^= g >> 16;
+    a = random_operands ? static_cast<int>(h) : 0x01010101;
+    b = random_operands ? static_cast<int>(g) : 0x02020202;
+}
+
+__global__ __launch_bounds__(256) void k_mfma_i8_rate(int iters, int random_operands, int *sink)
+{
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = v16i{0};
+    v4i av[4], bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            int a, b;
+            operand_words(i, c, random_operands, a, b);
+            av[i][c] = a;
+            bv[i][c] = b;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[i % 4], bv[i / 2], acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;  // keeps the loop alive
+}
+
+// FMT: 0 = fp8 e4m3 (32 bytes of operand per lane), 4 = fp4 e2m1 (16 bytes per lane; the upper half of the operand
+// registers is ignored by the instruction).  Random operand bytes are masked so that no fp8 operand is a NaN / huge
+// value: the sums stay finite and the loop is not optimised away.
+template <int FMT>
+__global__ __launch_bounds__(256) void k_mfma_f8f6f4_rate(int iters, int random_operands, float *sink)
+{
+    v16f acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = v16f{0.0f};
+    v8i av[2], bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            int a, b;
+            operand_words(i, c, random_operands, a, b);
+            if (FMT == 0) {  // keep the exponent field below its maximum: finite, small magnitudes
+                a &= 0xbfbfbfbf;
+                b &= 0xbfbfbfbf;
+            }
+            if (i < 2) av[i][c] = a;
+            bv[i][c] = b;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av[i % 2], bv[i / 2], acc[i], FMT, FMT, 0, 0x7f7f7f7f, 0,
+                                                                    0x7f7f7f7f);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void k_copy16(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+constexpr int RATE_BLOCKS = 256;  // one workgroup of 4 waves per compute unit: one wave per SIMD
+
+}  // namespace
+
+extern "C" {
+
+size_t tango_benchaid_mfma_i8_workspace_bytes(void) { return static_cast<size_t>(RATE_BLOCKS) * 256 * sizeof(int); }
+
+int tango_benchaid_mfma_i8_launch(int iters, int random_operands, void *ws, size_t ws_bytes, double *ops, void *stream)
+{
+    if (iters < 1 || iters > (1 << 24)) return TANGO_ERR_BAD_SHAPE;
+    if (!ws || !ops) return TANGO_ERR_NULL;
+    if (ws_bytes < tango_benchaid_mfma_i8_workspace_bytes()) return TANGO_ERR_WORKSPACE;
+    k_mfma_i8_rate<<<RATE_BLOCKS, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(iters, random_operands, static_cast<int *>(ws));
+    if (hipGetLastError() != hipSuccess) return TANGO_ERR_LAUNCH;
+    *ops = 2.0 * 32 * 32 * 32 * 8.0 * iters * RATE_BLOCKS * 4;
+    return TANGO_OK;
+}
+
+int tango_benchaid_mfma_f8f6f4_launch(int iters, int format, int random_operands, void *ws, size_t ws_bytes, double *ops,
+                                      void *stream)
+{
+    if (iters < 1 || iters > (1 << 24)) return TANGO_ERR_BAD_SHAPE;
+    if (format != 0 && format != 1) return TANGO_ERR_BAD_ENUM;
+    if (!ws || !ops) return TANGO_ERR_NULL;
+    if (ws_bytes < tango_benchaid_mfma_i8_workspace_bytes()) return TANGO_ERR_WORKSPACE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (format == 0)
+        k_mfma_f8f6f4_rate<0><<<RATE_BLOCKS, 256, 0, st>>>(iters, random_operands, static_cast<float *>(ws));
+    else
+        k_mfma_f8f6f4_rate<4><<<RATE_BLOCKS, 256, 0, st>>>(iters, random_operands, static_cast<float *>(ws));
+    if (hipGetLastError() != hipSuccess) return TANGO_ERR_LAUNCH;
+    *ops = 2.0 * 32 * 32 * 64 * 8.0 * iters * RATE_BLOCKS * 4;
+    return TANGO_OK;
+}
+
+int tango_benchaid_copy(const void *src, void *dst, size_t n_words16, void *stream)
+{
+    if (!src || !dst) return TANGO_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16) return TANGO_ERR_BAD_SHAPE;
+    if (n_words16 == 0) return TANGO_OK;
+    size_t blocks = (n_words16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    k_copy16<<<static_cast<unsigned>(blocks), 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n_words16);
+    if (hipGetLastError() != hipSuccess) return TANGO_ERR_LAUNCH;
+    return TANGO_OK;
+}
+
+}  // extern "C"

@@ -292,7 +292,7 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
 }
 
 __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const int8_t *__restrict__ P,
-                                                 const int8_t *__restrict__ Q, int32_t *acc_out, int64_t slab_rows,
+                                                 const int8_t *__restrict__ Q, long long *acc_out, int64_t slab_rows,
                                                  int tiles_k, int tiles_n)
 {
     __shared__ __align__(16) int8_t Pt[TT * LDM];
@@ -369,12 +369,14 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const 
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = k0 + rbase + rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-            if (row < K && col < N && acc[i] != 0) atomicAdd(acc_out + static_cast<int64_t>(row) * N + col, acc[i]);
+            if (row < K && col < N && acc[i] != 0)
+                atomicAdd(reinterpret_cast<unsigned long long *>(acc_out + static_cast<int64_t>(row) * N + col),
+                          static_cast<unsigned long long>(static_cast<long long>(acc[i])));
         }
     }
 }
 
-__global__ __launch_bounds__(256) void k_dequant_i32(const int32_t *__restrict__ acc, int64_t n, const float *sa,
+__global__ __launch_bounds__(256) void k_dequant_i64(const long long *__restrict__ acc, int64_t n, const float *sa,
                                                      const float *sb, float *__restrict__ out)
 {
     const float sc = (*sa) * (*sb);
@@ -468,7 +470,7 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     const float *am_A = absmax_A_in ? absmax_A_in : am;
     if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
     if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
-    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, Np * Kp / 4, st)) != TANGO_OK) return rc;
+    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, static_cast<int64_t>(Np) * Kp / 4, st)) != TANGO_OK) return rc;
     const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
     const unsigned gb = tango_grid_for(static_cast<size_t>(K) * N, 256);
     if (rounding == TANGO_RN)
@@ -497,7 +499,7 @@ extern "C" {
 size_t tango_qgemm_bwd_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (validate_mnk(M, N, K) != TANGO_OK) return 0;
-    return 256 + bt_bytes(K, N) + tango_round_up(static_cast<size_t>(K) * N * sizeof(int32_t), 256);
+    return 256 + bt_bytes(K, N) + tango_round_up(static_cast<size_t>(K) * N * sizeof(long long), 256);
 }
 
 int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
@@ -535,7 +537,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     if (absmax_dA && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_dA), 0u, 1, st)) != TANGO_OK) return rc;
     float *am = static_cast<float *>(ws);
     int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
-    int32_t *acc = reinterpret_cast<int32_t *>(BT + bt_bytes(K, N));
+    long long *acc = reinterpret_cast<long long *>(BT + bt_bytes(K, N));  // 64-bit sums of the weight gradient
     bool acc_zeroed = false;
     const float *amp = absmax_dC_in;
     if (!amp) {
@@ -555,8 +557,8 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         // the reduction index n) in the role of the transposed operand.
         const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));
         // (the zero padding of BT and, if the weight gradient follows, its accumulator: one launch)
-        if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(BT), Cp * Rp / 4, reinterpret_cast<uint32_t *>(acc),
-                                        dB ? K * N : 0, st)) != TANGO_OK)
+        if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(BT), static_cast<int64_t>(Cp) * Rp / 4,
+                                        reinterpret_cast<uint32_t *>(acc), dB ? 2 * K * N : 0, st)) != TANGO_OK)
             return rc;
         acc_zeroed = true;
         k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Rp, B_q, BT);
@@ -573,19 +575,20 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     }
     if (dB) {
         // dB = A_q^T . dC_q, reduction over the M rows, split into slabs
-        if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, K * N, st)) != TANGO_OK)
+        if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, 2 * K * N, st)) != TANGO_OK)
             return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
         int64_t slabs = 4096 / (tiles_k * tiles_n);
         slabs = std::min<int64_t>(slabs, M / (8 * MS));  // at least eight steps per workgroup before its 64 KB of atomics
         if (slabs < 1) slabs = 1;
-        int64_t slab_rows = tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS);
+        // a slab's int32 partial sums stay exact (2^17 rows x 127^2 < 2^31); the slabs are combined in 64 bits
+        int64_t slab_rows = std::min<int64_t>(tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS), int64_t(1) << 17);
         slabs = (M + slab_rows - 1) / slab_rows;
         const unsigned grid = static_cast<unsigned>(tiles_k * tiles_n * tango_round_up(static_cast<size_t>(slabs), 8));
         k_gemm_tn<<<grid, 256, 0, st>>>(M, static_cast<int>(K), static_cast<int>(N), A_q, dC_q, acc, slab_rows, tiles_k,
                                         tiles_n);
         TANGO_LAUNCH_CHECK();
-        k_dequant_i32<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(acc, K * N, s_A, s_dC, dB);
+        k_dequant_i64<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(acc, K * N, s_A, s_dC, dB);
         TANGO_LAUNCH_CHECK();
     }
     return TANGO_OK;

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/tango.h declares (no GPU needed)."""
+"""The C-ABI libraries load and export every symbol include/*.h declares (no GPU needed)."""
 import ctypes
 import os
 import re
@@ -8,8 +8,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tango.h")).read()
+def declared_symbols(header="tango.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tango_[a-z0-9_]+)\s*\(", text)))
 
@@ -28,6 +28,20 @@ def test_header_symbols_are_exported(lib):
     assert "tango_quantize" in names and "tango_qspmm_bwd" in names and len(names) >= 19
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_benchaid_header_symbols_are_exported(lib):
+    """The harness's measurement aids are a library and a header of their own; tango.h holds the method only."""
+    from paper_2308_00890_amd import benchaid, build as b
+
+    aid = ctypes.CDLL(b.AID_LIB)
+    names = declared_symbols("tango_benchaid.h")
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tango.h", "tango_benchaid.h"]
+    assert names == sorted(benchaid.SIGNATURES) and len(names) == 4
+    for n in names:
+        assert hasattr(aid, n), n
+        assert not hasattr(lib, n), "measurement aid exported by the method's library: " + n
+        assert n not in declared_symbols()
 
 
 def test_binding_lists_every_symbol():

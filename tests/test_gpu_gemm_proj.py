@@ -115,15 +115,25 @@ def test_qgemm_i8(T, M, K, N):
     assert host(am)[0] == want_am
 
 
-def test_mfma_rate_measurement_aid(T):
+def test_measurement_aids_of_the_harness(T):
+    """libtango_benchaid.so (not part of the method): the register-only matrix-core loops report their operation
+    counts and reject a short workspace; the plain copy copies."""
     import torch
 
-    ws = workspace(T.tango_mfma_i8_rate_workspace_bytes())
-    ops = T.tango_mfma_i8_rate_launch(10, 1, ws)
+    from paper_2308_00890_amd import benchaid as B
+
+    ws = workspace(B.tango_benchaid_mfma_i8_workspace_bytes())
+    assert B.tango_benchaid_mfma_i8_launch(10, 1, ws) == 2.0 * 32 * 32 * 32 * 8 * 10 * 256 * 4
+    for fmt in (0, 1):
+        assert B.tango_benchaid_mfma_f8f6f4_launch(10, fmt, 1, ws) == 2.0 * 32 * 32 * 64 * 8 * 10 * 256 * 4
     torch.cuda.synchronize()
-    assert ops == 2.0 * 32 * 32 * 32 * 8 * 10 * 256 * 4
     with pytest.raises(T.TangoError):
-        T.tango_mfma_i8_rate_launch(10, 1, workspace(16))
+        B.tango_benchaid_mfma_i8_launch(10, 1, workspace(16))
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    B.tango_benchaid_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
 
 
 PROJ_SHAPES = [(1024, 2, 32), (1001, 4, 64), (333, 3, 128), (500, 1, 256), (70, 8, 16), (17, 1, 1024), (5, 2, 4)]
