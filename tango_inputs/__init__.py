@@ -353,3 +353,15 @@ def layer_inputs(name: str, scale_down: int = 1, graph: Graph | None = None, k_i
     a_dst = xavier_uniform(heads, dim, (heads, dim), seed + 202)
     grad = normal((g.n_nodes, f), seed + 300)
     return LayerInputs(g, feat, weight, a_src, a_dst, grad, heads, dim, seed + 400)
+
+
+def stack_weights(li: LayerInputs, n_layers: int = 3):
+    """Weights of ``n_layers`` stacked layers on the inputs of one configuration (configuration 4: three layers,
+    K_in -> F -> F -> F): per layer a Xavier-uniform ``W`` (seeded per layer); the attention vectors of ``li`` are
+    used by every layer.  Returns (list of W, list of a_src, list of a_dst)."""
+    f = li.heads * li.dim
+    ws = []
+    for i in range(n_layers):
+        k = li.feat.shape[1] if i == 0 else f
+        ws.append(xavier_uniform(k, f, (k, f), li.sr_seed + 10 + i))
+    return ws, [li.a_src] * n_layers, [li.a_dst] * n_layers

@@ -161,6 +161,121 @@ def test_full_size_gat_layer_sampled(T, name):
     assert np.abs(diff).max() <= 1 and (diff != 0).mean() < 1e-3
 
 
+def test_full_size_three_layer_gat_config4_production_launch(T):
+    """Configuration 4 as stated: three stacked GAT layers (100 -> 3x128 -> 3x128 -> 3x128) on the 2.4 M-node graph,
+    forward through all three and backward through all three, in the launch bench.py times (ReLU inside the layers with
+    sign bits, abs-max hand-over in both directions, ReLU' applied where the input gradient is produced, edge-ordered
+    source codes, nothing else stored per edge).  The fp32 attention is dumped for this check only (same kernels).
+    Per layer: quantizers on sampled windows; GEMM, weight-gradient and input-gradient rows sampled; the edge stages
+    (scores, softmax, SDDMM-dot, softmax backward, edge-to-node sums) and the aggregation over the whole graph; the
+    reverse aggregation on sampled source rows with all their out-edges."""
+    import torch
+
+    li = ti.layer_inputs("gat_products")
+    g = li.graph
+    heads, dim = li.heads, li.dim
+    F = heads * dim
+    n = g.n_nodes
+    seed, slope, rounding = li.sr_seed, 0.2, orc.SR
+    Ws, a_srcs, a_dsts = ti.stack_weights(li, 3)
+    G = T.Graph.from_host(g)
+    stack = T.GatStack(G, dev(li.feat), [dev(w) for w in Ws], [dev(a) for a in a_srcs], [dev(a) for a in a_dsts],
+                       dev(li.grad_out), slope, rounding, seed, keep_alpha=True)
+    for L in stack.layers:
+        assert "alpha_q" not in L.t and "dalpha" not in L.t
+        if "relu_bits" in L.t:
+            L["relu_bits"].fill_(0xA5)  # stale contents must not survive the forward pass
+    stack.step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(44)
+    rows = np.sort(rng.choice(n, 96, replace=False))
+    urows = sample_rows(g, rng, 24, g.out_ptr)
+    sub2, eids2 = subgraph(g, out_edges_of(g, urows))
+    feat = li.feat
+    for i in range(3):
+        print("config 4, layer %d" % i, flush=True)
+        L = stack[i]
+        b = 16 * i
+        relu_out = i < 2
+        skip = ("ws", "H", "W", "a_src", "a_dst", "grad_out", "absmax_H", "absmax_grad_out", "dH_keep_bits", "dH")
+        o = {k: host(v) for k, v in L.t.items() if k not in skip}
+        sc = lambda k: o[k][0]
+        W, a_src, a_dst = Ws[i], a_srcs[i], a_dsts[i]
+
+        # ---- forward
+        am_H = np.abs(feat).max()
+        if i > 0:
+            assert am_H == host(stack[i - 1]["absmax_out"])[0], "abs-max handed up"
+        check_quantized("H_q", feat, o["H_q"], sc("s_H"), rounding, seed, b + orc.SID_H, rng, am=am_H)
+        check_quantized("W_q", W, o["W_q"], sc("s_W"), rounding, seed, b + orc.SID_W, rng)
+        C, _ = orc.dequant_i32(orc.igemm(o["H_q"][rows], o["W_q"]), sc("s_H"), sc("s_W"))
+        assert_bit_exact(o["Hp"][rows], C, "Hp rows")
+        assert sc("absmax_Hp") == np.abs(o["Hp"]).max()
+        assert_close(o["S"][rows], orc.head_proj(o["Hp"][rows], a_src), "S rows")
+        assert_close(o["D"][rows], orc.head_proj(o["Hp"][rows], a_dst), "D rows")
+        check_quantized("Hp_q", o["Hp"], o["Hp_q"], sc("s_Hp"), rounding, seed, b + orc.SID_HP, rng)
+        check_quantized("S_q", o["S"], o["S_q"], sc("s_S"), rounding, seed, b + orc.SID_S, rng)
+        check_quantized("D_q", o["D"], o["D_q"], sc("s_D"), rounding, seed, b + orc.SID_D, rng)
+        del o["Hp"]
+        assert_bit_exact(o["src_codes"], o["S_q"][g.in_src], "S_q of every edge's source")
+        del o["src_codes"]
+        E = orc.sddmm_add(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope)
+        assert_close(o["alpha"], orc.edge_softmax(g, E), "alpha")
+        del E
+        # the int8 attention exists only inside the kernels: the oracle's codes of the GPU's own fp32 attention
+        alpha_q, s_alpha = orc.quantize(o["alpha"], rounding, seed, b + orc.SID_ALPHA)
+        assert sc("s_alpha") == s_alpha
+        out, am = orc.spmm_in(g, alpha_q, s_alpha, o["Hp_q"], sc("s_Hp"))
+        if relu_out:
+            out = np.maximum(out, np.float32(0))
+            am = orc.absmax(out)
+        assert_bit_exact(o["out"], out, "out (whole tensor)")
+        del out
+        assert sc("absmax_out") == am
+        if relu_out:
+            bits = np.unpackbits(o["relu_bits"], bitorder="little")[: n * F].reshape(n, F)
+            assert_bit_exact(bits, (o["out"] > 0).astype(np.uint8), "ReLU sign bits")
+            del bits
+
+        # ---- backward
+        grad = li.grad_out if i == 2 else host(L["grad_out"])
+        am_g = None
+        if i < 2:  # written by the layer above with this layer's ReLU' applied, abs-max handed down
+            am_g = host(stack[i + 1]["absmax_dH"])[0]
+            assert am_g == np.abs(grad).max(), "abs-max handed down"
+            assert not grad[o["out"] <= 0].any(), "ReLU' mask on the incoming gradient"
+        check_quantized("g_q", grad, o["g_q"], sc("s_g"), rounding, seed, b + orc.SID_G, rng, am=am_g)
+        del grad
+        dalpha = orc.sddmm_dot(g, o["g_q"], sc("s_g"), o["Hp_q"], sc("s_Hp"), heads)
+        dE_sm = orc.edge_softmax_bwd(g, o["alpha"], dalpha)
+        del dalpha
+        _, dS, dD = orc.sddmm_add_bwd(g, o["S_q"], sc("s_S"), o["D_q"], sc("s_D"), slope, dE_sm)
+        del dE_sm
+        assert_close(o["dD"], dD, "dD")
+        assert_close(o["dS"], dS, "dS")
+        agg, _ = orc.spmm_rev(sub2, alpha_q[eids2], s_alpha, o["g_q"], sc("s_g"))
+        dHp, _, _, _ = orc.head_proj_bwd(o["dS"][urows], o["dD"][urows], a_src, a_dst, o["Hp_q"][urows], sc("s_Hp"), agg[urows])
+        del agg, alpha_q
+        assert_bit_exact(o["dHp"][urows], dHp, "dHp rows (all out-edges of sampled sources)")
+        assert sc("absmax_dHp") == np.abs(o["dHp"]).max()
+        check_quantized("dHp_q", o["dHp"], o["dHp_q"], sc("s_dHp"), rounding, seed, b + orc.SID_DHP, rng, am=sc("absmax_dHp"))
+        krows = np.sort(rng.choice(feat.shape[1], 6, replace=False))
+        dW, _ = orc.dequant_i32(orc.igemm(np.ascontiguousarray(o["H_q"][:, krows]), o["dHp_q"], transA=True), sc("s_H"), sc("s_dHp"))
+        assert_bit_exact(o["dW"][krows], dW, "dW rows (reduction over every node)")
+        X = (sc("s_Hp") * o["Hp_q"].astype(np.float32)).astype(np.float64).reshape(n, heads, dim)
+        assert_close(o["da_src"], np.einsum("vh,vhd->hd", o["dS"].astype(np.float64), X), "da_src", rtol=1e-5, atol=1e-5)
+        assert_close(o["da_dst"], np.einsum("vh,vhd->hd", o["dD"].astype(np.float64), X), "da_dst", rtol=1e-5, atol=1e-5)
+        del X
+        if i > 0:  # the input gradient leaves the GEMM with the lower layer's ReLU' applied
+            dH_rows = host(L["dH"][torch.from_numpy(rows).to("cuda:0")])
+            want, _ = orc.dequant_i32(orc.igemm(o["dHp_q"][rows], o["W_q"], transB=True), sc("s_dHp"), sc("s_W"))
+            want = np.where(feat[rows] > 0, want, np.float32(0)).astype(np.float32)  # feat = max(0, lower aggregate)
+            assert_bit_exact(dH_rows, want, "dH rows behind the lower layer's ReLU'")
+            # (absmax_dH is checked where the lower layer takes it: "abs-max handed down")
+        feat = o["out"]
+        del o
+
+
 def test_full_size_gcn_layer_config2(T):
     """Configuration 2 at full size: every stage of the GCN layer is integer-exact, so the whole oracle chain is run."""
     import torch
