@@ -179,6 +179,28 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                 void *stream);
 
 /*
+ * tango_qgemm for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as tango_qgemm, bit for bit, without `ws`: the scratch (two abs-max
+ * words and the zero-padded transposed int8 copy of B) is a fixed device array
+ * inside the library, TANGO_QGEMM_STATIC_SCRATCH_BYTES = 256 B + 2 MiB per GPU
+ * the library is used on, held until the process ends.  Shapes whose
+ * scratch does not fit -- round_up(N, 64) * round_up(K, 32) > 2 MiB, e.g.
+ * N = 1024 with K > 2048 -- are refused with TANGO_ERR_WORKSPACE before anything
+ * is launched.  Neither this call nor anything it calls allocates or frees.
+ * The array's device address is looked up on the first call on each device
+ * (that one call must not be made under stream capture).  All calls on one GPU
+ * share the array: calls that may overlap in time on one GPU (different
+ * streams, different host threads) race on it and must be serialised by the
+ * caller; calls on one stream are ordered and safe.
+ */
+#define TANGO_QGEMM_STATIC_SCRATCH_BYTES ((size_t)256 + ((size_t)2 << 20))
+int tango_qgemm_static(int64_t M, int64_t N, int64_t K, const float *A, const float *B, int rounding,
+                       uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
+                       int8_t *B_q, float *s_B, float *C, float *absmax_C, void *stream);
+
+/*
  * Backward of C = A.B from the cached quantized operands (Sec. 3.3): dC
  * (M x N, fp32) is quantized once (stream_id_dC; absmax_dC_in as in
  * tango_quantize) into dC_q / s_dC (outputs, kept by the caller), then

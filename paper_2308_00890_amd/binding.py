@@ -54,6 +54,7 @@ SIGNATURES = {
     "tango_quantize_relu_bwd": (_int, [_vp, _vp, _sz, _int, _u64, _u64, _vp, _vp, _vp, _sz, _vp]),
     "tango_qgemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "tango_qgemm": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "tango_qgemm_static": (_int, [_i64, _i64, _i64, _vp, _vp, _int, _u64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qgemm_i8": (_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_gat_attention_bwd_rec_bytes": (_sz, [_i64, _int]),
     "tango_gat_attention_bwd_dst_workspace_bytes": (_sz, [_i64, _int]),
@@ -241,6 +242,24 @@ def tango_qgemm(A, B, rounding, seed, sid_A, sid_B, A_q, s_A, B_q, s_B, C, absma
             _ptr(C, torch.float32), _ptr(absmax_C, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream(),
         ),
         "tango_qgemm",
+    )
+
+
+QGEMM_STATIC_SCRATCH_BYTES = 256 + (2 << 20)  # TANGO_QGEMM_STATIC_SCRATCH_BYTES of tango.h
+
+
+def tango_qgemm_static(A, B, rounding, seed, sid_A, sid_B, A_q, s_A, B_q, s_B, C, absmax_C):
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2:
+        raise TangoError("inner dimensions differ")
+    _check(
+        load_library().tango_qgemm_static(
+            M, N, K, _ptr(A, torch.float32), _ptr(B, torch.float32), rounding, seed, sid_A, sid_B,
+            _ptr(A_q, torch.int8), _ptr(s_A, torch.float32), _ptr(B_q, torch.int8), _ptr(s_B, torch.float32),
+            _ptr(C, torch.float32), _ptr(absmax_C, torch.float32), _stream(),
+        ),
+        "tango_qgemm_static",
     )
 
 

@@ -595,3 +595,54 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
 }
 
 
+
+// ---------------------------------------------------------------------------------------------------------------
+// tango_qgemm for callers that cannot allocate and have no workspace to pass (code under HIP graph capture, tight
+// serving loops, harnesses that forbid hipMalloc): the scratch of the forward GEMM (two abs-max words and the padded,
+// transposed int8 copy of B) lives in a fixed device array of the library instead of a caller workspace.
+// ---------------------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr size_t STATIC_SCRATCH_BYTES = TANGO_QGEMM_STATIC_SCRATCH_BYTES;  // covers every N, K with round_up(N,64)*round_up(K,32) <= 2 MiB
+
+// One copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address it stands for is looked up once per device and kept in scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void *scratch_ptr[MAX_DEVICES];  // device address of `scratch` on each device (written once; same value if two threads race)
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return TANGO_ERR_LAUNCH;
+    void *p = __atomic_load_n(&scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TANGO_ERR_LAUNCH;
+        __atomic_store_n(&scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return TANGO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tango_qgemm_static(int64_t M, int64_t N, int64_t K, const float *A, const float *B, int rounding, uint64_t seed,
+                       uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A, int8_t *B_q, float *s_B, float *C,
+                       float *absmax_C, void *stream)
+{
+    int rc = validate_mnk(M, N, K);
+    if (rc != TANGO_OK) return rc;
+    // the scratch this shape needs must fit the fixed array: refuse before anything is launched
+    TANGO_REQUIRE(tango_qgemm_workspace_bytes(M, N, K) <= STATIC_SCRATCH_BYTES, TANGO_ERR_WORKSPACE);
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != TANGO_OK) return rc;
+    // every word of the scratch that must start at zero (the abs-max words, the padding of the transposed B) is cleared
+    // by fill kernels inside the call below, on the caller's stream: contents left by an earlier call do not matter
+    return tango_qgemm_known_absmax(M, N, K, A, nullptr, B, rounding, seed, stream_id_A, stream_id_B, A_q, s_A, B_q, s_B, C,
+                                    absmax_C, ws, STATIC_SCRATCH_BYTES, stream);
+}
+
+}  // extern "C"

@@ -392,7 +392,7 @@ const char *tango_status_string(int status)
         case TANGO_ERR_BAD_SHAPE: return "bad shape, size or alignment";
         case TANGO_ERR_BAD_ENUM: return "unknown enum value";
         case TANGO_ERR_UNSUPPORTED: return "unsupported configuration";
-        case TANGO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TANGO_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or, for an entry point without one, the shape needs more scratch than the library holds)";
         case TANGO_ERR_LAUNCH: return "kernel launch refused by the HIP runtime";
         default: return "unknown status";
     }
