@@ -23,6 +23,7 @@
 #include "internal.hip.h"
 #include "attn_math.hip.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace {
@@ -126,7 +127,7 @@ struct spmm_args {
     float *absmax;         // or NULL
     int heads, dim, F;
     int chunk_shift;       // log2 of the edges per wavefront
-    int short_rows;        // k_spmm_short: rows a wave takes per pass (16 or 64)
+    int short_rows;        // k_spmm_short: rows a wave takes per pass
     int short_max;         // rows with at most this many edges are left to k_spmm_short (0: none)
     attn_params att;       // used by the ATT instantiations only
     int relu;              // out = max(0, .)
@@ -711,9 +712,9 @@ __global__ __launch_bounds__(64 * WAVES_PER_BLOCK) __attribute__((amdgpu_waves_p
     }
 }
 
-// Short rows (at most a.short_max <= 64 edges), plain weights: each group of LPR lanes owns one row and walks its
-// edges alone, so a wave works on G rows at once and a row needs no cross-group reduction, no atomics and no
-// chunk search.  Low-degree graphs spend most of their edges here; the chunked kernel above then only sees the
+// Short rows (at most a.short_max <= 64 edges), plain weights, small graphs: each group of LPR lanes owns one row and
+// walks its edges alone, so a wave works on G rows at once and a row needs no cross-group reduction, no atomics and no
+// chunk search.  Small low-degree graphs spend most of their edges here; the chunked kernel above then only sees the
 // longer rows.
 constexpr int SHORT_ROWS = 16;
 template <int VEC, bool HAS_EID, int UE>
@@ -733,9 +734,8 @@ __global__ __launch_bounds__(256) void k_spmm_short(spmm_args a)
     const float sc = (*a.s_w) * (*a.s_X);
     const int8_t *Xcol = a.X + col;
     int maxabs = 0;
-    // a wave takes a.short_rows rows per pass and walks a row's edges UE at a time.  Small graphs: 16 rows and eight
-    // edges (many waves, one round of gathers for the typical short row); large ones: 64 rows (one row-pointer load per
-    // 64 rows) and four edges (measured: faster there)
+    // a wave takes a.short_rows rows per pass and walks a row's edges UE at a time (small graphs: 16 rows, so that there
+    // are many waves, and eight edges, one round of gathers for the typical short row)
     const int RP = max(a.short_rows, G);  // rows per pass: at least one per group
     for (int64_t base = static_cast<int64_t>(wave) * RP; base < a.n; base += static_cast<int64_t>(nwaves) * RP) {
         const int rl = static_cast<int>(base) + lane;
@@ -799,6 +799,154 @@ __global__ __launch_bounds__(256) void k_spmm_short(spmm_args a)
                 maxabs = max(maxabs, max(max(abs(acc[j]), abs(acc[j + 1])), max(abs(acc[j + 2]), abs(acc[j + 3]))));
             }
         }
+    }
+    if (a.absmax) {
+        float m = static_cast<float>(maxabs) * sc;
+        m = tango_wave_max(m);
+        if (lane == 0 && m > 0.0f) tango_atomic_max_nonneg(a.absmax, m);
+    }
+}
+
+// Tiny rows (1 .. T edges, T = a.short_max = 4 or 8), plain weights at the edge's own position.  On a low-degree graph most rows are tiny (the
+// self-loop and a neighbour or two) and hold few of the edges: what such a row costs is its 4F bytes of output and the
+// chain row pointer -> neighbour index -> row gather, not arithmetic.  So the chain is taken apart: a wave takes 64 rows
+// per pass; lane l first fetches, for row base+l, the bounds and the (up to) T neighbour indices and weight codes of the
+// row - T wave-wide loads serve 64 rows - and leaves them in LDS; then each group of LPR lanes owns one row at a time,
+// reads its row's entry back (one broadcast LDS read) and issues nothing but the row gathers, T per row and RU rows deep,
+// back to back.  No loop depends on a row's length, so the lanes of a wave never wait for its longest row.
+template <int VEC, int T>
+__global__ __launch_bounds__(256) void k_spmm_tiny(spmm_args a)
+{
+    static_assert(T == 4 || T == 8, "one or two rounds of four edges");
+    using V = typename vec_bytes<VEC>::type;
+    // per wave and row: the T neighbour indices (0xffffffff: no such edge) and the packed weight codes of the T edges
+    __shared__ __align__(16) uint32_t nb_s[WAVES_PER_BLOCK][64][T];
+    __shared__ __align__(16) uint32_t w_s[WAVES_PER_BLOCK][64][T];   // heads 0-3 of edge j
+    __shared__ __align__(16) uint32_t w2_s[WAVES_PER_BLOCK][64][T];  // heads 4-7 of edge j
+    const int lane = threadIdx.x % TANGO_WAVE;
+    const int wv = threadIdx.x / TANGO_WAVE;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
+    const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
+    const int LPR = a.F / VEC;
+    const int G = 64 / LPR;
+    const int gi = lane / LPR;
+    const int li = lane - gi * LPR;
+    const bool active = gi < G;
+    const int col = li * VEC;
+    const int h = col / a.dim;
+    const bool upper_heads = h >= 4;
+    const uint32_t hshift = 8u * static_cast<uint32_t>(h & 3);
+    const float sc = (*a.s_w) * (*a.s_X);
+    const int8_t *Xcol = a.X + col;
+    int maxabs = 0;
+    constexpr int RU = 2;  // rows in flight per group
+    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+        {
+            const int64_t r = base + lane;
+            int pb = 0, deg = 0;
+            if (r < a.n) {
+                pb = a.ptr[r];
+                deg = a.ptr[r + 1] - pb;
+            }
+            if (deg > T) deg = 0;  // not mine: left to the chunked kernel
+            uint32_t nb[T], w[T], w2[T];
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                nb[j] = 0xffffffffu;  // "no edge"
+                w[j] = 0u;
+                w2[j] = 0u;
+                if (j < deg) {
+                    const int e = pb + j;
+                    nb[j] = static_cast<uint32_t>(a.idx[e]);
+                    const int64_t wp = static_cast<int64_t>(e) * a.heads;
+                    if (a.w_words) {
+                        w[j] = *reinterpret_cast<const uint32_t *>(a.w + wp);
+                        if (a.heads == 8) w2[j] = *reinterpret_cast<const uint32_t *>(a.w + wp + 4);
+                    } else {
+                        for (int hh = 0; hh < a.heads; ++hh) {
+                            const uint32_t b = static_cast<uint8_t>(a.w[wp + hh]);
+                            if (hh < 4)
+                                w[j] |= b << (8 * hh);
+                            else
+                                w2[j] |= b << (8 * (hh - 4));
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < T; j += 4) {
+                *reinterpret_cast<uint4 *>(&nb_s[wv][lane][j]) = make_uint4(nb[j], nb[j + 1], nb[j + 2], nb[j + 3]);
+                *reinterpret_cast<uint4 *>(&w_s[wv][lane][j]) = make_uint4(w[j], w[j + 1], w[j + 2], w[j + 3]);
+                if (a.heads > 4) *reinterpret_cast<uint4 *>(&w2_s[wv][lane][j]) = make_uint4(w2[j], w2[j + 1], w2[j + 2], w2[j + 3]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (active) {
+            for (int k0 = 0; k0 < 64; k0 += G * RU) {
+                uint32_t nbr[RU][T], wr[RU][T];
+                V xv[RU][T];
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int sl = min(k0 + u * G + gi, 63);
+                    const bool there = k0 + u * G + gi < 64;
+#pragma unroll
+                    for (int j = 0; j < T; j += 4) {
+                        const uint4 n4 = *reinterpret_cast<const uint4 *>(&nb_s[wv][sl][j]);
+                        const uint4 w4 = upper_heads ? *reinterpret_cast<const uint4 *>(&w2_s[wv][sl][j])
+                                                     : *reinterpret_cast<const uint4 *>(&w_s[wv][sl][j]);
+                        nbr[u][j] = there ? n4.x : 0xffffffffu; nbr[u][j + 1] = there ? n4.y : 0xffffffffu;
+                        nbr[u][j + 2] = there ? n4.z : 0xffffffffu; nbr[u][j + 3] = there ? n4.w : 0xffffffffu;
+                        wr[u][j] = w4.x; wr[u][j + 1] = w4.y; wr[u][j + 2] = w4.z; wr[u][j + 3] = w4.w;
+                    }
+#pragma unroll
+                    for (int j = 0; j < T; ++j) {
+                        xv[u][j] = V();
+                        if (nbr[u][j] != 0xffffffffu)
+                            xv[u][j] = *reinterpret_cast<const V *>(Xcol + static_cast<int64_t>(nbr[u][j]) * a.F);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    if (nbr[u][0] == 0xffffffffu) continue;  // no such row, an empty row or a longer one
+                    int acc[VEC];
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) acc[j] = 0;
+#pragma unroll
+                    for (int j = 0; j < T; j += 4) {
+                        const uint32_t wpack = ((wr[u][j] >> hshift) & 0xffu) | (((wr[u][j + 1] >> hshift) & 0xffu) << 8) |
+                                               (((wr[u][j + 2] >> hshift) & 0xffu) << 16) | (((wr[u][j + 3] >> hshift) & 0xffu) << 24);
+                        uint32_t w0[VEC / 4], w1[VEC / 4], w2[VEC / 4], w3[VEC / 4];
+                        unpack_words<VEC>(xv[u][j], w0);
+                        unpack_words<VEC>(xv[u][j + 1], w1);
+                        unpack_words<VEC>(xv[u][j + 2], w2);
+                        unpack_words<VEC>(xv[u][j + 3], w3);
+#pragma unroll
+                        for (int q = 0; q < VEC / 4; ++q) {
+                            uint32_t t[4];
+                            transpose4x4(w0[q], w1[q], w2[q], w3[q], t);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c)
+                                acc[4 * q + c] = __builtin_amdgcn_sdot4(static_cast<int>(t[c]), static_cast<int>(wpack), acc[4 * q + c], false);
+                        }
+                    }
+                    const int64_t row = base + k0 + u * G + gi;
+                    float *orow = a.out + row * a.F + col;
+#pragma unroll
+                    for (int j = 0; j < VEC; j += 4) {
+                        float4 o;
+                        o.x = static_cast<float>(acc[j + 0]) * sc;
+                        o.y = static_cast<float>(acc[j + 1]) * sc;
+                        o.z = static_cast<float>(acc[j + 2]) * sc;
+                        o.w = static_cast<float>(acc[j + 3]) * sc;
+                        *reinterpret_cast<float4 *>(orow + j) = o;
+                        maxabs = max(maxabs, max(max(abs(acc[j]), abs(acc[j + 1])), max(abs(acc[j + 2]), abs(acc[j + 3]))));
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the entries are overwritten by the next pass
     }
     if (a.absmax) {
         float m = static_cast<float>(maxabs) * sc;
@@ -1159,23 +1307,37 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     a.chunk_shift = 6;
     if ((a.nnz >> 10) >= 16384) a.chunk_shift = 10;  // at least 16 waves per SIMD worth of chunks
     else if ((a.nnz >> 8) >= 4096) a.chunk_shift = 8;
-    // low mean degree, weights at the edge's own position, rows of at most two cache lines: rows of up to 64
-    // edges go to the group-per-row kernel (measured: 3-20 % faster there, slower elsewhere)
+    // Low mean degree, plain weights.  Small graphs (too few rows to fill the chip with 64-row passes), either
+    // direction, rows of at most two cache lines: rows of up to 64 edges go to the group-per-row kernel (measured: 3-20 %
+    // faster there).  Large graphs, weights at the edge's own position: the tiny rows (the self-loop and a few
+    // neighbours: most of the rows, few of the edges) go to k_spmm_tiny, everything longer to the chunked kernel
+    // (measured on the scale-22 graph: 2.50 -> 2.09 ms at F = 128, 4.21 -> 3.56 ms at F = 256; with weights fetched
+    // through the edge-id map the dependent byte reads make it slower, so the reversed direction keeps one kernel).
     const bool small_graph = a.n < 64 * 1024 * 8;
-    a.short_max = (!x4 && !att && (!a.eid || small_graph) && a.F <= 256 && a.n > 0 && a.nnz / a.n <= 20) ? 64 : 0;
+    const bool low_degree = !x4 && !att && a.n > 0 && a.nnz / a.n <= 20;
+    int tiny = 0;
+    a.short_max = 0;
+    if (low_degree && small_graph && a.F <= 256) a.short_max = 64;
+    else if (low_degree && !a.eid && a.F <= 512) a.short_max = tiny = (a.F <= 128 ? 8 : 4);
     const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
     k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
     TANGO_LAUNCH_CHECK();
-    if (a.short_max > 0 && a.nnz > 0) {
+    if (tiny && a.nnz > 0) {
+        const int vec = pick_vec(a.F, dim, false, true);
+        const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 32);
+#define TANGO_SPMM_TINY(V_)                                        \
+    if (tiny == 4) k_spmm_tiny<V_, 4><<<sb, 256, 0, st>>>(a); \
+    else k_spmm_tiny<V_, 8><<<sb, 256, 0, st>>>(a);
+        if (vec == 4) { TANGO_SPMM_TINY(4) } else if (vec == 8) { TANGO_SPMM_TINY(8) } else { TANGO_SPMM_TINY(16) }
+#undef TANGO_SPMM_TINY
+        TANGO_LAUNCH_CHECK();
+    } else if (a.short_max > 0 && a.nnz > 0) {
         const int vec = pick_vec(a.F, dim, false, !a.eid);
-        // rows per wave pass: 64 (one row-pointer load per 64 rows) when that still gives every SIMD many waves, else 16
-        a.short_rows = small_graph ? SHORT_ROWS : 64;
+        a.short_rows = SHORT_ROWS;
         const int rp = std::max(a.short_rows, 64 / (a.F / vec));  // as in the kernel
         const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + rp - 1) / rp, 4, 256 * 32);
 #define TANGO_SPMM_SHORT(V_)                                     \
-    if (a.short_rows == 64)                                      \
-        k_spmm_short<V_, false, 4><<<sb, 256, 0, st>>>(a);       \
-    else if (a.eid)                                              \
+    if (a.eid)                                                   \
         k_spmm_short<V_, true, 8><<<sb, 256, 0, st>>>(a);        \
     else                                                         \
         k_spmm_short<V_, false, 8><<<sb, 256, 0, st>>>(a);

@@ -45,6 +45,9 @@ def graph(name):
             src = np.concatenate([everyone, everyone, np.full(n, 5), np.full(n, 4321), rng.integers(0, n, 30000)])
             dst = np.concatenate([np.full(n, 5), np.full(n, 4321), everyone, everyone, rng.integers(0, n, 30000)])
             g = ti.graph_from_edges(n, src, dst)
+        elif name == "wide":  # more than 2^19 nodes, mean degree ~4: the large-graph split of the plain SPMM (rows of up to
+            # 4 or 8 edges to the tiny-row kernel, the rest to the chunked one); no self-loops, so some rows are empty
+            g = ti.rmat_graph(540000, 1700000, seed=16, self_loops=False)
         elif name == "edgeless":  # nodes only
             g = ti.graph_from_edges(37, [], [], self_loops=False)
         elif name == "one":
@@ -75,6 +78,13 @@ CASES = [
     ("hub", 4, 64),
     ("hub", 3, 128),
     ("edgeless", 2, 32),
+    ("wide", 1, 32),
+    ("wide", 1, 128),
+    ("wide", 4, 16),
+    ("wide", 8, 8),
+    ("wide", 2, 32),
+    ("wide", 3, 128),
+    ("wide", 1, 512),
 ]
 
 
