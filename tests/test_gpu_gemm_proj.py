@@ -90,8 +90,11 @@ def test_qgemm_backward(T, M, K, N):
     assert_bit_exact(host(dB2), r["dB"], "dB (alone)")
 
 
-# (M, K, N) for the tiled int8 kernel: one tile, ragged M and N, K not a multiple of the 64-deep step, several tiles
-I8_SHAPES = [(256, 64, 256), (300, 80, 130), (1, 16, 1), (515, 1040, 777), (1024, 4096, 512), (257, 48, 513)]
+# (M, K, N) for the tiled int8 kernels: one tile, ragged M and N, K not a multiple of 128 (the kernel with register
+# staging), several tiles; K a multiple of 128 (the kernel with direct global -> LDS loads): one, two, three and many
+# K-steps, ragged M and N, eight tile columns (the XCD-aware tile order)
+I8_SHAPES = [(256, 64, 256), (300, 80, 130), (1, 16, 1), (515, 1040, 777), (1024, 4096, 512), (257, 48, 513),
+             (515, 1152, 777), (2048, 384, 2048), (130, 128, 2300), (1, 128, 1), (700, 640, 300), (300, 256, 256)]
 
 
 @pytest.mark.parametrize("M,K,N", I8_SHAPES)
