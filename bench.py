@@ -152,12 +152,17 @@ def primitive_records(torch, T, np, G, g, heads, dim, workload, iters, twins):
         torch.cuda.synchronize()
         ms = time_events(torch, fn, iters)
         recs.append(gather_kernel_record(kernel, workload, ms, alg, table, extra))
-        log("  %-28s %-34s %8.3f ms  %8.1f GB/s  (%5.1f %% of the HBM peak)" % (kernel, workload, ms, recs[-1]["GBs"], recs[-1]["pct_of_hbm_peak"]))
+        log("  %-46s %-34s %8.3f ms  %8.1f GB/s  (%5.1f %% of the HBM peak)" % (kernel, workload, ms, recs[-1]["GBs"], recs[-1]["pct_of_hbm_peak"]))
         return ms
 
     t_in = run("tango_qspmm in-edges", lambda: T.tango_qspmm(G, T.IN, heads, dim, w, s1, X, s2, out, am), spmm_bytes(n, nnz, heads, F), n * F)
     t_out = run("tango_qspmm out-edges", lambda: T.tango_qspmm(G, T.OUT, heads, dim, w, s1, Y, s2, out, am),
                 spmm_bytes(n, nnz, heads, F, reverse=True), n * F)
+    w_src = torch.empty_like(w)
+    T.tango_edge_to_src_order(G, heads, w, w_src)
+    run("tango_qspmm out-edges, weights in source order", lambda: T.tango_qspmm(G, T.OUT_SRC_ORDER, heads, dim, w_src, s1, Y, s2, out, am),
+        spmm_bytes(n, nnz, heads, F), n * F)
+    del w_src
     t_dot = run("tango_qsddmm dot", lambda: T.tango_qsddmm(G, T.SDDMM_DOT, heads, dim, X, s1, Y, s2, 0.0, E),
                 sddmm_dot_bytes(n, nnz, heads, F), n * F)
     del X, Y, w
@@ -363,8 +368,8 @@ def bench_qgemm_i8(args, torch, T, dev):
 
 
 def bench_sweep(args, torch, T, dev):
-    """Configuration 5.  One step = the fifteen quantized launches of the sweep (qSPMM in-edges, qSPMM out-edges and
-    qSDDMM-dot at the five widths); the per-kernel table is the result."""
+    """Configuration 5.  One step = the quantized launches of the sweep (qSPMM over in-edges, over out-edges with the
+    weights in either order, and qSDDMM-dot, at the five widths); the per-kernel table is the result."""
     import numpy as np
 
     import tango_inputs as ti
@@ -377,7 +382,7 @@ def bench_sweep(args, torch, T, dev):
     big = [r for r in q if not r["table_fits_on_chip"]]
     dom = min(big, key=lambda r: r["pct_of_hbm_peak"])
     out = {
-        "metric": "ms for the quantized sparse primitives of the sweep (qSPMM both directions + qSDDMM-dot, F = 32..512); "
+        "metric": "ms for the quantized sparse primitives of the sweep (qSPMM in-edges, out-edges with weights in either order, qSDDMM-dot; F = 32..512); "
                   "per kernel HBM GB/s and % of peak",
         "value": ms_per_step,
         "unit": "ms",
@@ -497,7 +502,9 @@ def main():
         T.tango_quantize(w, T.SR, li.sr_seed, 9, None, w_q, s_w, torch.empty(256, dtype=torch.uint8, device=dev))
         k = li.feat.shape[1]
         W_cat = to(ti.xavier_uniform(k, F, (k, nt * F), li.sr_seed + 20))
-        L = T.TypedLayer(G, G_src, nt, to(li.feat), W_cat, w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0)
+        w_src = torch.empty_like(w_q)
+        T.tango_edge_to_src_order(G_src, 1, w_q, w_src)
+        L = T.TypedLayer(G, G_src, nt, to(li.feat), W_cat, w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0, w_q_src_order=w_src)
         step = lambda: (T.tango_typed_layer_fwd(L), T.tango_typed_layer_bwd(L))
         heads = 1
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])
@@ -509,7 +516,9 @@ def main():
         w_q = torch.empty(w.shape, dtype=torch.int8, device=dev)
         s_w = torch.zeros(1, dtype=torch.float32, device=dev)
         T.tango_quantize(w, T.SR, li.sr_seed, 9, None, w_q, s_w, torch.empty(256, dtype=torch.uint8, device=dev))
-        L = T.GcnLayer(G, to(li.feat), to(li.weight), w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0)
+        w_src = torch.empty_like(w_q)  # the same codes in source-major order for the backward pass: also made once
+        T.tango_edge_to_src_order(G, 1, w_q, w_src)
+        L = T.GcnLayer(G, to(li.feat), to(li.weight), w_q, s_w, to(li.grad_out), T.SR, li.sr_seed, 0, w_q_src_order=w_src)
         step = lambda: (T.tango_gcn_layer_fwd(L), T.tango_gcn_layer_bwd(L))
         heads, F = 1, cfg["dim"]
         spmm = lambda: T.tango_qspmm(G, T.IN, 1, F, L["w_q"], L["s_w"], L["Hp_q"], L["s_Hp"], L["out"], L["absmax_out"])

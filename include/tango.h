@@ -58,7 +58,7 @@ typedef enum tango_status {
 
 enum { TANGO_RN = 0, TANGO_SR = 1 };
 enum { TANGO_SDDMM_ADD_LEAKYRELU = 0, TANGO_SDDMM_DOT = 1 };
-enum { TANGO_IN = 0, TANGO_OUT = 1 };
+enum { TANGO_IN = 0, TANGO_OUT = 1, TANGO_OUT_SRC_ORDER = 2 };
 
 /*
  * Graph G (Sec. 1: node features H, edge features E, graph G), both
@@ -322,7 +322,12 @@ int tango_edge_softmax_bwd(const tango_graph *g, int heads, const float *alpha, 
  * direction TANGO_IN : out[v][h][:] = (s_w*s_X) * sum_{e=(u->v)} w_q[e][h]*X_q[u][h][:]
  * direction TANGO_OUT: out[u][h][:] = (s_w*s_X) * sum_{e=(u->v)} w_q[e][h]*X_q[v][h][:]
  *                      (the same product on the reversed graph; needs out_*).
- * w_q: n_edges x heads int8 (destination-major positions in both directions);
+ * direction TANGO_OUT_SRC_ORDER: as TANGO_OUT, but w_q is indexed by the edge's
+ *                      source-major position (the order of out_dst), so no weight is fetched through
+ *                      out_eid (one dependent random byte read per edge less; out_eid may be NULL).
+ *                      For weights that do not change between iterations (GCN normalisation, typed
+ *                      layers): permute them once with tango_edge_to_src_order.
+ * w_q: n_edges x heads int8 (destination-major positions for TANGO_IN and TANGO_OUT);
  * X_q: n x F int8, F = heads*dim, dim a multiple of 4 and F <= 1024;
  * out: n x F fp32, 16-byte aligned; absmax_out (may be NULL) = max|out|.
  * Accumulation is exact int32 (wrap-around beyond 2^31).
@@ -330,6 +335,13 @@ int tango_edge_softmax_bwd(const tango_graph *g, int heads, const float *alpha, 
 int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q,
                 const float *s_w, const int8_t *X_q, const float *s_X, float *out, float *absmax_out,
                 void *stream);
+
+/*
+ * w_q_src[j][h] = w_q[out_eid[j]][h]: the edge codes (n_edges x heads int8) re-ordered from destination-major to
+ * source-major positions, the operand of tango_qspmm(TANGO_OUT_SRC_ORDER).  A cached quantized tensor in the sense of
+ * Sec. 3.3 "Inter-primitive optimization": made once per graph for fixed edge weights.  w_q and w_q_src must not overlap.
+ */
+int tango_edge_to_src_order(const tango_graph *g, int heads, const int8_t *w_q, int8_t *w_q_src, void *stream);
 
 /*
  * Backward of tango_qspmm(direction = TANGO_IN) given the quantized upstream
@@ -605,6 +617,9 @@ typedef struct tango_gcn_layer {
     float *dH;                        /* n x k_in or NULL */
     void *ws;
     size_t ws_bytes;
+    /* Optional (else NULL): w_q in source-major order (tango_edge_to_src_order), made once per graph; the backward
+     * pass then runs its reverse SPMM as TANGO_OUT_SRC_ORDER.  Same results. */
+    const int8_t *w_q_src_order;
 } tango_gcn_layer;
 
 size_t tango_gcn_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_in, int f_out);
@@ -654,6 +669,7 @@ typedef struct tango_typed_layer {
     float *dH;                        /* n x k_in or NULL */
     void *ws;
     size_t ws_bytes;                  /* >= tango_typed_layer_workspace_bytes(...) */
+    const int8_t *w_q_src_order;      /* optional (else NULL): w_q in g_src's order, as in tango_gcn_layer */
 } tango_typed_layer;
 
 size_t tango_typed_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int n_types, int k_in, int f_out);

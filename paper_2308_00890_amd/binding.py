@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libtango.so")
 
 RN, SR = 0, 1
 SDDMM_ADD_LEAKYRELU, SDDMM_DOT = 0, 1
-IN, OUT = 0, 1
+IN, OUT, OUT_SRC_ORDER = 0, 1, 2
 
 _lib = None
 
@@ -78,6 +78,7 @@ SIGNATURES = {
     "tango_edge_softmax_bwd": (_int, [_gp, _int, _vp, _vp, _vp, _vp]),
     "tango_qspmm": (_int, [_gp, _int, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "tango_qspmm_bwd": (_int, [_gp, _int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "tango_edge_to_src_order": (_int, [_gp, _int, _vp, _vp, _vp]),
 }
 
 
@@ -369,6 +370,11 @@ def tango_qspmm(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out):
     )
 
 
+def tango_edge_to_src_order(g, heads, w_q, w_q_src):
+    _check(load_library().tango_edge_to_src_order(g.ref(), heads, _ptr(w_q, torch.int8), _ptr(w_q_src, torch.int8), _stream()),
+           "tango_edge_to_src_order")
+
+
 def tango_gat_attention_bwd_rec_bytes(n_nodes, heads) -> int:
     return load_library().tango_gat_attention_bwd_rec_bytes(n_nodes, heads)
 
@@ -549,7 +555,7 @@ class tango_gcn_layer(ctypes.Structure):
         + [(n, _vp) for n in (
             "H", "W", "w_q", "s_w", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "out",
             "absmax_out", "grad_out", "g_q", "s_g", "dHp", "absmax_dHp", "dHp_q", "s_dHp", "dW", "dH", "ws")]
-        + [("ws_bytes", _sz)]
+        + [("ws_bytes", _sz), ("w_q_src_order", _vp)]
     )
 
 
@@ -560,7 +566,7 @@ class tango_typed_layer(ctypes.Structure):
         + [(n, _vp) for n in (
             "H", "W", "w_q", "s_w", "H_q", "s_H", "W_q", "s_W", "Hp", "absmax_Hp", "Hp_q", "s_Hp", "out",
             "absmax_out", "grad_out", "g_q", "s_g", "dHp", "absmax_dHp", "dHp_q", "s_dHp", "dW", "dH", "ws")]
-        + [("ws_bytes", _sz)]
+        + [("ws_bytes", _sz), ("w_q_src_order", _vp)]
     )
 
 
@@ -730,10 +736,13 @@ class GatStack:
 class GcnLayer(_LayerBuffers):
     _struct = tango_gcn_layer
 
-    def __init__(self, graph: "Graph", H, W, w_q, s_w, grad_out=None, rounding=SR, seed=0, layer_id=0, want_dH=True):
+    def __init__(self, graph: "Graph", H, W, w_q, s_w, grad_out=None, rounding=SR, seed=0, layer_id=0, want_dH=True,
+                 w_q_src_order=None):
         super().__init__()
         self.device = H.device
         self.graph = graph
+        if w_q_src_order is not None:  # the fixed edge weights in source-major order (tango_edge_to_src_order), optional
+            self._bind("w_q_src_order", w_q_src_order, torch.int8)
         n, k_in = H.shape
         f_out = W.shape[1]
         c = self.c
@@ -770,10 +779,12 @@ class TypedLayer(_LayerBuffers):
     _struct = tango_typed_layer
 
     def __init__(self, g_dst: "Graph", g_src: "Graph", n_types, H, W, w_q, s_w, grad_out=None, rounding=SR, seed=0,
-                 layer_id=0, want_dH=True):
+                 layer_id=0, want_dH=True, w_q_src_order=None):
         super().__init__()
         self.device = H.device
         self.g_dst, self.g_src = g_dst, g_src
+        if w_q_src_order is not None:
+            self._bind("w_q_src_order", w_q_src_order, torch.int8)
         n, k_in = H.shape
         f_cat = W.shape[1]
         f_out = f_cat // n_types

@@ -216,7 +216,11 @@ int tango_gcn_layer_bwd(const tango_gcn_layer *L, void *stream)
     const uint64_t sid = 16 * L->layer_id;
     TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n) * L->f_out, L->rounding, L->seed, sid + SID_G, nullptr,
                              L->g_q, L->s_g, sub, sub_bytes, stream));
-    TANGO_TRY(tango_qspmm(L->g, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
+    if (L->w_q_src_order)
+        TANGO_TRY(tango_qspmm(L->g, TANGO_OUT_SRC_ORDER, 1, L->f_out, L->w_q_src_order, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp,
+                              stream));
+    else
+        TANGO_TRY(tango_qspmm(L->g, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
     TANGO_TRY(tango_qgemm_bwd(n, L->f_out, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed,
                               sid + SID_DHP, L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
     return TANGO_OK;
@@ -274,7 +278,11 @@ int tango_typed_layer_bwd(const tango_typed_layer *L, void *stream)
     TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n) * L->f_out, L->rounding, L->seed, sid + SID_G, nullptr,
                              L->g_q, L->s_g, sub, sub_bytes, stream));
     // dZ: one output row per (source, type) pair, i.e. n rows of n_types*f_out
-    TANGO_TRY(tango_qspmm(L->g_src, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
+    if (L->w_q_src_order)
+        TANGO_TRY(tango_qspmm(L->g_src, TANGO_OUT_SRC_ORDER, 1, L->f_out, L->w_q_src_order, L->s_w, L->g_q, L->s_g, L->dHp,
+                              L->absmax_dHp, stream));
+    else
+        TANGO_TRY(tango_qspmm(L->g_src, TANGO_OUT, 1, L->f_out, L->w_q, L->s_w, L->g_q, L->s_g, L->dHp, L->absmax_dHp, stream));
     TANGO_TRY(tango_qgemm_bwd(n, FT, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
                               L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, L->dW, sub, sub_bytes, stream));
     return TANGO_OK;

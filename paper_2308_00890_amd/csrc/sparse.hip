@@ -1247,14 +1247,27 @@ int pick_vec_i4(int F, int dim)
     return 0;
 }
 
+// w_src[j][h] = w[eid[j]][h]: edge codes from destination-major to source-major order.
+__global__ __launch_bounds__(256) void k_edge_to_src_order(int64_t nnz, int heads, const int32_t *__restrict__ eid,
+                                                           const int8_t *__restrict__ w, int8_t *__restrict__ w_src)
+{
+    for (int64_t j = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; j < nnz;
+         j += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int64_t e = eid[j];
+        for (int h = 0; h < heads; ++h) w_src[j * heads + h] = w[e * heads + h];
+    }
+}
+
 int validate_graph_dir(const tango_graph *g, int direction)
 {
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
     TANGO_REQUIRE(g->n_nodes > 0 && g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31), TANGO_ERR_BAD_SHAPE);
     if (direction == TANGO_IN) {
         TANGO_REQUIRE(g->in_ptr && (g->n_edges == 0 || g->in_src), TANGO_ERR_NULL);
-    } else {
+    } else if (direction == TANGO_OUT) {
         TANGO_REQUIRE(g->out_ptr && (g->n_edges == 0 || (g->out_dst && g->out_eid)), TANGO_ERR_NULL);
+    } else {
+        TANGO_REQUIRE(g->out_ptr && (g->n_edges == 0 || g->out_dst), TANGO_ERR_NULL);
     }
     return TANGO_OK;
 }
@@ -1292,7 +1305,7 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     a.nnz = g->n_edges;
     a.ptr = direction == TANGO_IN ? g->in_ptr : g->out_ptr;
     a.idx = direction == TANGO_IN ? g->in_src : g->out_dst;
-    a.eid = direction == TANGO_IN ? nullptr : g->out_eid;
+    a.eid = direction == TANGO_OUT ? g->out_eid : nullptr;  // TANGO_OUT_SRC_ORDER: the weights are already in this order
     a.w = w_q;
     a.X = X_q;
     a.s_w = s_w;
@@ -1610,7 +1623,7 @@ extern "C" {
 int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
                 const int8_t *X_q, const float *s_X, float *out, float *absmax_out, void *stream)
 {
-    TANGO_REQUIRE(direction == TANGO_IN || direction == TANGO_OUT, TANGO_ERR_BAD_ENUM);
+    TANGO_REQUIRE(direction == TANGO_IN || direction == TANGO_OUT || direction == TANGO_OUT_SRC_ORDER, TANGO_ERR_BAD_ENUM);
     int rc = validate_graph_dir(g, direction);
     if (rc != TANGO_OK) return rc;
     rc = validate_feature_shape(heads, dim);
@@ -1618,6 +1631,18 @@ int tango_qspmm(const tango_graph *g, int direction, int heads, int dim, const i
     TANGO_REQUIRE(X_q && s_w && s_X && out && (g->n_edges == 0 || w_q), TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(out, 16) && tango_aligned(X_q, 16), TANGO_ERR_BAD_SHAPE);
     return tango_spmm_async(g, direction, heads, dim, w_q, s_w, X_q, s_X, out, absmax_out, tango_stream(stream));
+}
+
+int tango_edge_to_src_order(const tango_graph *g, int heads, const int8_t *w_q, int8_t *w_q_src, void *stream)
+{
+    TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
+    TANGO_REQUIRE(g->n_edges >= 0 && g->n_edges < (int64_t(1) << 31) && heads >= 1 && heads <= 8, TANGO_ERR_BAD_SHAPE);
+    if (g->n_edges == 0) return TANGO_OK;
+    TANGO_REQUIRE(g->out_eid && w_q && w_q_src, TANGO_ERR_NULL);
+    k_edge_to_src_order<<<tango_grid_for(static_cast<size_t>(g->n_edges), 256), 256, 0, tango_stream(stream)>>>(
+        g->n_edges, heads, g->out_eid, w_q, w_q_src);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
 }
 
 int tango_qspmm_i4(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,

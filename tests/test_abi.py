@@ -82,7 +82,8 @@ def test_layer_struct_layouts_match_the_header(tmp_path):
         "tango_graph": ["n_nodes", "n_edges", "in_ptr", "out_eid"],
         "tango_gat_layer": ["g", "slope", "seed", "H", "absmax_Hp", "alpha_q", "grad_out", "dalpha", "da_dst", "fused",
                             "row_lse", "absmax_alpha", "ws", "ws_bytes"],
-        "tango_gcn_layer": ["g", "f_out", "seed", "w_q", "Hp", "grad_out", "dH", "ws", "ws_bytes"],
+        "tango_gcn_layer": ["g", "f_out", "seed", "w_q", "Hp", "grad_out", "dH", "ws", "ws_bytes", "w_q_src_order"],
+        "tango_typed_layer": ["g_dst", "g_src", "n_types", "seed", "w_q", "Hp", "dH", "ws", "ws_bytes", "w_q_src_order"],
     }
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "tango.h"', "int main(void){"]
     for st, fs in fields.items():

@@ -89,8 +89,10 @@ CASES = [
 
 
 @pytest.mark.parametrize("gname,heads,dim", CASES)
-@pytest.mark.parametrize("direction", [0, 1])
+@pytest.mark.parametrize("direction", [0, 1, 2])
 def test_qspmm(T, gname, heads, dim, direction):
+    """direction 2 = TANGO_OUT_SRC_ORDER: the reversed graph with the weights handed over in source-major order (put
+    there by tango_edge_to_src_order); the result is that of direction 1."""
     import torch
 
     g = graph(gname)
@@ -102,7 +104,15 @@ def test_qspmm(T, gname, heads, dim, direction):
     out = empty((g.n_nodes, F), torch.float32)
     out.fill_(float("nan"))
     am = scalar(-1)
-    T.tango_qspmm(G, direction, heads, dim, dev(w), scalar(sw), dev(X), scalar(sx), out, am)
+    wd = dev(w)
+    if direction == 2:
+        w_src = empty((g.n_edges, heads), torch.int8)
+        w_src.fill_(55)
+        T.tango_edge_to_src_order(G, heads, wd, w_src)
+        torch.cuda.synchronize()
+        assert_bit_exact(host(w_src), w[g.out_eid], "weights in source-major order")
+        wd = w_src
+    T.tango_qspmm(G, direction, heads, dim, wd, scalar(sw), dev(X), scalar(sx), out, am)
     torch.cuda.synchronize()
     fn = orc.spmm_in if direction == 0 else orc.spmm_rev
     want, want_am = fn(g, w, sw, X, sx)

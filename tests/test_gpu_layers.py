@@ -354,7 +354,10 @@ def test_fused_gat_layer_without_edge_caches(T):
 
 
 @pytest.mark.parametrize("rounding", [orc.SR, orc.RN])
-def test_gcn_layer_stagewise(T, rounding):
+@pytest.mark.parametrize("src_order", [False, True])
+def test_gcn_layer_stagewise(T, rounding, src_order):
+    """src_order: the fixed edge weights are also handed over in source-major order (made once by
+    tango_edge_to_src_order), and the backward pass's reverse SPMM reads them without the edge-id map."""
     import torch
 
     g = ti.rmat_graph(5000, 40000, seed=23)
@@ -369,11 +372,17 @@ def test_gcn_layer_stagewise(T, rounding):
     G = T.Graph.from_host(g)
     from gpu_util import scalar
 
-    L = T.GcnLayer(G, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id)
+    w_src = None
+    if src_order:
+        w_src = torch.full((g.n_edges, 1), 99, dtype=torch.int8, device="cuda:0")
+        T.tango_edge_to_src_order(G, 1, dev(w_q), w_src)
+        torch.cuda.synchronize()
+        assert_bit_exact(host(w_src), w_q[g.out_eid], "edge weights in source-major order")
+    L = T.GcnLayer(G, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id, w_q_src_order=w_src)
     T.tango_gcn_layer_fwd(L)
     T.tango_gcn_layer_bwd(L)
     torch.cuda.synchronize()
-    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    o = {k: host(v) for k, v in L.t.items() if k not in ("ws", "w_q_src_order")}
     f = orc.gcn_layer_fwd(g, H, W, w_q, s_w, rounding, seed, layer_id)
     bw = orc.gcn_layer_bwd(g, f, w_q, s_w, up, rounding, seed, layer_id)
     # every stage is integer-exact given bit-identical inputs, so the whole chain is bit-exact
@@ -410,11 +419,16 @@ def test_typed_layer_stagewise(T, model, rounding):
     seed, layer_id = 77, 2
     w_q, s_w = orc.quantize(w, rounding, seed, orc.SID_EW)
     G_dst, G_src = T.Graph.from_host(tg.dst_view()), T.Graph.from_host(tg.src_view())
-    L = T.TypedLayer(G_dst, G_src, nt, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id)
+    w_src = None
+    if model == "rgcn":  # also with the weights handed over in the source view's order
+        w_src = torch.empty((tg.n_edges, 1), dtype=torch.int8, device="cuda:0")
+        T.tango_edge_to_src_order(G_src, 1, dev(w_q), w_src)
+    L = T.TypedLayer(G_dst, G_src, nt, dev(H), dev(W), dev(w_q), scalar(s_w), dev(up), rounding, seed, layer_id,
+                     w_q_src_order=w_src)
     T.tango_typed_layer_fwd(L)
     T.tango_typed_layer_bwd(L)
     torch.cuda.synchronize()
-    o = {k: host(v) for k, v in L.t.items() if k != "ws"}
+    o = {k: host(v) for k, v in L.t.items() if k not in ("ws", "w_q_src_order")}
     f = orc.typed_layer_fwd(tg, H, W, w_q, s_w, rounding, seed, layer_id)
     bw = orc.typed_layer_bwd(tg, f, w_q, s_w, up, rounding, seed, layer_id)
     for name in ("H_q", "W_q", "Hp", "Hp_q", "out"):
