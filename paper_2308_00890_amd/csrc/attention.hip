@@ -29,7 +29,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, const int8_t *src_codes, double *also_zero, hipStream_t st);
+                                   float *dD, const int8_t *src_codes, double *also_zero, bool prezeroed, hipStream_t st);
 int tango_validate_spmm_shape(int heads, int dim);
 int tango_validate_sddmm_dot_shape(int heads, int dim);
 int tango_spmm_async(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
@@ -257,15 +257,17 @@ int tango_attn_bwd_dst_async(const tango_graph *g, int heads, const int8_t *Sq, 
 
 int tango_attn_stats_async(const tango_graph *g, int heads, const int8_t *Sq, const float *sS, const int8_t *Dq,
                            const float *sD, float slope, float *row_lse, float *absmax_alpha,
-                           int *huge, int8_t *src_codes, hipStream_t st)
+                           int *huge, int8_t *src_codes, bool absmax_zeroed, hipStream_t st)
 {
     (void)huge;  // (the list of long rows is only used by the backward walk; here they are found inside the launch)
     const int n = g->n_nodes;
     const int grp = pick_group(n, g->n_edges);
     const int rpw = pick_rows_per_wave(n, grp);
     const unsigned grid = row_grid(n, grp, rpw);
-    int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
-    if (rc != TANGO_OK) return rc;
+    if (!absmax_zeroed) {
+        int rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_alpha), 0u, 1, st);
+        if (rc != TANGO_OK) return rc;
+    }
     // no row can be longer than HUGE_ROW unless the graph has that many edges
     const int huge_blocks = g->n_edges > HUGE_ROW ? static_cast<int>(std::min<int64_t>(HUGE_GRID, n)) : 0;
 #define CALL(HH)                                                                                             \
@@ -306,7 +308,8 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream)
+                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
+                                bool absmax_alpha_zeroed)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -330,7 +333,8 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
         rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(s_alpha), 0x3f800000u, 1, st);
         if (rc != TANGO_OK) return rc;
     }
-    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, huge, src_codes, st);
+    rc = tango_attn_stats_async(g, heads, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, huge, src_codes, absmax_alpha_zeroed,
+                                st);
     if (rc != TANGO_OK) return rc;
     return tango_spmm_attention_async(g, TANGO_IN, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, relu_out,
@@ -384,7 +388,7 @@ int tango_gat_attention_bwd_dst(const tango_graph *g, int heads, int dim, const 
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_gat_attention_bwd_dst_workspace_bytes(g->n_nodes, heads),
                   TANGO_ERR_WORKSPACE);
     return tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse,
-                                          static_cast<double *>(ws), rec, dD, nullptr, nullptr,
+                                          static_cast<double *>(ws), rec, dD, nullptr, nullptr, false,
                                           tango_stream(stream));
 }
 
@@ -425,6 +429,17 @@ int tango_gat_attention_bwd(const tango_graph *g, int heads, int dim, const int8
 
 }  // extern "C"
 
+// What tango_gat_attention_bwd_cached clears before its first kernel when it keeps no edge tensor: the accumulator of
+// dS and the three running sums per (node, head), which lie side by side in its workspace.
+void tango_gat_attention_bwd_zero_regions(const tango_graph *g, int heads, void *ws, tango_zero_regions &z)
+{
+    const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
+    const size_t nh_bytes = tango_round_up(static_cast<size_t>(nh) * sizeof(double), 256);
+    const size_t rec_bytes = tango_gat_attention_bwd_rec_bytes(g->n_nodes, heads);
+    tango_zero_regions_add(z, static_cast<char *>(ws) + 256 + rec_bytes, 2 * nh);             // dS_acc
+    tango_zero_regions_add(z, static_cast<char *>(ws) + 256 + rec_bytes + nh_bytes, 6 * nh);  // stats
+}
+
 // tango_gat_attention_bwd with the edge-ordered source codes the forward pass left (src_codes, may be NULL): the walk over
 // the in-edges then reads them in a stream instead of gathering from S_q.
 int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
@@ -432,7 +447,8 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
                                    const int8_t *alpha_q, const float *s_alpha, const float *absmax_alpha, int rounding,
                                    uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
                                    const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
-                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream)
+                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
+                                   bool prezeroed)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -464,7 +480,7 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
     if (edge_part && !alpha_q && !dalpha) {
         // no edge tensor at all: 5'', 4', 3'' in one walk over the in-edges, then 5' and 3' in one walk over the out-edges
         rc = tango_attn_bwd_dst_fused_async(g, heads, dim, dOut_q, s_dOut, X_q, s_X, S_q, s_S, D_q, s_D, slope, row_lse, stats,
-                                            rec, dD, src_codes, dS_acc, st);
+                                            rec, dD, src_codes, dS_acc, prezeroed, st);
         if (rc != TANGO_OK) return rc;
         return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                                  stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,

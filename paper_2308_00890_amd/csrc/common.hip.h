@@ -34,6 +34,30 @@ static inline unsigned tango_grid_for(size_t work_items, unsigned per_block, uns
     return static_cast<unsigned>(b);
 }
 
+// Up to six runs of 32-bit words to clear (accumulators and abs-max words that a later kernel of the same chain adds
+// to): passed by value to the one kernel that clears them, so that several clears cost one launch.
+struct tango_zero_regions {
+    uint32_t *p[6];
+    int64_t n[6];  // words in each run; unused entries hold 0
+    int count;
+};
+
+static inline void tango_zero_regions_add(tango_zero_regions &z, void *p, int64_t words)
+{
+    if (p && words > 0 && z.count < 6) {
+        z.p[z.count] = static_cast<uint32_t *>(p);
+        z.n[z.count] = words;
+        ++z.count;
+    }
+}
+
+// Thread `tid` of `nthreads` takes its share of every run.
+__device__ static inline void tango_zero_regions_apply(const tango_zero_regions &z, int64_t tid, int64_t nthreads)
+{
+    for (int r = 0; r < z.count; ++r)
+        for (int64_t i = tid; i < z.n[r]; i += nthreads) z.p[r][i] = 0u;
+}
+
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter-based random
 // bits for stochastic rounding (Sec. 3.2 "GPU-accelerated stochastic

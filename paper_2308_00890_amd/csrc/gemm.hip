@@ -27,6 +27,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int BM = 64;     // rows of A per workgroup
 constexpr int BN = 256;    // columns per sweep: 4 waves x 64
 constexpr int KMAX = 2048; // largest reduction length whose 64-row int8 panel fits LDS
+constexpr int64_t SMALL_B_ELEMS = 65536;  // weight matrices up to this size are prepared by one workgroup
 constexpr int LDS_PAD = 16;
 
 struct fused_args {
@@ -240,15 +241,76 @@ __global__ __launch_bounds__(256) void k_quantize_b(int K, int N, int Kp, const 
     }
 }
 
-// src (R x C int8) -> dst (Rp x Cp), dst zero-filled beforehand.
-__global__ __launch_bounds__(256) void k_pad_copy_i8(int R, int C, int Cp, const int8_t *__restrict__ src,
-                                                     int8_t *__restrict__ dst)
+// The same for a small B in ONE launch of one workgroup: clears the abs-max words of the call (absmax_A may be NULL),
+// finds max|B| (left in *absmax_B), then writes B_q and every byte of BT, padding included.  It replaces four launches
+// that are each a few microseconds of latency on graphs too small to hide them.
+template <int ROUNDING>
+__global__ __launch_bounds__(1024) void k_quantize_b_small(int K, int N, int Kp, int Np, const float *__restrict__ B,
+                                                           float *absmax_A, float *absmax_B, float *absmax_C, tango_rng rng,
+                                                           int8_t *__restrict__ B_q, float *s_B, int8_t *__restrict__ BT,
+                                                           tango_zero_regions also_zero)
 {
-    const int64_t total = static_cast<int64_t>(R) * C;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+    __shared__ float red[16];
+    const int total = K * N;
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < total; i += 1024) m = fmaxf(m, fabsf(B[i]));
+    m = tango_wave_max(m);
+    if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = m;
+    __syncthreads();
+    m = red[0];
+    for (int w = 1; w < 16; ++w) m = fmaxf(m, red[w]);
+    float s, inv;
+    tango_scale_from_absmax(m, s, inv);
+    if (threadIdx.x == 0) {
+        *s_B = s;
+        *absmax_B = m;
+        if (absmax_A) *absmax_A = 0.0f;
+        if (absmax_C) *absmax_C = 0.0f;
+    }
+    tango_zero_regions_apply(also_zero, threadIdx.x, 1024);
+    const int wpr = Kp / 4;  // 32-bit words per row of BT
+    for (int w = threadIdx.x; w < Np * wpr; w += 1024) {
+        const int n = w / wpr, k0 = (w - n * wpr) * 4;
+        uint32_t word = 0;
+        if (n < N) {
+            for (int j = 0; j < 4; ++j) {
+                const int k = k0 + j;
+                if (k >= K) break;
+                const int i = k * N + n;
+                uint32_t bits = 0;
+                if (ROUNDING == TANGO_SR) bits = tango_bits16(tango_philox_block(rng, static_cast<uint64_t>(i) >> 3), i & 7);
+                const int q = tango_round_clamp<ROUNDING>(B[i] * inv, bits);
+                B_q[i] = static_cast<int8_t>(q);
+                word |= (static_cast<uint32_t>(q) & 0xffu) << (8 * j);
+            }
+        }
+        reinterpret_cast<uint32_t *>(BT)[w] = word;
+    }
+}
+
+// src (R x C int8) -> dst (Rp x Cp bytes, Cp a multiple of 4), every byte of dst written (zero in the padding); the same
+// launch clears n_zero 32-bit words at zero_words (the weight-gradient accumulator) and one more at zero_one (an abs-max),
+// either of which may be NULL.
+__global__ __launch_bounds__(256) void k_pad_copy_i8(int R, int C, int Rp, int Cp, const int8_t *__restrict__ src,
+                                                     int8_t *__restrict__ dst, uint32_t *zero_words, int64_t n_zero,
+                                                     uint32_t *zero_one)
+{
+    const int wpr = Cp / 4;
+    const int64_t words = static_cast<int64_t>(Rp) * wpr;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && zero_one) *zero_one = 0u;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < words + n_zero;
          i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
-        const int r = static_cast<int>(i / C), c = static_cast<int>(i - static_cast<int64_t>(r) * C);
-        dst[static_cast<int64_t>(r) * Cp + c] = src[i];
+        if (i >= words) {
+            zero_words[i - words] = 0u;
+            continue;
+        }
+        const int r = static_cast<int>(i / wpr), c0 = static_cast<int>(i - static_cast<int64_t>(r) * wpr) * 4;
+        uint32_t word = 0;
+        if (r < R) {
+            for (int j = 0; j < 4 && c0 + j < C; ++j)
+                word |= static_cast<uint32_t>(static_cast<uint8_t>(src[static_cast<int64_t>(r) * C + c0 + j])) << (8 * j);
+        }
+        reinterpret_cast<uint32_t *>(dst)[i] = word;
     }
 }
 
@@ -450,7 +512,8 @@ int tango_qgemm(int64_t M, int64_t N, int64_t K, const float *A, const float *B,
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL): the pass over A that finds it is skipped.
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
                              int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
-                             int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream)
+                             int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream,
+                             const tango_zero_regions *also_zero)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
@@ -465,19 +528,36 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     int8_t *BT = static_cast<int8_t *>(ws) + 256;
     const int Kp = static_cast<int>(tango_round_up(K, 32)), Np = static_cast<int>(tango_round_up(N, 64));
 
-    if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(am), 2, reinterpret_cast<uint32_t *>(absmax_C), 1, st)) != TANGO_OK)
-        return rc;
     const float *am_A = absmax_A_in ? absmax_A_in : am;
-    if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
-    if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
-    if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, static_cast<int64_t>(Np) * Kp / 4, st)) != TANGO_OK) return rc;
     const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
-    const unsigned gb = tango_grid_for(static_cast<size_t>(K) * N, 256);
-    if (rounding == TANGO_RN)
-        k_quantize_b<TANGO_RN><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
-    else
-        k_quantize_b<TANGO_SR><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
-    TANGO_LAUNCH_CHECK();
+    tango_zero_regions zr{};
+    if (also_zero) zr = *also_zero;
+    if (K * N <= SMALL_B_ELEMS && static_cast<int64_t>(Np) * Kp <= 4 * SMALL_B_ELEMS) {
+        // a small weight matrix: everything that concerns B, and the clearing of the call's abs-max words, in one launch
+        if (rounding == TANGO_RN)
+            k_quantize_b_small<TANGO_RN><<<1, 1024, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
+                                                            absmax_C, rng_b, B_q, s_B, BT, zr);
+        else
+            k_quantize_b_small<TANGO_SR><<<1, 1024, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
+                                                            absmax_C, rng_b, B_q, s_B, BT, zr);
+        TANGO_LAUNCH_CHECK();
+        if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
+    } else {
+        TANGO_REQUIRE(zr.count <= 4, TANGO_ERR_BAD_SHAPE);
+        tango_zero_regions_add(zr, am, 2);
+        tango_zero_regions_add(zr, absmax_C, 1);
+        if ((rc = tango_zero_regions_async(zr, st)) != TANGO_OK) return rc;
+        if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
+        if ((rc = tango_absmax_accumulate_async(B, static_cast<size_t>(K) * N, am + 1, st)) != TANGO_OK) return rc;
+        if ((rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(BT), 0u, static_cast<int64_t>(Np) * Kp / 4, st)) != TANGO_OK)
+            return rc;
+        const unsigned gb = tango_grid_for(static_cast<size_t>(K) * N, 256);
+        if (rounding == TANGO_RN)
+            k_quantize_b<TANGO_RN><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
+        else
+            k_quantize_b<TANGO_SR><<<gb, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, B, am + 1, rng_b, B_q, s_B, BT);
+        TANGO_LAUNCH_CHECK();
+    }
 
     if (K > KMAX) {
         // the 64-row panel of A no longer fits LDS: quantize A in a pass of its own, then the tiled kernel on the int8
@@ -534,7 +614,6 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     TANGO_REQUIRE((!dA_keep_bits && !absmax_dA) || (dA && N <= KMAX), TANGO_ERR_UNSUPPORTED);
     TANGO_REQUIRE(!dA_keep_bits || (K % 32 == 0 && tango_aligned(dA_keep_bits, 4)), TANGO_ERR_BAD_SHAPE);
     hipStream_t st = tango_stream(stream);
-    if (absmax_dA && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(absmax_dA), 0u, 1, st)) != TANGO_OK) return rc;
     float *am = static_cast<float *>(ws);
     int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
     long long *acc = reinterpret_cast<long long *>(BT + bt_bytes(K, N));  // 64-bit sums of the weight gradient
@@ -556,13 +635,13 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         // dA = dC_q . B_q^T: the forward kernel with dC in the role of A and B_q (K x N, rows contiguous along
         // the reduction index n) in the role of the transposed operand.
         const int Rp = static_cast<int>(tango_round_up(N, 32)), Cp = static_cast<int>(tango_round_up(K, 64));
-        // (the zero padding of BT and, if the weight gradient follows, its accumulator: one launch)
-        if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(BT), static_cast<int64_t>(Cp) * Rp / 4,
-                                        reinterpret_cast<uint32_t *>(acc), dB ? 2 * K * N : 0, st)) != TANGO_OK)
-            return rc;
-        acc_zeroed = true;
-        k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(K) * N, 256), 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Rp, B_q, BT);
+        // (the padded copy of B_q, the clearing of max|dA| and, if the weight gradient follows, of its accumulator: one launch)
+        const int64_t n_zero = dB ? 2 * K * N : 0;
+        k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(Cp) * Rp / 4 + n_zero, 256), 256, 0, st>>>(
+            static_cast<int>(K), static_cast<int>(N), Cp, Rp, B_q, BT, reinterpret_cast<uint32_t *>(acc), n_zero,
+            reinterpret_cast<uint32_t *>(absmax_dA));
         TANGO_LAUNCH_CHECK();
+        acc_zeroed = true;
         fused_args a;
         a.M = M; a.N = static_cast<int>(K); a.K = static_cast<int>(N); a.Kp = Rp; a.Np = Cp;
         a.A = dC; a.absmax_A = amp; a.rng = tango_rng_make(seed, stream_id_dC);
@@ -579,7 +658,9 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
             return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
         int64_t slabs = 4096 / (tiles_k * tiles_n);
-        slabs = std::min<int64_t>(slabs, M / (8 * MS));  // at least eight steps per workgroup before its 64 KB of atomics
+        // at least eight steps per workgroup before its 64 KB of atomics; two where the whole product is a few dozen steps,
+        // which a couple of workgroups would otherwise walk as one long chain of dependent load - transpose - multiply steps
+        slabs = std::min<int64_t>(slabs, M / ((M < 65536 ? 2 : 8) * MS));
         if (slabs < 1) slabs = 1;
         // a slab's int32 partial sums stay exact (2^17 rows x 127^2 < 2^31); the slabs are combined in 64 bits
         int64_t slab_rows = std::min<int64_t>(tango_round_up(static_cast<size_t>((M + slabs - 1) / slabs), MS), int64_t(1) << 17);

@@ -9,6 +9,14 @@ int tango_fill_u32_async(uint32_t *p, uint32_t v, int64_t n, hipStream_t st);
 // p1[0..n1) = 0 and p2[0..n2) = 0 in one launch (either pointer may be NULL, its count is then ignored).
 int tango_zero2_u32_async(uint32_t *p1, int64_t n1, uint32_t *p2, int64_t n2, hipStream_t st);
 
+// Every run of z cleared in one launch.
+int tango_zero_regions_async(const tango_zero_regions &z, hipStream_t st);
+
+// Two tensors quantized (abs-max values known, device) in one launch; same results as two tango_quantize calls.
+int tango_quantize_pair_with_absmax_async(const float *x1, size_t n1, uint64_t stream_id1, const float *absmax1, int8_t *q1,
+                                          float *scale1, const float *x2, size_t n2, uint64_t stream_id2, const float *absmax2,
+                                          int8_t *q2, float *scale2, int rounding, uint64_t seed, hipStream_t st);
+
 // *out = max(*out, max|x|) with *out holding the bits of a non-negative float.
 int tango_absmax_accumulate_async(const float *x, size_t n, float *out, hipStream_t st);
 
@@ -26,7 +34,15 @@ int tango_quantize_bitmasked_async(const float *x, const uint8_t *mask_bits, siz
 bool tango_head_proj_quantize_supported(int heads, int dim);
 int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst,
                                    float *S, float *D, float *absmax_S, float *absmax_D, const float *absmax_X, int rounding,
-                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st);
+                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st,
+                                   bool absmax_zeroed = false);  // true: *absmax_S and *absmax_D were cleared by an earlier launch
+
+// Step 2' (tango_head_proj_bwd without its argument checks).  zeroed: the runs that tango_head_proj_bwd_zero_regions names
+// were cleared by an earlier launch of the same chain.
+int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
+                              const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
+                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed = false);
+void tango_head_proj_bwd_zero_regions(int heads, int dim, void *ws, float *absmax_dX, tango_zero_regions &z);
 
 // tango_qgemm_bwd with a ReLU' on dA's way out: dA_keep_bits (optional; bit i of the flat M x K tensor, 4-byte aligned,
 // K a multiple of 32 and at most 2048) clear -> dA[i] = 0; absmax_dA (optional, device) receives max|dA| as written.
@@ -38,7 +54,8 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL).
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,
                              int rounding, uint64_t seed, uint64_t stream_id_A, uint64_t stream_id_B, int8_t *A_q, float *s_A,
-                             int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream);
+                             int8_t *B_q, float *s_B, float *C, float *absmax_C, void *ws, size_t ws_bytes, void *stream,
+                             const tango_zero_regions *also_zero = nullptr);  // cleared by the call's first launch
 
 // Whether the forward attention SPMM can write its ReLU's sign bits for this shape (rows wider than 128 columns).
 bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim);
@@ -51,7 +68,8 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
                                 const int8_t *D_q, const float *s_D, float slope, const int8_t *X_q, const float *s_X,
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
-                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream);
+                                int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
+                                bool absmax_alpha_zeroed = false);  // true: *absmax_alpha was cleared by an earlier launch
 
 // tango_gat_attention_bwd with the edge-ordered source codes the forward pass left (src_codes, may be NULL).
 int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
@@ -59,7 +77,11 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
                                    const int8_t *alpha_q, const float *s_alpha, const float *absmax_alpha, int rounding,
                                    uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
                                    const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
-                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream);
+                                   float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
+                                   bool prezeroed = false);
+// The runs of the workspace that the call above clears first when it keeps no edge tensor (alpha_q and dalpha NULL);
+// a caller that clears them in an earlier launch of the same chain passes prezeroed = true.
+void tango_gat_attention_bwd_zero_regions(const tango_graph *g, int heads, void *ws, tango_zero_regions &z);
 
 // Quantize with a known abs-max (device float).
 int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,

@@ -9,7 +9,8 @@ namespace {
 // random-stream ids of the tensors of one layer (layer l uses 16*l + id)
 enum { SID_H = 1, SID_W = 2, SID_HP = 3, SID_S = 4, SID_D = 5, SID_ALPHA = 6, SID_G = 7, SID_DHP = 8 };
 
-// layout of the layer workspace: 256 bytes of scalars, then the largest sub-call workspace
+// layout of the layer workspace: 256 bytes of scalars, the column-sum accumulators of step 2' (outside the shared
+// part, so that the backward pass can clear them in its first launch), then the largest sub-call workspace
 // (S and D are updated by one kernel at the same time: kept in different 128-byte lines)
 enum { SC_ABSMAX_S = 0, SC_ABSMAX_D = 32, SC_ABSMAX_ALPHA = 16, SC_ABSMAX_G = 48 };
 
@@ -40,7 +41,7 @@ size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_i
     const size_t c = tango_head_proj_bwd_workspace_bytes(n_nodes, heads, dim);
     const size_t d = tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads);
     const size_t e = tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads);
-    return 256 + max3(a, b, max3(c, d, e));
+    return 256 + c + max3(a, b, max3(d, e, 0));
 }
 
 int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
@@ -57,38 +58,46 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                       L->ws_bytes >= tango_gat_layer_workspace_bytes(n, nnz, L->k_in, L->heads, L->dim),
                   TANGO_ERR_WORKSPACE);
     float *sc = static_cast<float *>(L->ws);
-    void *sub = static_cast<char *>(L->ws) + 256;
-    const size_t sub_bytes = L->ws_bytes - 256;
+    const size_t hpb = tango_head_proj_bwd_workspace_bytes(n, L->heads, L->dim);
+    void *sub = static_cast<char *>(L->ws) + 256 + hpb;
+    const size_t sub_bytes = L->ws_bytes - 256 - hpb;
     const uint64_t sid = 16 * L->layer_id;
+    const bool proj_fused = tango_head_proj_quantize_supported(L->heads, L->dim) && tango_aligned(L->Hp, 16) &&
+                            tango_aligned(L->Hp_q, 8) && tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16);
 
-    // step 1: H' = H.W, quantize-on-load, cached H_q / W_q, fused abs-max of H'
+    // step 1: H' = H.W, quantize-on-load, cached H_q / W_q, fused abs-max of H'.  Its first launch also clears the
+    // abs-max words that steps 2 and 4 accumulate into (each clear of its own would be one more launch in the chain).
+    tango_zero_regions zr{};
+    if (proj_fused) {
+        tango_zero_regions_add(zr, sc + SC_ABSMAX_S, 1);
+        tango_zero_regions_add(zr, sc + SC_ABSMAX_D, 1);
+    }
+    if (L->fused) tango_zero_regions_add(zr, L->absmax_alpha, 1);
     TANGO_TRY(tango_qgemm_known_absmax(n, F, L->k_in, L->H, L->absmax_H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W,
-                                       L->H_q, L->s_H, L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream));
+                                       L->H_q, L->s_H, L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream, &zr));
     // step 2: S, D in fp32, with their abs-max
     // and the sequential quantization of the tensors the sparse primitives will access randomly (Sec. 3.3): H' in the
     // same pass over H' where the shape allows
-    if (tango_head_proj_quantize_supported(L->heads, L->dim) && tango_aligned(L->Hp, 16) && tango_aligned(L->Hp_q, 8) &&
-        tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16)) {
+    if (proj_fused) {
         TANGO_TRY(tango_head_proj_quantize_async(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
                                                  sc + SC_ABSMAX_D, L->absmax_Hp, L->rounding, L->seed, sid + SID_HP, L->Hp_q,
-                                                 L->s_Hp, tango_stream(stream)));
+                                                 L->s_Hp, tango_stream(stream), true));
     } else {
         TANGO_TRY(tango_head_proj(n, L->heads, L->dim, L->Hp, L->a_src, L->a_dst, L->S, L->D, sc + SC_ABSMAX_S,
                                   sc + SC_ABSMAX_D, stream));
         TANGO_TRY(tango_quantize(L->Hp, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_HP, L->absmax_Hp,
                                  L->Hp_q, L->s_Hp, nullptr, 0, stream));
     }
-    TANGO_TRY(tango_quantize(L->S, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_S, sc + SC_ABSMAX_S,
-                             L->S_q, L->s_S, nullptr, 0, stream));
-    TANGO_TRY(tango_quantize(L->D, static_cast<size_t>(n * L->heads), L->rounding, L->seed, sid + SID_D, sc + SC_ABSMAX_D,
-                             L->D_q, L->s_D, nullptr, 0, stream));
+    TANGO_TRY(tango_quantize_pair_with_absmax_async(L->S, static_cast<size_t>(n * L->heads), sid + SID_S, sc + SC_ABSMAX_S, L->S_q,
+                                                    L->s_S, L->D, static_cast<size_t>(n * L->heads), sid + SID_D,
+                                                    sc + SC_ABSMAX_D, L->D_q, L->s_D, L->rounding, L->seed, tango_stream(stream)));
     if (L->fused) {
         // steps 3-5 fused: E and alpha never reach memory in fp32
         return tango_gat_attention_fwd_act(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->Hp_q, L->s_Hp,
                                            L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
                                            L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out,
                                            gat_uses_relu_bits(L) ? L->relu_bits : nullptr, L->src_codes, sub, sub_bytes,
-                                           stream);
+                                           stream, true);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -120,9 +129,24 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
                       L->ws_bytes >= tango_gat_layer_workspace_bytes(n, nnz, L->k_in, L->heads, L->dim),
                   TANGO_ERR_WORKSPACE);
-    void *sub = static_cast<char *>(L->ws) + 256;
-    const size_t sub_bytes = L->ws_bytes - 256;
+    float *sc = static_cast<float *>(L->ws);
+    void *hp_ws = static_cast<char *>(L->ws) + 256;
+    const size_t hpb = tango_head_proj_bwd_workspace_bytes(n, L->heads, L->dim);
+    void *sub = static_cast<char *>(L->ws) + 256 + hpb;
+    const size_t sub_bytes = L->ws_bytes - 256 - hpb;
     const uint64_t sid = 16 * L->layer_id;
+    hipStream_t st = tango_stream(stream);
+
+    // Everything the backward chain accumulates into is cleared by ONE launch at its head: the accumulator and abs-max
+    // of step 2', the abs-max of the upstream gradient (when it has to be found here) and, when the attention part
+    // keeps no edge tensor, its per-node sums.
+    const bool att_prezero = L->fused && !L->alpha_q && !L->dalpha;
+    const bool find_absmax_g = !L->absmax_grad_out && !L->relu_out;
+    tango_zero_regions zr{};
+    tango_head_proj_bwd_zero_regions(L->heads, L->dim, hp_ws, L->absmax_dHp, zr);
+    if (find_absmax_g) tango_zero_regions_add(zr, sc + SC_ABSMAX_G, 1);
+    if (att_prezero) tango_gat_attention_bwd_zero_regions(L->g, L->heads, sub, zr);
+    TANGO_TRY(tango_zero_regions_async(zr, st));
 
     // the upstream gradient is quantized once and shared by steps 5' and 5''
     if (L->absmax_grad_out) {
@@ -142,15 +166,17 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                                                   sid + SID_G, L->g_q, L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G,
                                                   tango_stream(stream)));
     } else {
-        TANGO_TRY(tango_quantize(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G, nullptr, L->g_q,
-                                 L->s_g, sub, sub_bytes, stream));
+        TANGO_REQUIRE(tango_aligned(L->grad_out, 4), TANGO_ERR_BAD_SHAPE);
+        TANGO_TRY(tango_absmax_accumulate_async(L->grad_out, static_cast<size_t>(n * F), sc + SC_ABSMAX_G, st));
+        TANGO_TRY(tango_quantize_with_absmax_async(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G,
+                                                   sc + SC_ABSMAX_G, L->g_q, L->s_g, st));
     }
     if (L->fused) {
         // 5', 5'', 4', 3', 3'' from the forward caches; dE is never written
         TANGO_TRY(tango_gat_attention_bwd_cached(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,
                                                  L->alpha_q, L->s_alpha, L->absmax_alpha, L->rounding, L->seed,
                                                  sid + SID_ALPHA, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp, nullptr, L->dalpha,
-                                                 L->dS, L->dD, L->src_codes, sub, sub_bytes, stream));
+                                                 L->dS, L->dD, L->src_codes, sub, sub_bytes, stream, att_prezero));
     } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
     TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,
@@ -162,8 +188,11 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                                stream));
     }
     // 2' fused with dH' = dH'_agg + dH'_att and its abs-max
-    TANGO_TRY(tango_head_proj_bwd(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
-                                  L->absmax_dHp, L->da_src, L->da_dst, sub, sub_bytes, stream));
+    TANGO_REQUIRE(F <= 1024 && L->dim % 4 == 0 && tango_aligned(L->dHp, 16) && tango_aligned(L->Hp_q, 4) &&
+                      tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16),
+                  TANGO_ERR_BAD_SHAPE);
+    TANGO_TRY(tango_head_proj_bwd_async(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
+                                        L->absmax_dHp, L->da_src, L->da_dst, hp_ws, st, true));
     // 1': both GEMMs from the cached H_q, W_q
     TANGO_REQUIRE((!L->dH_keep_bits && !L->absmax_dH) || L->dH, TANGO_ERR_NULL);
     TANGO_TRY(tango_qgemm_bwd_masked(n, F, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,

@@ -343,14 +343,15 @@ bool tango_head_proj_quantize_supported(int heads, int dim)
 // 8-byte aligned; only where tango_head_proj_quantize_supported.  The results are those of the two separate calls.
 int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X, const float *a_src, const float *a_dst,
                                    float *S, float *D, float *absmax_S, float *absmax_D, const float *absmax_X, int rounding,
-                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st)
+                                   uint64_t seed, uint64_t stream_id, int8_t *X_q, float *s_X, hipStream_t st, bool absmax_zeroed)
 {
     TANGO_REQUIRE(tango_head_proj_quantize_supported(heads, dim), TANGO_ERR_UNSUPPORTED);
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(n > 0 && X && a_src && a_dst && S && D && absmax_X && X_q, TANGO_ERR_NULL);
     TANGO_REQUIRE(tango_aligned(X, 16) && tango_aligned(X_q, 8), TANGO_ERR_BAD_SHAPE);
     int rc;
-    if ((rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 1, reinterpret_cast<uint32_t *>(absmax_D), 1, st)) != TANGO_OK)
+    if (!absmax_zeroed &&
+        (rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(absmax_S), 1, reinterpret_cast<uint32_t *>(absmax_D), 1, st)) != TANGO_OK)
         return rc;
     const tango_rng rng = tango_rng_make(seed, stream_id);
     const size_t ngroups = static_cast<size_t>(n) * (heads * dim / 8);
@@ -367,12 +368,14 @@ int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X
 
 int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
                               const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
-                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st)
+                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed)
 {
     const int F = heads * dim;
     double *acc = static_cast<double *>(ws);
-    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(acc), 4 * F * ACC_COPIES, reinterpret_cast<uint32_t *>(absmax_dX), 1, st);
-    if (rc != TANGO_OK) return rc;
+    if (!zeroed) {
+        int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(acc), 4 * F * ACC_COPIES, reinterpret_cast<uint32_t *>(absmax_dX), 1, st);
+        if (rc != TANGO_OK) return rc;
+    }
     const int rpb = 256 / (F / 4);
     k_head_proj_bwd<<<tango_grid_for(static_cast<size_t>((n + rpb - 1) / rpb), 8, 256 * 4), 256, 0, st>>>(
         n, heads, dim, dS, dD, a_src, a_dst, X_q, s_X, dX_agg, dX, absmax_dX, acc);
@@ -380,6 +383,12 @@ int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, co
     k_head_proj_bwd_finish<<<(F + 255) / 256, 256, 0, st>>>(F, acc, da_src, da_dst);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
+}
+
+void tango_head_proj_bwd_zero_regions(int heads, int dim, void *ws, float *absmax_dX, tango_zero_regions &z)
+{
+    tango_zero_regions_add(z, ws, static_cast<int64_t>(4) * heads * dim * ACC_COPIES);
+    tango_zero_regions_add(z, absmax_dX, 1);
 }
 
 extern "C" {

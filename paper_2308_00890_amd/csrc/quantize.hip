@@ -80,19 +80,19 @@ __global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ x, siz
 }
 
 // Vector path: x 16-byte aligned, q 8-byte aligned.  One thread-iteration = 8 elements.
+// (bid, nblocks: this workgroup's index among those that share the tensor - the launch may hold two tensors)
 template <int ROUNDING, int MASKED = 0>
-__global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
-                                                      const float *__restrict__ absmax, tango_rng rng,
-                                                      int8_t *__restrict__ q, float *scale_out,
-                                                      const float *__restrict__ mask = nullptr,
-                                                      const uint8_t *__restrict__ mask_bits = nullptr)
+__device__ __forceinline__ void quantize_vec_body(const float *__restrict__ x, size_t n, const float *__restrict__ absmax,
+                                                  const tango_rng &rng, int8_t *__restrict__ q, float *scale_out,
+                                                  const float *__restrict__ mask, const uint8_t *__restrict__ mask_bits,
+                                                  unsigned bid, unsigned nblocks)
 {
     float s, inv;
     tango_scale_from_absmax(*absmax, s, inv);
-    if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
+    if (bid == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
     const size_t n8 = n / 8;
-    const size_t tid = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    const size_t nthr = static_cast<size_t>(gridDim.x) * blockDim.x;
+    const size_t tid = static_cast<size_t>(bid) * blockDim.x + threadIdx.x;
+    const size_t nthr = static_cast<size_t>(nblocks) * blockDim.x;
     const float4 *x4 = reinterpret_cast<const float4 *>(x);
     uint2 *q8 = reinterpret_cast<uint2 *>(q);
     // four independent 32-byte pieces per iteration keep enough loads in flight to cover the memory latency
@@ -146,6 +146,36 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
             q[j] = static_cast<int8_t>(tango_round_clamp<ROUNDING>(xv * inv, tango_bits16(b, static_cast<int>(j & 7))));
         }
     }
+}
+
+template <int ROUNDING, int MASKED = 0>
+__global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ x, size_t n,
+                                                      const float *__restrict__ absmax, tango_rng rng,
+                                                      int8_t *__restrict__ q, float *scale_out,
+                                                      const float *__restrict__ mask = nullptr,
+                                                      const uint8_t *__restrict__ mask_bits = nullptr)
+{
+    quantize_vec_body<ROUNDING, MASKED>(x, n, absmax, rng, q, scale_out, mask, mask_bits, blockIdx.x, gridDim.x);
+}
+
+// Two tensors in one launch (the first g1 workgroups take the first): for the small tensors of a layer, whose
+// quantizations would otherwise be two dependent launches of a few microseconds each.
+struct quantize_job {
+    const float *x;
+    size_t n;
+    const float *absmax;
+    tango_rng rng;
+    int8_t *q;
+    float *scale_out;
+};
+template <int ROUNDING>
+__global__ __launch_bounds__(256) void k_quantize_pair(quantize_job j1, quantize_job j2, unsigned g1)
+{
+    if (blockIdx.x < g1)
+        quantize_vec_body<ROUNDING, 0>(j1.x, j1.n, j1.absmax, j1.rng, j1.q, j1.scale_out, nullptr, nullptr, blockIdx.x, g1);
+    else
+        quantize_vec_body<ROUNDING, 0>(j2.x, j2.n, j2.absmax, j2.rng, j2.q, j2.scale_out, nullptr, nullptr, blockIdx.x - g1,
+                                       gridDim.x - g1);
 }
 
 // Scalar path for unaligned pointers: one element per thread-iteration (same results, slower).
@@ -301,6 +331,23 @@ int tango_zero2_u32_async(uint32_t *p1, int64_t n1, uint32_t *p2, int64_t n2, hi
     return TANGO_OK;
 }
 
+static __global__ void k_zero_regions(tango_zero_regions z)
+{
+    tango_zero_regions_apply(z, static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x,
+                             static_cast<int64_t>(gridDim.x) * blockDim.x);
+}
+
+// Every run of z in one launch.
+int tango_zero_regions_async(const tango_zero_regions &z, hipStream_t st)
+{
+    int64_t longest = 0;
+    for (int r = 0; r < z.count; ++r) longest = z.n[r] > longest ? z.n[r] : longest;
+    if (longest == 0) return TANGO_OK;
+    k_zero_regions<<<tango_grid_for(static_cast<size_t>(longest), 256, 256 * 64), 256, 0, st>>>(z);
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
 int tango_fill_u32_async(uint32_t *p, uint32_t v, int64_t n, hipStream_t st)
 {
     if (n <= 0) return TANGO_OK;
@@ -337,6 +384,27 @@ int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uin
         else
             k_quantize_scalar<TANGO_SR><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
     }
+    TANGO_LAUNCH_CHECK();
+    return TANGO_OK;
+}
+
+// Two quantizations with known abs-max values in one launch (falls back to two launches for unaligned tensors).
+int tango_quantize_pair_with_absmax_async(const float *x1, size_t n1, uint64_t stream_id1, const float *absmax1, int8_t *q1,
+                                          float *scale1, const float *x2, size_t n2, uint64_t stream_id2, const float *absmax2,
+                                          int8_t *q2, float *scale2, int rounding, uint64_t seed, hipStream_t st)
+{
+    if (!(tango_aligned(x1, 16) && tango_aligned(q1, 8) && tango_aligned(x2, 16) && tango_aligned(q2, 8))) {
+        int rc = tango_quantize_with_absmax_async(x1, n1, rounding, seed, stream_id1, absmax1, q1, scale1, st);
+        if (rc != TANGO_OK) return rc;
+        return tango_quantize_with_absmax_async(x2, n2, rounding, seed, stream_id2, absmax2, q2, scale2, st);
+    }
+    const quantize_job j1{x1, n1, absmax1, tango_rng_make(seed, stream_id1), q1, scale1};
+    const quantize_job j2{x2, n2, absmax2, tango_rng_make(seed, stream_id2), q2, scale2};
+    const unsigned g1 = tango_grid_for(n1 / 8 + 1, 256 * 2), g2 = tango_grid_for(n2 / 8 + 1, 256 * 2);
+    if (rounding == TANGO_RN)
+        k_quantize_pair<TANGO_RN><<<g1 + g2, 256, 0, st>>>(j1, j2, g1);
+    else
+        k_quantize_pair<TANGO_SR><<<g1 + g2, 256, 0, st>>>(j1, j2, g1);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }

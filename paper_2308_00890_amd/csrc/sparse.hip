@@ -133,6 +133,10 @@ struct spmm_args {
     int relu;              // out = max(0, .)
     uint16_t *relu_bits;   // with relu, optional: bit i = (out[i] > 0) over the flat n x F output (F % 64 == 0, 16 columns per lane)
     int w_words;           // the head codes of an edge can be read as 32-bit words (heads 4 or 8, w 4-byte aligned)
+    const double *cvt_src; // k_spmm_finalize also writes cvt_dst[i] = float(cvt_src[i]), i < cvt_n (the fused dS sums,
+    float *cvt_dst;        // complete once the main kernel has ended); NULL: nothing to convert
+    int64_t cvt_n;
+    int fin_rows;          // rows a wave of k_spmm_prepare / k_spmm_finalize looks at per pass (64, or 8 on small graphs)
 };
 
 // True when row [b, t) is cut by a chunk boundary (it then goes through the atomic path).
@@ -148,10 +152,10 @@ __global__ __launch_bounds__(256) void k_spmm_prepare(spmm_args a)
     const int lane = threadIdx.x % TANGO_WAVE;
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
     const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
-    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+    for (int64_t base = static_cast<int64_t>(wave) * a.fin_rows; base < a.n; base += static_cast<int64_t>(nwaves) * a.fin_rows) {
         const int r = static_cast<int>(base) + lane;
         bool flag = false;
-        if (r < a.n) {
+        if (lane < a.fin_rows && r < a.n) {
             const int b = a.ptr[r], t = a.ptr[r + 1];
             flag = (t == b) || row_is_split(b, t, a.chunk_shift, a.short_max);
         }
@@ -177,10 +181,10 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / TANGO_WAVE;
     const int nwaves = gridDim.x * blockDim.x / TANGO_WAVE;
     float m = 0.0f;
-    for (int64_t base = static_cast<int64_t>(wave) * 64; base < a.n; base += static_cast<int64_t>(nwaves) * 64) {
+    for (int64_t base = static_cast<int64_t>(wave) * a.fin_rows; base < a.n; base += static_cast<int64_t>(nwaves) * a.fin_rows) {
         const int r = static_cast<int>(base) + lane;
         bool flag = false;
-        if (r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1], a.chunk_shift, a.short_max);
+        if (lane < a.fin_rows && r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1], a.chunk_shift, a.short_max);
         unsigned long long mask = __ballot(flag);
         while (mask) {
             const int k = __ffsll(static_cast<long long>(mask)) - 1;
@@ -201,6 +205,11 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
         }
     }
     if (a.absmax) tango_block_max_update(m, a.absmax);
+    if (a.cvt_src) {
+        for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < a.cvt_n;
+             i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+            a.cvt_dst[i] = static_cast<float>(a.cvt_src[i]);
+    }
 }
 
 // t[c] = (r0.byte c, r1.byte c, r2.byte c, r3.byte c): 4x4 byte transpose with v_perm_b32.
@@ -1294,10 +1303,14 @@ bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim)
 
 static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
                        const int8_t *X_q, const float *s_X, float *out, float *absmax_out, const attn_params *att,
-                       hipStream_t st, bool x4 = false)
+                       hipStream_t st, bool x4 = false, float *dS_out = nullptr)
 {
     spmm_args a;
     if (att) a.att = *att;
+    // dS_out (reverse attention pass fused with step 3' only): the fp32 copy of the dS sums, written by the last launch
+    a.cvt_src = (att && att->rec && dS_out) ? att->dS_acc : nullptr;
+    a.cvt_dst = dS_out;
+    a.cvt_n = static_cast<int64_t>(g->n_nodes) * heads;
     a.relu = (att && direction == TANGO_IN) ? att->relu_out : 0;
     a.relu_bits = (a.relu && att->relu_bits && tango_spmm_relu_bits_supported(g->n_nodes, heads, dim)) ? att->relu_bits : nullptr;
     a.w_words = (heads == 4 || heads == 8) && w_q != nullptr && tango_aligned(w_q, 4);
@@ -1332,7 +1345,10 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     a.short_max = 0;
     if (low_degree && small_graph && a.F <= 256) a.short_max = 64;
     else if (low_degree && !a.eid && a.F <= 512) a.short_max = tiny = (a.F <= 128 ? 8 : 4);
-    const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 8);
+    // (a wave of the two helper kernels handles the flagged rows of its pass one after the other: on a small graph
+    // short passes spread that chain of dependent row accesses over many more waves)
+    a.fin_rows = a.n < 64 * 1024 ? 8 : 64;
+    const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + a.fin_rows - 1) / a.fin_rows, 4, 256 * 8);
     k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
     TANGO_LAUNCH_CHECK();
     if (tiny && a.nnz > 0) {
@@ -1457,10 +1473,12 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
     att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0; att.relu_bits = nullptr; att.src_codes = nullptr;
-    rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st);
+    rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st, false, dS);
     if (rc != TANGO_OK) return rc;
-    k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
-    TANGO_LAUNCH_CHECK();
+    if (g->n_edges == 0) {  // no edge, no main kernel and no finalize launch: dS = 0 from the cleared sums
+        k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
+        TANGO_LAUNCH_CHECK();
+    }
     return TANGO_OK;
 }
 
@@ -1522,13 +1540,16 @@ __global__ __launch_bounds__(256) void k_attn_dst_finish(int64_t nh, int heads, 
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
-                                   float *dD, const int8_t *src_codes, double *also_zero, hipStream_t st)
+                                   float *dD, const int8_t *src_codes, double *also_zero, bool prezeroed, hipStream_t st)
 {
-    // also_zero (may be NULL): n x heads more doubles zeroed by the same launch (the source-side pass's accumulator)
+    // also_zero (may be NULL): n x heads more doubles zeroed by the same launch (the source-side pass's accumulator);
+    // prezeroed: both were cleared by an earlier launch on this stream
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
-    int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(stats), 6 * nh,
-                                   reinterpret_cast<uint32_t *>(also_zero), 2 * nh, st);
-    if (rc != TANGO_OK) return rc;
+    if (!prezeroed) {
+        int rc = tango_zero2_u32_async(reinterpret_cast<uint32_t *>(stats), 6 * nh,
+                                       reinterpret_cast<uint32_t *>(also_zero), 2 * nh, st);
+        if (rc != TANGO_OK) return rc;
+    }
     if (g->n_edges > 0) {
         sddmm_dot_args a;
         a.n = g->n_nodes;
