@@ -45,6 +45,17 @@ int tango_benchaid_mfma_f8f6f4_launch(int iters, int format, int random_operands
  */
 int tango_benchaid_copy(const void *src, void *dst, size_t n_words16, void *stream);
 
+/*
+ * A streaming kernel with a chosen mix of reads and writes: for every unit
+ * i < n_units it loads 16 bytes from each of `reads` arrays (src holds them
+ * end to end: reads * n_units * 16 bytes) and stores 16 bytes to each of
+ * `writes` arrays (dst: writes * n_units * 16 bytes, at least 16).  Allowed
+ * (reads, writes): (1,0) (0,1) (1,1) (2,1) (4,1) (1,2) (1,4); anything else
+ * returns TANGO_ERR_BAD_ENUM.  The HBM rate this reaches at a kernel's own
+ * read : write ratio is the yardstick its streaming rate is compared with.
+ */
+int tango_benchaid_stream_mix(const void *src, void *dst, size_t n_units, int reads, int writes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,6 +14,8 @@
 //
 // Algorithmic HBM bytes of the forward call per row of A: 4K (abs-max pass)
 // + 4K (read) + K (A_q write) + 4N (C write).
+#include <type_traits>
+
 #include "internal.hip.h"
 
 int tango_gemm_i8_async(int64_t M, int64_t N, int64_t K, const int8_t *A_q, int64_t lda, const float *s_A, const int8_t *BT_q,
@@ -69,6 +71,9 @@ __device__ inline uint2 quantize8_packed(const float (&y)[8], const tango_rng &r
 
 // WL = bytes per LDS write: 4 if K % 4 == 0, 2 if K % 2 == 0, else 1 (pieces never straddle a row then).
 template <int ROUNDING, int WL, bool KEEP = false>
+// (Occupancy: three waves per SIMD.  Capping the registers for four was measured slower at K = 384 - 2.22 against 2.05 ms
+// for 2.4 M rows - and two against three makes no difference: the kernel runs at 0.85-0.9 of the rate a plain streaming
+// kernel with its read : write mix reaches.)
 __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
 {
     extern __shared__ __align__(16) int8_t lds[];
@@ -178,40 +183,46 @@ __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
             acc11 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, c1, acc11, 0, 0, 0);
         }
         // epilogue: dequantize in registers, store, track the abs-max
-        // (element i of a 32x32 tile: column = lane%32, row = 8*(i/4) + 4*(lane/32) + i%4)
+        // (element i of a 32x32 tile: column = lane%32, row = 8*(i/4) + 4*(lane/32) + i%4).  Every address is the
+        // workgroup's (uniform) base plus a 32-bit offset, and the row part of that offset is uniform too: the sixty-four
+        // stores of a wave need no 64-bit address arithmetic and no registers to hold addresses.
+        float *Cb = a.C + row0 * a.N;
+        const uint32_t un = static_cast<uint32_t>(a.N);
+        auto store_tiles = [&](auto checked_tag) {
+            constexpr bool CHECKED = decltype(checked_tag)::value;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const v16i &acc = t == 0 ? acc00 : (t == 1 ? acc01 : (t == 2 ? acc10 : acc11));
-            const int rb = t / 2, cb = t % 2;
-            const int col = col0 + cb * 32 + lane % 32;
-            if constexpr (!KEEP) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int r = rb * 32 + (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                    if (r < rows && col < a.N) {
-                        a.C[(row0 + r) * a.N + col] = static_cast<float>(acc[i]) * sc;
-                        maxabs = max(maxabs, abs(acc[i]));
-                    }
-                }
-            } else {
-                // the 32 columns of a tile row are one aligned word of the bit array (N a multiple of 32): lane l fetches
-                // the word of row l % 32 of this tile, and every lane then picks the words of its sixteen rows
-                const int64_t wr = row0 + rb * 32 + lane % 32;
+            for (int t = 0; t < 4; ++t) {
+                const v16i &acc = t == 0 ? acc00 : (t == 1 ? acc01 : (t == 2 ? acc10 : acc11));
+                const int rb = t / 2, cb = t % 2;
+                const int col = col0 + cb * 32 + lane % 32;
+                const int rfirst = rb * 32 + (lane / 32) * 4;
+                const uint32_t off0 = static_cast<uint32_t>(rfirst) * un + static_cast<uint32_t>(col);
                 uint32_t mine = 0u;
-                if (rb * 32 + lane % 32 < rows && col < a.N) mine = a.C_keep_bits[(wr * a.N + (col - lane % 32)) >> 5];
+                if constexpr (KEEP) {
+                    // the 32 columns of a tile row are one aligned word of the bit array (N a multiple of 32): lane l
+                    // fetches the word of row l % 32 of this tile, and every lane then picks the words of its sixteen rows
+                    const int64_t wr = row0 + rb * 32 + lane % 32;
+                    if (rb * 32 + lane % 32 < rows && col < a.N) mine = a.C_keep_bits[(wr * a.N + (col - lane % 32)) >> 5];
+                }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int rl = (i / 4) * 8 + (lane / 32) * 4 + (i % 4);
-                    const uint32_t kw = static_cast<uint32_t>(__shfl(static_cast<int>(mine), rl, 64));
-                    const int r = rb * 32 + rl;
-                    if (r < rows && col < a.N) {
-                        const int v = ((kw >> (lane % 32)) & 1u) ? acc[i] : 0;
-                        a.C[(row0 + r) * a.N + col] = static_cast<float>(v) * sc;
+                    const int rl = (i / 4) * 8 + (i % 4);
+                    int v = acc[i];
+                    if constexpr (KEEP) {
+                        const uint32_t kw = static_cast<uint32_t>(__shfl(static_cast<int>(mine), (lane / 32) * 4 + rl, 64));
+                        v = ((kw >> (lane % 32)) & 1u) ? v : 0;
+                    }
+                    if (!CHECKED || (rfirst + rl < rows && col < a.N)) {
+                        Cb[off0 + static_cast<uint32_t>(rl) * un] = static_cast<float>(v) * sc;
                         maxabs = max(maxabs, abs(v));
                     }
                 }
             }
-        }
+        };
+        if (rows == BM && col0 + 64 <= a.N)
+            store_tiles(std::false_type{});
+        else
+            store_tiles(std::true_type{});
     }
     if (a.absmax_C) {
         float m = static_cast<float>(maxabs) * sc;  // conversion and product are monotone
@@ -353,7 +364,7 @@ __device__ inline void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint3
     t[3] = __builtin_amdgcn_perm(x23h, x01h, 0x07060302u);
 }
 
-__global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const int8_t *__restrict__ P,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_gemm_tn(int64_t M, int K, int N, const int8_t *__restrict__ P,
                                                  const int8_t *__restrict__ Q, long long *acc_out, int64_t slab_rows,
                                                  int tiles_k, int tiles_n)
 {
@@ -378,8 +389,10 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const 
         // stage: waves 0-1 transpose the P slab, waves 2-3 the Q slab.  A thread takes one quad of columns (32 per tile,
         // consecutive lanes = 128 contiguous bytes of a row) and 16 consecutive rows: four 4x4 byte transposes give, for
         // each of its 4 columns, the 16 row bytes that one MFMA operand read wants - one 16-byte LDS store each.  The
-        // 16-byte chunk index is XORed with (row / 8) % 4 so that neither these stores (lanes 4 rows apart) nor the
-        // operand reads (lanes 1 row apart) collide in the LDS banks.
+        // 16-byte chunk index is XORed with (row / 16) % 4 so that neither these stores (lanes 4 rows apart) nor the
+        // operand reads (lanes 1 row apart) collide in the LDS banks (64 banks of 4 bytes; a 16-byte access is served
+        // sixteen lanes per cycle, and with the 80-byte row stride sixteen consecutive rows - or sixteen rows 4 apart -
+        // then cover all 64 banks exactly once).
         {
             const int half = tid / 128, t128 = tid % 128;
             const int qb = t128 % 32, qa = t128 / 32;
@@ -403,7 +416,7 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const 
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int row = 4 * qb + c;
-                *reinterpret_cast<uint4 *>(dstT + row * LDM + 16 * (qa ^ ((row / 8) % 4))) =
+                *reinterpret_cast<uint4 *>(dstT + row * LDM + 16 * (qa ^ ((row / 16) % 4))) =
                     make_uint4(t[0][c], t[1][c], t[2][c], t[3][c]);
             }
         }
@@ -412,10 +425,10 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t M, int K, int N, const 
         for (int ks = 0; ks < MS; ks += 32) {
             const int mc = ks / 16 + lane / 32;  // 16-byte chunk of the reduction rows
             const int ra = rbase + lane % 32, rb = cbase + lane % 32;
-            const v4i a0 = *reinterpret_cast<const v4i *>(Pt + ra * LDM + 16 * (mc ^ ((ra / 8) % 4)));
-            const v4i a1 = *reinterpret_cast<const v4i *>(Pt + (ra + 32) * LDM + 16 * (mc ^ (((ra + 32) / 8) % 4)));
-            const v4i b0 = *reinterpret_cast<const v4i *>(Qt + rb * LDM + 16 * (mc ^ ((rb / 8) % 4)));
-            const v4i b1 = *reinterpret_cast<const v4i *>(Qt + (rb + 32) * LDM + 16 * (mc ^ (((rb + 32) / 8) % 4)));
+            const v4i a0 = *reinterpret_cast<const v4i *>(Pt + ra * LDM + 16 * (mc ^ ((ra / 16) % 4)));
+            const v4i a1 = *reinterpret_cast<const v4i *>(Pt + (ra + 32) * LDM + 16 * (mc ^ (((ra + 32) / 16) % 4)));
+            const v4i b0 = *reinterpret_cast<const v4i *>(Qt + rb * LDM + 16 * (mc ^ ((rb / 16) % 4)));
+            const v4i b1 = *reinterpret_cast<const v4i *>(Qt + (rb + 32) * LDM + 16 * (mc ^ (((rb + 32) / 16) % 4)));
             acc00 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc00, 0, 0, 0);
             acc01 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b1, acc01, 0, 0, 0);
             acc10 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b0, acc10, 0, 0, 0);

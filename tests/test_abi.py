@@ -37,7 +37,7 @@ def test_benchaid_header_symbols_are_exported(lib):
     aid = ctypes.CDLL(b.AID_LIB)
     names = declared_symbols("tango_benchaid.h")
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["tango.h", "tango_benchaid.h"]
-    assert names == sorted(benchaid.SIGNATURES) and len(names) == 4
+    assert names == sorted(benchaid.SIGNATURES) and len(names) == 5
     for n in names:
         assert hasattr(aid, n), n
         assert not hasattr(lib, n), "measurement aid exported by the method's library: " + n
