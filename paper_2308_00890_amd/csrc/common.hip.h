@@ -40,15 +40,19 @@ struct tango_zero_regions {
     uint32_t *p[6];
     int64_t n[6];  // words in each run; unused entries hold 0
     int count;
+    int overflow;  // set when a seventh run was asked for: the launch that would clear the list is refused
 };
 
 static inline void tango_zero_regions_add(tango_zero_regions &z, void *p, int64_t words)
 {
-    if (p && words > 0 && z.count < 6) {
-        z.p[z.count] = static_cast<uint32_t *>(p);
-        z.n[z.count] = words;
-        ++z.count;
+    if (!p || words <= 0) return;
+    if (z.count >= 6) {
+        z.overflow = 1;
+        return;
     }
+    z.p[z.count] = static_cast<uint32_t *>(p);
+    z.n[z.count] = words;
+    ++z.count;
 }
 
 // Thread `tid` of `nthreads` takes its share of every run.

@@ -29,7 +29,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int BM = 64;     // rows of A per workgroup
 constexpr int BN = 256;    // columns per sweep: 4 waves x 64
 constexpr int KMAX = 2048; // largest reduction length whose 64-row int8 panel fits LDS
-constexpr int64_t SMALL_B_ELEMS = 65536;  // weight matrices up to this size are prepared by one workgroup
+// weight matrices up to this size are prepared by one workgroup (eight strided elements per thread; measured at 38,400
+// elements the lone workgroup's chain of dependent iterations takes 51 us, longer than the four launches it replaces)
+constexpr int64_t SMALL_B_ELEMS = 8192;
 constexpr int LDS_PAD = 16;
 
 struct fused_args {
@@ -545,6 +547,7 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
     tango_zero_regions zr{};
     if (also_zero) zr = *also_zero;
+    TANGO_REQUIRE(!zr.overflow, TANGO_ERR_BAD_SHAPE);
     if (K * N <= SMALL_B_ELEMS && static_cast<int64_t>(Np) * Kp <= 4 * SMALL_B_ELEMS) {
         // a small weight matrix: everything that concerns B, and the clearing of the call's abs-max words, in one launch
         if (rounding == TANGO_RN)

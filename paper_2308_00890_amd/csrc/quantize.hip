@@ -340,6 +340,7 @@ static __global__ void k_zero_regions(tango_zero_regions z)
 // Every run of z in one launch.
 int tango_zero_regions_async(const tango_zero_regions &z, hipStream_t st)
 {
+    TANGO_REQUIRE(!z.overflow, TANGO_ERR_BAD_SHAPE);
     int64_t longest = 0;
     for (int r = 0; r < z.count; ++r) longest = z.n[r] > longest ? z.n[r] : longest;
     if (longest == 0) return TANGO_OK;

@@ -33,8 +33,8 @@ GEMM_SHAPES = [
     (3000, 2048, 40),
     (300, 4112, 136),  # reduction longer than the panel kernel takes: quantization pass + tiled int8 kernel
     (260, 72, 2320),   # ... and the same for the dA product of the backward pass (its reduction length is N)
-    (200, 256, 256),   # the largest weight matrix that one workgroup prepares (65,536 elements)
-    (200, 260, 256),   # ... and the first size that takes the multi-launch preparation
+    (200, 128, 64),    # the largest weight matrix that one workgroup prepares (8,192 elements)
+    (200, 132, 64),    # ... and a size just above, which takes the multi-launch preparation
 ]
 
 
