@@ -673,7 +673,9 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         if (!acc_zeroed && (rc = tango_fill_u32_async(reinterpret_cast<uint32_t *>(acc), 0u, 2 * K * N, st)) != TANGO_OK)
             return rc;
         const int tiles_k = static_cast<int>((K + TT - 1) / TT), tiles_n = static_cast<int>((N + TT - 1) / TT);
-        int64_t slabs = 4096 / (tiles_k * tiles_n);
+        // about 2,048 workgroups in all: enough to fill the chip several times over, and half the 64-bit atomics of 4,096
+        // (measured at 233 k x 602 x 256: 0.38 -> 0.31 ms)
+        int64_t slabs = 2048 / (tiles_k * tiles_n);
         // at least eight steps per workgroup before its 64 KB of atomics; two where the whole product is a few dozen steps,
         // which a couple of workgroups would otherwise walk as one long chain of dependent load - transpose - multiply steps
         slabs = std::min<int64_t>(slabs, M / ((M < 65536 ? 2 : 8) * MS));
