@@ -395,9 +395,10 @@ def bench_sweep(args, torch, T, dev):
     q = [r for r in recs if "f32" not in r["kernel"]]
     ms_per_step = sum(r["ms"] for r in q)
     worst = max(q, key=lambda r: r["ms"])
-    # the record the 60 % target is judged on: widths whose table does not fit on chip (F >= 128: 537 MB and up)
+    # the dominant launch of the sweep is its longest one; the lowest HBM fraction among the launches whose table is
+    # HBM-resident (where the 60 % target is judged: F >= 128, 537 MB and up) is reported beside it
     big = [r for r in q if not r["table_fits_on_chip"]]
-    dom = min(big, key=lambda r: r["effective_rate_over_hbm_peak_pct"])
+    low = min(big, key=lambda r: r["effective_rate_over_hbm_peak_pct"])
     out = {
         "metric": "ms for the quantized sparse primitives of the sweep (qSPMM in-edges, out-edges with weights in either order, qSDDMM-dot; F = 32..512); "
                   "per kernel HBM GB/s and % of peak",
@@ -415,16 +416,18 @@ def bench_sweep(args, torch, T, dev):
         "config": {"workload": "config 5 (sweep22): R-MAT scale 22, %d nodes, %d edges incl. self-loops (mean degree 16), one "
                                "head, F = 32, 64, 128, 256, 512; every launch timed alone with HIP events" % (g.n_nodes, g.n_edges)},
         "roofline": {
-            "kernel": dom["kernel"] + ", " + dom["workload"] + " (the slowest fraction among the launches whose table is HBM-resident)",
-            "bound": "hbm",
-            "achieved": dom["GBs"],
-            "peak": HBM_PEAK_GBS,
+            "kernel": worst["kernel"] + ", " + worst["workload"] + " (the longest launch of the sweep)",
+            "bound": worst["bound"],
+            "achieved": worst["GBs"],
+            "peak": HBM_PEAK_GBS if worst["frac_of_hbm_peak"] is not None else None,
             "unit": "GB/s",
-            "frac": dom["GBs"] / HBM_PEAK_GBS,
+            "frac": worst["frac_of_hbm_peak"],
             "traffic": None,
-            "algorithmic_bytes_per_launch": dom["algorithmic_GB"] * 1e9,
-            "ms_per_launch": dom["ms"],
+            "algorithmic_bytes_per_launch": worst["algorithmic_GB"] * 1e9,
+            "ms_per_launch": worst["ms"],
         },
+        "lowest_hbm_fraction": {"kernel": low["kernel"] + ", " + low["workload"], "GBs": low["GBs"],
+                                "frac_of_hbm_peak": low["GBs"] / HBM_PEAK_GBS, "ms_per_launch": low["ms"]},
         "sparse_kernels": recs,
         "longest_launch": worst["kernel"] + ", " + worst["workload"],
     }
