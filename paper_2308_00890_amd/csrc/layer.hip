@@ -129,6 +129,10 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     TANGO_REQUIRE(L->ws && tango_aligned(L->ws, 256) &&
                       L->ws_bytes >= tango_gat_layer_workspace_bytes(n, nnz, L->k_in, L->heads, L->dim),
                   TANGO_ERR_WORKSPACE);
+    // (what step 2' needs of its operands, checked before anything is enqueued)
+    TANGO_REQUIRE(F <= 1024 && L->dim % 4 == 0 && tango_aligned(L->dHp, 16) && tango_aligned(L->Hp_q, 4) &&
+                      tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16),
+                  TANGO_ERR_BAD_SHAPE);
     float *sc = static_cast<float *>(L->ws);
     void *hp_ws = static_cast<char *>(L->ws) + 256;
     const size_t hpb = tango_head_proj_bwd_workspace_bytes(n, L->heads, L->dim);
@@ -188,9 +192,6 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                                stream));
     }
     // 2' fused with dH' = dH'_agg + dH'_att and its abs-max
-    TANGO_REQUIRE(F <= 1024 && L->dim % 4 == 0 && tango_aligned(L->dHp, 16) && tango_aligned(L->Hp_q, 4) &&
-                      tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16),
-                  TANGO_ERR_BAD_SHAPE);
     TANGO_TRY(tango_head_proj_bwd_async(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
                                         L->absmax_dHp, L->da_src, L->da_dst, hp_ws, st, true));
     // 1': both GEMMs from the cached H_q, W_q
