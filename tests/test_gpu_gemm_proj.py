@@ -139,6 +139,19 @@ def test_measurement_aids_of_the_harness(T):
     B.tango_benchaid_copy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+    # the stream-mix yardstick: every unit's stores carry the XOR of its loads (and its own index in the first word)
+    n_units = 5000
+    a = torch.randint(-2**31, 2**31 - 1, (2 * n_units * 4,), dtype=torch.int32, device="cuda:0")
+    out = torch.zeros(2 * n_units * 4, dtype=torch.int32, device="cuda:0")
+    B.tango_benchaid_stream_mix(a, out, n_units, 2, 1)
+    torch.cuda.synchronize()
+    x = a.view(2, n_units, 4)
+    want = x[0] ^ x[1] ^ torch.tensor([0, 1, 2, 3], dtype=torch.int32, device="cuda:0")
+    want[:, 0] ^= torch.arange(n_units, dtype=torch.int32, device="cuda:0")
+    assert torch.equal(out.view(2, n_units, 4)[0], want)
+    assert int(out.view(2, n_units, 4)[1].abs().sum()) == 0  # one store per unit: the second array stays untouched
+    with pytest.raises(T.TangoError):
+        B.tango_benchaid_stream_mix(a, out, n_units, 3, 3)  # not one of the built mixes
 
 
 PROJ_SHAPES = [(1024, 2, 32), (1001, 4, 64), (333, 3, 128), (500, 1, 256), (70, 8, 16), (17, 1, 1024), (5, 2, 4)]
