@@ -19,13 +19,13 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
                                float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, const int8_t *src_codes,
-                               hipStream_t st);
+                               hipStream_t st, bool out_prezeroed = false);
 int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, const int8_t *Sq, const float *sS,
                                       const int8_t *Dq, const float *sD, float slope, const float *row_lse,
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
                                       const float *s_X, const void *rec, double *dS_acc, float *out,
-                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st);
+                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st, bool out_prezeroed = false);
 int tango_attn_bwd_dst_fused_async(const tango_graph *g, int heads, int dim, const int8_t *dOut_q, const float *s_dOut,
                                    const int8_t *X_q, const float *s_X, const int8_t *Sq, const float *sS, const int8_t *Dq,
                                    const float *sD, float slope, const float *row_lse, double *stats, void *rec,
@@ -309,7 +309,7 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
                                 int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
-                                bool absmax_alpha_zeroed)
+                                bool absmax_alpha_zeroed, bool out_prezeroed)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -338,7 +338,7 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
     if (rc != TANGO_OK) return rc;
     return tango_spmm_attention_async(g, TANGO_IN, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding,
                                       seed, stream_id_alpha, alpha_q, s_alpha, alpha_dump, X_q, s_X, out, absmax_out, relu_out,
-                                      static_cast<uint16_t *>(relu_bits), src_codes, st);
+                                      static_cast<uint16_t *>(relu_bits), src_codes, st, out_prezeroed);
 }
 
 extern "C" {
@@ -448,7 +448,7 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
                                    uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
                                    const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
                                    float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
-                                   bool prezeroed)
+                                   bool prezeroed, bool out_prezeroed)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     TANGO_REQUIRE(g != nullptr, TANGO_ERR_NULL);
@@ -484,7 +484,7 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
         if (rc != TANGO_OK) return rc;
         return tango_spmm_attention_rev_ds_async(g, heads, dim, S_q, s_S, D_q, s_D, slope, row_lse, absmax_alpha, rounding, seed,
                                                  stream_id_alpha, s_alpha, dOut_q, s_dOut, X_q, s_X, rec, dS_acc, dX_agg,
-                                                 absmax_dX, dS, true, st);
+                                                 absmax_dX, dS, true, st, out_prezeroed);
     }
     if (edge_part && !alpha_q) {
         // 5'' over in-edges (dalpha, the only fp32 edge tensor of the backward pass), 4' and 3'' over in-edges, then

@@ -34,19 +34,19 @@ static inline unsigned tango_grid_for(size_t work_items, unsigned per_block, uns
     return static_cast<unsigned>(b);
 }
 
-// Up to six runs of 32-bit words to clear (accumulators and abs-max words that a later kernel of the same chain adds
+// Up to eight runs of 32-bit words to clear (accumulators and abs-max words that a later kernel of the same chain adds
 // to): passed by value to the one kernel that clears them, so that several clears cost one launch.
 struct tango_zero_regions {
-    uint32_t *p[6];
-    int64_t n[6];  // words in each run; unused entries hold 0
+    uint32_t *p[8];
+    int64_t n[8];  // words in each run; unused entries hold 0
     int count;
-    int overflow;  // set when a seventh run was asked for: the launch that would clear the list is refused
+    int overflow;  // set when a ninth run was asked for: the launch that would clear the list is refused
 };
 
 static inline void tango_zero_regions_add(tango_zero_regions &z, void *p, int64_t words)
 {
     if (!p || words <= 0) return;
-    if (z.count >= 6) {
+    if (z.count >= 8) {
         z.overflow = 1;
         return;
     }
@@ -253,6 +253,16 @@ __device__ static inline double tango_wave_sum(double v)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
+}
+
+// An abs-max handed from one kernel to the next is either one word (count == 1) or `count` partial maxima, one per
+// workgroup of the producing launch (no atomics, and so no launch that clears their target first); every lane returns
+// the maximum.  count <= 64.
+__device__ static inline float tango_absmax_load(const float *p, int count)
+{
+    if (count == 1) return *p;
+    const int lane = threadIdx.x % TANGO_WAVE;
+    return tango_wave_max(lane < count ? p[lane] : 0.0f);
 }
 
 // max over non-negative floats through their bit patterns (monotone for x >= 0).

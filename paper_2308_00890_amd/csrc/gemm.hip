@@ -29,9 +29,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int BM = 64;     // rows of A per workgroup
 constexpr int BN = 256;    // columns per sweep: 4 waves x 64
 constexpr int KMAX = 2048; // largest reduction length whose 64-row int8 panel fits LDS
-// weight matrices up to this size are prepared by one workgroup (eight strided elements per thread; measured at 38,400
-// elements the lone workgroup's chain of dependent iterations takes 51 us, longer than the four launches it replaces)
+// weight matrices up to this size are prepared by one launch in which every workgroup finds max|B| for itself
 constexpr int64_t SMALL_B_ELEMS = 8192;
+constexpr int64_t SMALL_A_ELEMS = 1 << 20;  // an A of up to this size has its abs-max found by that same launch
 constexpr int LDS_PAD = 16;
 
 struct fused_args {
@@ -40,6 +40,7 @@ struct fused_args {
     int Kp, Np;      // padded: Kp multiple of 32 (BT row length), Np multiple of 64 (BT rows)
     const float *A;  // M x K fp32
     const float *absmax_A;
+    int absmax_A_count;  // 1, or the number of partial maxima at absmax_A (tango_absmax_load)
     tango_rng rng;
     int8_t *A_q;     // M x K
     float *s_A;      // out
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void k_qgemm_fused(fused_args a)
 
     // ---- phase 1: stream the panel (a contiguous range of A), quantize, keep it in LDS and write it back
     float s, inv;
-    tango_scale_from_absmax(*a.absmax_A, s, inv);
+    tango_scale_from_absmax(tango_absmax_load(a.absmax_A, a.absmax_A_count), s, inv);
     if (blockIdx.x == 0 && tid == 0) *a.s_A = s;
     const int64_t flat0 = row0 * a.K;  // multiple of 8 because row0 is a multiple of 64
     const int cnt = rows * a.K;
@@ -254,35 +255,59 @@ __global__ __launch_bounds__(256) void k_quantize_b(int K, int N, int Kp, const 
     }
 }
 
-// The same for a small B in ONE launch of one workgroup: clears the abs-max words of the call (absmax_A may be NULL),
-// finds max|B| (left in *absmax_B), then writes B_q and every byte of BT, padding included.  It replaces four launches
-// that are each a few microseconds of latency on graphs too small to hide them.
+// The same for a small B in ONE launch: clears the abs-max words of the call (absmax_A may be NULL) and the runs of
+// also_zero, finds max|B| (left in *absmax_B), then writes B_q and every byte of BT, padding included.  Every workgroup
+// finds max|B| for itself - B is a few thousand elements, reading it again costs less than a grid-wide reduction and the
+// launch that would have to clear its target - and takes its share of the words to write and to clear.  It replaces four
+// launches that are each a few microseconds of latency on graphs too small to hide them.
 template <int ROUNDING>
-__global__ __launch_bounds__(1024) void k_quantize_b_small(int K, int N, int Kp, int Np, const float *__restrict__ B,
-                                                           float *absmax_A, float *absmax_B, float *absmax_C, tango_rng rng,
-                                                           int8_t *__restrict__ B_q, float *s_B, int8_t *__restrict__ BT,
-                                                           tango_zero_regions also_zero)
+__global__ __launch_bounds__(256) void k_quantize_b_small(int K, int N, int Kp, int Np, const float *__restrict__ B,
+                                                          float *absmax_A, float *absmax_B, float *absmax_C, tango_rng rng,
+                                                          int8_t *__restrict__ B_q, float *s_B, int8_t *__restrict__ BT,
+                                                          tango_zero_regions also_zero, const float *__restrict__ A, int64_t a_elems,
+                                                          float *__restrict__ a_partials)
 {
-    __shared__ float red[16];
+    __shared__ float red[4];
+    const int64_t tid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x, nthr = static_cast<int64_t>(gridDim.x) * 256;
+    if (a_partials) {
+        // a small A whose abs-max is not known: this workgroup's share of max|A|, left as one of gridDim.x partial maxima
+        // for the GEMM kernel to reduce (no atomics, so no launch that clears their target, and no launch of its own)
+        float ma = 0.0f;
+        const float4 *A4 = reinterpret_cast<const float4 *>(A);  // (A is 16-byte aligned: the entry point requires it)
+        for (int64_t i = tid; i < a_elems / 4; i += nthr) {
+            const float4 v = A4[i];
+            ma = fmaxf(ma, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        for (int64_t i = a_elems / 4 * 4 + tid; i < a_elems; i += nthr) ma = fmaxf(ma, fabsf(A[i]));
+        ma = tango_wave_max(ma);
+        if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = ma;
+        __syncthreads();
+        if (threadIdx.x == 0) a_partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        __syncthreads();
+    }
+    __shared__ float Bs[SMALL_B_ELEMS];  // B itself: read from memory once, the second pass takes it from here
     const int total = K * N;
     float m = 0.0f;
-    for (int i = threadIdx.x; i < total; i += 1024) m = fmaxf(m, fabsf(B[i]));
+    for (int i = threadIdx.x; i < total; i += 256) {
+        const float v = B[i];
+        Bs[i] = v;
+        m = fmaxf(m, fabsf(v));
+    }
     m = tango_wave_max(m);
     if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = m;
     __syncthreads();
-    m = red[0];
-    for (int w = 1; w < 16; ++w) m = fmaxf(m, red[w]);
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     float s, inv;
     tango_scale_from_absmax(m, s, inv);
-    if (threadIdx.x == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         *s_B = s;
         *absmax_B = m;
         if (absmax_A) *absmax_A = 0.0f;
         if (absmax_C) *absmax_C = 0.0f;
     }
-    tango_zero_regions_apply(also_zero, threadIdx.x, 1024);
+    tango_zero_regions_apply(also_zero, tid, nthr);
     const int wpr = Kp / 4;  // 32-bit words per row of BT
-    for (int w = threadIdx.x; w < Np * wpr; w += 1024) {
+    for (int w = static_cast<int>(tid); w < Np * wpr; w += static_cast<int>(nthr)) {
         const int n = w / wpr, k0 = (w - n * wpr) * 4;
         uint32_t word = 0;
         if (n < N) {
@@ -292,7 +317,7 @@ __global__ __launch_bounds__(1024) void k_quantize_b_small(int K, int N, int Kp,
                 const int i = k * N + n;
                 uint32_t bits = 0;
                 if (ROUNDING == TANGO_SR) bits = tango_bits16(tango_philox_block(rng, static_cast<uint64_t>(i) >> 3), i & 7);
-                const int q = tango_round_clamp<ROUNDING>(B[i] * inv, bits);
+                const int q = tango_round_clamp<ROUNDING>(Bs[i] * inv, bits);
                 B_q[i] = static_cast<int8_t>(q);
                 word |= (static_cast<uint32_t>(q) & 0xffu) << (8 * j);
             }
@@ -544,22 +569,34 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     const int Kp = static_cast<int>(tango_round_up(K, 32)), Np = static_cast<int>(tango_round_up(N, 64));
 
     const float *am_A = absmax_A_in ? absmax_A_in : am;
+    int am_A_count = 1;
     const tango_rng rng_b = tango_rng_make(seed, stream_id_B);
     tango_zero_regions zr{};
     if (also_zero) zr = *also_zero;
     TANGO_REQUIRE(!zr.overflow, TANGO_ERR_BAD_SHAPE);
     if (K * N <= SMALL_B_ELEMS && static_cast<int64_t>(Np) * Kp <= 4 * SMALL_B_ELEMS) {
         // a small weight matrix: everything that concerns B, and the clearing of the call's abs-max words, in one launch
+        int64_t zwords = 0;
+        for (int r = 0; r < zr.count; ++r) zwords += zr.n[r];
+        // (max|A| of a small A: per-workgroup partial maxima behind the two abs-max words of the workspace header)
+        const bool a_partials = !absmax_A_in && M * K <= SMALL_A_ELEMS;
+        const int64_t longest = std::max<int64_t>(std::max<int64_t>(static_cast<int64_t>(Np) * Kp / 4, zwords), a_partials ? M * K / 4 : 0);
+        const unsigned gs = tango_grid_for(static_cast<size_t>(longest), 256 * 2, 60);
+        if (a_partials) {
+            am_A = am + 2;
+            am_A_count = static_cast<int>(gs);
+        }
         if (rounding == TANGO_RN)
-            k_quantize_b_small<TANGO_RN><<<1, 1024, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
-                                                            absmax_C, rng_b, B_q, s_B, BT, zr);
+            k_quantize_b_small<TANGO_RN><<<gs, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
+                                                           absmax_C, rng_b, B_q, s_B, BT, zr, A, M * K, a_partials ? am + 2 : nullptr);
         else
-            k_quantize_b_small<TANGO_SR><<<1, 1024, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
-                                                            absmax_C, rng_b, B_q, s_B, BT, zr);
+            k_quantize_b_small<TANGO_SR><<<gs, 256, 0, st>>>(static_cast<int>(K), static_cast<int>(N), Kp, Np, B, am, am + 1,
+                                                           absmax_C, rng_b, B_q, s_B, BT, zr, A, M * K, a_partials ? am + 2 : nullptr);
         TANGO_LAUNCH_CHECK();
-        if (!absmax_A_in && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK) return rc;
+        if (!absmax_A_in && !a_partials && (rc = tango_absmax_accumulate_async(A, static_cast<size_t>(M) * K, am, st)) != TANGO_OK)
+            return rc;
     } else {
-        TANGO_REQUIRE(zr.count <= 4, TANGO_ERR_BAD_SHAPE);
+        TANGO_REQUIRE(zr.count <= 6, TANGO_ERR_BAD_SHAPE);
         tango_zero_regions_add(zr, am, 2);
         tango_zero_regions_add(zr, absmax_C, 1);
         if ((rc = tango_zero_regions_async(zr, st)) != TANGO_OK) return rc;
@@ -578,14 +615,14 @@ int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, co
     if (K > KMAX) {
         // the 64-row panel of A no longer fits LDS: quantize A in a pass of its own, then the tiled kernel on the int8
         // operands (BT: N rows of Kp bytes, zero-padded)
-        if ((rc = tango_quantize_with_absmax_async(A, static_cast<size_t>(M) * K, rounding, seed, stream_id_A, am_A, A_q, s_A, st)) !=
-            TANGO_OK)
+        if ((rc = tango_quantize_with_absmax_async(A, static_cast<size_t>(M) * K, rounding, seed, stream_id_A, am_A, A_q, s_A, st,
+                                                   am_A_count)) != TANGO_OK)
             return rc;
         return tango_gemm_i8_async(M, N, K, A_q, K, s_A, BT, Kp, s_B, C, absmax_C, st);
     }
     fused_args a;
     a.M = M; a.N = static_cast<int>(N); a.K = static_cast<int>(K); a.Kp = Kp; a.Np = Np;
-    a.A = A; a.absmax_A = am_A; a.rng = tango_rng_make(seed, stream_id_A);
+    a.A = A; a.absmax_A = am_A; a.absmax_A_count = am_A_count; a.rng = tango_rng_make(seed, stream_id_A);
     a.A_q = A_q; a.s_A = s_A; a.BT = BT; a.s_B = s_B; a.C = C; a.absmax_C = absmax_C; a.C_keep_bits = nullptr;
     return launch_fused(a, rounding, st);
 }
@@ -660,7 +697,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         acc_zeroed = true;
         fused_args a;
         a.M = M; a.N = static_cast<int>(K); a.K = static_cast<int>(N); a.Kp = Rp; a.Np = Cp;
-        a.A = dC; a.absmax_A = amp; a.rng = tango_rng_make(seed, stream_id_dC);
+        a.A = dC; a.absmax_A = amp; a.absmax_A_count = 1; a.rng = tango_rng_make(seed, stream_id_dC);
         a.A_q = dC_q; a.s_A = s_dC; a.BT = BT; a.s_B = s_B; a.C = dA; a.absmax_C = absmax_dA; a.C_keep_bits = dA_keep_bits;
         if ((rc = launch_fused(a, rounding, st)) != TANGO_OK) return rc;
     } else {

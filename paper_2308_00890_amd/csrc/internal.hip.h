@@ -69,7 +69,8 @@ int tango_gat_attention_fwd_act(const tango_graph *g, int heads, int dim, const 
                                 int rounding, uint64_t seed, uint64_t stream_id_alpha, float *row_lse, int8_t *alpha_q,
                                 float *s_alpha, float *absmax_alpha, float *alpha_dump, float *out, float *absmax_out,
                                 int relu_out, void *relu_bits, int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
-                                bool absmax_alpha_zeroed = false);  // true: *absmax_alpha was cleared by an earlier launch
+                                bool absmax_alpha_zeroed = false,  // true: *absmax_alpha was cleared by an earlier launch
+                                bool out_prezeroed = false);  // true: so were all of out, relu_bits and *absmax_out
 
 // tango_gat_attention_bwd with the edge-ordered source codes the forward pass left (src_codes, may be NULL).
 int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, const int8_t *S_q, const float *s_S,
@@ -78,11 +79,16 @@ int tango_gat_attention_bwd_cached(const tango_graph *g, int heads, int dim, con
                                    uint64_t seed, uint64_t stream_id_alpha, const int8_t *X_q, const float *s_X,
                                    const int8_t *dOut_q, const float *s_dOut, float *dX_agg, float *absmax_dX, float *dalpha,
                                    float *dS, float *dD, const int8_t *src_codes, void *ws, size_t ws_bytes, void *stream,
-                                   bool prezeroed = false);
+                                   bool prezeroed = false, bool out_prezeroed = false);  // out_prezeroed: all of dX_agg is zero already
 // The runs of the workspace that the call above clears first when it keeps no edge tensor (alpha_q and dalpha NULL);
 // a caller that clears them in an earlier launch of the same chain passes prezeroed = true.
 void tango_gat_attention_bwd_zero_regions(const tango_graph *g, int heads, void *ws, tango_zero_regions &z);
 
 // Quantize with a known abs-max (device float).
+// (absmax_count > 1: `absmax` holds that many partial maxima, see tango_absmax_partials_async; x, q vector-aligned then)
 int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
-                                     const float *absmax, int8_t *q, float *scale_out, hipStream_t st);
+                                     const float *absmax, int8_t *q, float *scale_out, hipStream_t st, int absmax_count = 1);
+
+// For a small tensor: per-workgroup maxima of |x| into partials[0 .. *count) (x 16-byte aligned, *count <= 64) and the
+// runs of z cleared, in one launch: an abs-max without atomics, hence without a launch that clears their target first.
+int tango_absmax_partials_async(const float *x, size_t n, float *partials, int *count, const tango_zero_regions &z, hipStream_t st);

@@ -9,10 +9,14 @@ namespace {
 // random-stream ids of the tensors of one layer (layer l uses 16*l + id)
 enum { SID_H = 1, SID_W = 2, SID_HP = 3, SID_S = 4, SID_D = 5, SID_ALPHA = 6, SID_G = 7, SID_DHP = 8 };
 
-// layout of the layer workspace: 256 bytes of scalars, the column-sum accumulators of step 2' (outside the shared
+// layout of the layer workspace: 256 bytes of scalars, 256 bytes of partial maxima (small tensors' abs-max without
+// atomics), the column-sum accumulators of step 2' (outside the shared
 // part, so that the backward pass can clear them in its first launch), then the largest sub-call workspace
 // (S and D are updated by one kernel at the same time: kept in different 128-byte lines)
 enum { SC_ABSMAX_S = 0, SC_ABSMAX_D = 32, SC_ABSMAX_ALPHA = 16, SC_ABSMAX_G = 48 };
+
+constexpr size_t HDR = 512;                 // scalars + partial maxima
+constexpr int64_t SMALL_OUT_WORDS = 65536;  // outputs up to this size are cleared whole by the first launch of a chain
 
 size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 
@@ -41,7 +45,7 @@ size_t tango_gat_layer_workspace_bytes(int64_t n_nodes, int64_t n_edges, int k_i
     const size_t c = tango_head_proj_bwd_workspace_bytes(n_nodes, heads, dim);
     const size_t d = tango_gat_attention_bwd_workspace_bytes(n_nodes, n_edges, heads);
     const size_t e = tango_gat_attention_workspace_bytes(n_nodes, n_edges, heads);
-    return 256 + c + max3(a, b, max3(d, e, 0));
+    return HDR + c + max3(a, b, max3(d, e, 0));
 }
 
 int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
@@ -59,8 +63,8 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                   TANGO_ERR_WORKSPACE);
     float *sc = static_cast<float *>(L->ws);
     const size_t hpb = tango_head_proj_bwd_workspace_bytes(n, L->heads, L->dim);
-    void *sub = static_cast<char *>(L->ws) + 256 + hpb;
-    const size_t sub_bytes = L->ws_bytes - 256 - hpb;
+    void *sub = static_cast<char *>(L->ws) + HDR + hpb;
+    const size_t sub_bytes = L->ws_bytes - HDR - hpb;
     const uint64_t sid = 16 * L->layer_id;
     const bool proj_fused = tango_head_proj_quantize_supported(L->heads, L->dim) && tango_aligned(L->Hp, 16) &&
                             tango_aligned(L->Hp_q, 8) && tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16);
@@ -73,6 +77,14 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
         tango_zero_regions_add(zr, sc + SC_ABSMAX_D, 1);
     }
     if (L->fused) tango_zero_regions_add(zr, L->absmax_alpha, 1);
+    // small graphs: the same launch clears the whole output (a few thousand words), which spares the aggregation its own
+    // launch for clearing the rows it adds to
+    const bool out_prezero = L->fused && n * F <= SMALL_OUT_WORDS;
+    if (out_prezero) {
+        tango_zero_regions_add(zr, L->out, n * F);
+        tango_zero_regions_add(zr, L->absmax_out, 1);
+        if (gat_uses_relu_bits(L)) tango_zero_regions_add(zr, L->relu_bits, n * F / 32);
+    }
     TANGO_TRY(tango_qgemm_known_absmax(n, F, L->k_in, L->H, L->absmax_H, L->W, L->rounding, L->seed, sid + SID_H, sid + SID_W,
                                        L->H_q, L->s_H, L->W_q, L->s_W, L->Hp, L->absmax_Hp, sub, sub_bytes, stream, &zr));
     // step 2: S, D in fp32, with their abs-max
@@ -97,7 +109,7 @@ int tango_gat_layer_fwd(const tango_gat_layer *L, void *stream)
                                            L->rounding, L->seed, sid + SID_ALPHA, L->row_lse, L->alpha_q, L->s_alpha,
                                            L->absmax_alpha, L->alpha, L->out, L->absmax_out, L->relu_out,
                                            gat_uses_relu_bits(L) ? L->relu_bits : nullptr, L->src_codes, sub, sub_bytes,
-                                           stream, true);
+                                           stream, true, out_prezero);
     }
     // step 3: SDDMM-add with on-the-fly dequantization + LeakyReLU
     TANGO_TRY(tango_qsddmm(L->g, TANGO_SDDMM_ADD_LEAKYRELU, L->heads, 1, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->E,
@@ -134,10 +146,11 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                       tango_aligned(L->a_src, 16) && tango_aligned(L->a_dst, 16),
                   TANGO_ERR_BAD_SHAPE);
     float *sc = static_cast<float *>(L->ws);
-    void *hp_ws = static_cast<char *>(L->ws) + 256;
+    float *partials = sc + 64;  // 64 floats
+    void *hp_ws = static_cast<char *>(L->ws) + HDR;
     const size_t hpb = tango_head_proj_bwd_workspace_bytes(n, L->heads, L->dim);
-    void *sub = static_cast<char *>(L->ws) + 256 + hpb;
-    const size_t sub_bytes = L->ws_bytes - 256 - hpb;
+    void *sub = static_cast<char *>(L->ws) + HDR + hpb;
+    const size_t sub_bytes = L->ws_bytes - HDR - hpb;
     const uint64_t sid = 16 * L->layer_id;
     hipStream_t st = tango_stream(stream);
 
@@ -148,9 +161,19 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
     const bool find_absmax_g = !L->absmax_grad_out && !L->relu_out;
     tango_zero_regions zr{};
     tango_head_proj_bwd_zero_regions(L->heads, L->dim, hp_ws, L->absmax_dHp, zr);
-    if (find_absmax_g) tango_zero_regions_add(zr, sc + SC_ABSMAX_G, 1);
     if (att_prezero) tango_gat_attention_bwd_zero_regions(L->g, L->heads, sub, zr);
-    TANGO_TRY(tango_zero_regions_async(zr, st));
+    const bool dHp_prezero = att_prezero && n * F <= SMALL_OUT_WORDS;  // (as in the forward pass, for the reverse aggregation)
+    if (dHp_prezero) tango_zero_regions_add(zr, L->dHp, n * F);
+    // a small upstream gradient whose abs-max has to be found here: the clearing launch also leaves per-workgroup maxima
+    // of |grad_out|, which the quantizer reduces - one launch less than clear, abs-max, quantize
+    const bool g_partials = find_absmax_g && n * F <= 16 * SMALL_OUT_WORDS && tango_aligned(L->grad_out, 16) && tango_aligned(L->g_q, 8);
+    int g_count = 1;
+    if (g_partials) {
+        TANGO_TRY(tango_absmax_partials_async(L->grad_out, static_cast<size_t>(n * F), partials, &g_count, zr, st));
+    } else {
+        if (find_absmax_g) tango_zero_regions_add(zr, sc + SC_ABSMAX_G, 1);
+        TANGO_TRY(tango_zero_regions_async(zr, st));
+    }
 
     // the upstream gradient is quantized once and shared by steps 5' and 5''
     if (L->absmax_grad_out) {
@@ -169,6 +192,9 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
             TANGO_TRY(tango_quantize_masked_async(L->grad_out, L->out, static_cast<size_t>(n * F), L->rounding, L->seed,
                                                   sid + SID_G, L->g_q, L->s_g, static_cast<float *>(L->ws) + SC_ABSMAX_G,
                                                   tango_stream(stream)));
+    } else if (g_partials) {
+        TANGO_TRY(tango_quantize_with_absmax_async(L->grad_out, static_cast<size_t>(n * F), L->rounding, L->seed, sid + SID_G,
+                                                   partials, L->g_q, L->s_g, st, g_count));
     } else {
         TANGO_REQUIRE(tango_aligned(L->grad_out, 4), TANGO_ERR_BAD_SHAPE);
         TANGO_TRY(tango_absmax_accumulate_async(L->grad_out, static_cast<size_t>(n * F), sc + SC_ABSMAX_G, st));
@@ -180,7 +206,7 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
         TANGO_TRY(tango_gat_attention_bwd_cached(L->g, L->heads, L->dim, L->S_q, L->s_S, L->D_q, L->s_D, L->slope, L->row_lse,
                                                  L->alpha_q, L->s_alpha, L->absmax_alpha, L->rounding, L->seed,
                                                  sid + SID_ALPHA, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp, nullptr, L->dalpha,
-                                                 L->dS, L->dD, L->src_codes, sub, sub_bytes, stream, att_prezero));
+                                                 L->dS, L->dD, L->src_codes, sub, sub_bytes, stream, att_prezero, dHp_prezero));
     } else {
     // 5' (SPMM on the reversed graph) and 5'' (SDDMM-dot)
     TANGO_TRY(tango_qspmm_bwd(L->g, L->heads, L->dim, L->alpha_q, L->s_alpha, L->Hp_q, L->s_Hp, L->g_q, L->s_g, L->dHp,

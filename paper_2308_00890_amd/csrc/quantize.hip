@@ -85,10 +85,10 @@ template <int ROUNDING, int MASKED = 0>
 __device__ __forceinline__ void quantize_vec_body(const float *__restrict__ x, size_t n, const float *__restrict__ absmax,
                                                   const tango_rng &rng, int8_t *__restrict__ q, float *scale_out,
                                                   const float *__restrict__ mask, const uint8_t *__restrict__ mask_bits,
-                                                  unsigned bid, unsigned nblocks)
+                                                  unsigned bid, unsigned nblocks, int absmax_count = 1)
 {
     float s, inv;
-    tango_scale_from_absmax(*absmax, s, inv);
+    tango_scale_from_absmax(tango_absmax_load(absmax, absmax_count), s, inv);
     if (bid == 0 && threadIdx.x == 0 && scale_out) *scale_out = s;
     const size_t n8 = n / 8;
     const size_t tid = static_cast<size_t>(bid) * blockDim.x + threadIdx.x;
@@ -153,9 +153,29 @@ __global__ __launch_bounds__(256) void k_quantize_vec(const float *__restrict__ 
                                                       const float *__restrict__ absmax, tango_rng rng,
                                                       int8_t *__restrict__ q, float *scale_out,
                                                       const float *__restrict__ mask = nullptr,
-                                                      const uint8_t *__restrict__ mask_bits = nullptr)
+                                                      const uint8_t *__restrict__ mask_bits = nullptr, int absmax_count = 1)
 {
-    quantize_vec_body<ROUNDING, MASKED>(x, n, absmax, rng, q, scale_out, mask, mask_bits, blockIdx.x, gridDim.x);
+    quantize_vec_body<ROUNDING, MASKED>(x, n, absmax, rng, q, scale_out, mask, mask_bits, blockIdx.x, gridDim.x, absmax_count);
+}
+
+// partials[b] = max|x| over workgroup b's share (b < gridDim.x <= 64); the same launch clears the runs of z.
+__global__ __launch_bounds__(256) void k_absmax_partials(const float *__restrict__ x, size_t n, float *__restrict__ partials,
+                                                         tango_zero_regions z)
+{
+    __shared__ float red[4];
+    const size_t tid = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x, nthr = static_cast<size_t>(gridDim.x) * 256;
+    tango_zero_regions_apply(z, static_cast<int64_t>(tid), static_cast<int64_t>(nthr));
+    float m = 0.0f;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    for (size_t i = tid; i < n / 4; i += nthr) {
+        const float4 v = x4[i];
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    for (size_t i = n / 4 * 4 + tid; i < n; i += nthr) m = fmaxf(m, fabsf(x[i]));
+    m = tango_wave_max(m);
+    if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
 // Two tensors in one launch (the first g1 workgroups take the first): for the small tensors of a layer, whose
@@ -368,17 +388,33 @@ int tango_absmax_accumulate_async(const float *x, size_t n, float *out, hipStrea
     return TANGO_OK;
 }
 
+// For a small tensor: per-workgroup maxima of |x| into partials[0 .. *count) (x 16-byte aligned, *count <= 64), and the
+// runs of z cleared, in one launch; tango_quantize_with_absmax_async takes (partials, *count) in place of an abs-max word.
+int tango_absmax_partials_async(const float *x, size_t n, float *partials, int *count, const tango_zero_regions &z, hipStream_t st)
+{
+    TANGO_REQUIRE(!z.overflow && tango_aligned(x, 16), TANGO_ERR_BAD_SHAPE);
+    int64_t longest = static_cast<int64_t>(n / 4);
+    for (int r = 0; r < z.count; ++r) longest = z.n[r] > longest ? z.n[r] : longest;
+    const unsigned nb = tango_grid_for(static_cast<size_t>(longest), 256 * 2, 64);
+    k_absmax_partials<<<nb, 256, 0, st>>>(x, n, partials, z);
+    TANGO_LAUNCH_CHECK();
+    *count = static_cast<int>(nb);
+    return TANGO_OK;
+}
+
 int tango_quantize_with_absmax_async(const float *x, size_t n, int rounding, uint64_t seed, uint64_t stream_id,
-                                     const float *absmax, int8_t *q, float *scale_out, hipStream_t st)
+                                     const float *absmax, int8_t *q, float *scale_out, hipStream_t st, int absmax_count)
 {
     const tango_rng rng = tango_rng_make(seed, stream_id);
+    TANGO_REQUIRE(absmax_count >= 1 && absmax_count <= 64, TANGO_ERR_BAD_SHAPE);
     if (tango_aligned(x, 16) && tango_aligned(q, 8)) {
         const unsigned grid = tango_grid_for(n / 8 + 1, 256 * 2);
         if (rounding == TANGO_RN)
-            k_quantize_vec<TANGO_RN><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+            k_quantize_vec<TANGO_RN><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out, nullptr, nullptr, absmax_count);
         else
-            k_quantize_vec<TANGO_SR><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);
+            k_quantize_vec<TANGO_SR><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out, nullptr, nullptr, absmax_count);
     } else {
+        TANGO_REQUIRE(absmax_count == 1, TANGO_ERR_BAD_SHAPE);  // (partial maxima are only handed to the vector path)
         const unsigned grid = tango_grid_for(n + 1, 256 * 8);
         if (rounding == TANGO_RN)
             k_quantize_scalar<TANGO_RN><<<grid, 256, 0, st>>>(x, n, absmax, rng, q, scale_out);

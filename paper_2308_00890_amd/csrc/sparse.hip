@@ -186,6 +186,37 @@ __global__ __launch_bounds__(256) void k_spmm_finalize(spmm_args a)
         bool flag = false;
         if (lane < a.fin_rows && r < a.n) flag = row_is_split(a.ptr[r], a.ptr[r + 1], a.chunk_shift, a.short_max);
         unsigned long long mask = __ballot(flag);
+        if (!a.relu_bits) {
+            // several flagged rows at a time: a row is covered by F/4 lanes with four columns each, 64 / (F/4) rows side by
+            // side (one row after the other left most lanes idle on narrow rows, and each row is a dependent
+            // load - store round trip)
+            const int lpr = min(64, a.F / 4), G = 64 / lpr;
+            const int gi = lane / lpr, li = lane - gi * lpr;
+            while (mask) {
+                int myk = -1;
+                for (int g2 = 0; g2 < G && mask; ++g2) {
+                    const int k = __ffsll(static_cast<long long>(mask)) - 1;
+                    mask &= mask - 1;
+                    if (gi == g2) myk = k;
+                }
+                if (myk >= 0) {
+                    float4 *row4 = reinterpret_cast<float4 *>(a.out + (base + myk) * a.F);
+                    for (int c4 = li; c4 < a.F / 4; c4 += lpr) {
+                        const float4 v = row4[c4];
+                        int a0 = __float_as_int(v.x), a1 = __float_as_int(v.y), a2 = __float_as_int(v.z), a3 = __float_as_int(v.w);
+                        if (a.relu) {
+                            a0 = max(a0, 0); a1 = max(a1, 0); a2 = max(a2, 0); a3 = max(a3, 0);
+                        }
+                        float4 o;
+                        o.x = static_cast<float>(a0) * sc; o.y = static_cast<float>(a1) * sc;
+                        o.z = static_cast<float>(a2) * sc; o.w = static_cast<float>(a3) * sc;
+                        row4[c4] = o;
+                        m = fmaxf(m, fmaxf(fmaxf(fabsf(o.x), fabsf(o.y)), fmaxf(fabsf(o.z), fabsf(o.w))));
+                    }
+                }
+            }
+            continue;
+        }
         while (mask) {
             const int k = __ffsll(static_cast<long long>(mask)) - 1;
             mask &= mask - 1;
@@ -1303,7 +1334,7 @@ bool tango_spmm_relu_bits_supported(int64_t n_nodes, int heads, int dim)
 
 static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, const int8_t *w_q, const float *s_w,
                        const int8_t *X_q, const float *s_X, float *out, float *absmax_out, const attn_params *att,
-                       hipStream_t st, bool x4 = false, float *dS_out = nullptr)
+                       hipStream_t st, bool x4 = false, float *dS_out = nullptr, bool out_prezeroed = false)
 {
     spmm_args a;
     if (att) a.att = *att;
@@ -1352,8 +1383,12 @@ static int spmm_launch(const tango_graph *g, int direction, int heads, int dim, 
     const int64_t rows_per_boundary = a.nnz > 0 ? (static_cast<int64_t>(a.n) << a.chunk_shift) / a.nnz : 64;
     a.fin_rows = rows_per_boundary < 16 ? 8 : 64;
     const unsigned row_blocks = tango_grid_for((static_cast<size_t>(a.n) + a.fin_rows - 1) / a.fin_rows, 4, 256 * 8);
-    k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
-    TANGO_LAUNCH_CHECK();
+    // (out_prezeroed: an earlier launch of the caller's chain cleared all of out, the sign bits and *absmax_out, which
+    // covers what the prepare pass clears - the rows the main kernel adds to or never writes)
+    if (!out_prezeroed) {
+        k_spmm_prepare<<<row_blocks, 256, 0, st>>>(a);
+        TANGO_LAUNCH_CHECK();
+    }
     if (tiny && a.nnz > 0) {
         const int vec = pick_vec(a.F, dim, false, true);
         const unsigned sb = tango_grid_for((static_cast<size_t>(a.n) + 63) / 64, 4, 256 * 32);
@@ -1442,7 +1477,7 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
                                const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                int8_t *alpha_q, float *s_alpha, float *alpha_dump, const int8_t *X_q, const float *s_X,
                                float *out, float *absmax_out, int relu_out, uint16_t *relu_bits, const int8_t *src_codes,
-                               hipStream_t st)
+                               hipStream_t st, bool out_prezeroed)
 {
     attn_params att;
     att.relu_out = relu_out;
@@ -1453,7 +1488,7 @@ int tango_spmm_attention_async(const tango_graph *g, int direction, int heads, i
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = alpha_q; att.s_alpha = s_alpha; att.alpha_dump = alpha_dump;
     att.Xrow = nullptr; att.s_Xrow = nullptr; att.rec = nullptr; att.dS_acc = nullptr;
-    return spmm_launch(g, direction, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st);
+    return spmm_launch(g, direction, heads, dim, alpha_q, s_alpha, X_q, s_X, out, absmax_out, &att, st, false, nullptr, out_prezeroed);
 }
 
 // Steps 5' and 3' in one walk over the out-edges (attention codes recomputed): out = the reverse SPMM of dOut_q,
@@ -1464,7 +1499,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
                                       const float *absmax_alpha, int rounding, uint64_t seed, uint64_t stream_id,
                                       const float *s_alpha, const int8_t *dOut_q, const float *s_dOut, const int8_t *X_q,
                                       const float *s_X, const void *rec, double *dS_acc, float *out,
-                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st)
+                                      float *absmax_out, float *dS, bool dS_acc_zeroed, hipStream_t st, bool out_prezeroed)
 {
     const int64_t nh = static_cast<int64_t>(g->n_nodes) * heads;
     int rc = TANGO_OK;
@@ -1476,7 +1511,7 @@ int tango_spmm_attention_rev_ds_async(const tango_graph *g, int heads, int dim, 
     att.rng = tango_rng_make(seed, stream_id); att.rounding = rounding;
     att.alpha_q = nullptr; att.s_alpha = const_cast<float *>(s_alpha); att.alpha_dump = nullptr;
     att.Xrow = X_q; att.s_Xrow = s_X; att.rec = rec; att.dS_acc = dS_acc; att.relu_out = 0; att.relu_bits = nullptr; att.src_codes = nullptr;
-    rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st, false, dS);
+    rc = spmm_launch(g, TANGO_OUT, heads, dim, nullptr, s_alpha, dOut_q, s_dOut, out, absmax_out, &att, st, false, dS, out_prezeroed);
     if (rc != TANGO_OK) return rc;
     if (g->n_edges == 0) {  // no edge, no main kernel and no finalize launch: dS = 0 from the cleared sums
         k_f64_to_f32<<<tango_grid_for(static_cast<size_t>(nh), 256), 256, 0, st>>>(dS_acc, nh, dS);
