@@ -255,6 +255,29 @@ __device__ static inline double tango_wave_sum(double v)
     return v;
 }
 
+// The last step of the head-projection backward (step 2'): da_src[c], da_dst[c] = the sums over `copies` partial
+// accumulators of 2F doubles.  A few hundred additions: done by one workgroup of whatever launch follows in the chain
+// instead of in a launch of its own.
+struct tango_colsum_job {
+    const double *acc;  // NULL: nothing to do
+    int F, copies;
+    float *da_src, *da_dst;
+};
+
+__device__ static inline void tango_colsum_apply(const tango_colsum_job &j)
+{
+    if (!j.acc) return;
+    for (int c = threadIdx.x; c < j.F; c += blockDim.x) {
+        double ts = 0.0, td = 0.0;
+        for (int k = 0; k < j.copies; ++k) {
+            ts += j.acc[static_cast<size_t>(k) * 2 * j.F + c];
+            td += j.acc[static_cast<size_t>(k) * 2 * j.F + j.F + c];
+        }
+        j.da_src[c] = static_cast<float>(ts);
+        j.da_dst[c] = static_cast<float>(td);
+    }
+}
+
 // An abs-max handed from one kernel to the next is either one word (count == 1) or `count` partial maxima, one per
 // workgroup of the producing launch (no atomics, and so no launch that clears their target first); every lane returns
 // the maximum.  count <= 64.

@@ -267,25 +267,22 @@ __global__ __launch_bounds__(256) void k_quantize_b_small(int K, int N, int Kp, 
                                                           tango_zero_regions also_zero, const float *__restrict__ A, int64_t a_elems,
                                                           float *__restrict__ a_partials)
 {
-    __shared__ float red[4];
+    __shared__ float red[4], red_a[4];
+    __shared__ float Bs[SMALL_B_ELEMS];  // B itself: read from memory once, the second pass takes it from here
     const int64_t tid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x, nthr = static_cast<int64_t>(gridDim.x) * 256;
+    // a small A whose abs-max is not known (a_partials != NULL): this workgroup's share of max|A|, left as one of
+    // gridDim.x partial maxima for the GEMM kernel to reduce (no atomics, so no launch that clears their target, and no
+    // launch of its own).  Its loads go out together with those of B: one memory round trip for both.
+    tango_zero_regions_apply(also_zero, tid, nthr);  // (stores that nothing below waits for)
+    float ma = 0.0f;
     if (a_partials) {
-        // a small A whose abs-max is not known: this workgroup's share of max|A|, left as one of gridDim.x partial maxima
-        // for the GEMM kernel to reduce (no atomics, so no launch that clears their target, and no launch of its own)
-        float ma = 0.0f;
         const float4 *A4 = reinterpret_cast<const float4 *>(A);  // (A is 16-byte aligned: the entry point requires it)
         for (int64_t i = tid; i < a_elems / 4; i += nthr) {
             const float4 v = A4[i];
             ma = fmaxf(ma, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
         for (int64_t i = a_elems / 4 * 4 + tid; i < a_elems; i += nthr) ma = fmaxf(ma, fabsf(A[i]));
-        ma = tango_wave_max(ma);
-        if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = ma;
-        __syncthreads();
-        if (threadIdx.x == 0) a_partials[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        __syncthreads();
     }
-    __shared__ float Bs[SMALL_B_ELEMS];  // B itself: read from memory once, the second pass takes it from here
     const int total = K * N;
     float m = 0.0f;
     for (int i = threadIdx.x; i < total; i += 256) {
@@ -294,9 +291,14 @@ __global__ __launch_bounds__(256) void k_quantize_b_small(int K, int N, int Kp, 
         m = fmaxf(m, fabsf(v));
     }
     m = tango_wave_max(m);
-    if (threadIdx.x % TANGO_WAVE == 0) red[threadIdx.x / TANGO_WAVE] = m;
+    ma = tango_wave_max(ma);
+    if (threadIdx.x % TANGO_WAVE == 0) {
+        red[threadIdx.x / TANGO_WAVE] = m;
+        red_a[threadIdx.x / TANGO_WAVE] = ma;
+    }
     __syncthreads();
     m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    if (a_partials && threadIdx.x == 0) a_partials[blockIdx.x] = fmaxf(fmaxf(red_a[0], red_a[1]), fmaxf(red_a[2], red_a[3]));
     float s, inv;
     tango_scale_from_absmax(m, s, inv);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -305,7 +307,6 @@ __global__ __launch_bounds__(256) void k_quantize_b_small(int K, int N, int Kp, 
         if (absmax_A) *absmax_A = 0.0f;
         if (absmax_C) *absmax_C = 0.0f;
     }
-    tango_zero_regions_apply(also_zero, tid, nthr);
     const int wpr = Kp / 4;  // 32-bit words per row of BT
     for (int w = static_cast<int>(tid); w < Np * wpr; w += static_cast<int>(nthr)) {
         const int n = w / wpr, k0 = (w - n * wpr) * 4;
@@ -331,8 +332,9 @@ __global__ __launch_bounds__(256) void k_quantize_b_small(int K, int N, int Kp, 
 // either of which may be NULL.
 __global__ __launch_bounds__(256) void k_pad_copy_i8(int R, int C, int Rp, int Cp, const int8_t *__restrict__ src,
                                                      int8_t *__restrict__ dst, uint32_t *zero_words, int64_t n_zero,
-                                                     uint32_t *zero_one)
+                                                     uint32_t *zero_one, tango_colsum_job tail)
 {
+    if (blockIdx.x == gridDim.x - 1) tango_colsum_apply(tail);  // (a job left over from the previous step of the chain)
     const int wpr = Cp / 4;
     const int64_t words = static_cast<int64_t>(Rp) * wpr;
     if (blockIdx.x == 0 && threadIdx.x == 0 && zero_one) *zero_one = 0u;
@@ -652,7 +654,7 @@ int tango_qgemm_bwd(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const fl
 int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
                            const float *s_B, const float *dC, int rounding, uint64_t seed, uint64_t stream_id_dC,
                            const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, const uint32_t *dA_keep_bits,
-                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream)
+                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream, const tango_colsum_job *tail)
 {
     TANGO_REQUIRE(rounding == TANGO_RN || rounding == TANGO_SR, TANGO_ERR_BAD_ENUM);
     int rc = validate_mnk(M, N, K);
@@ -666,6 +668,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
     TANGO_REQUIRE(ws && tango_aligned(ws, 256) && ws_bytes >= tango_qgemm_bwd_workspace_bytes(M, N, K), TANGO_ERR_WORKSPACE);
     TANGO_REQUIRE((!dA_keep_bits && !absmax_dA) || (dA && N <= KMAX), TANGO_ERR_UNSUPPORTED);
     TANGO_REQUIRE(!dA_keep_bits || (K % 32 == 0 && tango_aligned(dA_keep_bits, 4)), TANGO_ERR_BAD_SHAPE);
+    TANGO_REQUIRE(!tail || (dA && N <= KMAX), TANGO_ERR_UNSUPPORTED);  // (the launch that takes the job exists only then)
     hipStream_t st = tango_stream(stream);
     float *am = static_cast<float *>(ws);
     int8_t *BT = static_cast<int8_t *>(ws) + 256;           // B_q padded: Kp64 rows x Np32 bytes
@@ -692,7 +695,7 @@ int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, c
         const int64_t n_zero = dB ? 2 * K * N : 0;
         k_pad_copy_i8<<<tango_grid_for(static_cast<size_t>(Cp) * Rp / 4 + n_zero, 256), 256, 0, st>>>(
             static_cast<int>(K), static_cast<int>(N), Cp, Rp, B_q, BT, reinterpret_cast<uint32_t *>(acc), n_zero,
-            reinterpret_cast<uint32_t *>(absmax_dA));
+            reinterpret_cast<uint32_t *>(absmax_dA), tail ? *tail : tango_colsum_job{nullptr, 0, 0, nullptr, nullptr});
         TANGO_LAUNCH_CHECK();
         acc_zeroed = true;
         fused_args a;

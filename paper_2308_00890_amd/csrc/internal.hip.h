@@ -41,7 +41,8 @@ int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X
 // were cleared by an earlier launch of the same chain.
 int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
                               const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
-                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed = false);
+                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed = false,
+                              tango_colsum_job *deferred = nullptr);  // non-NULL: the final column sums are left to the caller's next launch
 void tango_head_proj_bwd_zero_regions(int heads, int dim, void *ws, float *absmax_dX, tango_zero_regions &z);
 
 // tango_qgemm_bwd with a ReLU' on dA's way out: dA_keep_bits (optional; bit i of the flat M x K tensor, 4-byte aligned,
@@ -49,7 +50,8 @@ void tango_head_proj_bwd_zero_regions(int heads, int dim, void *ws, float *absma
 int tango_qgemm_bwd_masked(int64_t M, int64_t N, int64_t K, const int8_t *A_q, const float *s_A, const int8_t *B_q,
                            const float *s_B, const float *dC, int rounding, uint64_t seed, uint64_t stream_id_dC,
                            const float *absmax_dC_in, int8_t *dC_q, float *s_dC, float *dA, const uint32_t *dA_keep_bits,
-                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream);
+                           float *absmax_dA, float *dB, void *ws, size_t ws_bytes, void *stream,
+                           const tango_colsum_job *tail = nullptr);  // done by the call's first launch (only with dA and N <= 2048)
 
 // tango_qgemm with max|A| already on the device (absmax_A_in, may be NULL).
 int tango_qgemm_known_absmax(int64_t M, int64_t N, int64_t K, const float *A, const float *absmax_A_in, const float *B,

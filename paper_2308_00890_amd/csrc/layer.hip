@@ -218,13 +218,16 @@ int tango_gat_layer_bwd(const tango_gat_layer *L, void *stream)
                                stream));
     }
     // 2' fused with dH' = dH'_agg + dH'_att and its abs-max
+    // (its last step, a few hundred additions, rides on the first launch of the GEMM pair where that launch exists)
+    tango_colsum_job tail{nullptr, 0, 0, nullptr, nullptr};
+    const bool defer_tail = L->dH != nullptr && F <= 2048;
     TANGO_TRY(tango_head_proj_bwd_async(n, L->heads, L->dim, L->dS, L->dD, L->a_src, L->a_dst, L->Hp_q, L->s_Hp, L->dHp, L->dHp,
-                                        L->absmax_dHp, L->da_src, L->da_dst, hp_ws, st, true));
+                                        L->absmax_dHp, L->da_src, L->da_dst, hp_ws, st, true, defer_tail ? &tail : nullptr));
     // 1': both GEMMs from the cached H_q, W_q
     TANGO_REQUIRE((!L->dH_keep_bits && !L->absmax_dH) || L->dH, TANGO_ERR_NULL);
     TANGO_TRY(tango_qgemm_bwd_masked(n, F, L->k_in, L->H_q, L->s_H, L->W_q, L->s_W, L->dHp, L->rounding, L->seed, sid + SID_DHP,
                                      L->absmax_dHp, L->dHp_q, L->s_dHp, L->dH, static_cast<const uint32_t *>(L->dH_keep_bits),
-                                     L->absmax_dH, L->dW, sub, sub_bytes, stream));
+                                     L->absmax_dH, L->dW, sub, sub_bytes, stream, defer_tail ? &tail : nullptr));
     return TANGO_OK;
 }
 

@@ -291,19 +291,7 @@ __global__ __launch_bounds__(256) void k_head_proj_bwd(int64_t n, int heads, int
     if (absmax_dX) tango_block_max_update(m, absmax_dX);
 }
 
-__global__ void k_head_proj_bwd_finish(int F, const double *acc, float *da_src, float *da_dst)
-{
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c < F) {
-        double ts = 0.0, td = 0.0;
-        for (int k = 0; k < ACC_COPIES; ++k) {
-            ts += acc[static_cast<size_t>(k) * 2 * F + c];
-            td += acc[static_cast<size_t>(k) * 2 * F + F + c];
-        }
-        da_src[c] = static_cast<float>(ts);
-        da_dst[c] = static_cast<float>(td);
-    }
-}
+__global__ void k_head_proj_bwd_finish(tango_colsum_job job) { tango_colsum_apply(job); }
 
 }  // namespace
 
@@ -368,7 +356,8 @@ int tango_head_proj_quantize_async(int64_t n, int heads, int dim, const float *X
 
 int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, const float *dD, const float *a_src,
                               const float *a_dst, const int8_t *X_q, const float *s_X, const float *dX_agg, float *dX,
-                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed)
+                              float *absmax_dX, float *da_src, float *da_dst, void *ws, hipStream_t st, bool zeroed,
+                              tango_colsum_job *deferred)
 {
     const int F = heads * dim;
     double *acc = static_cast<double *>(ws);
@@ -380,7 +369,12 @@ int tango_head_proj_bwd_async(int64_t n, int heads, int dim, const float *dS, co
     k_head_proj_bwd<<<tango_grid_for(static_cast<size_t>((n + rpb - 1) / rpb), 8, 256 * 4), 256, 0, st>>>(
         n, heads, dim, dS, dD, a_src, a_dst, X_q, s_X, dX_agg, dX, absmax_dX, acc);
     TANGO_LAUNCH_CHECK();
-    k_head_proj_bwd_finish<<<(F + 255) / 256, 256, 0, st>>>(F, acc, da_src, da_dst);
+    const tango_colsum_job job{acc, F, ACC_COPIES, da_src, da_dst};
+    if (deferred) {  // the caller hands the column sums to the next launch of its chain
+        *deferred = job;
+        return TANGO_OK;
+    }
+    k_head_proj_bwd_finish<<<1, 256, 0, st>>>(job);
     TANGO_LAUNCH_CHECK();
     return TANGO_OK;
 }
