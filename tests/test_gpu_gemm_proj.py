@@ -35,6 +35,7 @@ GEMM_SHAPES = [
     (260, 72, 2320),   # ... and the same for the dA product of the backward pass (its reduction length is N)
     (200, 128, 64),    # the largest weight matrix that one workgroup prepares (8,192 elements)
     (200, 132, 64),    # ... and a size just above, which takes the multi-launch preparation
+    (20000, 64, 64),   # small weights, but an A above the size whose abs-max is handed over as partial maxima
 ]
 
 
